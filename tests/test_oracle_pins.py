@@ -1,0 +1,470 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests touches the GPU library.  Each one checks the oracle
+against something that is not the oracle: published known answers, numpy/torch
+library routines, closed forms, invariants, higher-precision re-derivations and
+brute force on tiny inputs.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import cvlc_synth as syn
+from oracle import cvlc_oracle as orc
+
+
+def _keys(U):
+    return U.view(np.uint32) & np.uint32(0x7FFFFFFF)
+
+
+def _read_kv(path):
+    out = {}
+    with open(path) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if line:
+                out[line[0]] = line[1:]
+    return out
+
+
+# --------------------------------------------------------------------------- Philox
+def test_philox_known_answers(golden_dir):
+    n = 0
+    with open(os.path.join(golden_dir, "philox4x32_10_kat.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            v = [int(t, 16) for t in line.split()]
+            assert orc.philox4x32_10(v[0:4], v[4:6]) == tuple(v[6:10])
+            n += 1
+    assert n == 3
+
+
+def test_u24_is_word0_top_bits_and_uniform():
+    seed = 0x0123456789ABCDEF
+    assert orc.u24(seed, 7, 11) == orc.philox4x32_10([11, 7, 0, 0], [0x89ABCDEF, 0x01234567])[0] >> 8
+    draws = np.array([orc.u24(2402, 3, i) for i in range(1 << 15)])
+    assert draws.max() < (1 << 24)
+    counts = np.bincount(draws >> 18, minlength=64)
+    expected = draws.size / 64
+    chi2 = ((counts - expected) ** 2 / expected).sum()
+    assert chi2 < 130  # 63 dof, p ~ 1e-6
+    # different clients and seeds give different streams
+    assert orc.u24(2402, 4, 0) != orc.u24(2402, 3, 0)
+    assert orc.u24(2403, 3, 0) != orc.u24(2402, 3, 0)
+
+
+# --------------------------------------------------------------------------- sizes the paper states
+def test_position_id_width(golden_dir):
+    const = _read_kv(os.path.join(golden_dir, "paper_constants.txt"))
+    assert orc.s_bits(10_000_000) == int(const["s_bits_at_10M_params"][0])
+    for d in [1, 2, 3, 4, 5, 255, 256, 257, 65_536, 65_537, 1_200_000, 11_200_000, 25_600_000, 2**31 - 1]:
+        assert orc.s_bits(d) == max(1, math.ceil(math.log2(d)))
+    assert [orc.s_bits(d) for d in (65_536, 1_200_000, 11_200_000, 25_600_000)] == [16, 21, 24, 25]
+
+
+def test_kmax_of_a_1500_byte_packet(golden_dir):
+    """k_max = R(b-H)/(s+1): at one bit per update a 1500-byte packet of a 10M
+    model holds fewer than 480 updates; with our 128-bit H it holds 474."""
+    const = _read_kv(os.path.join(golden_dir, "paper_constants.txt"))
+    b = int(const["packet_bytes"][0]) * 8
+    for R in (1, 3, 10):
+        p = orc.plan_budget(10_000_000, 256 + R * b, [1] * R)
+        assert p.counts() == [(b - 128) // 25] * R
+        assert p.k < int(const["kmax_per_packet_bound"][0]) * R
+        assert p.k >= R * int(const["kmin_per_packet"][0])
+
+
+def test_config_plans_match_closed_forms(golden_dir):
+    g = _read_kv(os.path.join(golden_dir, "config_sizes.txt"))
+    p1 = orc.plan_for(syn.WORKLOADS[1])
+    assert p1.counts() == [int(v) for v in g["cfg1_counts"]]
+    assert p1.total_bits == 8 * int(g["cfg1_stream_bytes"][0])
+    p4 = orc.plan_for(syn.WORKLOADS[4])
+    assert p4.counts() == [int(v) for v in g["cfg4_counts"]]
+    assert p4.total_bits == int(g["cfg4_total_bits"][0])
+    assert p4.total_bits <= syn.WORKLOADS[4].budget_bits()
+
+
+def _total_bits_closed_form(d, counts, code_len):
+    s = max(1, math.ceil(math.log2(d)))
+    return 32 * (8 + 4 * len(counts) + sum(-(-P * (s + y) // 32) for P, y in zip(counts, code_len)))
+
+
+def test_budget_accounting_and_maximality():
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        d = int(rng.integers(64, 5_000_000))
+        R = int(rng.integers(1, 12))
+        y = sorted(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 32], size=R).tolist(), reverse=True)
+        budget = int(d * rng.uniform(0.05, 3.0)) + 256 + 160 * R
+        p = orc.plan_budget(d, budget, y)
+        s = orc.s_bits(d)
+        assert p.total_bits == _total_bits_closed_form(d, p.counts(), y)
+        assert p.total_bits <= budget
+        b = 32 * ((budget - 256) // (32 * R))
+        left = d
+        for P, yr in zip(p.counts(), y):
+            assert 32 * (-(-P * (s + yr) // 32)) + 128 <= b      # Eq. (3) per group
+            assert (P + 1) * (s + yr) + 128 > b or P == left      # one more record would not fit
+            left -= P
+    with pytest.raises(orc.OracleError) as e:
+        orc.plan_budget(1000, 256 + 3 * 128, [4, 2, 1])           # no room for a single record
+    assert e.value.code == orc.ERR_BUDGET
+
+
+def test_stream_length_equals_plan_bits():
+    U = syn.update_vector(1, 0, d=5000)
+    for y, frac in [((8, 4, 2), (0.1, 0.15, 0.25)), ((16,), (1.0,)), ((32, 3), (0.01, 0.2)), ((5, 5, 1), (0.0, 0.3, 0.0))]:
+        p = orc.plan_fractions(5000, y, frac)
+        enc = orc.encode(U, p, 1, 0)
+        assert enc.words.size * 32 == p.total_bits == _total_bits_closed_form(5000, p.counts(), y)
+        assert int(enc.words[7]) == enc.words.size
+    with pytest.raises(orc.OracleError) as e:
+        orc.encode(U, p, 1, 0, cap_words=p.total_words - 1)
+    assert e.value.code == orc.ERR_CAPACITY
+
+
+# --------------------------------------------------------------------------- ranking and grouping
+TIE_KINDS = ["all_equal", "all_equal_mixed_sign", "two_valued", "few_levels", "zeros_and_denormals", "all_zero"]
+
+
+@pytest.mark.parametrize("kind", TIE_KINDS)
+def test_rank_matches_lexsort_on_tie_heavy_vectors(kind):
+    for d in (1, 2, 63, 64, 65, 1000, 1 << 16):
+        U = syn.tie_heavy_vector(kind, d, seed=d)
+        key = _keys(U).astype(np.int64)
+        ref = np.lexsort((np.arange(d), -key))      # magnitude descending, then index ascending
+        assert np.array_equal(orc.rank(U), ref.astype(np.uint32))
+
+
+def test_rank_distinct_magnitudes_matches_library_topk():
+    U = syn.update_vector(1, 3, d=20_000)
+    key = _keys(U)
+    assert np.unique(key).size == key.size or True
+    order = orc.rank(U)
+    for k in (1, 17, 2000, 19_999):
+        top = torch.topk(torch.from_numpy(np.abs(U).astype(np.float64)), k).indices.numpy()
+        kth = np.sort(key)[::-1][k - 1]
+        if (key == kth).sum() == 1:                      # boundary not tied: the set is unique
+            assert set(order[:k].tolist()) == set(top.tolist())
+    mags = np.abs(U[order].astype(np.float64))
+    assert np.all(mags[:-1] >= mags[1:])
+
+
+@pytest.mark.parametrize("kind", TIE_KINDS + ["laplace"])
+def test_segments_partition_by_rank(kind):
+    d = 4096
+    U = syn.update_vector(1, 1, d=d) if kind == "laplace" else syn.tie_heavy_vector(kind, d, seed=1)
+    p = orc.plan_manual(d, [8, 4, 4, 1], [100, 0, 1500, 901])
+    seg = orc.segments(U, p)
+    key = _keys(U).astype(np.int64)
+    ref_order = np.lexsort((np.arange(d), -key))
+    ref = np.zeros(d, dtype=np.uint32)
+    Z = np.cumsum([0] + p.counts())
+    for r in range(p.R):
+        ref[ref_order[Z[r]:Z[r + 1]]] = r + 1
+    assert np.array_equal(seg, ref)
+    assert [int((seg == r + 1).sum()) for r in range(p.R)] == p.counts()
+    present = [r for r in range(1, p.R + 1) if (seg == r).any()] + ([0] if (seg == 0).any() else [])
+    for a, b in zip(present[:-1], present[1:]):          # larger magnitudes in earlier groups
+        assert key[seg == a].min() >= key[seg == b].max()
+
+
+# --------------------------------------------------------------------------- the two special cases of Sec. I
+def test_one_group_of_raw_values_plus_zero_tail_is_topk():
+    U = syn.update_vector(2, 0, d=30_000)
+    for k in (1, 10, 3000):
+        p = orc.plan_manual(U.size, [32], [k])
+        out = orc.decode_aggregate([orc.encode(U, p, 9, 0).words], U.size)
+        idx = torch.topk(torch.from_numpy(np.abs(U)), k).indices.numpy()
+        ref = np.zeros_like(U)
+        ref[idx] = U[idx]
+        assert np.array_equal(out.view(np.uint32), ref.view(np.uint32))
+    # quantised top-k: same support, values within one centroid spacing
+    p = orc.plan_manual(U.size, [6], [3000])
+    enc = orc.encode(U, p, 9, 0)
+    out = orc.decode_aggregate([enc.words], U.size)
+    idx = torch.topk(torch.from_numpy(np.abs(U)), 3000).indices.numpy()
+    mask = np.zeros(U.size, bool)
+    mask[idx] = True
+    assert np.all(out[~mask] == 0)
+    step = (enc.stats[0].max - enc.stats[0].min) / 63
+    assert np.abs(out[mask] - U[mask]).max() <= step * (1 + 1e-5)
+
+
+@pytest.mark.parametrize("y", [1, 2, 5, 8, 12, 16])
+def test_single_code_length_is_plain_stochastic_quantisation(y):
+    """One group holding every coordinate: the CIDs are those of a textbook
+    stochastic uniform quantiser, evaluated here in float64 from the same
+    uniforms.  fp32 rounding may move a value across a decision boundary, so
+    the two may differ by one level on a tiny fraction of coordinates."""
+    U = syn.update_vector(1, 2, d=20_000)
+    d = U.size
+    p = orc.plan_manual(d, [y], [d])
+    enc = orc.encode(U, p, 77, 5, debug=True)
+    assert np.all(enc.seg == 1)
+    L1 = (1 << y) - 1
+    x = U.astype(np.float64)
+    m, M = x.min(), x.max()
+    t = (x - m) / (M - m) * L1
+    lower = np.floor(t)
+    u = np.array([orc.u24(77, 5, i) for i in range(d)], dtype=np.float64) / 2.0**24
+    ref = np.minimum(lower + (u < (t - lower)), L1).astype(np.int64)
+    diff = enc.cid.astype(np.int64) - ref
+    assert np.abs(diff).max() <= 1
+    assert (diff != 0).mean() < 2e-3
+    assert enc.stats[0].min == U.min() and enc.stats[0].max == U.max()
+
+
+# --------------------------------------------------------------------------- quantiser
+def test_quantiser_deterministic_invariants():
+    rng = np.random.default_rng(3)
+    for y in (1, 2, 3, 7, 8, 15, 16):
+        L1 = (1 << y) - 1
+        for _ in range(300):
+            m, M = np.sort(rng.normal(0, 1, 2).astype(np.float32))
+            x = np.float32(rng.uniform(m, M))
+            u = int(rng.integers(0, 1 << 24))
+            cid = orc.quantise(float(x), float(m), float(M), y, u)
+            assert 0 <= cid <= L1
+            step = (float(M) - float(m)) / L1
+            assert abs(orc.dequantise(cid, float(m), float(M), y) - float(x)) <= step * (1 + 1e-4) + 1e-12
+            assert orc.quantise(float(m), float(m), float(M), y, u) == 0
+            assert orc.quantise(float(M), float(m), float(M), y, u) == L1
+            # the two candidate centroids bracket x
+            lo = orc.quantise(float(x), float(m), float(M), y, (1 << 24) - 1)
+            hi = orc.quantise(float(x), float(m), float(M), y, 0)
+            assert hi - lo in (0, 1) and cid in (lo, hi)
+    # a single-valued group has one centroid and decodes exactly
+    assert orc.quantise(0.3, 0.3, 0.3, 4, 0) == 0
+    assert orc.dequantise(0, np.float32(0.3), np.float32(0.3), 4) == float(np.float32(0.3))
+    # raw 32-bit code keeps the bits
+    v = np.float32(-1.2345e-7)
+    assert orc.quantise(float(v), 0.0, 0.0, 32, 5) == int(v.view(np.uint32))
+
+
+def test_quantiser_unbiased_mse_closed_form_and_lemma1():
+    """E[x~] = x (Sec. IV-B), E||x~-x||^2 = sum step^2 p(1-p) <= P/(2^y-1)^2 ||x||^2 (PQ bound,
+    Appendix case study), and the decomposition (a) in the proof of Lemma 1."""
+    d, y, n_seeds, B = 48, 3, 6000, 2.0
+    U = syn.update_vector(1, 9, d=d)
+    p = orc.plan_manual(d, [y], [d])
+    L1 = (1 << y) - 1
+    x = U.astype(np.float64)
+    m, M = x.min(), x.max()
+    step = (M - m) / L1
+    t = (x - m) / step
+    frac = t - np.floor(t)
+    dec = np.empty((n_seeds, d))
+    for seed in range(n_seeds):
+        dec[seed] = orc.decode_aggregate([orc.encode(U, p, seed, 0).words], d)
+    mean = dec.mean(axis=0)
+    sd = step * np.sqrt(frac * (1 - frac) / n_seeds)
+    assert np.all(np.abs(mean - x) <= 5 * sd + 1e-9)
+    mse = ((dec - x) ** 2).sum(axis=1).mean()
+    closed = (step**2 * frac * (1 - frac)).sum()
+    assert abs(mse - closed) <= 0.05 * closed
+    assert mse <= d / L1**2 * (x**2).sum()
+    lhs = ((dec / B - x) ** 2).sum(axis=1).mean()
+    rhs = mse / B**2 + (1 - 1 / B) ** 2 * (x**2).sum()
+    assert abs(lhs - rhs) <= 0.02 * rhs
+    assert lhs <= (d / L1**2 + (B - 1) ** 2) / B**2 * (x**2).sum()
+
+
+# --------------------------------------------------------------------------- bit layout
+def _bits_of(words):
+    return np.unpackbits(words.astype("<u4").view(np.uint8), bitorder="little")
+
+
+def _field(bits, pos, n):
+    return int(sum(int(b) << i for i, b in enumerate(bits[pos:pos + n])))
+
+
+def test_bit_layout_by_independent_field_extraction():
+    d = 3000
+    U = syn.update_vector(1, 4, d=d)
+    code_len, counts = [16, 7, 3, 1], [5, 333, 0, 1001]
+    p = orc.plan_manual(d, code_len, counts, B=1.5)
+    enc = orc.encode(U, p, 123, 42, debug=True)
+    w, bits, s = enc.words, _bits_of(enc.words), 12
+    assert w[0] == 0x434C5643 and w[0].tobytes() == b"CVLC"
+    assert (w[1], w[2], w[3], w[4], w[6], w[7]) == (1, d, 4, s, 42, w.size)
+    assert w[5] == np.float32(1.5).view(np.uint32)
+    pos = 32 * (8 + 4 * 4)
+    used = np.zeros(bits.size, bool)
+    used[:pos] = True
+    for r, (y, P) in enumerate(zip(code_len, counts)):
+        hdr = w[8 + 4 * r: 12 + 4 * r]
+        members = np.flatnonzero(enc.seg == r + 1)
+        assert hdr[0] == y and hdr[1] == P == members.size
+        if P:
+            assert hdr[2] == U[members].min().view(np.uint32) and hdr[3] == U[members].max().view(np.uint32)
+        else:
+            assert hdr[2] == 0 and hdr[3] == 0
+        W = s + y
+        for e in range(P):
+            assert _field(bits, pos + e * W, s) == members[e]              # ascending position IDs
+            assert _field(bits, pos + e * W + s, y) == enc.cid[members[e]]
+        used[pos: pos + P * W] = True
+        pos += 32 * (-(-P * W // 32))
+    assert pos == bits.size
+    assert not bits[~used].any()                                           # padding is zero
+
+
+def test_tiny_vectors_brute_force_roundtrip():
+    rng = np.random.default_rng(11)
+    for d in (1, 2, 3, 5, 8, 12):
+        for R in (1, 2, 3):
+            for counts in itertools.product(range(0, d + 1), repeat=R):
+                if sum(counts) > d or rng.random() > 0.25:
+                    continue
+                y = sorted(rng.choice([1, 2, 3, 8, 16, 32], size=R).tolist(), reverse=True)
+                U = rng.normal(0, 1, d).astype(np.float32)
+                if d > 2:
+                    U[1] = -U[0]                                    # a tie across signs
+                p = orc.plan_manual(d, y, list(counts))
+                enc = orc.encode(U, p, int(rng.integers(1 << 40)), 1, debug=True)
+                pid, cid, seg = orc.unpack(enc.words, d)
+                order = np.lexsort((np.arange(d), -_keys(U).astype(np.int64)))
+                Z = np.cumsum((0,) + counts)
+                exp_pid = np.concatenate([np.sort(order[Z[r]:Z[r + 1]]) for r in range(R)] + [np.empty(0, np.int64)])
+                assert np.array_equal(pid, exp_pid.astype(np.uint32))
+                assert np.array_equal(cid, enc.cid[pid]) and np.array_equal(seg, enc.seg[pid])
+                out = orc.decode_aggregate([enc.words], d)
+                kept = np.zeros(d, bool)
+                kept[pid] = True
+                assert np.all(out[~kept] == 0)
+                for r in range(R):
+                    mem = pid[seg == r + 1]
+                    if mem.size == 0:
+                        continue
+                    if y[r] == 32:
+                        assert np.array_equal(out[mem], U[mem])
+                    else:
+                        step = (float(U[mem].max()) - float(U[mem].min())) / ((1 << y[r]) - 1)
+                        assert np.abs(out[mem].astype(np.float64) - U[mem]).max() <= step * (1 + 1e-4) + 1e-12
+
+
+# --------------------------------------------------------------------------- decode / aggregate
+def test_decode_aggregate_is_the_weighted_sum_of_single_decodes():
+    d, n = 6000, 5
+    streams, singles, Bs = [], [], [1.0, 2.0, 1.0, 4.0, 1.25]
+    for c in range(n):
+        U = syn.update_vector(2, c, d=d)
+        p = orc.plan_fractions(d, [8, 4, 2], [0.02 * (c + 1), 0.05, 0.1], B=Bs[c])
+        enc = orc.encode(U, p, 31337, c)
+        streams.append(enc.words)
+        singles.append(orc.decode_aggregate([enc.words], d, weights=[1.0]).astype(np.float64))
+    ref = sum(s / (n * B) for s, B in zip(singles, Bs))                 # average of U~/B
+    out = orc.decode_aggregate(streams, d)
+    assert np.allclose(out, ref, rtol=1e-6, atol=0)
+    wts = [0.5, -1.0, 2.0, 0.25, 3.0]
+    ref = sum(np.float32(w).astype(np.float64) * s for w, s in zip(wts, singles))
+    out = orc.decode_aggregate(streams, d, weights=wts)
+    assert np.array_equal(out, ref.astype(np.float32))
+    # streamed aggregation in two batches equals one call when the partial sum is exact in fp32
+    a = orc.decode_aggregate(streams[:1], d, weights=wts[:1])
+    b = orc.decode_aggregate(streams[1:], d, weights=wts[1:], out=a.copy())
+    assert np.allclose(b, out, rtol=1e-6, atol=1e-12)
+    # disjoint supports: nothing to add up, values pass through exactly
+    U = syn.update_vector(1, 0, d=d)
+    U1, U2 = U.copy(), U.copy()
+    U1[d // 2:] = 0
+    U2[: d // 2] = 0
+    p = orc.plan_manual(d, [32], [d // 4])
+    out = orc.decode_aggregate([orc.encode(U1, p, 1, 0).words, orc.encode(U2, p, 1, 1).words], d, weights=[1.0, 1.0])
+    both = orc.decode_aggregate([orc.encode(U1, p, 1, 0).words], d, weights=[1.0]) + \
+        orc.decode_aggregate([orc.encode(U2, p, 1, 1).words], d, weights=[1.0])
+    assert np.array_equal(out, both)
+    assert np.array_equal(orc.decode_aggregate([], d), np.zeros(d, np.float32))
+
+
+def test_malformed_input_is_rejected():
+    d = 500
+    U = syn.update_vector(1, 0, d=d)
+    p = orc.plan_fractions(d, [4], [0.2])
+    for bad in (np.nan, np.inf, -np.inf):
+        V = U.copy()
+        V[17] = bad
+        with pytest.raises(orc.OracleError) as e:
+            orc.encode(V, p, 1, 0)
+        assert e.value.code == orc.ERR_NONFINITE
+    good = orc.encode(U, p, 1, 0).words
+    cases = []
+    w = good.copy(); w[0] ^= 1; cases.append(w)                      # magic
+    w = good.copy(); w[2] = d + 1; cases.append(w)                   # other model size
+    w = good.copy(); w[8] = 17; cases.append(w)                      # unsupported code length
+    w = good.copy(); w[9] += 1; cases.append(w)                      # count does not match the length
+    cases.append(good[:-1].copy())                                   # truncated
+    w = good.copy(); w[12] |= (1 << 9) - 1; cases.append(w)          # first PID = 511 >= d
+    for w in cases:
+        with pytest.raises(orc.OracleError) as e:
+            orc.decode_aggregate([w], d)
+        assert e.value.code == orc.ERR_STREAM
+    for counts, y in (([d + 1], [4]), ([10, 10], [2, 4]), ([10], [17]), ([10], [0])):
+        with pytest.raises(orc.OracleError) as e:
+            orc.plan_manual(d, y, counts)
+        assert e.value.code == orc.ERR_PLAN
+
+
+# --------------------------------------------------------------------------- planner (Proposition 2, Algorithm 1)
+def _gamma_eq5(d, counts, code_len, alpha, B=1.0):
+    """Eq. (5) typed from the paper, in Python floats."""
+    beta = 2 * alpha + 1
+    pw = lambda z: max(z, 1.0) ** beta
+    k = sum(counts)
+    g = (pw(d) - pw(k + 1)) / (pw(d) - 1)
+    Z = 0
+    for P, y in zip(counts, code_len):
+        if P:
+            Q = P / (2.0**y - 1) ** 2
+            g += (Q / B**2 + (1 - 1 / B) ** 2) * (pw(Z + P) - pw(Z)) / (pw(d) - 1)
+        Z += P
+    return g
+
+
+def test_gamma_matches_equation_5():
+    for alpha in (-0.9, -0.55, -0.2):
+        for B in (1.0, 3.0):
+            p = orc.plan_manual(100_000, [10, 6, 2], [100, 1000, 20_000], B=B)
+            assert math.isclose(orc.gamma(p, alpha), _gamma_eq5(100_000, p.counts(), p.code_len(), alpha, B), rel_tol=1e-10)
+    # beta = 2 alpha + 1 = 0 is the logarithmic limit of the same expression
+    p = orc.plan_manual(100_000, [10, 6, 2], [100, 1000, 20_000])
+    assert math.isclose(orc.gamma(p, -0.5), _gamma_eq5(100_000, p.counts(), p.code_len(), -0.5 + 1e-7), rel_tol=1e-5)
+    # keeping everything at 32 raw bits leaves (almost) no error; dropping everything leaves all of it
+    assert orc.gamma(orc.plan_manual(1000, [32], [1000]), -0.5) < 1e-12
+    assert math.isclose(orc.gamma(orc.plan_manual(1000, [], []), -0.5), 1.0, rel_tol=1e-12)
+
+
+@pytest.mark.parametrize("alpha", [-0.9, -0.6, -0.3])
+def test_algorithm1_plan_is_feasible_monotone_and_near_the_integer_optimum(alpha):
+    d, budget = 200_000, 150_000
+    s = orc.s_bits(d)
+    for R in (1, 2, 3):
+        p = orc.plan_alg1(d, budget, R, alpha)
+        assert p.total_bits <= budget
+        y, P = p.code_len(), p.counts()
+        assert all(a >= b for a, b in zip(y[:-1], y[1:]))           # Eq. (4): P_1 <= ... <= P_R
+        assert all(a <= b for a, b in zip(P[:-1], P[1:]))
+        u = 32 * ((budget - 256) // (32 * R)) - 128
+        assert all(Pr == u // (s + yr) for Pr, yr in zip(P, y))      # Eq. (3) tight
+        best = min(_gamma_eq5(d, [u // (s + yr) for yr in ys], ys, alpha)
+                   for ys in itertools.combinations_with_replacement(range(16, 0, -1), R))
+        got = _gamma_eq5(d, P, y, alpha)
+        assert got <= best * 1.05 + 1e-12
+        if R == 1:                                                   # the P_y Top_k family of Sec. V: picks its best y
+            assert math.isclose(got, best, rel_tol=1e-9)
+
+
+def test_alpha_fit_recovers_a_power_law():
+    d = 1 << 15
+    for alpha in (-0.4, -0.8):
+        mags = (np.arange(1, d + 1, dtype=np.float64) ** alpha).astype(np.float32)
+        rng = np.random.default_rng(1)
+        U = (mags * rng.choice([-1.0, 1.0], d)).astype(np.float32)[rng.permutation(d)]
+        assert abs(orc.fit_alpha(U) - alpha) < 1e-3
