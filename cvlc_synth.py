@@ -54,7 +54,8 @@ class Workload:
         if self.cfg == 5:  # per-client budget, uniform in [0.25, 2] bit/coord
             rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([2402, 3770, 5, client, 99])))
             return int(self.d * rng.uniform(0.25, 2.0))
-        assert self.bits_per_coord is not None
+        if self.bits_per_coord is None:  # plan fixed by fractions: no budget
+            return 0
         return int(self.d * self.bits_per_coord)
 
 

@@ -1,0 +1,154 @@
+/*
+ * cvlc.h -- C ABI of the MI355X (gfx950) implementation of Fed-CVLC's per-round
+ * hot path: compress a client's model-update vector with variable-length codes
+ * and, on the parameter server, decode and aggregate many clients' streams.
+ *
+ * Conventions
+ *   - Every function returns CVLC_OK (0) or a negative cvlc_status; none throws
+ *     or aborts.  Errors that the host can see (null pointers, plan shape,
+ *     capacities, workspace size) are returned before anything is launched.
+ *   - "d_" arguments are DEVICE pointers, everything else is HOST memory.  All
+ *     buffers are owned by the caller; the library keeps no state between calls
+ *     and allocates no device memory.
+ *   - GPU entry points only enqueue work on `hip_stream` (a hipStream_t, NULL =
+ *     the default stream) and return; results are ready when the stream has
+ *     drained.  Conditions only the device can see (a NaN in the update, a
+ *     malformed stream) set bits in a status word at the start of the
+ *     workspace; read it with cvlc_device_status().
+ *   - The library needs a gfx950 device; there is no CPU fallback.
+ */
+#ifndef CVLC_H
+#define CVLC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum cvlc_status {
+  CVLC_OK = 0,
+  CVLC_ERR_ARG = -1,       /* null pointer, zero size, misaligned buffer          */
+  CVLC_ERR_PLAN = -2,      /* plan violates Eq. (3)-(4) or an unsupported length  */
+  CVLC_ERR_BUDGET = -3,    /* the bit budget cannot hold even k_min = R updates   */
+  CVLC_ERR_CAPACITY = -4,  /* stream buffer or workspace too small                */
+  CVLC_ERR_NONFINITE = -5, /* reserved for host-side checks of non-finite input   */
+  CVLC_ERR_STREAM = -6,    /* stream shorter than a header                        */
+  CVLC_ERR_DEVICE = -7     /* a HIP call failed                                   */
+} cvlc_status;
+
+/* bits of the device status word */
+#define CVLC_DEV_NONFINITE 1u /* update holds NaN/Inf, or a group's max-min overflows  */
+#define CVLC_DEV_STREAM 2u    /* malformed stream: header, code length, PID >= d, order */
+#define CVLC_DEV_INTERNAL 4u  /* an internal consistency check failed                   */
+
+#define CVLC_MAX_CODED 31u    /* at most 31 coded groups plus the implicit 0-bit tail   */
+#define CVLC_STATS_STRIDE 32u /* stats entries per client: groups 1..R, then the tail   */
+
+/* The code-length plan of one client for one round (Algorithm 1's output
+ * k*, P_r*, y_r*): coded group r = 1..R takes the P_r updates of ranks
+ * (Z_{r-1}, Z_r] by magnitude and spends y_r bits on each; ranks beyond
+ * k = P_1+...+P_R are sparsified away (code length 0). */
+typedef struct cvlc_plan_t {
+  uint32_t d;                        /* number of model updates, 1 .. 2^31-1          */
+  uint32_t n_coded;                  /* R                                             */
+  uint32_t s;                        /* position-ID width ceil(log2 d) (below Eq. (2)) */
+  uint32_t code_len[CVLC_MAX_CODED]; /* y_r, non-increasing, each in 1..16 or 32 (raw) */
+  uint32_t count[CVLC_MAX_CODED];    /* P_r, may be 0                                 */
+  uint64_t total_bits;               /* exact stream size, headers and padding included */
+  float B;                           /* scale factor of Lemma 1, > 0 (1 = no scaling) */
+  uint32_t quant;                    /* 0 = PQ (uniform centroids on [min,max])       */
+} cvlc_plan_t;
+
+/* Per-group statistics returned by the encoder: entries 0..R-1 are the coded
+ * groups, entry R the sparsified tail (min = max = 0 there; its sumsq is the
+ * sparsification error energy of Proposition 1's first term). */
+typedef struct cvlc_seg_stats_t {
+  float min, max;
+  double sumsq;
+  uint32_t count;
+  uint32_t reserved;
+} cvlc_seg_stats_t;
+
+/* s = ceil(log2 d), at least 1 (Sec. IV-C, below Eq. (2)). */
+uint32_t cvlc_position_bits(uint32_t d);
+
+/* CPU.  Builds a plan for a d-dimensional update with n_coded groups.
+ *   fractions != NULL (with code_len): group r takes the fraction fractions[r]
+ *       of the d coordinates; budget_bits is ignored.
+ *   fractions == NULL, code_len != NULL: group sizes from the budget, every
+ *       group getting the same bit share b, P_r = floor((b-H)/(s+y_r)), Eq. (3).
+ *   both NULL: Algorithm 1 -- enumerate k, sweep the atomic operation of Eq. (6)
+ *       over adjacent groups, pick the plan minimising gamma of Eq. (5) for the
+ *       power-law exponent alpha of Definition 1 (alpha < 0).
+ * The stream layout charges a 256-bit global header and H = 128 bits per group.
+ * Returns CVLC_ERR_BUDGET when the budget cannot hold one update per group. */
+int cvlc_plan(uint32_t d, uint64_t budget_bits, uint32_t n_coded, const uint32_t* code_len,
+              const double* fractions, double alpha, float B, cvlc_plan_t* out);
+
+/* CPU.  Checks a caller-built plan (sizes, monotone code lengths, total_bits). */
+int cvlc_plan_validate(const cvlc_plan_t* plan);
+
+/* CPU.  Exact stream size in bits for the plan's d, code_len and count. */
+uint64_t cvlc_plan_total_bits(const cvlc_plan_t* plan);
+
+/* CPU.  gamma of Eq. (5) for the plan under exponent alpha. */
+double cvlc_plan_gamma(const cvlc_plan_t* plan, double alpha);
+
+/* Bytes a stream buffer must hold for this plan (= total_bits / 8). */
+size_t cvlc_stream_capacity(const cvlc_plan_t* plan);
+
+/* Scratch bytes cvlc_encode_batch needs for n_clients vectors of length d, and
+ * cvlc_decode_aggregate needs for n_clients streams of a d-dimensional model. */
+size_t cvlc_encode_workspace_bytes(uint32_t d, uint32_t n_clients);
+size_t cvlc_decode_workspace_bytes(uint32_t d, uint32_t n_clients);
+
+/* GPU.  Compresses n clients' update vectors (Sec. IV-B sparsification and
+ * quantisation, Algorithm 1's final loop, packet format of Sec. IV-D).
+ *   plans[i]         host; all plans must share the same d
+ *   d_updates[i]     host array of device pointers, each d fp32, 16-byte aligned
+ *   seed             key of the counter-based rounding generator
+ *   client_ids[i]    host; written to the header and mixed into the generator
+ *   d_streams_out[i] host array of device pointers, 4-byte aligned, each at
+ *                    least capacities[i] >= cvlc_stream_capacity(&plans[i]) bytes
+ *   d_workspace      device, 256-byte aligned, ws_bytes >= cvlc_encode_workspace_bytes(d, n)
+ *   d_stats_out      device or NULL: n * CVLC_STATS_STRIDE cvlc_seg_stats_t
+ * The stream is bit-identical for identical (update, plan, seed, client id).
+ * Calls that share a workspace must not overlap in time. */
+int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* d_updates,
+                      uint64_t seed, const uint32_t* client_ids, void* const* d_streams_out,
+                      const size_t* capacities, void* d_workspace, size_t ws_bytes,
+                      cvlc_seg_stats_t* d_stats_out, void* hip_stream);
+
+/* GPU.  One client; same as cvlc_encode_batch with n = 1. */
+int cvlc_encode(const cvlc_plan_t* plan, const float* d_update, uint64_t seed, uint32_t client_id,
+                void* d_stream_out, size_t capacity, void* d_workspace, size_t ws_bytes,
+                cvlc_seg_stats_t* d_stats_out, void* hip_stream);
+
+/* GPU.  Parameter-server side (Sec. III step 3 with the scaling of Sec. IV-B):
+ * d_out[j] = sum_i w_i * xhat_{i,j}, xhat the centroid value stored for
+ * position j in stream i, 0 where the stream holds nothing.
+ *   d_streams[i]    host array of device pointers, 4-byte aligned
+ *   stream_bytes[i] host; bytes readable at d_streams[i]
+ *   weights         host or NULL; NULL => w_i = 1/(n * B_i), B_i from the header
+ *   flags bit 0     0 = overwrite d_out, 1 = add to the values already there
+ * Products and sums are carried in fp64 and rounded to fp32 once.  A malformed
+ * stream sets CVLC_DEV_STREAM; its offending records are skipped and nothing is
+ * written out of bounds. */
+#define CVLC_DECODE_ACCUMULATE 1u
+int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t* stream_bytes,
+                          const float* weights, float* d_out, uint32_t d, uint32_t flags,
+                          void* d_workspace, size_t ws_bytes, void* hip_stream);
+
+/* Waits for hip_stream and copies the workspace's device status word to
+ * *status_out (0 = clean, else CVLC_DEV_* bits). */
+int cvlc_device_status(const void* d_workspace, void* hip_stream, uint32_t* status_out);
+
+/* Static description of a status code. */
+const char* cvlc_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CVLC_H */

@@ -636,11 +636,14 @@ int orc_decode_aggregate(uint32_t n, const uint32_t* const* streams, const uint6
     for (uint32_t r = 0; r < h.R; ++r) {
       uint32_t W = h.s + h.y[r];
       const uint32_t* seg_words = streams[i] + h.payload_word[r];
+      uint32_t prev_pid = 0;
       for (uint32_t e = 0; e < h.P[r]; ++e) {
         uint64_t record = get_bits(seg_words, (uint64_t)e * W, W);
         uint32_t pid = (uint32_t)(record & (((uint64_t)1 << h.s) - 1u));
         uint32_t cid = (uint32_t)(record >> h.s);
-        if (pid >= d) { free(acc); return ORC_ERR_STREAM; }
+        /* a group's records come in strictly ascending position */
+        if (pid >= d || (e > 0 && pid <= prev_pid)) { free(acc); return ORC_ERR_STREAM; }
+        prev_pid = pid;
         acc[pid] += w * (double)orc_dequantise(cid, h.m[r], h.M[r], h.y[r]);
       }
     }

@@ -1,0 +1,296 @@
+"""GPU parity: libcvlc's HIP path against the CPU oracle, element by element,
+through the C ABI (paper_2402_03770_amd.cvlc is argument marshalling only).
+
+Bars: streams, group assignments (which records land in which group) and CIDs
+are compared bit for bit; min/max exactly; sums of squares to 1e-6 relative;
+the aggregate to 1e-5 * sum_i |w_i xhat_ij| per element (fp summation order is
+free), single-client decode bit for bit.
+"""
+import ctypes as C
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+import cvlc_synth as syn
+import paper_2402_03770_amd.cvlc as cv
+from oracle import cvlc_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def to_lib_plan(po: orc.Plan) -> cv.Plan:
+    """The same plan in the library's struct (plans are inputs to both sides)."""
+    return cv.plan_manual(po.d, po.code_len(), po.counts(), B=float(po.B))
+
+
+def gpu_encode(host_updates, oracle_plans, seed, client_ids, want_stats=True):
+    n = len(host_updates)
+    d = host_updates[0].size
+    plans = [to_lib_plan(p) for p in oracle_plans]
+    updates = [torch.from_numpy(u).to(DEV) for u in host_updates]
+    streams = [cv.new_stream_buffer(p, DEV) for p in plans]
+    for s in streams:
+        s.fill_(-1)  # the encoder must overwrite every word
+    ws = cv.new_workspace(cv.encode_workspace_bytes(d, n), DEV)
+    stats = torch.zeros(n * cv.STATS_STRIDE * C.sizeof(cv.SegStats), dtype=torch.uint8, device=DEV) if want_stats else None
+    cv.encode_batch(plans, updates, seed, client_ids, streams, ws, stats)
+    status = cv.device_status(ws)
+    words = [s.cpu().numpy().view(np.uint32)[: p.stream_bytes // 4] for s, p in zip(streams, plans)]
+    st = [cv.read_stats(stats, c, plans[c].n_coded) for c in range(n)] if want_stats else None
+    return words, st, status, streams
+
+
+def assert_stream_equal(got, ref, what=""):
+    assert got.size == ref.size, what
+    if not np.array_equal(got, ref):
+        bad = np.flatnonzero(got != ref)
+        raise AssertionError(f"{what}: {bad.size} of {ref.size} words differ, first at word {bad[0]}: "
+                             f"{got[bad[0]]:#x} != {ref[bad[0]]:#x}")
+
+
+def assert_stats_close(got, ref, R):
+    for r in range(R + 1):
+        assert got[r].count == ref[r].count, r
+        assert np.float32(got[r].min).view(np.uint32) == np.float32(ref[r].min).view(np.uint32), r
+        assert np.float32(got[r].max).view(np.uint32) == np.float32(ref[r].max).view(np.uint32), r
+        assert got[r].sumsq == pytest.approx(ref[r].sumsq, rel=1e-6, abs=1e-300), r
+
+
+def check_encode(host_updates, oracle_plans, seed, client_ids):
+    words, stats, status, streams = gpu_encode(host_updates, oracle_plans, seed, client_ids)
+    assert status == 0
+    refs = []
+    for c, (u, p) in enumerate(zip(host_updates, oracle_plans)):
+        ref = orc.encode(u, p, seed, client_ids[c])
+        assert_stream_equal(words[c], ref.words, f"client {c}")
+        assert_stats_close(stats[c], ref.stats, p.R)
+        refs.append(ref.words)
+    return refs, streams
+
+
+def gpu_decode(streams_dev, d, weights=None, accumulate_into=None):
+    out = torch.full((d,), float("nan"), dtype=torch.float32, device=DEV) if accumulate_into is None else accumulate_into
+    ws = cv.new_workspace(cv.decode_workspace_bytes(d, len(streams_dev)), DEV)
+    cv.decode_aggregate(streams_dev, out, ws, weights=weights, accumulate=accumulate_into is not None)
+    return out.cpu().numpy(), cv.device_status(ws)
+
+
+def abs_terms(ref_streams, d, weights=None):
+    """sum_i |w_i xhat_ij| from the oracle's single-client decodes."""
+    n = len(ref_streams)
+    tot = np.zeros(d)
+    for i, s in enumerate(ref_streams):
+        w = weights[i] if weights is not None else None
+        single = orc.decode_aggregate([s], d, weights=[1.0]).astype(np.float64)
+        B = float(s[5:6].view(np.float32)[0])
+        tot += np.abs(single) * (abs(float(np.float32(w))) if w is not None else 1.0 / (n * B))
+    return tot
+
+
+def check_decode(ref_streams, d, weights=None):
+    dev_streams = [torch.from_numpy(s.view(np.int32)).to(DEV) for s in ref_streams]
+    got, status = gpu_decode(dev_streams, d, weights)
+    assert status == 0
+    ref = orc.decode_aggregate(ref_streams, d, weights=weights)
+    tol = 1e-5 * abs_terms(ref_streams, d, weights)
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    assert np.all(err <= tol), f"max excess {np.max(err - tol)}"
+    return got, ref
+
+
+# --------------------------------------------------------------------------- configuration 1, full size
+def test_cfg1_roundtrip_bit_exact():
+    w = syn.WORKLOADS[1]
+    U = syn.update_vector(1, 0)
+    p = orc.plan_for(w)
+    refs, dev_streams = check_encode([U], [p], w.quant_seed, [0])
+    got, status = gpu_decode(dev_streams, w.d, weights=[1.0])
+    assert status == 0
+    ref = orc.decode_aggregate(refs, w.d, weights=[1.0])
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))      # one client: bit exact
+    kept = orc.segments(U, p) > 0
+    assert np.all(got[~kept] == 0) and kept.sum() == p.k
+
+
+def test_encode_is_deterministic_and_seed_sensitive():
+    U = syn.update_vector(1, 5, d=50_000)
+    p = orc.plan_fractions(U.size, [6, 3, 1], [0.05, 0.1, 0.2])
+    a, _, sa, _ = gpu_encode([U], [p], 11, [4], want_stats=False)
+    b, _, sb, _ = gpu_encode([U], [p], 11, [4], want_stats=False)
+    c, _, _, _ = gpu_encode([U], [p], 12, [4], want_stats=False)
+    e, _, _, _ = gpu_encode([U], [p], 11, [5], want_stats=False)
+    assert sa == 0 and sb == 0
+    assert np.array_equal(a[0], b[0])
+    assert not np.array_equal(a[0], c[0]) and not np.array_equal(a[0], e[0])
+
+
+# --------------------------------------------------------------------------- shapes: ragged tails, tiny inputs, odd plans
+@pytest.mark.parametrize("d", [1, 2, 15, 16, 17, 63, 64, 65, 1000, 4095, 4096, 4097, 8191, 12_289, 100_003])
+def test_ragged_sizes(d):
+    rng = np.random.default_rng(d)
+    U = syn.update_vector(1, d % 7, d=d)
+    R = int(min(4, d))
+    cuts = np.sort(rng.integers(0, d + 1, size=R))
+    counts = np.diff(np.concatenate([[0], cuts])).tolist()
+    y = sorted(rng.choice([1, 2, 5, 8, 16, 32], size=R).tolist(), reverse=True)
+    p = orc.plan_manual(d, y, counts)
+    refs, _ = check_encode([U], [p], 1000 + d, [d % 5])
+    check_decode(refs, d)
+
+
+def test_degenerate_plans():
+    d = 20_000
+    U = syn.update_vector(2, 1, d=d)
+    cases = [
+        ([], []),                                  # nothing coded: header-only stream
+        ([8], [d]),                                # everything coded: plain quantisation
+        ([32], [d]),                               # everything raw
+        ([16, 8, 4], [0, 0, 0]),                   # empty groups only
+        ([16, 8, 8, 2], [0, 7, 0, 1]),             # empty groups between tiny ones
+        ([4, 4, 4], [1, 1, 1]),                    # single-member groups: one centroid each
+        ([1] * 31, [100] * 31),                    # the maximum number of groups
+        ([16] + [3] * 30, [1] + [600] * 30),
+    ]
+    for y, counts in cases:
+        p = orc.plan_manual(d, y, counts)
+        refs, _ = check_encode([U], [p], 5, [9])
+        check_decode(refs, d)
+
+
+TIE_KINDS = ["all_equal", "all_equal_mixed_sign", "two_valued", "few_levels", "zeros_and_denormals", "all_zero"]
+
+
+@pytest.mark.parametrize("kind", TIE_KINDS)
+def test_tie_heavy_vectors(kind):
+    for d in (777, 65_536, 70_001):
+        U = syn.tie_heavy_vector(kind, d, seed=d)
+        p = orc.plan_manual(d, [8, 4, 4, 1], [d // 50, 0, d // 3, d // 4])
+        refs, _ = check_encode([U], [p], 3, [1])
+        check_decode(refs, d)
+
+
+def test_boundary_ties_inside_smooth_data():
+    """A smooth vector into which runs of equal magnitudes (mixed signs) are planted
+    right at the group boundaries."""
+    d = 300_000
+    U = syn.update_vector(1, 8, d=d)
+    order = np.argsort(-np.abs(U), kind="stable")
+    counts = [3000, 7000, 20_000]
+    for Z in np.cumsum(counts):
+        members = order[Z - 40: Z + 40]
+        U[members] = np.abs(U[order[Z]]) * np.where(np.arange(80) % 3 == 0, -1.0, 1.0).astype(np.float32)
+    p = orc.plan_manual(d, [8, 4, 2], counts)
+    refs, _ = check_encode([U], [p], 8, [2])
+    check_decode(refs, d)
+
+
+# --------------------------------------------------------------------------- batches of clients with different plans
+def test_batch_with_mixed_plans():
+    d = 150_000
+    host, plans = [], []
+    for c in range(6):
+        host.append(syn.update_vector(2 if c % 2 else 3, c, d=d))
+        R = [3, 7, 15, 16, 31, 1][c]
+        plans.append(orc.plan_alg1(d, int(d * (0.4 + 0.3 * c)), R, -0.6, B=[1.0, 2.0, 1.0, 1.5, 1.0, 3.0][c]))
+    ids = [10, 11, 12, 13, 14, 15]
+    refs, _ = check_encode(host, plans, 99, ids)
+    check_decode(refs, d)
+    check_decode(refs, d, weights=[0.5, -1.0, 2.0, 0.25, 1.0, 1e-3])
+
+
+@pytest.mark.parametrize("cfg,d,n", [(2, 1_200_000, 8), (3, 700_001, 4), (4, 1_000_000, 4), (5, 800_000, 3)])
+def test_workloads_at_oracle_friendly_sizes(cfg, d, n):
+    w = syn.WORKLOADS[cfg]
+    host = [syn.update_vector(cfg, c, d=d) for c in range(n)]
+    plans = [orc.plan_for(w, client=c, alpha=orc.fit_alpha(host[c]), d=d) for c in range(n)]
+    refs, _ = check_encode(host, plans, w.quant_seed, list(range(n)))
+    check_decode(refs, d)
+
+
+# --------------------------------------------------------------------------- decode / aggregate specifics
+def test_decode_accumulate_mode_and_empty_batch():
+    d = 90_000
+    refs = []
+    for c in range(5):
+        U = syn.update_vector(2, c, d=d)
+        refs.append(orc.encode(U, orc.plan_fractions(d, [8, 3], [0.02, 0.1]), 7, c).words)
+    wts = [1.0, 0.5, 0.25, 2.0, 4.0]
+    dev = [torch.from_numpy(s.view(np.int32)).to(DEV) for s in refs]
+    first, st = gpu_decode(dev[:2], d, weights=wts[:2])
+    assert st == 0
+    acc = torch.from_numpy(first.copy()).to(DEV)
+    both, st = gpu_decode(dev[2:], d, weights=wts[2:], accumulate_into=acc)
+    assert st == 0
+    ref_first = orc.decode_aggregate(refs[:2], d, weights=wts[:2])
+    ref = orc.decode_aggregate(refs[2:], d, weights=wts[2:], out=ref_first.copy())
+    tol = 1e-5 * abs_terms(refs, d, wts) + 1e-30
+    assert np.all(np.abs(both.astype(np.float64) - ref) <= tol)
+    none, st = gpu_decode([], d)
+    assert st == 0 and np.all(none == 0)
+
+
+def test_malformed_streams_set_status_and_stay_in_bounds():
+    d = 40_000
+    U = syn.update_vector(1, 0, d=d)
+    good = orc.encode(U, orc.plan_fractions(d, [8, 2], [0.05, 0.2]), 1, 0).words
+    cases = []
+    w = good.copy(); w[0] ^= 1; cases.append(w)                           # magic
+    w = good.copy(); w[2] = d + 1; cases.append(w)                        # other model size
+    w = good.copy(); w[8] = 17; cases.append(w)                           # unsupported code length
+    w = good.copy(); w[9] += 1; cases.append(w)                           # count does not match the length
+    w = good.copy(); w[16] |= (1 << 16) - 1; cases.append(w)              # first PID = 65535 >= d
+    w = good.copy(); w[16:20] = good[40:44]; cases.append(w)              # positions out of order
+    for w in cases:
+        with pytest.raises(orc.OracleError):
+            orc.decode_aggregate([w], d)
+        out, status = gpu_decode([torch.from_numpy(w.view(np.int32)).to(DEV)], d)
+        assert status & cv.DEV_STREAM
+        assert np.all(np.isfinite(out))
+    out, status = gpu_decode([torch.from_numpy(good.view(np.int32)).to(DEV)], d)   # the untouched stream still decodes
+    assert status == 0
+
+
+def test_non_finite_update_sets_status():
+    d = 30_000
+    p = orc.plan_fractions(d, [8], [0.1])
+    for bad in (np.nan, np.inf, -np.inf):
+        U = syn.update_vector(1, 0, d=d)
+        U[12_345] = bad
+        _, _, status, _ = gpu_encode([U], [p], 1, [0], want_stats=False)
+        assert status & cv.DEV_NONFINITE
+        with pytest.raises(orc.OracleError):
+            orc.encode(U, p, 1, 0)
+
+
+# --------------------------------------------------------------------------- full benchmark size
+def _parallel(fn, items, workers=12):
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        return list(ex.map(fn, items))
+
+
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_full_size_32_clients(cfg):
+    """The benchmark's launch configuration: 32 clients, d = 11.2M, one batched encode
+    and one decode-aggregate.  Every client's stream is compared with the oracle's, and
+    the aggregate is compared element by element."""
+    w = syn.WORKLOADS[cfg]
+    n, d = w.n_clients, w.d
+    host = _parallel(lambda c: syn.update_vector(cfg, c), range(n), workers=8)
+    alpha = -0.5
+    plans = [orc.plan_for(w, client=c, alpha=alpha) for c in range(1)] * n
+    words, stats, status, dev_streams = gpu_encode(host, plans, w.quant_seed, list(range(n)))
+    assert status == 0
+    refs = _parallel(lambda c: orc.encode(host[c], plans[c], w.quant_seed, c), range(n))
+    for c in range(n):
+        assert_stream_equal(words[c], refs[c].words, f"cfg {cfg} client {c}")
+        assert_stats_close(stats[c], refs[c].stats, plans[c].R)
+    got, status = gpu_decode(dev_streams, d)
+    assert status == 0
+    ref_streams = [r.words for r in refs]
+    ref = orc.decode_aggregate(ref_streams, d)
+    tol = 1e-5 * abs_terms(ref_streams, d)
+    assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= tol)

@@ -1,0 +1,104 @@
+"""Host-side checks of libcvlc that need no GPU: the library loads, exports
+every symbol the header declares, its planner agrees with the oracle's, and
+argument errors are reported before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import cvlc_synth as syn
+import paper_2402_03770_amd.cvlc as cv
+from oracle import cvlc_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "cvlc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(cvlc_[a-z_0-9]+)\s*\(", text)
+    assert len(set(names)) >= 12
+    lib = cv.lib()
+    for name in set(names):
+        assert hasattr(lib, name), name
+
+
+def _same(pg, po):
+    return pg.counts() == po.counts() and pg.code_lens() == po.code_len() and pg.total_bits == po.total_bits \
+        and pg.s == po.s and pg.d == po.d
+
+
+def test_planner_matches_oracle_on_the_workloads():
+    for cfg, w in syn.WORKLOADS.items():
+        for alpha in (-0.35, -0.7):
+            po = orc.plan_for(w, client=3, alpha=alpha)
+            if w.mode == "fractions":
+                pg = cv.plan(w.d, code_len=w.code_len, fractions=w.fractions)
+            elif w.mode == "budget":
+                pg = cv.plan(w.d, w.budget_bits(3), code_len=w.code_len)
+            else:
+                pg = cv.plan(w.d, w.budget_bits(3), n_coded=w.n_coded, alpha=alpha)
+            assert _same(pg, po), cfg
+            assert w.mode == "fractions" or pg.total_bits <= w.budget_bits(3)
+            assert cv.plan_gamma(pg, alpha) == pytest.approx(orc.gamma(po, alpha), rel=1e-12)
+
+
+def test_planner_matches_oracle_on_random_inputs():
+    rng = np.random.default_rng(17)
+    for _ in range(60):
+        d = int(rng.integers(100, 3_000_000))
+        R = int(rng.integers(1, 9))
+        budget = int(d * rng.uniform(0.1, 2.5)) + 256 + 200 * R
+        alpha = float(rng.uniform(-0.95, -0.1))
+        B = float(rng.choice([1.0, 1.5, 4.0]))
+        y = sorted(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 32], size=R).tolist(), reverse=True)
+        assert _same(cv.plan(d, budget, code_len=y, B=B), orc.plan_budget(d, budget, y, B))
+        assert _same(cv.plan(d, budget, n_coded=R, alpha=alpha, B=B), orc.plan_alg1(d, budget, R, alpha, B))
+        frac = rng.dirichlet(np.ones(R + 1))[:R].tolist()
+        assert _same(cv.plan(d, code_len=y, fractions=frac, B=B), orc.plan_fractions(d, y, frac, B))
+
+
+def test_plan_errors():
+    with pytest.raises(cv.CvlcError) as e:
+        cv.plan(1000, 256 + 3 * 128, code_len=[4, 2, 1])
+    assert e.value.code == -3
+    with pytest.raises(cv.CvlcError) as e:
+        cv.plan(1000, 10_000, code_len=[17])
+    assert e.value.code == -2
+    for counts, y in (([1001], [4]), ([10, 10], [2, 4]), ([10], [0])):
+        with pytest.raises(cv.CvlcError) as e:
+            cv.plan_manual(1000, y, counts)
+        assert e.value.code == -2
+    p = cv.plan_manual(1000, [8, 2], [10, 100])
+    assert p.total_bits == 32 * (8 + 8 + -(-10 * 18 // 32) + -(-100 * 12 // 32)) == 8 * cv.stream_capacity(p)
+    assert cv.position_bits(10_000_000) == 24
+
+
+def test_argument_errors_are_returned_before_any_launch():
+    """Null pointers, misalignment and short buffers never reach the device."""
+    lib = cv.lib()
+    p = cv.plan_manual(1000, [8], [100])
+    vp = C.c_void_p
+    good_ws = cv.encode_workspace_bytes(1000, 1)
+    assert good_ws > 0 and cv.encode_workspace_bytes(1000, 2) > good_ws
+    upd, out, ws = 0x1000, 0x2000, 0x10000
+    call = lambda u, o, cap, w, wsz: lib.cvlc_encode(C.byref(p), vp(u), 1, 0, vp(o), cap, vp(w), wsz, None, None)
+    assert call(None, out, 4096, ws, good_ws) == -1
+    assert call(upd + 4, out, 4096, ws, good_ws) == -1          # update not 16-byte aligned
+    assert call(upd, out + 2, 4096, ws, good_ws) == -1          # stream not 4-byte aligned
+    assert call(upd, out, p.stream_bytes - 1, ws, good_ws) == -4
+    assert call(upd, out, 4096, ws, good_ws - 1) == -4
+    assert call(upd, out, 4096, ws + 8, good_ws) == -1          # workspace not 256-byte aligned
+    bad = cv.Plan.from_buffer_copy(p)
+    bad.total_bits += 32
+    assert lib.cvlc_encode(C.byref(bad), vp(upd), 1, 0, vp(out), 4096, vp(ws), good_ws, None, None) == -2
+    streams = (vp * 1)(out)
+    sizes = (C.c_size_t * 1)(16)
+    dws = cv.decode_workspace_bytes(1000, 1)
+    assert lib.cvlc_decode_aggregate(1, streams, sizes, None, vp(0x3000), 1000, 0, vp(ws), dws, None) == -6
+    sizes[0] = 4096
+    assert lib.cvlc_decode_aggregate(1, streams, sizes, None, None, 1000, 0, vp(ws), dws, None) == -1
+    assert lib.cvlc_decode_aggregate(1, streams, sizes, None, vp(0x3000), 1000, 0, vp(ws), dws - 1, None) == -4
+    assert cv.status_string(-4) == "buffer too small"

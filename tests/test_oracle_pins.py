@@ -402,6 +402,7 @@ def test_malformed_input_is_rejected():
     w = good.copy(); w[9] += 1; cases.append(w)                      # count does not match the length
     cases.append(good[:-1].copy())                                   # truncated
     w = good.copy(); w[12] |= (1 << 9) - 1; cases.append(w)          # first PID = 511 >= d
+    w = good.copy(); w[12:14] = good[20:22]; cases.append(w)         # positions no longer ascending
     for w in cases:
         with pytest.raises(orc.OracleError) as e:
             orc.decode_aggregate([w], d)
