@@ -503,6 +503,12 @@ static uint64_t get_bits(const uint32_t* words, uint64_t bitpos, uint32_t nbits)
   return v;
 }
 
+/* Order used for a group's min and max: numeric order, and -0 below +0, so
+ * that the stored extremes do not depend on the order the group is visited in. */
+static int value_below(float a, float b) {
+  return a < b || (a == b && signbit(a) && !signbit(b));
+}
+
 /* Compress one client's update vector.
  *   words_out   cap_words 32-bit words, receives plan->total_bits/32 words
  *   stats_out   R+1 entries (groups 1..R, then the sparsified tail), or NULL
@@ -551,8 +557,8 @@ int orc_encode(const float* U, const orc_plan* p, uint64_t seed, uint32_t client
     double sumsq = 0.0;
     for (uint32_t e = 0; e < P; ++e) {
       float x = U[members[e]];
-      if (e == 0 || x < m) m = x;
-      if (e == 0 || x > M) M = x;
+      if (e == 0 || value_below(x, m)) m = x;
+      if (e == 0 || value_below(M, x)) M = x;
       sumsq += (double)x * (double)x;
     }
     if (P > 0 && !isfinite(M - m)) { free(order); return ORC_ERR_NONFINITE; }

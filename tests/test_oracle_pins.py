@@ -316,6 +316,13 @@ def test_bit_layout_by_independent_field_extraction():
     assert not bits[~used].any()                                           # padding is zero
 
 
+def test_signed_zero_extremes_do_not_depend_on_order():
+    for U in (np.array([0.0, -0.0, 0.0], np.float32), np.array([-0.0, 0.0, -0.0], np.float32)):
+        enc = orc.encode(U, orc.plan_manual(3, [4], [3]), 1, 0)
+        assert enc.words[10] == 0x80000000 and enc.words[11] == 0      # min = -0, max = +0
+        assert np.array_equal(orc.decode_aggregate([enc.words], 3), np.zeros(3, np.float32))
+
+
 def test_tiny_vectors_brute_force_roundtrip():
     rng = np.random.default_rng(11)
     for d in (1, 2, 3, 5, 8, 12):
