@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the Fed-CVLC hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic updates: one
+batched encode of all clients' vectors (resident in HBM) followed by one
+decode-aggregate of their streams into a dense fp32 vector.  Prints ONE JSON
+line; `value` counts the input coordinates (clients x d) a step accounts for.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E peak
+PLANNER_ALPHA = -0.5      # power-law exponent handed to Algorithm 1 for the planned workloads
+
+
+def make_plans(cv, w, n, d):
+    if w.mode == "fractions":
+        return [cv.plan(d, code_len=w.code_len, fractions=w.fractions)] * n
+    if w.mode == "budget":
+        return [cv.plan(d, w.budget_bits(c), code_len=w.code_len) for c in range(n)]
+    cache = {}
+    plans = []
+    for c in range(n):
+        b = w.budget_bits(c)
+        if b not in cache:
+            cache[b] = cv.plan(d, b, n_coded=w.n_coded, alpha=PLANNER_ALPHA)
+        plans.append(cache[b])
+    return plans
+
+
+def cpu_baseline(host_updates, w, d, seconds_cap=25.0):
+    """The oracle, single thread, on as many clients as fit the time cap (at least one)."""
+    from oracle import cvlc_oracle as orc
+
+    streams, t_enc, done = [], 0.0, 0
+    for c, U in enumerate(host_updates):
+        plan = orc.plan_for(w, client=c, alpha=PLANNER_ALPHA, d=d)
+        t0 = time.perf_counter()
+        streams.append(orc.encode(U, plan, w.quant_seed, c).words)
+        t_enc += time.perf_counter() - t0
+        done += 1
+        if t_enc > seconds_cap * 0.8:
+            break
+    t0 = time.perf_counter()
+    orc.decode_aggregate(streams, d)
+    t_dec = time.perf_counter() - t0
+    total = t_enc + t_dec
+    return {
+        "value": done * d / total / 1e9, "unit": "G-coords/s", "cores": 1, "kind": "oracle",
+        "sample": f"{done} of {len(host_updates)} clients, d={d}: encode {t_enc:.2f}s + decode-aggregate {t_dec:.2f}s, single thread",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--cfg", type=int, default=3, help="workload number (cvlc_synth.WORKLOADS)")
+    ap.add_argument("--clients", type=int, default=0, help="override the number of clients")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stages", action="store_true", help="also print a per-stage event breakdown to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import cvlc_synth as syn
+    import paper_2402_03770_amd.cvlc as cv
+
+    cv.lib()  # fail loudly if libcvlc.so is missing
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w = syn.WORKLOADS[args.cfg]
+    n = args.clients or w.n_clients
+    d = w.d
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        host = list(ex.map(lambda c: syn.update_vector(args.cfg, c), range(n)))
+    updates = [torch.from_numpy(u).to(dev) for u in host]
+    plans = make_plans(cv, w, n, d)
+    streams = [cv.new_stream_buffer(p, dev) for p in plans]
+    enc_ws = cv.new_workspace(cv.encode_workspace_bytes(d, n), dev)
+    dec_ws = cv.new_workspace(cv.decode_workspace_bytes(d, n), dev)
+    out = torch.empty(d, dtype=torch.float32, device=dev)
+    ids = list(range(n))
+    stream_bytes = sum(p.stream_bytes for p in plans)
+
+    def encode():
+        cv.encode_batch(plans, updates, w.quant_seed, ids, streams, enc_ws)
+
+    def decode():
+        cv.decode_aggregate(streams, out, dec_ws)
+
+    def timed(fn, steps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    for _ in range(args.warmup):
+        encode()
+        decode()
+    assert cv.device_status(enc_ws) == 0 and cv.device_status(dec_ws) == 0
+
+    # timed region: K whole steps; the dominant kernel is bracketed with HIP events on its own stream
+    cv.profile_start(["enc_filter"])
+    t_step = timed(lambda: (encode(), decode()), args.steps)
+    prof = cv.profile_stop()
+    filter_ms = prof["enc_filter"][0] / prof["enc_filter"][1]
+
+    t_enc = timed(encode, args.steps)
+    t_dec = timed(decode, args.steps)
+    assert cv.device_status(enc_ws) == 0 and cv.device_status(dec_ws) == 0
+
+    if args.stages:
+        cv.profile_start()
+        timed(lambda: (encode(), decode()), args.steps)
+        for name, (ms, cnt) in cv.profile_stop().items():
+            print(f"  stage {name:13s} {1e3 * ms / cnt:9.1f} us", file=sys.stderr)
+
+    enc_bytes = 4.0 * n * d + stream_bytes            # compulsory read of every update + stream written
+    dec_bytes = stream_bytes + 4.0 * d                # streams read + dense vector written
+    filter_bytes = 4.0 * n * d                        # what the filter launch must read
+    achieved = filter_bytes / (filter_ms * 1e-3) / 1e9
+    result = {
+        "metric": "encode + decode-aggregate G-coords/s and % of HBM peak, 1 MI355X",
+        "value": n * d / t_step / 1e9,
+        "unit": "G-coords/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"cfg{args.cfg} {w.name}: {n} clients, d={d}, {w.n_coded} coded groups + 0-bit tail, "
+                               f"{stream_bytes * 8 / (n * d):.3f} bit/coord", "clients": n, "d": d},
+        "encode": {"ms": t_enc * 1e3, "g_coords_s": n * d / t_enc / 1e9, "algorithmic_gb": enc_bytes / 1e9,
+                   "hbm_frac": enc_bytes / t_enc / 1e9 / HBM_PEAK_GBS},
+        "decode_aggregate": {"ms": t_dec * 1e3, "g_coords_s": n * d / t_dec / 1e9, "algorithmic_gb": dec_bytes / 1e9,
+                             "hbm_frac": dec_bytes / t_dec / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"bound": "hbm", "kernel": "filter_kernel<0>", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "launch_ms": filter_ms},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(host, w, d)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -145,6 +145,29 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
  * *status_out (0 = clean, else CVLC_DEV_* bits). */
 int cvlc_device_status(const void* d_workspace, void* hip_stream, uint32_t* status_out);
 
+/* Profiling aid (not part of the hot path).  Between cvlc_profile_start and
+ * cvlc_profile_stop every cvlc_encode_batch / cvlc_decode_aggregate call of this
+ * process brackets the stages selected in stage_mask (bit i = stage i) with a
+ * pair of HIP events on the call's stream.  cvlc_profile_stop waits for those
+ * events and returns, per stage, the summed elapsed milliseconds and the number
+ * of brackets; both arrays hold CVLC_PROFILE_STAGES entries.  Not thread safe. */
+enum {
+  CVLC_STAGE_ENC_SETUP = 0,    /* clear scratch, upload per-client parameters   */
+  CVLC_STAGE_ENC_SAMPLE = 1,   /* sample histogram -> candidate threshold       */
+  CVLC_STAGE_ENC_FILTER = 2,   /* the full pass over the update vectors         */
+  CVLC_STAGE_ENC_REFILTER = 3, /* second full pass, only if the sample misjudged */
+  CVLC_STAGE_ENC_SELECT = 4,   /* exact boundary keys + ties                    */
+  CVLC_STAGE_ENC_CLASSIFY = 5, /* group counts and statistics                   */
+  CVLC_STAGE_ENC_LAYOUT = 6,   /* prefix sums, headers                          */
+  CVLC_STAGE_ENC_EMIT = 7,     /* quantise + pack                               */
+  CVLC_STAGE_DEC_SETUP = 8,    /* upload + header parsing                       */
+  CVLC_STAGE_DEC_TABLE = 9,    /* per-list tile boundaries                      */
+  CVLC_STAGE_DEC_TILES = 10,   /* fused decode + accumulate                     */
+  CVLC_PROFILE_STAGES = 11
+};
+int cvlc_profile_start(uint32_t stage_mask);
+int cvlc_profile_stop(float* ms_per_stage, uint32_t* brackets_per_stage);
+
 /* Static description of a status code. */
 const char* cvlc_status_string(int status);
 

@@ -167,4 +167,14 @@ __host__ __device__ __forceinline__ void centroid_spacing(float m, float M, uint
 
 int hip_check(hipError_t e);  // hipSuccess -> CVLC_OK, else CVLC_ERR_DEVICE
 
+// Brackets a stage of a call with HIP events while profiling is switched on
+// (cvlc_profile_start); does nothing otherwise.
+void profile_mark(int stage, bool begin, hipStream_t stream);
+struct StageScope {
+  int stage;
+  hipStream_t stream;
+  StageScope(int stage_, hipStream_t stream_) : stage(stage_), stream(stream_) { profile_mark(stage, true, stream); }
+  ~StageScope() { profile_mark(stage, false, stream); }
+};
+
 }  // namespace cvlc

@@ -238,6 +238,7 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
   uint32_t* table = reinterpret_cast<uint32_t*>(base + L.table);
   const uint32_t n_lists = n * CVLC_MAX_CODED;
 
+  profile_mark(CVLC_STAGE_DEC_SETUP, true, stream);
   int rc = hip_check(hipMemsetAsync(status, 0, 256, stream));
   if (rc) return rc;
   if (n > 0) {
@@ -260,11 +261,18 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
       hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(sargs), chunk);
     }
     hipLaunchKernelGGL(parse_headers_kernel, dim3(n), dim3(64), 0, stream, sargs, descs, d, n, status);
+  }
+  profile_mark(CVLC_STAGE_DEC_SETUP, false, stream);
+  if (n > 0) {
+    StageScope scope(CVLC_STAGE_DEC_TABLE, stream);
     hipLaunchKernelGGL(tile_table_kernel, dim3(8, n_lists), dim3(kBlock), 0, stream, descs, table, d, L.n_tiles,
                        n_lists, status);
   }
-  hipLaunchKernelGGL(decode_tiles_kernel, dim3(L.n_tiles), dim3(kBlock), 0, stream, descs, table, d_out, d,
-                     L.n_tiles, n_lists, flags & CVLC_DECODE_ACCUMULATE, status);
+  {
+    StageScope scope(CVLC_STAGE_DEC_TILES, stream);
+    hipLaunchKernelGGL(decode_tiles_kernel, dim3(L.n_tiles), dim3(kBlock), 0, stream, descs, table, d_out, d,
+                       L.n_tiles, n_lists, flags & CVLC_DECODE_ACCUMULATE, status);
+  }
   return hip_check(hipGetLastError());
 }
 

@@ -986,6 +986,7 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   const uint32_t n_src = d / 16u;
   const uint32_t n_s = n_src < kSampleChunksMax ? n_src : kSampleChunksMax;
 
+  profile_mark(CVLC_STAGE_ENC_SETUP, true, stream);
   if ((rc = hip_check(hipMemsetAsync(base + L.status, 0, 256, stream)))) return rc;
   if ((rc = hip_check(hipMemsetAsync(base + L.zero_begin, 0, L.zero_end - L.zero_begin, stream)))) return rc;
 
@@ -1026,33 +1027,52 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
     }
   }
 
+  profile_mark(CVLC_STAGE_ENC_SETUP, false, stream);
+
   auto spread = [n](uint32_t want_total, uint32_t cap) {  // workgroups per client
     uint32_t g = (want_total + n - 1) / n;
     if (g > cap) g = cap;
     return g < 1 ? 1u : g;
   };
   if (any_sampled) {
+    StageScope scope(CVLC_STAGE_ENC_SAMPLE, stream);
     const uint32_t g = spread(512, (n_s * 4u + kBlock - 1) / kBlock);
     hipLaunchKernelGGL(sample_hist_kernel, dim3(g, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, n_s, n_src);
   }
   {
     const uint32_t g = spread(2048, L.n_tiles);
-    hipLaunchKernelGGL(filter_kernel<0>, dim3(g, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+    {
+      StageScope scope(CVLC_STAGE_ENC_FILTER, stream);
+      hipLaunchKernelGGL(filter_kernel<0>, dim3(g, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+    }
+    StageScope scope(CVLC_STAGE_ENC_REFILTER, stream);
     hipLaunchKernelGGL(filter_kernel<1>, dim3(g, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
   }
   const uint32_t g_sel = spread(1024, (d + kBlock * 8 - 1) / (kBlock * 8));
-  hipLaunchKernelGGL(select_l1_kernel, dim3(g_sel, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
-  const uint32_t groups = (max_R + kSlotGroup - 1) / kSlotGroup;
-  // one launch per group of boundaries; clients with fewer boundaries leave it at once
-  for (uint32_t gr = 0; gr < groups; ++gr)
-    hipLaunchKernelGGL(select_l23_kernel<2>, dim3(g_sel, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws, gr);
-  for (uint32_t gr = 0; gr < groups; ++gr)
-    hipLaunchKernelGGL(select_l23_kernel<3>, dim3(g_sel, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws, gr);
-  hipLaunchKernelGGL(tie_resolve_kernel, dim3(kTieBlocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+  {
+    StageScope scope(CVLC_STAGE_ENC_SELECT, stream);
+    hipLaunchKernelGGL(select_l1_kernel, dim3(g_sel, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+    const uint32_t groups = (max_R + kSlotGroup - 1) / kSlotGroup;
+    // one launch per group of boundaries; clients with fewer boundaries leave it at once
+    for (uint32_t gr = 0; gr < groups; ++gr)
+      hipLaunchKernelGGL(select_l23_kernel<2>, dim3(g_sel, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+    for (uint32_t gr = 0; gr < groups; ++gr)
+      hipLaunchKernelGGL(select_l23_kernel<3>, dim3(g_sel, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+    hipLaunchKernelGGL(tie_resolve_kernel, dim3(kTieBlocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+  }
   const uint32_t g_chunk = spread(2048, L.max_chunks);
-  hipLaunchKernelGGL(classify_kernel, dim3(g_chunk, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
-  hipLaunchKernelGGL(layout_kernel, dim3(n), dim3(1024), 0, stream, ws.params, ws.ctl, ws, d_stats_out);
-  hipLaunchKernelGGL(emit_kernel, dim3(g_chunk, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws, seed);
+  {
+    StageScope scope(CVLC_STAGE_ENC_CLASSIFY, stream);
+    hipLaunchKernelGGL(classify_kernel, dim3(g_chunk, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+  }
+  {
+    StageScope scope(CVLC_STAGE_ENC_LAYOUT, stream);
+    hipLaunchKernelGGL(layout_kernel, dim3(n), dim3(1024), 0, stream, ws.params, ws.ctl, ws, d_stats_out);
+  }
+  {
+    StageScope scope(CVLC_STAGE_ENC_EMIT, stream);
+    hipLaunchKernelGGL(emit_kernel, dim3(g_chunk, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws, seed);
+  }
   return hip_check(hipGetLastError());
 }
 

@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstring>
 #include <limits>
+#include <vector>
 
 #include "cvlc_common.h"
 
@@ -299,4 +300,62 @@ const char* cvlc_status_string(int status) {
 
 namespace cvlc {
 int hip_check(hipError_t e) { return e == hipSuccess ? CVLC_OK : CVLC_ERR_DEVICE; }
+
+namespace {
+struct Bracket {
+  int stage;
+  hipEvent_t begin, end;
+};
+bool g_profiling = false;
+uint32_t g_stage_mask = 0;
+std::vector<Bracket> g_brackets;
+}  // namespace
+
+void profile_mark(int stage, bool begin, hipStream_t stream) {
+  if (!g_profiling || !((g_stage_mask >> stage) & 1u)) return;
+  if (begin) {
+    Bracket b{stage, nullptr, nullptr};
+    if (hipEventCreate(&b.begin) != hipSuccess || hipEventCreate(&b.end) != hipSuccess) return;
+    (void)hipEventRecord(b.begin, stream);
+    g_brackets.push_back(b);
+  } else {
+    for (size_t i = g_brackets.size(); i-- > 0;)
+      if (g_brackets[i].stage == stage) {
+        (void)hipEventRecord(g_brackets[i].end, stream);
+        break;
+      }
+  }
+}
 }  // namespace cvlc
+
+extern "C" {
+
+int cvlc_profile_start(uint32_t stage_mask) {
+  if (cvlc::g_profiling) return CVLC_ERR_ARG;
+  cvlc::g_stage_mask = stage_mask;
+  cvlc::g_brackets.clear();
+  cvlc::g_profiling = true;
+  return CVLC_OK;
+}
+
+int cvlc_profile_stop(float* ms_per_stage, uint32_t* brackets_per_stage) {
+  if (!cvlc::g_profiling || !ms_per_stage || !brackets_per_stage) return CVLC_ERR_ARG;
+  cvlc::g_profiling = false;
+  for (int i = 0; i < CVLC_PROFILE_STAGES; ++i) { ms_per_stage[i] = 0.0f; brackets_per_stage[i] = 0; }
+  int rc = CVLC_OK;
+  for (auto& b : cvlc::g_brackets) {
+    float ms = 0.0f;
+    if (hipEventSynchronize(b.end) == hipSuccess && hipEventElapsedTime(&ms, b.begin, b.end) == hipSuccess) {
+      ms_per_stage[b.stage] += ms;
+      brackets_per_stage[b.stage] += 1;
+    } else {
+      rc = CVLC_ERR_DEVICE;
+    }
+    (void)hipEventDestroy(b.begin);
+    (void)hipEventDestroy(b.end);
+  }
+  cvlc::g_brackets.clear();
+  return rc;
+}
+
+}  // extern "C"

@@ -87,6 +87,8 @@ def lib() -> C.CDLL:
         L.cvlc_decode_aggregate.argtypes = [C.c_uint32, C.POINTER(vp), szp, C.POINTER(C.c_float), vp, C.c_uint32,
                                             C.c_uint32, vp, C.c_size_t, vp]
         L.cvlc_device_status.argtypes = [vp, vp, u32p]
+        L.cvlc_profile_start.argtypes = [C.c_uint32]
+        L.cvlc_profile_stop.argtypes = [C.POINTER(C.c_float), u32p]
         L.cvlc_status_string.argtypes = [C.c_int]
         L.cvlc_status_string.restype = C.c_char_p
         _lib = L
@@ -216,3 +218,24 @@ def read_stats(stats_out: torch.Tensor, client: int, n_coded: int) -> List[SegSt
     size = C.sizeof(SegStats)
     base = client * STATS_STRIDE * size
     return [SegStats.from_buffer_copy(raw[base + r * size: base + (r + 1) * size]) for r in range(n_coded + 1)]
+
+
+PROFILE_STAGES = ["enc_setup", "enc_sample", "enc_filter", "enc_refilter", "enc_select", "enc_classify",
+                  "enc_layout", "enc_emit", "dec_setup", "dec_table", "dec_tiles"]
+
+
+def profile_start(stages: Sequence[str] = tuple(PROFILE_STAGES)) -> None:
+    """cvlc_profile_start for the named stages."""
+    mask = 0
+    for name in stages:
+        mask |= 1 << PROFILE_STAGES.index(name)
+    _check(lib().cvlc_profile_start(mask), "cvlc_profile_start")
+
+
+def profile_stop() -> dict:
+    """cvlc_profile_stop: {stage: (total_ms, brackets)} for the stages that ran."""
+    n = len(PROFILE_STAGES)
+    ms = (C.c_float * n)()
+    cnt = (C.c_uint32 * n)()
+    _check(lib().cvlc_profile_stop(ms, cnt), "cvlc_profile_stop")
+    return {PROFILE_STAGES[i]: (float(ms[i]), int(cnt[i])) for i in range(n) if cnt[i]}
