@@ -21,7 +21,8 @@ constexpr uint32_t kSegHeaderBits = 32u * kSegHeaderWords;
 constexpr uint32_t kBlock = 256;           // threads per workgroup (4 wavefronts)
 constexpr uint32_t kWave = 64;
 constexpr uint32_t kWavesPerBlock = kBlock / kWave;
-constexpr uint32_t kTile = 4096;           // update coordinates per filter tile
+constexpr uint32_t kSubTile = 1024;        // coordinates one wavefront holds in registers (16 per lane)
+constexpr uint32_t kRegion = 8192;         // coordinates one wavefront filters as a unit (8 sub-tiles)
 constexpr uint32_t kChunk = 2048;          // candidates per classify/emit chunk
 constexpr uint32_t kSampleBins = 4096;     // sample histogram on key >> 19
 constexpr uint32_t kSampleShift = 19;
@@ -29,7 +30,9 @@ constexpr uint32_t kL1Bins = 2048;         // level-1 digit: key >> 20 (8 expone
 constexpr uint32_t kDigitBins = 1024;      // level-2 and level-3 digits: 10 bits each
 constexpr uint32_t kSlotGroup = 15;        // boundaries refined per level-2/3 launch (60 KB of LDS)
 constexpr uint32_t kSampleChunksMax = 16384;  // 64-byte pieces in the sample (256 Ki coordinates)
-constexpr uint32_t kTieBlocks = 64;        // workgroups per client in the tie-resolution pass
+constexpr uint32_t kTieCap = 2048;         // boundary-class members kept per histogram slot for tie resolution
+constexpr uint32_t kSampleBlocks = 4;      // workgroups per client in the sample pass
+constexpr uint32_t kMaxGroups = 3;         // ceil(31 / kSlotGroup)
 constexpr uint32_t kStatsStride = CVLC_STATS_STRIDE;
 
 // Per-client inputs of one encode call, written to the workspace by small
@@ -51,26 +54,18 @@ static_assert(sizeof(ClientParams) % 8 == 0, "ClientParams must stay 8-byte gran
 
 // Per-client scratch state, zero-filled at the start of every encode call.
 struct ClientCtl {
-  uint32_t tile_counter[2];  // next filter tile to claim (pass 0: sampled threshold, pass 1: keep all)
-  uint32_t n_cand[2];        // candidates found by each filter pass
-  uint32_t tau_lo;           // candidate threshold key from the sample
-  uint32_t done_sample, done_l1, done_tie;
-  uint32_t done_l23[2][3];   // [level-2|level-3][slot group]
-  uint32_t need_tie;         // some boundary cuts through a class of equal magnitudes
+  uint32_t tau_lo;           // candidate threshold key from the sample (0: keep every coordinate)
+  uint32_t n_cand;           // candidates kept by the filter pass that counts
+  uint32_t refilter;         // 1: the sampled threshold kept fewer than k, the keep-all pass must run
   uint32_t pad0;
+  uint32_t tie_cnt[kMaxGroups][16];  // kept-aside class members per (boundary group, histogram slot)
   uint32_t sel_prefix[32];   // key prefix fixed so far for boundary r (0xFFFFFFFF: Z_r = 0)
   uint32_t sel_rem[32];      // rank of the boundary element inside the prefix class, 1-based from the top
-  uint32_t sel_slot[32];     // boundary whose histogram this one shares
-  uint32_t tau[32];          // Z_r-th largest key
+  uint32_t tau[32];          // Z_r-th largest key (0xFFFFFFFF: Z_r = 0)
   uint32_t iota[32];         // largest index among the key == tau_r coordinates inside the top Z_r
-  uint32_t tie_need[32];     // boundary r needs iota resolved
   uint32_t seg_max_enc[32];  // max over the group of ordered(x); 0 = empty
   uint32_t seg_negmin_enc[32];  // max over the group of ~ordered(x); 0 = empty
-  uint32_t tie_partial[kTieBlocks][32];
-  uint32_t hist_sample[kSampleBins];
-  uint32_t hist1[kL1Bins];
-  uint32_t hist2[CVLC_MAX_CODED][kDigitBins];
-  uint32_t hist3[CVLC_MAX_CODED][kDigitBins];
+  uint32_t hist_sample[kSampleBins];  // sample histogram, accumulated with device-wide atomics
 };
 
 // ---- decoder -------------------------------------------------------------------
@@ -112,6 +107,20 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
     if (lane >= (uint32_t)o) v += t;
   }
   return v;
+}
+
+// hist[bin] += 1 for every lane with `active`, using one LDS atomic per distinct
+// bin in the wavefront (lanes that share a bin elect the lowest one).  Must be
+// reached by all lanes of the wavefront.  `bin` must fit in NBITS bits.
+template <int NBITS>
+__device__ __forceinline__ void wave_hist_add(uint32_t* hist, uint32_t bin, bool active) {
+  uint64_t same = __ballot(active);
+#pragma unroll
+  for (int bit = 0; bit < NBITS; ++bit) {
+    const uint64_t set = __ballot((bin >> bit) & 1u);
+    same &= ((bin >> bit) & 1u) ? set : ~set;
+  }
+  if (active && lane_id() == (uint32_t)__builtin_ctzll(same)) atomicAdd(&hist[bin], (uint32_t)__popcll(same));
 }
 
 // Loads/stores that other workgroups of the same kernel must observe.

@@ -6,16 +6,27 @@
 // kernels find, for every group boundary Z_r, the exact Z_r-th largest
 // magnitude (radix-histogram selection) and classify coordinates against those
 // thresholds, which yields the same groups as a full sort with ties broken by
-// position.  Launch chain per batch of clients:
-//   sample_hist   strided sample of |U| -> conservative candidate threshold
-//   filter        the one full pass over U: keep coordinates above the
-//                 threshold, in position order (decoupled look-back scan)
-//   select_l1/l23 three histogram levels (11+10+10 key bits) over the
-//                 candidates -> exact boundary keys and tie quotas
-//   tie_resolve   where a boundary cuts a class of equal magnitudes, the
-//                 position of the last member inside the boundary
-//   classify      per chunk: group of every candidate, per-group count,
-//                 min/max/sum of squares
+// position.  Launch chain per batch of clients (no kernel waits on another
+// workgroup and none needs a memory fence; every dependency is a kernel
+// boundary):
+//   sample_hist   strided sample of |U| -> histogram of the top 12 key bits
+//   sample_walk   conservative candidate threshold tau_lo from that histogram
+//   filter        the one full pass over U.  Every wavefront owns regions of
+//                 8192 consecutive coordinates and writes the coordinates with
+//                 key >= tau_lo to the front of the region's slot, in position
+//                 order; it also counts the level-1 digit (top 11 key bits) of
+//                 what it keeps and sums the squares of what it drops
+//   scan_l1       prefix over the region counts; level-1 bins of the boundaries
+//   select_pass   level 2 (and, fused, gathering the region runs into one dense
+//                 position-ordered candidate list), then level 3: LDS
+//                 histograms of the next 10 key bits of the candidates that
+//                 match a boundary's prefix
+//   select_walk   adds up the histograms, fixes the next digit of every
+//                 boundary; after level 3 the exact boundary keys and, where a
+//                 boundary cuts a class of equal magnitudes, the position of
+//                 its last member inside the boundary
+//   classify      per chunk of candidates: group of every candidate, per-group
+//                 count, min/max/sum of squares
 //   layout        prefix of the per-chunk counts, headers, statistics
 //   emit          stochastic rounding (Philox4x32-10) and bit packing
 #include <hip/hip_runtime.h>
@@ -30,28 +41,47 @@ namespace {
 
 // ------------------------------------------------------------------ workspace layout
 struct EncodeLayout {
-  size_t status, params, ctl, tile_state, tile_sumsq, cand_idx, cand_val, chunk_cnt, chunk_sumsq, total;
-  size_t zero_begin, zero_end;  // [ctl, tile_state] is cleared at the start of a call
-  uint32_t n_tiles, max_chunks;
+  size_t status, ctl, params, region_cnt, region_off, region_sumsq, cand_sparse, cand_dense, chunk_cnt, chunk_sumsq,
+      tie_list, hist1_part, sel_part, total;
+  size_t zero_bytes;        // [status, params) is cleared at the start of a call
+  uint32_t n_regions, max_chunks;
+  uint32_t filter_blocks;   // workgroups per client in the filter pass
+  uint32_t sel_blocks;      // workgroups per client in a level-2/3 selection pass
 };
 
 size_t align256(size_t v) { return (v + 255u) & ~(size_t)255u; }
 
 EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   EncodeLayout L;
-  L.n_tiles = (uint32_t)(((uint64_t)d + kTile - 1) / kTile);
+  L.n_regions = (uint32_t)(((uint64_t)d + kRegion - 1) / kRegion);
   L.max_chunks = (uint32_t)(((uint64_t)d + kChunk - 1) / kChunk);
+  // filter: one resident round of workgroups (8 per CU), every wavefront the same number of regions
+  {
+    const uint32_t max_blocks = 2048u / n > 0 ? 2048u / n : 1u;
+    const uint32_t max_waves = max_blocks * kWavesPerBlock;
+    const uint32_t rounds = (L.n_regions + max_waves - 1) / max_waves;
+    const uint32_t waves = (L.n_regions + rounds - 1) / rounds;
+    L.filter_blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
+  }
+  {
+    uint32_t b = (512u + n - 1) / n;
+    L.sel_blocks = b < 2 ? 2u : (b > 32 ? 32u : b);
+  }
   size_t off = 0;
   L.status = off; off = align256(off + 256);
+  L.ctl = off; off = align256(off + (size_t)n * sizeof(ClientCtl));
+  L.zero_bytes = off;
   L.params = off; off = align256(off + (size_t)n * sizeof(ClientParams));
-  L.ctl = off; L.zero_begin = off; off = align256(off + (size_t)n * sizeof(ClientCtl));
-  L.tile_state = off; off = align256(off + (size_t)n * 2 * L.n_tiles * sizeof(uint64_t));
-  L.zero_end = off;
-  L.tile_sumsq = off; off = align256(off + (size_t)n * L.n_tiles * sizeof(double));
-  L.cand_idx = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
-  L.cand_val = off; off = align256(off + (size_t)n * d * sizeof(float));
+  L.region_cnt = off; off = align256(off + (size_t)n * L.n_regions * sizeof(uint32_t));
+  L.region_off = off; off = align256(off + (size_t)n * (L.n_regions + 1) * sizeof(uint32_t));
+  L.region_sumsq = off; off = align256(off + (size_t)n * L.n_regions * sizeof(double));
+  L.cand_sparse = off; off = align256(off + (size_t)n * d * sizeof(uint2));
+  L.cand_dense = off; off = align256(off + (size_t)n * d * sizeof(uint2));
   L.chunk_cnt = off; off = align256(off + (size_t)n * L.max_chunks * 32 * sizeof(uint32_t));
   L.chunk_sumsq = off; off = align256(off + (size_t)n * L.max_chunks * 32 * sizeof(double));
+  L.tie_list = off; off = align256(off + (size_t)n * kSlotGroup * kTieCap * sizeof(uint2));
+  L.hist1_part = off; off = align256(off + (size_t)n * L.filter_blocks * kL1Bins * sizeof(uint32_t));
+  L.sel_part = off; off = align256(off + (size_t)n * L.sel_blocks * kSlotGroup * kDigitBins * sizeof(uint32_t));
   L.total = off;
   return L;
 }
@@ -60,13 +90,17 @@ struct Workspace {  // device pointers into the caller's workspace
   uint32_t* status;
   ClientParams* params;
   ClientCtl* ctl;
-  uint64_t* tile_state;
-  double* tile_sumsq;
-  uint32_t* cand_idx;
-  float* cand_val;
+  uint32_t* region_cnt;
+  uint32_t* region_off;
+  double* region_sumsq;
+  uint2* cand_sparse;  // (position, value bits) runs at the front of every region's slot
+  uint2* cand_dense;   // the same candidates, contiguous per client, in position order
   uint32_t* chunk_cnt;
   double* chunk_sumsq;
-  uint32_t d, n_tiles, max_chunks;
+  uint2* tie_list;
+  uint32_t* hist1_part;
+  uint32_t* sel_part;
+  uint32_t d, n_regions, max_chunks, filter_blocks, sel_blocks;
 };
 
 // ------------------------------------------------------------------ parameter upload
@@ -81,90 +115,119 @@ __global__ void upload_kernel(uint32_t* dst, UploadChunk c) {
 }
 
 // ------------------------------------------------------------------ small device helpers
-__device__ __forceinline__ uint32_t final_ncand(const ClientCtl* ctl, const ClientParams& p) {
-  const uint32_t n0 = ctl->n_cand[0];
-  return n0 >= p.k ? n0 : ctl->n_cand[1];
-}
-__device__ __forceinline__ uint32_t final_pass(const ClientCtl* ctl, const ClientParams& p) {
-  return ctl->n_cand[0] >= p.k ? 0u : 1u;
-}
-
-// Exclusive prefix sum of one value per thread over the workgroup (kBlock threads),
-// in thread order; *total receives the sum.  `scratch` holds kWavesPerBlock words.
+// Exclusive prefix sum of one value per thread over a workgroup of NW
+// wavefronts, in thread order; *total receives the sum.  `scratch` holds NW words.
+template <uint32_t NW>
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
   const uint32_t incl = wave_incl_scan_u32(v);
+  const uint32_t wave = threadIdx.x / kWave;
   __syncthreads();
-  if (lane_id() == kWave - 1) scratch[wave_id()] = incl;
+  if (lane_id() == kWave - 1) scratch[wave] = incl;
   __syncthreads();
   uint32_t before = 0, sum = 0;
 #pragma unroll
-  for (uint32_t w = 0; w < kWavesPerBlock; ++w) {
+  for (uint32_t w = 0; w < NW; ++w) {
     const uint32_t t = scratch[w];
-    if (w < wave_id()) before += t;
+    if (w < wave) before += t;
     sum += t;
   }
   *total = sum;
   return before + incl - v;
 }
 
-// The last workgroup of a (client, phase) to arrive gets true: everything the
-// other workgroups wrote before arriving is then visible through agent-scope loads.
-__device__ __forceinline__ bool arrive_last(uint32_t* counter, uint32_t expected) {
-  __shared__ uint32_t s_last;
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) s_last = (atomicAdd(counter, 1u) == expected - 1u) ? 1u : 0u;
-  __syncthreads();
-  const bool last = s_last != 0;
-  if (last) __threadfence();
-  return last;
+// Number of set bits of the four masks in lanes below the caller's.
+__device__ __forceinline__ uint32_t lanes_below4(uint64_t m0, uint64_t m1, uint64_t m2, uint64_t m3) {
+  uint32_t acc = __builtin_amdgcn_mbcnt_lo((uint32_t)m0, 0u);
+  acc = __builtin_amdgcn_mbcnt_hi((uint32_t)(m0 >> 32), acc);
+  acc = __builtin_amdgcn_mbcnt_lo((uint32_t)m1, acc);
+  acc = __builtin_amdgcn_mbcnt_hi((uint32_t)(m1 >> 32), acc);
+  acc = __builtin_amdgcn_mbcnt_lo((uint32_t)m2, acc);
+  acc = __builtin_amdgcn_mbcnt_hi((uint32_t)(m2 >> 32), acc);
+  acc = __builtin_amdgcn_mbcnt_lo((uint32_t)m3, acc);
+  acc = __builtin_amdgcn_mbcnt_hi((uint32_t)(m3 >> 32), acc);
+  return acc;
 }
+
+constexpr uint32_t kWideBlock = 1024;
+constexpr uint32_t kWideWaves = kWideBlock / kWave;
 
 // ------------------------------------------------------------------ 1. sample histogram
 // Reads n_s 64-byte pieces spread evenly over the vector and histograms the
-// magnitude keys on their top 12 bits.  The last workgroup walks the histogram
-// from the top to the sample rank the host derived from k/d plus a 6-sigma
-// margin; the lower edge of that bin becomes the candidate threshold.
-__global__ __launch_bounds__(kBlock) void sample_hist_kernel(const ClientParams* __restrict__ params,
-                                                             ClientCtl* __restrict__ ctls, uint32_t n_s,
-                                                             uint32_t n_src) {
+// magnitude keys on their top 12 bits.  kSampleBlocks workgroups of 1024
+// threads per client each take a slice of the pieces, issue their loads eight
+// deep, and add their non-empty bins to the client's histogram.
+__global__ __launch_bounds__(kWideBlock) void sample_hist_kernel(const ClientParams* __restrict__ params,
+                                                                 ClientCtl* __restrict__ ctls, uint32_t n_s,
+                                                                 uint32_t n_src) {
   __shared__ uint32_t hist[kSampleBins];
-  __shared__ uint32_t scan_tmp[kWavesPerBlock];
-  const ClientParams& p = params[blockIdx.y];
-  ClientCtl* ctl = ctls + blockIdx.y;
-  if (p.sample_rank == 0) {  // keep-all plan: threshold stays 0
-    return;
-  }
-  for (uint32_t i = threadIdx.x; i < kSampleBins; i += kBlock) hist[i] = 0;
+  const uint32_t client = blockIdx.y;
+  const ClientParams& p = params[client];
+  ClientCtl* ctl = ctls + client;
+  if (p.sample_rank == 0) return;  // keep-all plan: the threshold stays 0
+  for (uint32_t i = threadIdx.x; i < kSampleBins; i += kWideBlock) hist[i] = 0;
   __syncthreads();
   const float4* src = reinterpret_cast<const float4*>(p.update);
   const uint32_t total_q = n_s * 4u;
-  for (uint32_t q = blockIdx.x * kBlock + threadIdx.x; q < total_q; q += gridDim.x * kBlock) {
-    const uint32_t j = q >> 2, part = q & 3u;
-    const uint64_t piece = (uint64_t)j * n_src / n_s;
-    const float4 v = src[piece * 4u + part];
-    atomicAdd(&hist[(__float_as_uint(v.x) & 0x7FFFFFFFu) >> kSampleShift], 1u);
-    atomicAdd(&hist[(__float_as_uint(v.y) & 0x7FFFFFFFu) >> kSampleShift], 1u);
-    atomicAdd(&hist[(__float_as_uint(v.z) & 0x7FFFFFFFu) >> kSampleShift], 1u);
-    atomicAdd(&hist[(__float_as_uint(v.w) & 0x7FFFFFFFu) >> kSampleShift], 1u);
+  const uint32_t per_block = (total_q + gridDim.x - 1) / gridDim.x;
+  const uint32_t q_begin = blockIdx.x * per_block;
+  const uint32_t q_end = min(total_q, q_begin + per_block);
+  for (uint32_t base = q_begin; base < q_end; base += kWideBlock * 8u) {
+    float4 v[8];
+    bool live[8];
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) {
+      const uint32_t q = base + u * kWideBlock + threadIdx.x;
+      live[u] = q < q_end;
+      v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      if (live[u]) {
+        const uint32_t j = q >> 2, part = q & 3u;
+        const uint64_t piece = (uint64_t)j * n_src / n_s;
+        v[u] = src[piece * 4u + part];
+      }
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) {
+      // most sampled magnitudes share a handful of bins: merge equal bins inside the wavefront first
+      wave_hist_add<12>(hist, (__float_as_uint(v[u].x) & 0x7FFFFFFFu) >> kSampleShift, live[u]);
+      wave_hist_add<12>(hist, (__float_as_uint(v[u].y) & 0x7FFFFFFFu) >> kSampleShift, live[u]);
+      wave_hist_add<12>(hist, (__float_as_uint(v[u].z) & 0x7FFFFFFFu) >> kSampleShift, live[u]);
+      wave_hist_add<12>(hist, (__float_as_uint(v[u].w) & 0x7FFFFFFFu) >> kSampleShift, live[u]);
+    }
   }
   __syncthreads();
-  for (uint32_t i = threadIdx.x; i < kSampleBins; i += kBlock)
-    if (hist[i]) atomicAdd(&ctl->hist_sample[i], hist[i]);
-  if (!arrive_last(&ctl->done_sample, gridDim.x)) return;
+  for (uint32_t i = threadIdx.x; i < kSampleBins; i += kWideBlock) {
+    const uint32_t h = hist[i];
+    if (h) atomicAdd(&ctl->hist_sample[i], h);
+  }
+}
 
-  // thread t owns the 16 bins [top-15, top], top = 4095 - 16 t: walk from large keys down
-  constexpr uint32_t per = kSampleBins / kBlock;
+// One workgroup per client walks the sample histogram from the large keys down
+// to the sample rank the host derived from k/d plus a 6-sigma margin.  The
+// lower edge of that bin becomes the candidate threshold.
+__global__ __launch_bounds__(kWideBlock) void sample_walk_kernel(const ClientParams* __restrict__ params,
+                                                                 ClientCtl* __restrict__ ctls) {
+  __shared__ uint32_t scan_tmp[kWideWaves];
+  const uint32_t client = blockIdx.x;
+  const ClientParams& p = params[client];
+  ClientCtl* ctl = ctls + client;
+  if (p.sample_rank == 0) return;
+  // thread t owns the 4 bins [top-3, top], top = 4095 - 4 t
+  constexpr uint32_t per = kSampleBins / kWideBlock;
   const uint32_t top = kSampleBins - 1 - per * threadIdx.x;
-  uint32_t mine = 0;
-  for (uint32_t i = 0; i < per; ++i) mine += load_agent(&ctl->hist_sample[top - i]);
+  uint32_t h[per], mine = 0;
+#pragma unroll
+  for (uint32_t i = 0; i < per; ++i) {
+    h[i] = ctl->hist_sample[top - i];
+    mine += h[i];
+  }
   uint32_t total;
-  const uint32_t above = block_excl_scan(mine, scan_tmp, &total);
+  const uint32_t above = block_excl_scan<kWideWaves>(mine, scan_tmp, &total);
   const uint32_t target = p.sample_rank;
   if (above < target && target <= above + mine) {
     uint32_t acc = above, bin = top;
+#pragma unroll
     for (uint32_t i = 0; i < per; ++i) {
-      acc += load_agent(&ctl->hist_sample[top - i]);
+      acc += h[i];
       if (acc >= target) { bin = top - i; break; }
     }
     ctl->tau_lo = bin << kSampleShift;
@@ -173,60 +236,75 @@ __global__ __launch_bounds__(kBlock) void sample_hist_kernel(const ClientParams*
 }
 
 // ------------------------------------------------------------------ 2. filter (the full pass)
-constexpr uint64_t kFlagAgg = 1ull << 62;     // tile's own candidate count is published
-constexpr uint64_t kFlagPrefix = 2ull << 62;  // inclusive prefix up to this tile is published
-constexpr uint64_t kFlagMask = 3ull << 62;
-constexpr uint32_t kSpinLimit = 1u << 24;
+// A wavefront streams a region in sub-tiles of 1024 coordinates, read as four
+// float4 per lane (the j-th at j*256 + lane*4), so position order inside a
+// sub-tile is (j, lane, component).  The next sub-tile's loads are issued
+// before the current one is processed.
+struct SubTile {
+  float v[4][4];
+};
 
-// Exclusive prefix of `agg` over the tiles before `tile` of the same client
-// (decoupled look-back).  Called by all 64 lanes of one wavefront.  Tiles are
-// claimed through an atomic counter, so every earlier tile already belongs to
-// a running workgroup and publishes its count without waiting on anyone.  The
-// spin is bounded: on expiry the internal-error bit is set and 0 is assumed.
-__device__ uint32_t lookback_exclusive(uint64_t* state, uint32_t tile, uint32_t agg, uint32_t* status) {
-  const uint32_t lane = lane_id();
-  if (tile == 0) {
-    if (lane == 0) store_agent(&state[0], kFlagPrefix | agg);
-    return 0;
-  }
-  if (lane == 0) store_agent(&state[tile], kFlagAgg | agg);
-  uint32_t excl = 0;
-  int64_t base = (int64_t)tile - 1;
-  while (true) {
-    const int64_t idx = base - (int64_t)lane;
-    uint64_t v = kFlagPrefix;  // positions before tile 0 act as an empty prefix
-    if (idx >= 0) {
-      uint32_t spins = 0;
-      v = load_agent(&state[idx]);
-      while ((v & kFlagMask) == 0 && ++spins < kSpinLimit) {
-        __builtin_amdgcn_s_sleep(2);
-        v = load_agent(&state[idx]);
-      }
-      if ((v & kFlagMask) == 0) {
-        atomicOr(status, CVLC_DEV_INTERNAL);
-        v = kFlagPrefix;
-      }
+__device__ __forceinline__ void load_subtile(SubTile& t, const float* __restrict__ U, uint32_t sbase, uint32_t lane,
+                                             uint32_t d) {
+  if (sbase + kSubTile <= d) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float4 q = *reinterpret_cast<const float4*>(U + sbase + j * 256u + lane * 4u);
+      t.v[j][0] = q.x; t.v[j][1] = q.y; t.v[j][2] = q.z; t.v[j][3] = q.w;
     }
-    const uint64_t has_prefix = __ballot((v & kFlagMask) == kFlagPrefix);
-    const uint32_t first = has_prefix ? (uint32_t)__builtin_ctzll(has_prefix) : 64u;
-    const uint32_t val = (lane <= first) ? (uint32_t)(v & 0xFFFFFFFFull) : 0u;
-    excl += wave_sum_u32(val);
-    if (has_prefix) break;
-    base -= 64;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t e0 = sbase + j * 256u + lane * 4u;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) t.v[j][c] = (e0 + c < d) ? U[e0 + c] : 0.0f;
+    }
   }
-  if (lane == 0) store_agent(&state[tile], kFlagPrefix | (uint64_t)(excl + agg));
-  return excl;
 }
 
-// One tile = 4096 coordinates; wavefront w owns the contiguous 1024 starting at
-// w*1024 and reads them as four float4 per lane (j-th load at j*256 + lane*4),
-// so position order inside a wavefront is (j, lane, component).
+// Keeps the coordinates of one sub-tile whose key reaches tau_lo: appended to
+// `out` at *run in position order, counted in the level-1 histogram.  The
+// squares of the others go to *sq; *kmax tracks the largest key seen.
+template <bool TAIL>
+__device__ __forceinline__ void filter_subtile(const SubTile& t, uint32_t sbase, uint32_t lane, uint32_t d,
+                                               uint32_t tau_lo, uint2* __restrict__ out, uint32_t* run, double* sq,
+                                               uint32_t* kmax, uint32_t* s_hist) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t e0 = sbase + j * 256u + lane * 4u;
+    uint32_t bits[4];
+    bool keep[4];
+    uint64_t m[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      bits[c] = __float_as_uint(t.v[j][c]);
+      const uint32_t key = bits[c] & 0x7FFFFFFFu;
+      *kmax = max(*kmax, key);
+      keep[c] = key >= tau_lo && (!TAIL || e0 + c < d);
+      m[c] = __ballot(keep[c]);
+      if (!keep[c]) *sq += (double)t.v[j][c] * (double)t.v[j][c];  // coordinates past d were loaded as 0
+    }
+    if (m[0] | m[1] | m[2] | m[3]) {
+      uint32_t pos = *run + lanes_below4(m[0], m[1], m[2], m[3]);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if (keep[c]) {
+          out[pos] = make_uint2(e0 + c, bits[c]);
+          atomicAdd(&s_hist[(bits[c] & 0x7FFFFFFFu) >> 20], 1u);
+          ++pos;
+        }
+      }
+      *run += (uint32_t)(__popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]));
+    }
+  }
+}
+
+// PASS 0 filters against the sampled threshold; PASS 1 keeps everything and
+// only runs for clients whose PASS 0 kept fewer than k coordinates.
 template <int PASS>
 __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __restrict__ params,
                                                         ClientCtl* __restrict__ ctls, Workspace ws) {
-  __shared__ uint32_t s_tile, s_prefix;
-  __shared__ uint32_t s_wtot[kWavesPerBlock];
-  __shared__ double s_wsq[kWavesPerBlock];
+  __shared__ uint32_t s_hist[kL1Bins];
   const uint32_t client = blockIdx.y;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
@@ -234,335 +312,449 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __re
   if (PASS == 0) {
     tau_lo = ctl->tau_lo;
   } else {
-    if (ctl->n_cand[0] >= p.k) return;  // the sampled threshold kept enough
+    if (!ctl->refilter) return;  // the sampled threshold kept enough
     tau_lo = 0;
   }
-  const uint32_t d = ws.d, n_tiles = ws.n_tiles;
+  const uint32_t d = ws.d, n_regions = ws.n_regions;
   const float* __restrict__ U = p.update;
-  uint64_t* state = ws.tile_state + ((size_t)client * 2 + PASS) * n_tiles;
-  uint32_t* out_idx = ws.cand_idx + (size_t)client * d;
-  float* out_val = ws.cand_val + (size_t)client * d;
-  const uint32_t lane = lane_id(), wave = wave_id();
+  const uint32_t lane = lane_id();
+  for (uint32_t i = threadIdx.x; i < kL1Bins; i += kBlock) s_hist[i] = 0;
+  __syncthreads();
 
-  while (true) {
-    __syncthreads();
-    if (threadIdx.x == 0) s_tile = atomicAdd(&ctl->tile_counter[PASS], 1u);
-    __syncthreads();
-    const uint32_t tile = s_tile;
-    if (tile >= n_tiles) break;
-    const uint32_t wbase = tile * kTile + wave * (kTile / kWavesPerBlock);
-
-    float v[4][4];
-    uint32_t flags[4];
+  uint32_t kmax = 0;
+  const uint32_t n_waves = gridDim.x * kWavesPerBlock;
+  for (uint32_t region = blockIdx.x * kWavesPerBlock + wave_id(); region < n_regions; region += n_waves) {
+    const uint32_t rbase = region * kRegion;
+    const uint32_t rend = (d - rbase < kRegion) ? d : rbase + kRegion;
+    uint2* __restrict__ out = ws.cand_sparse + (size_t)client * d + rbase;
+    uint32_t run = 0;
     double sq = 0.0;
-    bool bad = false;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t e0 = wbase + j * 256u + lane * 4u;
-      if (e0 + 3u < d) {
-        const float4 q = *reinterpret_cast<const float4*>(U + e0);
-        v[j][0] = q.x; v[j][1] = q.y; v[j][2] = q.z; v[j][3] = q.w;
+    SubTile cur, nxt;
+    load_subtile(cur, U, rbase, lane, d);
+    for (uint32_t sbase = rbase; sbase < rend; sbase += kSubTile) {
+      const bool more = sbase + kSubTile < rend;
+      if (more) load_subtile(nxt, U, sbase + kSubTile, lane, d);
+      if (sbase + kSubTile <= d) {
+        filter_subtile<false>(cur, sbase, lane, d, tau_lo, out, &run, &sq, &kmax, s_hist);
       } else {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) v[j][c] = (e0 + c < d) ? U[e0 + c] : 0.0f;
+        filter_subtile<true>(cur, sbase, lane, d, tau_lo, out, &run, &sq, &kmax, s_hist);
       }
-      uint32_t f = 0;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const uint32_t key = __float_as_uint(v[j][c]) & 0x7FFFFFFFu;
-        const bool in_range = e0 + c < d;
-        bad |= key >= 0x7F800000u;
-        if (in_range && key >= tau_lo) {
-          f |= 1u << c;
-        } else {
-          sq += (double)v[j][c] * (double)v[j][c];  // padding contributes 0
-        }
-      }
-      flags[j] = f;
-    }
-    if (bad) atomicOr(ws.status, CVLC_DEV_NONFINITE);
-
-    // position-ordered offsets inside the wavefront
-    uint32_t pre[4], wtot = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t cnt = __popc(flags[j]);
-      const uint64_t b0 = __ballot(cnt & 1u), b1 = __ballot(cnt & 2u), b2 = __ballot(cnt & 4u);
-      pre[j] = wtot + lanes_below(b0) + 2u * lanes_below(b1) + 4u * lanes_below(b2);
-      wtot += (uint32_t)__popcll(b0) + 2u * (uint32_t)__popcll(b1) + 4u * (uint32_t)__popcll(b2);
+      if (more) cur = nxt;
     }
     sq = wave_sum_f64(sq);
-    if (lane == 0) { s_wtot[wave] = wtot; s_wsq[wave] = sq; }
-    __syncthreads();
-    uint32_t woff = 0, agg = 0;
-#pragma unroll
-    for (uint32_t w = 0; w < kWavesPerBlock; ++w) {
-      if (w < wave) woff += s_wtot[w];
-      agg += s_wtot[w];
-    }
-    if (wave == 0) {
-      const uint32_t excl = lookback_exclusive(state, tile, agg, ws.status);
-      if (lane == 0) {
-        s_prefix = excl;
-        ws.tile_sumsq[(size_t)client * n_tiles + tile] = (s_wsq[0] + s_wsq[1]) + (s_wsq[2] + s_wsq[3]);
-        if (tile == n_tiles - 1) ctl->n_cand[PASS] = excl + agg;
-      }
-    }
-    __syncthreads();
-    const uint32_t tile_off = s_prefix + woff;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      uint32_t f = flags[j];
-      if (f) {
-        uint32_t pos = tile_off + pre[j];
-        const uint32_t e0 = wbase + j * 256u + lane * 4u;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          if (f & (1u << c)) {
-            if (pos < d) {  // always true for a consistent prefix; guards the bounded-spin fallback
-              out_idx[pos] = e0 + c;
-              out_val[pos] = v[j][c];
-            }
-            ++pos;
-          }
-        }
-      }
+    if (lane == 0) {
+      ws.region_cnt[(size_t)client * n_regions + region] = run;
+      ws.region_sumsq[(size_t)client * n_regions + region] = sq;
     }
   }
+  if (kmax >= 0x7F800000u) atomicOr(ws.status, CVLC_DEV_NONFINITE);
+  __syncthreads();
+  uint32_t* part = ws.hist1_part + ((size_t)client * gridDim.x + blockIdx.x) * kL1Bins;
+  for (uint32_t i = threadIdx.x; i < kL1Bins; i += kBlock) part[i] = s_hist[i];
 }
 
-// ------------------------------------------------------------------ 3. selection, level 1
-// Histogram of the candidates' top 11 key bits; the last workgroup locates, for
-// every boundary Z_r, the bin holding the Z_r-th largest key and the rank left
-// inside that bin.
-__global__ __launch_bounds__(kBlock) void select_l1_kernel(const ClientParams* __restrict__ params,
-                                                           ClientCtl* __restrict__ ctls, Workspace ws) {
+// ------------------------------------------------------------------ 3. region prefix + selection level 1
+// One workgroup per client.  Turns the region counts into exclusive offsets
+// (the candidates' position-ordered numbering), then adds up the level-1
+// histograms the filter's workgroups stored and locates, for every boundary
+// Z_r, the bin holding the Z_r-th largest key and the rank left inside it.
+template <int PASS>
+__global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams* __restrict__ params,
+                                                             ClientCtl* __restrict__ ctls, Workspace ws) {
   __shared__ uint32_t hist[kL1Bins];
-  __shared__ uint32_t incl[kL1Bins];  // count of keys in bins >= b
-  __shared__ uint32_t scan_tmp[kWavesPerBlock];
-  const uint32_t client = blockIdx.y;
+  __shared__ uint32_t incl[kL1Bins];  // keys in bins >= b
+  __shared__ uint32_t scan_tmp[kWideWaves];
+  const uint32_t client = blockIdx.x, tid = threadIdx.x;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  const uint32_t n = final_ncand(ctl, p);
-  const float* val = ws.cand_val + (size_t)client * ws.d;
-  for (uint32_t i = threadIdx.x; i < kL1Bins; i += kBlock) hist[i] = 0;
-  __syncthreads();
-  for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < n; i += gridDim.x * kBlock)
-    atomicAdd(&hist[(__float_as_uint(val[i]) & 0x7FFFFFFFu) >> 20], 1u);
-  __syncthreads();
-  for (uint32_t i = threadIdx.x; i < kL1Bins; i += kBlock)
-    if (hist[i]) atomicAdd(&ctl->hist1[i], hist[i]);
-  if (!arrive_last(&ctl->done_l1, gridDim.x)) return;
-
-  constexpr uint32_t per = kL1Bins / kBlock;  // 8 bins per thread, from the top down
-  const uint32_t top = kL1Bins - 1 - per * threadIdx.x;
-  uint32_t h[per], mine = 0;
-  for (uint32_t i = 0; i < per; ++i) { h[i] = load_agent(&ctl->hist1[top - i]); mine += h[i]; }
-  uint32_t total;
-  uint32_t run = block_excl_scan(mine, scan_tmp, &total);
-  for (uint32_t i = 0; i < per; ++i) {
-    run += h[i];
-    hist[top - i] = h[i];
-    incl[top - i] = run;
+  if (PASS == 1 && !ctl->refilter) return;
+  const uint32_t n_regions = ws.n_regions;
+  const uint32_t* cnt = ws.region_cnt + (size_t)client * n_regions;
+  uint32_t* off = ws.region_off + (size_t)client * (n_regions + 1);
+  uint32_t run = 0;
+  for (uint32_t base = 0; base < n_regions; base += kWideBlock) {
+    const uint32_t j = base + tid;
+    const uint32_t v = j < n_regions ? cnt[j] : 0u;
+    uint32_t tot;
+    const uint32_t excl = block_excl_scan<kWideWaves>(v, scan_tmp, &tot);
+    if (j < n_regions) off[j] = run + excl;
+    run += tot;
   }
+  if (tid == 0) {
+    off[n_regions] = run;
+    ctl->n_cand = run;
+  }
+  if (PASS == 0 && run < p.k) {  // the sample misjudged the threshold: everything is redone by pass 1
+    if (tid == 0) ctl->refilter = 1u;
+    return;
+  }
+
+  const uint32_t n_parts = ws.filter_blocks;
+  const uint32_t* parts = ws.hist1_part + (size_t)client * n_parts * kL1Bins;
+  // thread t owns bins 2t and 2t+1 while adding up, and reads them back from the top for the scan
+  uint2 sum = make_uint2(0u, 0u);
+  for (uint32_t b = 0; b < n_parts; ++b) {
+    const uint2 h = *reinterpret_cast<const uint2*>(parts + (size_t)b * kL1Bins + 2u * tid);
+    sum.x += h.x;
+    sum.y += h.y;
+  }
+  hist[2u * tid] = sum.x;
+  hist[2u * tid + 1] = sum.y;
   __syncthreads();
-  if (threadIdx.x < p.R) {
-    const uint32_t r = threadIdx.x, Z = p.Z[r];
-    if (Z == 0 || Z > total) {  // Z > total cannot happen once the filter kept >= k
-      ctl->sel_prefix[r] = 0xFFFFFFFFu;
-      ctl->sel_rem[r] = 0;
-      if (Z > total) atomicOr(ws.status, CVLC_DEV_INTERNAL);
-    } else {
-      uint32_t lo = 0, hi = kL1Bins - 1;  // largest bin b with incl[b] >= Z
-      while (lo < hi) {
-        const uint32_t mid = (lo + hi + 1) >> 1;
-        if (incl[mid] >= Z) lo = mid; else hi = mid - 1;
+  const uint32_t top = kL1Bins - 1 - 2u * tid;
+  const uint32_t h0 = hist[top], h1 = hist[top - 1];
+  uint32_t total;
+  const uint32_t above = block_excl_scan<kWideWaves>(h0 + h1, scan_tmp, &total);
+  incl[top] = above + h0;
+  incl[top - 1] = above + h0 + h1;
+  __syncthreads();
+  if (tid < 32) {
+    uint32_t pre = 0xFFFFFFFFu, rem = 0;
+    if (tid < p.R) {
+      const uint32_t Z = p.Z[tid];
+      if (Z > total) atomicOr(ws.status, CVLC_DEV_INTERNAL);  // cannot happen once the filter kept >= k
+      if (Z != 0 && Z <= total) {
+        uint32_t lo = 0, hi = kL1Bins - 1;  // largest bin b with incl[b] >= Z
+        while (lo < hi) {
+          const uint32_t mid = (lo + hi + 1) >> 1;
+          if (incl[mid] >= Z) lo = mid; else hi = mid - 1;
+        }
+        pre = lo;
+        rem = Z - (incl[lo] - hist[lo]);
       }
-      ctl->sel_prefix[r] = lo;
-      ctl->sel_rem[r] = Z - (incl[lo] - hist[lo]);
     }
+    ctl->sel_prefix[tid] = pre;
+    ctl->sel_rem[tid] = rem;
+    ctl->tau[tid] = 0xFFFFFFFFu;  // boundaries with Z_r = 0 keep "nothing inside"
+    ctl->iota[tid] = 0u;
   }
 }
 
 // ------------------------------------------------------------------ 4. selection, levels 2 and 3
 // LEVEL 2 refines bits 19..10, LEVEL 3 bits 9..0 of the boundary keys of one
 // group of up to kSlotGroup boundaries.  Boundaries that share a prefix share a
-// histogram ("slot", the first such boundary of the group).
+// histogram ("slot").  The pass kernel histograms, in LDS, the next digit of
+// every candidate whose key starts with a slot's prefix and stores one partial
+// histogram per workgroup; the walk kernel (one workgroup per client) adds the
+// partials up and, one wavefront per boundary, walks the digits from the top.
+// During level 3 the few candidates matching a boundary's 21-bit prefix are
+// also kept aside, so that a boundary cutting through a class of equal keys
+// can find the position of the last member inside it (ties rank by position).
+constexpr uint32_t kNoSlot = 0xFFFFFFFFu;
+
+struct SlotTable {
+  uint32_t prefix[kSlotGroup];  // slot -> key prefix (11 bits at level 2, 21 bits at level 3)
+  uint32_t leader[kSlotGroup];  // boundary inside the group -> its slot, kNoSlot for Z_r = 0
+  uint32_t n;
+};
+
+// Slots in order of first appearance among the group's boundaries.  Run by one thread.
+__device__ void build_slots(SlotTable& st, const ClientCtl* ctl, uint32_t r0, uint32_t nb) {
+  uint32_t ns = 0;
+  for (uint32_t b = 0; b < nb; ++b) {
+    const uint32_t pre = ctl->sel_prefix[r0 + b];
+    uint32_t slot = kNoSlot;
+    if (pre != 0xFFFFFFFFu) {
+      for (uint32_t q = 0; q < ns; ++q)
+        if (st.prefix[q] == pre) slot = q;
+      if (slot == kNoSlot) {
+        slot = ns++;
+        st.prefix[slot] = pre;
+      }
+    }
+    st.leader[b] = slot;
+  }
+  st.n = ns;
+}
+
+struct SelectShared {
+  uint32_t hist[kSlotGroup * kDigitBins];
+  SlotTable slots;
+  uint32_t bin_slot[kL1Bins / 8];                // top 11 key bits -> 1 + (level 2: slot, level 3: bin id), 4 bits each
+  uint32_t digit_map[kSlotGroup][kDigitBins / 32];  // level 3: second digits present per bin id
+  uint32_t tie_full[kSlotGroup];                 // this workgroup has seen the slot's kept-aside list overflow
+
+  __device__ __forceinline__ uint32_t bin_tag(uint32_t top11) const {
+    return (bin_slot[top11 >> 3] >> ((top11 & 7u) * 4u)) & 15u;
+  }
+  __device__ __forceinline__ void set_bin_tag(uint32_t top11, uint32_t tag) {  // single thread, tag <= 15
+    bin_slot[top11 >> 3] |= tag << ((top11 & 7u) * 4u);
+  }
+};
+static_assert(kSlotGroup <= 15, "bin tags are 4 bits wide");
+static_assert(sizeof(SelectShared) <= 65536, "SelectShared must fit the 64 KB static LDS limit");
+
+// Counts one candidate per lane (`live` lanes only).  Must be reached by all
+// lanes of the wavefront.
 template <int LEVEL>
-__global__ __launch_bounds__(kBlock) void select_l23_kernel(const ClientParams* __restrict__ params,
-                                                            ClientCtl* __restrict__ ctls, Workspace ws,
-                                                            uint32_t group) {
-  __shared__ uint32_t hist[kSlotGroup][kDigitBins];
-  __shared__ uint32_t s_prefix[kSlotGroup];  // prefix per slot leader
-  __shared__ uint32_t s_leader[kSlotGroup];  // local slot of every boundary in the group
-  __shared__ uint32_t s_bitmap[kL1Bins / 32];
-  __shared__ uint32_t s_nslots;
-  constexpr uint32_t match_shift = LEVEL == 2 ? 20u : 10u;
-  constexpr uint32_t digit_shift = LEVEL == 2 ? 10u : 0u;
-  const uint32_t client = blockIdx.y;
-  const ClientParams& p = params[client];
-  ClientCtl* ctl = ctls + client;
-  const uint32_t r0 = group * kSlotGroup;
-  if (p.R <= r0) return;  // this client has no boundary in the group
-  const uint32_t nb = min(p.R - r0, kSlotGroup);
-  const uint32_t n = final_ncand(ctl, p);
-  const float* val = ws.cand_val + (size_t)client * ws.d;
-
-  for (uint32_t i = threadIdx.x; i < kSlotGroup * kDigitBins; i += kBlock) (&hist[0][0])[i] = 0;
-  for (uint32_t i = threadIdx.x; i < kL1Bins / 32; i += kBlock) s_bitmap[i] = 0;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t ns = 0;
-    for (uint32_t b = 0; b < nb; ++b) {
-      const uint32_t pre = ctl->sel_prefix[r0 + b];
-      uint32_t slot = 0xFFFFFFFFu;
-      if (pre != 0xFFFFFFFFu) {
-        for (uint32_t q = 0; q < ns; ++q)
-          if (s_prefix[q] == pre) slot = q;
-        if (slot == 0xFFFFFFFFu) {
-          slot = ns++;
-          s_prefix[slot] = pre;
-          const uint32_t top11 = LEVEL == 2 ? pre : pre >> 10;
-          s_bitmap[top11 >> 5] |= 1u << (top11 & 31u);
+__device__ __forceinline__ void select_count(SelectShared& S, uint32_t key, uint32_t idx, bool live, uint32_t* tie_cnt,
+                                             uint2* __restrict__ ties) {
+  uint32_t q = kNoSlot;
+  if (live) {
+    const uint32_t tag = S.bin_tag(key >> 20);
+    if (tag) {
+      if (LEVEL == 2) {
+        atomicAdd(&S.hist[(tag - 1) * kDigitBins + ((key >> 10) & (kDigitBins - 1))], 1u);
+      } else {
+        const uint32_t second = (key >> 10) & (kDigitBins - 1);
+        if ((S.digit_map[tag - 1][second >> 5] >> (second & 31u)) & 1u) {
+          const uint32_t pre = key >> 10, ns = S.slots.n;
+          for (uint32_t qq = 0; qq < ns; ++qq)
+            if (S.slots.prefix[qq] == pre) q = qq;
+          if (q != kNoSlot) atomicAdd(&S.hist[q * kDigitBins + (key & (kDigitBins - 1))], 1u);
         }
       }
-      s_leader[b] = slot;
     }
-    s_nslots = ns;
   }
-  __syncthreads();
-  const uint32_t ns = s_nslots;
-  if (ns > 0) {
-    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < n; i += gridDim.x * kBlock) {
-      const uint32_t key = __float_as_uint(val[i]) & 0x7FFFFFFFu;
-      const uint32_t top11 = key >> 20;
-      if ((s_bitmap[top11 >> 5] >> (top11 & 31u)) & 1u) {
-        const uint32_t pre = key >> match_shift;
-        for (uint32_t q = 0; q < ns; ++q)
-          if (s_prefix[q] == pre) {
-            atomicAdd(&hist[q][(key >> digit_shift) & (kDigitBins - 1)], 1u);
-            break;
-          }
+  if (LEVEL == 3) {
+    uint64_t todo = __ballot(q != kNoSlot);
+    while (todo) {  // one round per distinct slot present in the wavefront
+      const uint32_t leader = (uint32_t)__builtin_ctzll(todo);
+      const uint32_t qs = __builtin_amdgcn_readlane(q, leader);
+      const bool mine = q == qs;
+      const uint64_t peers = __ballot(mine);
+      uint32_t base = kTieCap;
+      if (lane_id() == leader && !S.tie_full[qs]) {
+        base = atomicAdd(&tie_cnt[qs], (uint32_t)__popcll(peers));
+        if (base >= kTieCap) S.tie_full[qs] = 1u;  // the count is past the cap for good: stop adding to it
       }
-    }
-  }
-  __syncthreads();
-  uint32_t(*ghist)[kDigitBins] = LEVEL == 2 ? ctl->hist2 : ctl->hist3;
-  for (uint32_t i = threadIdx.x; i < ns * kDigitBins; i += kBlock) {
-    const uint32_t q = i / kDigitBins, b = i % kDigitBins;
-    if (hist[q][b]) atomicAdd(&ghist[r0 + q][b], hist[q][b]);
-  }
-  if (!arrive_last(&ctl->done_l23[LEVEL - 2][group], gridDim.x)) return;
-
-  // One wavefront per boundary: lane l owns the 16 digits [top-15, top], top = 1023 - 16 l.
-  for (uint32_t b = wave_id(); b < nb; b += kWavesPerBlock) {
-    const uint32_t r = r0 + b, slot = s_leader[b];
-    if (slot == 0xFFFFFFFFu) {  // Z_r = 0: nothing is inside this boundary
-      if (LEVEL == 3 && lane_id() == 0) { ctl->tau[r] = 0xFFFFFFFFu; ctl->iota[r] = 0; ctl->tie_need[r] = 0; }
-      continue;
-    }
-    const uint32_t* gh = ghist[r0 + slot];
-    const uint32_t top = kDigitBins - 1 - 16u * lane_id();
-    uint32_t h[16], mine = 0;
-    for (uint32_t i = 0; i < 16; ++i) { h[i] = load_agent(&gh[top - i]); mine += h[i]; }
-    const uint32_t above = wave_incl_scan_u32(mine) - mine;
-    const uint32_t rem = ctl->sel_rem[r];
-    if (above < rem && rem <= above + mine) {
-      uint32_t acc = above;
-      for (uint32_t i = 0; i < 16; ++i) {
-        if (acc + h[i] >= rem) {
-          const uint32_t full = (s_prefix[slot] << 10) | (top - i);
-          const uint32_t left = rem - acc;  // rank inside the digit class, 1-based
-          if (LEVEL == 2) {
-            ctl->sel_prefix[r] = full;
-            ctl->sel_rem[r] = left;
-          } else {
-            ctl->tau[r] = full;
-            ctl->sel_rem[r] = left;         // tie quota q_r
-            const bool need = left < h[i];  // the class of equal keys straddles the boundary
-            ctl->tie_need[r] = need ? 1u : 0u;
-            ctl->iota[r] = 0xFFFFFFFFu;
-            if (need) atomicOr(&ctl->need_tie, 1u);
-          }
-          break;
-        }
-        acc += h[i];
+      base = __builtin_amdgcn_readlane(base, leader);
+      if (mine) {
+        const uint32_t pos = base + lanes_below(peers);
+        if (pos < kTieCap) ties[qs * kTieCap + pos] = make_uint2(idx, key & (kDigitBins - 1));
       }
+      todo &= ~peers;
     }
   }
 }
 
-// ------------------------------------------------------------------ 5. ties at a boundary
-// For boundaries whose key class straddles Z_r: the position of the q_r-th
-// member of the class in position order.  Each workgroup counts the class
-// members in its slice of the candidate list; the last one finds the slice
-// that holds the q_r-th member and walks it.
-__global__ __launch_bounds__(kBlock) void tie_resolve_kernel(const ClientParams* __restrict__ params,
-                                                             ClientCtl* __restrict__ ctls, Workspace ws) {
-  __shared__ uint32_t s_cnt[32];
-  __shared__ uint32_t s_tau[32];
-  __shared__ uint32_t s_need[32];
-  __shared__ uint32_t scan_tmp[kWavesPerBlock];
-  __shared__ uint32_t s_found;
-  const uint32_t client = blockIdx.y;
+// SPARSE: read the candidates from the filter's region runs and also copy them
+// to the dense list (first pass after a filter); otherwise read the dense list.
+template <int LEVEL, bool SPARSE>
+__global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientParams* __restrict__ params,
+                                                                 ClientCtl* __restrict__ ctls, Workspace ws,
+                                                                 uint32_t group) {
+  __shared__ SelectShared S;
+  const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  if (!ctl->need_tie) return;
-  const uint32_t n = final_ncand(ctl, p);
-  const float* val = ws.cand_val + (size_t)client * ws.d;
-  const uint32_t* idx = ws.cand_idx + (size_t)client * ws.d;
-  if (threadIdx.x < 32) {
-    const bool live = threadIdx.x < p.R;
-    s_cnt[threadIdx.x] = 0;
-    s_tau[threadIdx.x] = live ? ctl->tau[threadIdx.x] : 0xFFFFFFFFu;
-    s_need[threadIdx.x] = live ? ctl->tie_need[threadIdx.x] : 0u;
-  }
-  __syncthreads();
-  const uint32_t span = (uint32_t)((((uint64_t)n + gridDim.x - 1) / gridDim.x + kBlock - 1) / kBlock * kBlock);
-  const uint64_t begin64 = (uint64_t)blockIdx.x * span;
-  const uint32_t begin = (uint32_t)(begin64 < n ? begin64 : n);
-  const uint32_t end = (uint32_t)(begin64 + span < n ? begin64 + span : n);
-  for (uint32_t i = begin + threadIdx.x; i < end; i += kBlock) {
-    const uint32_t key = __float_as_uint(val[i]) & 0x7FFFFFFFu;
-    for (uint32_t r = 0; r < p.R; ++r)
-      if (s_need[r] && key == s_tau[r]) atomicAdd(&s_cnt[r], 1u);
-  }
-  __syncthreads();
-  if (threadIdx.x < 32) store_agent(&ctl->tie_partial[blockIdx.x][threadIdx.x], s_cnt[threadIdx.x]);
-  if (!arrive_last(&ctl->done_tie, gridDim.x)) return;
+  const uint32_t r0 = group * kSlotGroup;
+  const uint32_t nb = p.R > r0 ? min(p.R - r0, kSlotGroup) : 0u;
+  if (nb == 0 && !SPARSE) return;  // this client has no boundary in the group
+  const uint32_t d = ws.d;
+  uint2* __restrict__ dense = ws.cand_dense + (size_t)client * d;
+  uint2* ties = ws.tie_list + (size_t)client * kSlotGroup * kTieCap;
+  uint32_t* tie_cnt = ctl->tie_cnt[group];
 
-  for (uint32_t r = 0; r < p.R; ++r) {
-    if (!s_need[r]) continue;
-    const uint32_t quota = ctl->sel_rem[r];
-    // slice holding the quota-th member
-    uint32_t before = 0, slice = 0;
-    for (slice = 0; slice < gridDim.x; ++slice) {
-      const uint32_t c = load_agent(&ctl->tie_partial[slice][r]);
-      if (before + c >= quota) break;
-      before += c;
-    }
-    if (slice == gridDim.x) {  // fewer members than the quota: histogram and list disagree
-      if (threadIdx.x == 0) atomicOr(ws.status, CVLC_DEV_INTERNAL);
-      continue;
-    }
-    const uint64_t sb = (uint64_t)slice * span;
-    const uint32_t s_begin = (uint32_t)(sb < n ? sb : n), s_end = (uint32_t)(sb + span < n ? sb + span : n);
-    uint32_t left = quota - before;  // 1-based rank inside the slice
-    __syncthreads();
-    if (threadIdx.x == 0) s_found = 0;
-    __syncthreads();
-    for (uint32_t base = s_begin; base < s_end; base += kBlock) {
-      const uint32_t i = base + threadIdx.x;
-      const uint32_t hit = (i < s_end && (__float_as_uint(val[i]) & 0x7FFFFFFFu) == s_tau[r]) ? 1u : 0u;
-      uint32_t tot;
-      const uint32_t rank = block_excl_scan(hit, scan_tmp, &tot);
-      if (hit && rank + 1 == left) {
-        ctl->iota[r] = idx[i];
-        s_found = 1;
+  for (uint32_t i = tid; i < kSlotGroup * kDigitBins; i += kWideBlock) S.hist[i] = 0;
+  for (uint32_t i = tid; i < kL1Bins / 8; i += kWideBlock) S.bin_slot[i] = 0;
+  for (uint32_t i = tid; i < kSlotGroup * (kDigitBins / 32); i += kWideBlock) (&S.digit_map[0][0])[i] = 0;
+  if (tid < kSlotGroup) S.tie_full[tid] = 0;
+  __syncthreads();
+  if (tid == 0) {
+    build_slots(S.slots, ctl, r0, nb);
+    uint32_t nbins = 0;
+    for (uint32_t q = 0; q < S.slots.n; ++q) {
+      const uint32_t pre = S.slots.prefix[q];
+      if (LEVEL == 2) {
+        S.set_bin_tag(pre, q + 1);
+      } else {
+        const uint32_t top11 = pre >> 10, second = pre & (kDigitBins - 1);
+        if (S.bin_tag(top11) == 0) S.set_bin_tag(top11, ++nbins);
+        S.digit_map[S.bin_tag(top11) - 1][second >> 5] |= 1u << (second & 31u);
       }
+    }
+  }
+  __syncthreads();
+
+  if (SPARSE) {
+    const uint32_t n_regions = ws.n_regions;
+    const uint32_t* cnt = ws.region_cnt + (size_t)client * n_regions;
+    const uint32_t* off = ws.region_off + (size_t)client * (n_regions + 1);
+    const uint2* __restrict__ sparse = ws.cand_sparse + (size_t)client * d;
+    const uint32_t wpc = gridDim.x * kWideWaves;  // wavefronts per client
+    // a wavefront takes regions gw, gw + wpc, ...; their counts and offsets are fetched 64 at a time
+    for (uint32_t first = blockIdx.x * kWideWaves + wave; first < n_regions; first += wpc * kWave) {
+      const uint32_t mine = first + lane * wpc;
+      uint32_t c = 0, o = 0;
+      if (mine < n_regions) {
+        c = cnt[mine];
+        o = off[mine];
+      }
+      const uint32_t left = (n_regions - first + wpc - 1) / wpc;
+      const uint32_t nr = left < kWave ? left : kWave;
+      for (uint32_t l = 0; l < nr; ++l) {
+        const uint32_t rc = __builtin_amdgcn_readlane(c, l), ro = __builtin_amdgcn_readlane(o, l);
+        const uint2* __restrict__ src = sparse + (size_t)(first + l * wpc) * kRegion;
+        uint2* __restrict__ dst = dense + ro;
+        for (uint32_t b = 0; b < rc; b += kWave * 4u) {
+          uint2 e[4];
+          bool live[4];
+#pragma unroll
+          for (uint32_t u = 0; u < 4; ++u) {
+            const uint32_t i = b + u * kWave + lane;
+            live[u] = i < rc;
+            e[u] = make_uint2(0u, 0u);
+            if (live[u]) e[u] = src[i];
+          }
+#pragma unroll
+          for (uint32_t u = 0; u < 4; ++u) {
+            if (b + u * kWave >= rc) break;  // uniform
+            if (live[u]) dst[b + u * kWave + lane] = e[u];
+            if (nb) select_count<LEVEL>(S, e[u].y & 0x7FFFFFFFu, e[u].x, live[u], tie_cnt, ties);
+          }
+        }
+      }
+    }
+  } else {
+    const uint32_t n = ctl->n_cand;
+    const uint32_t span = (uint32_t)(((uint64_t)n + gridDim.x - 1) / gridDim.x);
+    const uint64_t begin64 = (uint64_t)blockIdx.x * span;
+    const uint32_t begin = (uint32_t)(begin64 < n ? begin64 : n);
+    const uint32_t end = (uint32_t)(begin64 + span < n ? begin64 + span : n);
+    for (uint32_t base = begin; base < end; base += kWideBlock * 8u) {
+      uint2 e[8];
+      bool live[8];
+#pragma unroll
+      for (uint32_t u = 0; u < 8; ++u) {
+        const uint32_t i = base + u * kWideBlock + tid;
+        live[u] = i < end;
+        e[u] = make_uint2(0u, 0u);
+        if (live[u]) e[u] = dense[i];
+      }
+#pragma unroll
+      for (uint32_t u = 0; u < 8; ++u) {
+        if (base + u * kWideBlock + wave * kWave >= end) break;  // uniform per wavefront
+        select_count<LEVEL>(S, e[u].y & 0x7FFFFFFFu, e[u].x, live[u], tie_cnt, ties);
+      }
+    }
+  }
+  __syncthreads();
+  if (nb == 0) return;
+  uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * kSlotGroup * kDigitBins;
+  const uint32_t used = S.slots.n * kDigitBins;
+  for (uint32_t i = tid; i < used; i += kWideBlock) part[i] = S.hist[i];
+}
+
+template <int LEVEL>
+__global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientParams* __restrict__ params,
+                                                                 ClientCtl* __restrict__ ctls, Workspace ws,
+                                                                 uint32_t group) {
+  __shared__ SlotTable slots;
+  __shared__ uint32_t s_slow[kSlotGroup];
+  __shared__ uint32_t s_found;
+  __shared__ uint32_t scan_tmp[kWideWaves];
+  const uint32_t client = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+  const ClientParams& p = params[client];
+  ClientCtl* ctl = ctls + client;
+  const uint32_t r0 = group * kSlotGroup;
+  if (p.R <= r0) return;
+  const uint32_t nb = min(p.R - r0, kSlotGroup);
+  const uint32_t n_parts = ws.sel_blocks;
+  const uint32_t* parts = ws.sel_part + (size_t)client * n_parts * kSlotGroup * kDigitBins;
+  const uint2* ties = ws.tie_list + (size_t)client * kSlotGroup * kTieCap;
+  if (tid == 0) build_slots(slots, ctl, r0, nb);
+  if (tid < kSlotGroup) s_slow[tid] = 0;
+  __syncthreads();
+
+  // one wavefront per boundary; lane l owns digits [top-15, top], top = 1023 - 16 l
+  if (wave < nb && slots.leader[wave] != kNoSlot) {
+    const uint32_t r = r0 + wave, slot = slots.leader[wave];
+    const uint32_t top = kDigitBins - 1 - 16u * lane;
+    uint32_t h[16], mine = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < 16; ++i) h[i] = 0;
+    for (uint32_t b = 0; b < n_parts; ++b) {
+      const uint4* src = reinterpret_cast<const uint4*>(&parts[((size_t)b * kSlotGroup + slot) * kDigitBins + top - 15]);
+#pragma unroll
+      for (uint32_t q = 0; q < 4; ++q) {  // src[q] holds digits top-15+4q .. top-12+4q
+        const uint4 w = src[q];
+        h[15 - 4 * q] += w.x; h[14 - 4 * q] += w.y; h[13 - 4 * q] += w.z; h[12 - 4 * q] += w.w;
+      }
+    }
+#pragma unroll
+    for (uint32_t i = 0; i < 16; ++i) mine += h[i];
+    const uint32_t above = wave_incl_scan_u32(mine) - mine;
+    const uint32_t rem = ctl->sel_rem[r];
+    uint32_t need = 0, digit = 0, quota = 0;
+    const bool here = above < rem && rem <= above + mine;
+    if (here) {
+      uint32_t acc = above;
+#pragma unroll
+      for (uint32_t i = 0; i < 16; ++i) {
+        if (quota == 0 && acc + h[i] >= rem) {
+          digit = top - i;
+          quota = rem - acc;  // rank inside the digit class, 1-based
+          need = (LEVEL == 3 && quota < h[i]) ? 1u : 0u;
+        }
+        acc += h[i];
+      }
+    }
+    if (__ballot(here) == 0 && lane == 0) atomicOr(ws.status, CVLC_DEV_INTERNAL);  // histogram short of the rank
+    if (here) {
+      const uint32_t full = (slots.prefix[slot] << 10) | digit;
+      if (LEVEL == 2) {
+        ctl->sel_prefix[r] = full;
+        ctl->sel_rem[r] = quota;
+      } else {
+        ctl->tau[r] = full;
+        ctl->sel_rem[r] = quota;     // tie quota q_r
+        ctl->iota[r] = 0xFFFFFFFFu;  // every member of the class is inside unless it straddles Z_r
+      }
+    }
+    if (LEVEL == 3) {
+      // the class of equal keys straddles the boundary: find its quota-th member in position order
+      const uint64_t who = __ballot(need != 0);
+      if (who) {
+        const uint32_t src_lane = (uint32_t)__builtin_ctzll(who);
+        const uint32_t w_digit = __shfl(digit, src_lane, 64), w_quota = __shfl(quota, src_lane, 64);
+        const uint32_t kept = ctl->tie_cnt[group][slot];
+        if (kept <= kTieCap) {
+          const uint2* list = ties + slot * kTieCap;
+          for (uint32_t e = lane; e < kept; e += kWave) {
+            const uint2 me = list[e];
+            if (me.y != w_digit) continue;
+            uint32_t before = 0;
+            for (uint32_t o = 0; o < kept; ++o) {
+              const uint2 other = list[o];
+              before += (other.y == w_digit && other.x < me.x) ? 1u : 0u;
+            }
+            if (before + 1 == w_quota) ctl->iota[r] = me.x;
+          }
+        } else if (lane == 0) {
+          s_slow[wave] = 1;  // too many to keep aside: walk the whole candidate list below
+        }
+      }
+    }
+  }
+  if (LEVEL == 3) {
+    __syncthreads();
+    const uint32_t n = ctl->n_cand;
+    const uint2* __restrict__ dense = ws.cand_dense + (size_t)client * ws.d;
+    for (uint32_t b = 0; b < nb; ++b) {
+      if (!s_slow[b]) continue;
+      const uint32_t r = r0 + b;
+      const uint32_t tau = ctl->tau[r];
+      uint32_t left = ctl->sel_rem[r];
       __syncthreads();
-      if (s_found || tot >= left) break;
-      left -= tot;
+      if (tid == 0) s_found = 0;
+      __syncthreads();
+      for (uint32_t base = 0; base < n; base += kWideBlock) {
+        const uint32_t i = base + tid;
+        uint2 e = make_uint2(0u, 0xFFFFFFFFu);
+        if (i < n) e = dense[i];
+        const uint32_t hit = (i < n && (e.y & 0x7FFFFFFFu) == tau) ? 1u : 0u;
+        uint32_t tot;
+        const uint32_t rank = block_excl_scan<kWideWaves>(hit, scan_tmp, &tot);
+        if (hit && rank + 1 == left) {
+          ctl->iota[r] = e.x;
+          s_found = 1;
+        }
+        __syncthreads();
+        if (s_found || tot >= left) break;
+        left -= tot;
+      }
+      if (tid == 0 && !s_found) atomicOr(ws.status, CVLC_DEV_INTERNAL);
     }
   }
 }
@@ -607,9 +799,8 @@ __global__ __launch_bounds__(kBlock) void classify_kernel(const ClientParams* __
   const uint32_t client = blockIdx.y;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  const uint32_t n = final_ncand(ctl, p), R = p.R;
-  const float* val = ws.cand_val + (size_t)client * ws.d;
-  const uint32_t* idx = ws.cand_idx + (size_t)client * ws.d;
+  const uint32_t n = ctl->n_cand, R = p.R;
+  const uint2* __restrict__ cand = ws.cand_dense + (size_t)client * ws.d;
 
   for (uint32_t w = blockIdx.x * kBlock + threadIdx.x; w < p.total_words; w += gridDim.x * kBlock) p.stream[w] = 0;
 
@@ -622,8 +813,9 @@ __global__ __launch_bounds__(kBlock) void classify_kernel(const ClientParams* __
     for (uint32_t j = 0; j < kChunk / kBlock; ++j) {
       const uint32_t i = c * kChunk + wave_id() * (kChunk / kWavesPerBlock) + j * kWave + lane_id();
       if (i < n) {
-        const float x = val[i];
-        const uint32_t g = classify(thr, R, __float_as_uint(x) & 0x7FFFFFFFu, idx[i]);
+        const uint2 e = cand[i];
+        const float x = __uint_as_float(e.y);
+        const uint32_t g = classify(thr, R, e.y & 0x7FFFFFFFu, e.x);
         atomicAdd(&s_cnt[g], 1u);
         atomicAdd(&s_sq[g], (double)x * (double)x);
         const uint32_t o = ordered_bits(x);
@@ -659,7 +851,7 @@ __global__ __launch_bounds__(1024) void layout_kernel(const ClientParams* __rest
   const uint32_t client = blockIdx.x;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  const uint32_t n = final_ncand(ctl, p), R = p.R;
+  const uint32_t n = ctl->n_cand, R = p.R;
   const uint32_t n_chunks = (n + kChunk - 1) / kChunk;
   const uint32_t lane = lane_id(), wave = threadIdx.x / kWave;
   uint32_t* cnt = ws.chunk_cnt + (size_t)client * ws.max_chunks * 32;
@@ -679,11 +871,11 @@ __global__ __launch_bounds__(1024) void layout_kernel(const ClientParams* __rest
     }
     if (lane == 0) { s_total[g] = run; s_sq[g] = sq; }
   }
-  // energy of the coordinates the filter dropped, in tile order
+  // energy of the coordinates the filter dropped, region by region
   {
-    const double* tsq = ws.tile_sumsq + (size_t)client * ws.n_tiles;
+    const double* rsq = ws.region_sumsq + (size_t)client * ws.n_regions;
     double acc = 0.0;
-    for (uint32_t t = threadIdx.x; t < ws.n_tiles; t += 1024) acc += tsq[t];
+    for (uint32_t t = threadIdx.x; t < ws.n_regions; t += 1024) acc += rsq[t];
     acc = wave_sum_f64(acc);
     if (lane == 0) s_tail[wave] = acc;
   }
@@ -770,6 +962,7 @@ __global__ __launch_bounds__(kBlock) void emit_kernel(const ClientParams* __rest
   __shared__ Thresholds thr;
   __shared__ uint32_t s_stage[kStageWords];
   __shared__ uint32_t s_wcnt[kWavesPerBlock][32];  // per wavefront, per group: members in this chunk
+  __shared__ volatile uint32_t s_run[kWavesPerBlock][32];
   __shared__ uint32_t s_base[32];                  // first record index of this chunk in each group
   __shared__ uint32_t s_lim[32];                   // one past this chunk's last record index in each group
   __shared__ uint32_t s_P[32];                     // planned group sizes
@@ -782,10 +975,9 @@ __global__ __launch_bounds__(kBlock) void emit_kernel(const ClientParams* __rest
   const uint32_t client = blockIdx.y;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  const uint32_t n = final_ncand(ctl, p), R = p.R;
+  const uint32_t n = ctl->n_cand, R = p.R;
   const uint32_t sbits = position_bits(ws.d);
-  const float* val = ws.cand_val + (size_t)client * ws.d;
-  const uint32_t* idx = ws.cand_idx + (size_t)client * ws.d;
+  const uint2* __restrict__ cand = ws.cand_dense + (size_t)client * ws.d;
   uint32_t* stream = p.stream;
   const uint32_t lane = lane_id(), wave = wave_id();
   const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
@@ -825,8 +1017,9 @@ __global__ __launch_bounds__(kBlock) void emit_kernel(const ClientParams* __rest
       const uint32_t i = c * kChunk + wave * (kChunk / kWavesPerBlock) + j * kWave + lane;
       grp[j] = 0xFFFFFFFFu;
       if (i < n) {
-        x[j] = val[i];
-        pid[j] = idx[i];
+        const uint2 e = cand[i];
+        x[j] = __uint_as_float(e.y);
+        pid[j] = e.x;
         grp[j] = classify(thr, R, __float_as_uint(x[j]) & 0x7FFFFFFFu, pid[j]);
         if (grp[j] < R) atomicAdd(&s_wcnt[wave][grp[j]], 1u);
       }
@@ -862,23 +1055,28 @@ __global__ __launch_bounds__(kBlock) void emit_kernel(const ClientParams* __rest
     for (uint32_t i = threadIdx.x; i < staged; i += kBlock) s_stage[i] = 0;
     __syncthreads();
     // sweep 2: rank inside (group, chunk) in position order, quantise, pack into LDS.
-    // Lane g of a wavefront keeps the running rank of group g for that wavefront.
-    uint32_t running = 0;
-    if (lane < R)
-      for (uint32_t w = 0; w < wave; ++w) running += s_wcnt[w][lane];
+    // s_run[wave][g] is the number of group-g records of this chunk that precede the
+    // wavefront's current 64 candidates; it is read and advanced by the wavefront alone.
+    if (lane < 32) {
+      uint32_t before = 0;
+      for (uint32_t w = 0; w < wave; ++w) before += s_wcnt[w][lane];
+      s_run[wave][lane] = before;
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const bool coded = grp[j] < R;
+      const uint32_t g5 = grp[j] & 31u;
+      uint64_t same = __ballot(coded);  // lanes holding a coded record of the same group as this lane
+#pragma unroll
+      for (int bit = 0; bit < 5; ++bit) {
+        const uint64_t set = __ballot((g5 >> bit) & 1u);
+        same &= ((g5 >> bit) & 1u) ? set : ~set;
+      }
       uint32_t my_rank = 0;
-      uint64_t todo = __ballot(coded);
-      while (todo) {
-        const uint32_t leader = (uint32_t)__builtin_ctzll(todo);
-        const uint32_t g = __shfl(grp[j], leader, 64);
-        const uint64_t same = __ballot(coded && grp[j] == g);
-        const uint32_t start = __shfl(running, g, 64);
-        if (coded && grp[j] == g) my_rank = start + lanes_below(same);
-        if (lane == g) running += (uint32_t)__popcll(same);
-        todo &= ~same;
+      if (coded) {
+        const uint32_t start = s_run[wave][g5];
+        my_rank = start + lanes_below(same);
+        if (lane == (uint32_t)__builtin_ctzll(same)) s_run[wave][g5] = start + (uint32_t)__popcll(same);
       }
       if (coded && s_base[grp[j]] + my_rank < s_lim[grp[j]]) {
         const uint32_t g = grp[j], y = p.y[g], W = s_W[g];
@@ -923,6 +1121,7 @@ int validate_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* d_u
                    void* d_workspace, size_t ws_bytes) {
   if (n == 0 || !plans || !d_updates || !client_ids || !d_streams || !capacities || !d_workspace) return CVLC_ERR_ARG;
   if (reinterpret_cast<uintptr_t>(d_workspace) % 256u) return CVLC_ERR_ARG;
+  if (n > 65535u) return CVLC_ERR_ARG;  // clients index the grid's y dimension
   const uint32_t d = plans[0].d;
   for (uint32_t i = 0; i < n; ++i) {
     const int rc = cvlc_plan_validate(&plans[i]);
@@ -972,23 +1171,28 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   ws.status = reinterpret_cast<uint32_t*>(base + L.status);
   ws.params = reinterpret_cast<ClientParams*>(base + L.params);
   ws.ctl = reinterpret_cast<ClientCtl*>(base + L.ctl);
-  ws.tile_state = reinterpret_cast<uint64_t*>(base + L.tile_state);
-  ws.tile_sumsq = reinterpret_cast<double*>(base + L.tile_sumsq);
-  ws.cand_idx = reinterpret_cast<uint32_t*>(base + L.cand_idx);
-  ws.cand_val = reinterpret_cast<float*>(base + L.cand_val);
+  ws.region_cnt = reinterpret_cast<uint32_t*>(base + L.region_cnt);
+  ws.region_off = reinterpret_cast<uint32_t*>(base + L.region_off);
+  ws.region_sumsq = reinterpret_cast<double*>(base + L.region_sumsq);
+  ws.cand_sparse = reinterpret_cast<uint2*>(base + L.cand_sparse);
+  ws.cand_dense = reinterpret_cast<uint2*>(base + L.cand_dense);
   ws.chunk_cnt = reinterpret_cast<uint32_t*>(base + L.chunk_cnt);
   ws.chunk_sumsq = reinterpret_cast<double*>(base + L.chunk_sumsq);
+  ws.tie_list = reinterpret_cast<uint2*>(base + L.tie_list);
+  ws.hist1_part = reinterpret_cast<uint32_t*>(base + L.hist1_part);
+  ws.sel_part = reinterpret_cast<uint32_t*>(base + L.sel_part);
   ws.d = d;
-  ws.n_tiles = L.n_tiles;
+  ws.n_regions = L.n_regions;
   ws.max_chunks = L.max_chunks;
+  ws.filter_blocks = L.filter_blocks;
+  ws.sel_blocks = L.sel_blocks;
 
   // sample geometry: 64-byte pieces spread evenly; all of them when the vector is short
   const uint32_t n_src = d / 16u;
   const uint32_t n_s = n_src < kSampleChunksMax ? n_src : kSampleChunksMax;
 
   profile_mark(CVLC_STAGE_ENC_SETUP, true, stream);
-  if ((rc = hip_check(hipMemsetAsync(base + L.status, 0, 256, stream)))) return rc;
-  if ((rc = hip_check(hipMemsetAsync(base + L.zero_begin, 0, L.zero_end - L.zero_begin, stream)))) return rc;
+  if ((rc = hip_check(hipMemsetAsync(base + L.status, 0, L.zero_bytes, stream)))) return rc;
 
   // per-client parameters, shipped as kernel arguments
   uint32_t max_R = 0;
@@ -1026,41 +1230,42 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
       hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(ws.params), chunk);
     }
   }
-
   profile_mark(CVLC_STAGE_ENC_SETUP, false, stream);
 
-  auto spread = [n](uint32_t want_total, uint32_t cap) {  // workgroups per client
-    uint32_t g = (want_total + n - 1) / n;
-    if (g > cap) g = cap;
-    return g < 1 ? 1u : g;
-  };
   if (any_sampled) {
     StageScope scope(CVLC_STAGE_ENC_SAMPLE, stream);
-    const uint32_t g = spread(512, (n_s * 4u + kBlock - 1) / kBlock);
-    hipLaunchKernelGGL(sample_hist_kernel, dim3(g, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, n_s, n_src);
+    hipLaunchKernelGGL(sample_hist_kernel, dim3(kSampleBlocks, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, n_s,
+                       n_src);
+    hipLaunchKernelGGL(sample_walk_kernel, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl);
   }
   {
-    const uint32_t g = spread(2048, L.n_tiles);
-    {
-      StageScope scope(CVLC_STAGE_ENC_FILTER, stream);
-      hipLaunchKernelGGL(filter_kernel<0>, dim3(g, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
-    }
-    StageScope scope(CVLC_STAGE_ENC_REFILTER, stream);
-    hipLaunchKernelGGL(filter_kernel<1>, dim3(g, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+    StageScope scope(CVLC_STAGE_ENC_FILTER, stream);
+    hipLaunchKernelGGL(filter_kernel<0>, dim3(L.filter_blocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
   }
-  const uint32_t g_sel = spread(1024, (d + kBlock * 8 - 1) / (kBlock * 8));
+  {
+    StageScope scope(CVLC_STAGE_ENC_REFILTER, stream);
+    hipLaunchKernelGGL(scan_l1_kernel<0>, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
+    if (any_sampled) {  // only clients whose sampled threshold kept too few do anything here
+      hipLaunchKernelGGL(filter_kernel<1>, dim3(L.filter_blocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+      hipLaunchKernelGGL(scan_l1_kernel<1>, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
+    }
+  }
   {
     StageScope scope(CVLC_STAGE_ENC_SELECT, stream);
-    hipLaunchKernelGGL(select_l1_kernel, dim3(g_sel, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+    const dim3 grid(L.sel_blocks, n);
     const uint32_t groups = (max_R + kSlotGroup - 1) / kSlotGroup;
-    // one launch per group of boundaries; clients with fewer boundaries leave it at once
-    for (uint32_t gr = 0; gr < groups; ++gr)
-      hipLaunchKernelGGL(select_l23_kernel<2>, dim3(g_sel, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws, gr);
-    for (uint32_t gr = 0; gr < groups; ++gr)
-      hipLaunchKernelGGL(select_l23_kernel<3>, dim3(g_sel, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws, gr);
-    hipLaunchKernelGGL(tie_resolve_kernel, dim3(kTieBlocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+    // the first pass also gathers the region runs into the dense candidate list (also when nothing is coded)
+    hipLaunchKernelGGL((select_pass_kernel<2, true>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
+    for (uint32_t gr = 0; gr < groups; ++gr) {
+      if (gr > 0)
+        hipLaunchKernelGGL((select_pass_kernel<2, false>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+      hipLaunchKernelGGL(select_walk_kernel<2>, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+      hipLaunchKernelGGL((select_pass_kernel<3, false>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+      hipLaunchKernelGGL(select_walk_kernel<3>, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+    }
   }
-  const uint32_t g_chunk = spread(2048, L.max_chunks);
+  uint32_t g_chunk = (2048u + n - 1) / n;
+  if (g_chunk > L.max_chunks) g_chunk = L.max_chunks;
   {
     StageScope scope(CVLC_STAGE_ENC_CLASSIFY, stream);
     hipLaunchKernelGGL(classify_kernel, dim3(g_chunk, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
