@@ -31,7 +31,7 @@ constexpr uint32_t kDigitBins = 1024;      // level-2 and level-3 digits: 10 bit
 constexpr uint32_t kSlotGroup = 15;        // boundaries refined per level-2/3 launch (60 KB of LDS)
 constexpr uint32_t kSampleChunksMax = 16384;  // 64-byte pieces in the sample (256 Ki coordinates)
 constexpr uint32_t kTieCap = 2048;         // boundary-class members kept per histogram slot for tie resolution
-constexpr uint32_t kSampleBlocks = 4;      // workgroups per client in the sample pass
+constexpr uint32_t kSampleBlocks = 16;     // workgroups per client in the sample pass
 constexpr uint32_t kMaxGroups = 3;         // ceil(31 / kSlotGroup)
 constexpr uint32_t kStatsStride = CVLC_STATS_STRIDE;
 
@@ -66,6 +66,7 @@ struct ClientCtl {
   uint32_t seg_max_enc[32];  // max over the group of ordered(x); 0 = empty
   uint32_t seg_negmin_enc[32];  // max over the group of ~ordered(x); 0 = empty
   uint32_t hist_sample[kSampleBins];  // sample histogram, accumulated with device-wide atomics
+  uint32_t hist_l1[2][kL1Bins];       // level-1 digit counts of the candidates, per filter pass, likewise
 };
 
 // ---- decoder -------------------------------------------------------------------

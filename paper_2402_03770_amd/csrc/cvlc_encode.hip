@@ -42,27 +42,29 @@ namespace {
 // ------------------------------------------------------------------ workspace layout
 struct EncodeLayout {
   size_t status, ctl, params, region_cnt, region_off, region_sumsq, cand_sparse, cand_dense, chunk_cnt, chunk_sumsq,
-      tie_list, hist1_part, sel_part, total;
+      tie_list, sel_part, total;
   size_t zero_bytes;        // [status, params) is cleared at the start of a call
   uint32_t n_regions, max_chunks;
-  uint32_t filter_blocks;   // workgroups per client in the filter pass
   uint32_t sel_blocks;      // workgroups per client in a level-2/3 selection pass
 };
 
 size_t align256(size_t v) { return (v + 255u) & ~(size_t)255u; }
 
+// Workgroups per client in the filter pass: all of them resident at once
+// (`resident` workgroups fit the device), every wavefront the same number of regions.
+constexpr uint32_t kFilterBlocksCap = 2048;  // 8 workgroups on each of 256 CUs
+uint32_t filter_blocks_per_client(uint32_t n_regions, uint32_t n, uint32_t resident) {
+  const uint32_t max_blocks = resident / n > 0 ? resident / n : 1u;
+  const uint32_t max_waves = max_blocks * kWavesPerBlock;
+  const uint32_t rounds = (n_regions + max_waves - 1) / max_waves;
+  const uint32_t waves = (n_regions + rounds - 1) / rounds;
+  return (waves + kWavesPerBlock - 1) / kWavesPerBlock;
+}
+
 EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   EncodeLayout L;
   L.n_regions = (uint32_t)(((uint64_t)d + kRegion - 1) / kRegion);
   L.max_chunks = (uint32_t)(((uint64_t)d + kChunk - 1) / kChunk);
-  // filter: one resident round of workgroups (8 per CU), every wavefront the same number of regions
-  {
-    const uint32_t max_blocks = 2048u / n > 0 ? 2048u / n : 1u;
-    const uint32_t max_waves = max_blocks * kWavesPerBlock;
-    const uint32_t rounds = (L.n_regions + max_waves - 1) / max_waves;
-    const uint32_t waves = (L.n_regions + rounds - 1) / rounds;
-    L.filter_blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
-  }
   {
     uint32_t b = (512u + n - 1) / n;
     L.sel_blocks = b < 2 ? 2u : (b > 32 ? 32u : b);
@@ -80,7 +82,6 @@ EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   L.chunk_cnt = off; off = align256(off + (size_t)n * L.max_chunks * 32 * sizeof(uint32_t));
   L.chunk_sumsq = off; off = align256(off + (size_t)n * L.max_chunks * 32 * sizeof(double));
   L.tie_list = off; off = align256(off + (size_t)n * kSlotGroup * kTieCap * sizeof(uint2));
-  L.hist1_part = off; off = align256(off + (size_t)n * L.filter_blocks * kL1Bins * sizeof(uint32_t));
   L.sel_part = off; off = align256(off + (size_t)n * L.sel_blocks * kSlotGroup * kDigitBins * sizeof(uint32_t));
   L.total = off;
   return L;
@@ -98,7 +99,6 @@ struct Workspace {  // device pointers into the caller's workspace
   uint32_t* chunk_cnt;
   double* chunk_sumsq;
   uint2* tie_list;
-  uint32_t* hist1_part;
   uint32_t* sel_part;
   uint32_t d, n_regions, max_chunks, filter_blocks, sel_blocks;
 };
@@ -148,37 +148,43 @@ __device__ __forceinline__ uint32_t lanes_below4(uint64_t m0, uint64_t m1, uint6
   return acc;
 }
 
+// Pointers read from the parameter block are generic; the update vectors live in
+// global memory, and saying so lets the loads be issued as global loads.
+typedef const float __attribute__((address_space(1))) * GlobalFloatPtr;
+typedef float __attribute__((ext_vector_type(4))) Float4V;
+typedef const Float4V __attribute__((address_space(1))) * GlobalFloat4Ptr;
+
 constexpr uint32_t kWideBlock = 1024;
 constexpr uint32_t kWideWaves = kWideBlock / kWave;
 
 // ------------------------------------------------------------------ 1. sample histogram
 // Reads n_s 64-byte pieces spread evenly over the vector and histograms the
-// magnitude keys on their top 12 bits.  kSampleBlocks workgroups of 1024
-// threads per client each take a slice of the pieces, issue their loads eight
-// deep, and add their non-empty bins to the client's histogram.
-__global__ __launch_bounds__(kWideBlock) void sample_hist_kernel(const ClientParams* __restrict__ params,
-                                                                 ClientCtl* __restrict__ ctls, uint32_t n_s,
-                                                                 uint32_t n_src) {
+// magnitude keys on their top 12 bits.  kSampleBlocks workgroups per client each
+// take a slice of the pieces, issue their loads eight deep, and add their
+// non-empty bins to the client's histogram.
+__global__ __launch_bounds__(kBlock) void sample_hist_kernel(const ClientParams* __restrict__ params,
+                                                             ClientCtl* __restrict__ ctls, uint32_t n_s,
+                                                             uint32_t n_src) {
   __shared__ uint32_t hist[kSampleBins];
   const uint32_t client = blockIdx.y;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   if (p.sample_rank == 0) return;  // keep-all plan: the threshold stays 0
-  for (uint32_t i = threadIdx.x; i < kSampleBins; i += kWideBlock) hist[i] = 0;
+  for (uint32_t i = threadIdx.x; i < kSampleBins; i += kBlock) hist[i] = 0;
   __syncthreads();
-  const float4* src = reinterpret_cast<const float4*>(p.update);
+  GlobalFloat4Ptr src = (GlobalFloat4Ptr)p.update;
   const uint32_t total_q = n_s * 4u;
   const uint32_t per_block = (total_q + gridDim.x - 1) / gridDim.x;
   const uint32_t q_begin = blockIdx.x * per_block;
   const uint32_t q_end = min(total_q, q_begin + per_block);
-  for (uint32_t base = q_begin; base < q_end; base += kWideBlock * 8u) {
-    float4 v[8];
+  for (uint32_t base = q_begin; base < q_end; base += kBlock * 8u) {
+    Float4V v[8];
     bool live[8];
 #pragma unroll
     for (uint32_t u = 0; u < 8; ++u) {
-      const uint32_t q = base + u * kWideBlock + threadIdx.x;
+      const uint32_t q = base + u * kBlock + threadIdx.x;
       live[u] = q < q_end;
-      v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      v[u] = Float4V{0.0f, 0.0f, 0.0f, 0.0f};
       if (live[u]) {
         const uint32_t j = q >> 2, part = q & 3u;
         const uint64_t piece = (uint64_t)j * n_src / n_s;
@@ -187,15 +193,14 @@ __global__ __launch_bounds__(kWideBlock) void sample_hist_kernel(const ClientPar
     }
 #pragma unroll
     for (uint32_t u = 0; u < 8; ++u) {
-      // most sampled magnitudes share a handful of bins: merge equal bins inside the wavefront first
-      wave_hist_add<12>(hist, (__float_as_uint(v[u].x) & 0x7FFFFFFFu) >> kSampleShift, live[u]);
-      wave_hist_add<12>(hist, (__float_as_uint(v[u].y) & 0x7FFFFFFFu) >> kSampleShift, live[u]);
-      wave_hist_add<12>(hist, (__float_as_uint(v[u].z) & 0x7FFFFFFFu) >> kSampleShift, live[u]);
-      wave_hist_add<12>(hist, (__float_as_uint(v[u].w) & 0x7FFFFFFFu) >> kSampleShift, live[u]);
+      if (live[u]) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) atomicAdd(&hist[(__float_as_uint(v[u][c]) & 0x7FFFFFFFu) >> kSampleShift], 1u);
+      }
     }
   }
   __syncthreads();
-  for (uint32_t i = threadIdx.x; i < kSampleBins; i += kWideBlock) {
+  for (uint32_t i = threadIdx.x; i < kSampleBins; i += kBlock) {
     const uint32_t h = hist[i];
     if (h) atomicAdd(&ctl->hist_sample[i], h);
   }
@@ -244,12 +249,12 @@ struct SubTile {
   float v[4][4];
 };
 
-__device__ __forceinline__ void load_subtile(SubTile& t, const float* __restrict__ U, uint32_t sbase, uint32_t lane,
-                                             uint32_t d) {
+__device__ __forceinline__ void load_subtile(SubTile& t, GlobalFloatPtr U, uint32_t sbase, uint32_t lane, uint32_t d) {
   if (sbase + kSubTile <= d) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const float4 q = *reinterpret_cast<const float4*>(U + sbase + j * 256u + lane * 4u);
+      // read once, never again: keep the stream out of the way of what the caches hold
+      const Float4V q = __builtin_nontemporal_load(reinterpret_cast<GlobalFloat4Ptr>(U + sbase + j * 256u + lane * 4u));
       t.v[j][0] = q.x; t.v[j][1] = q.y; t.v[j][2] = q.z; t.v[j][3] = q.w;
     }
   } else {
@@ -262,13 +267,60 @@ __device__ __forceinline__ void load_subtile(SubTile& t, const float* __restrict
   }
 }
 
-// Keeps the coordinates of one sub-tile whose key reaches tau_lo: appended to
-// `out` at *run in position order, counted in the level-1 histogram.  The
-// squares of the others go to *sq; *kmax tracks the largest key seen.
+// Kept coordinates are staged per wavefront in LDS and leave in rows of 64 (one
+// coalesced 512-byte store each); a row also feeds the level-1 histogram.  Loads
+// and stores share one outstanding-operation counter on this hardware, so a
+// wavefront that has just stored must wait for the store's acknowledgement
+// before it can consume its next loads: rows are therefore held back until the
+// stage could not take another four float4 per lane, or the region ends.
+constexpr uint32_t kStageCap = 448;
+constexpr uint32_t kStageFlushAt = kStageCap - 256;  // more staged than this: flush
+
+struct FilterWave {
+  uint2* stage;            // this wavefront's staging rows in LDS
+  uint2* __restrict__ out; // the region's slot in global memory
+  uint32_t* hist;          // the workgroup's level-1 histogram in LDS
+  uint32_t fill;           // staged entries (uniform)
+  uint32_t run;            // entries already written to `out` (uniform)
+};
+
+// LDS accesses of one wavefront complete in order; this keeps the compiler from
+// moving them across the point where lanes read what other lanes wrote.
+__device__ __forceinline__ void wave_lds_fence() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
+
+__device__ __forceinline__ void flush_rows(FilterWave& w, uint32_t lane, bool all) {
+  wave_lds_fence();
+  uint32_t g = 0;
+  for (; g + kWave <= w.fill; g += kWave) {
+    const uint2 e = w.stage[g + lane];
+    w.out[w.run + g + lane] = e;
+    atomicAdd(&w.hist[(e.y & 0x7FFFFFFFu) >> 20], 1u);
+  }
+  const uint32_t left = w.fill - g;  // < 64
+  if (left) {
+    uint2 e = make_uint2(0u, 0u);
+    if (lane < left) e = w.stage[g + lane];
+    if (all) {
+      if (lane < left) {
+        w.out[w.run + g + lane] = e;
+        atomicAdd(&w.hist[(e.y & 0x7FFFFFFFu) >> 20], 1u);
+      }
+      g += left;
+    } else if (g) {  // move the partial row to the front
+      wave_lds_fence();
+      if (lane < left) w.stage[lane] = e;
+    }
+  }
+  w.run += g;
+  w.fill -= g;
+  wave_lds_fence();
+}
+
+// Stages the coordinates of one sub-tile whose key reaches tau_lo, in position
+// order.  The squares of the others go to *sq; *kmax tracks the largest key seen.
 template <bool TAIL>
 __device__ __forceinline__ void filter_subtile(const SubTile& t, uint32_t sbase, uint32_t lane, uint32_t d,
-                                               uint32_t tau_lo, uint2* __restrict__ out, uint32_t* run, double* sq,
-                                               uint32_t* kmax, uint32_t* s_hist) {
+                                               uint32_t tau_lo, FilterWave& w, double* sq, uint32_t* kmax) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const uint32_t e0 = sbase + j * 256u + lane * 4u;
@@ -282,19 +334,20 @@ __device__ __forceinline__ void filter_subtile(const SubTile& t, uint32_t sbase,
       *kmax = max(*kmax, key);
       keep[c] = key >= tau_lo && (!TAIL || e0 + c < d);
       m[c] = __ballot(keep[c]);
-      if (!keep[c]) *sq += (double)t.v[j][c] * (double)t.v[j][c];  // coordinates past d were loaded as 0
+      const double dropped = (double)(keep[c] ? 0.0f : t.v[j][c]);  // coordinates past d were loaded as 0
+      *sq = fma(dropped, dropped, *sq);
     }
     if (m[0] | m[1] | m[2] | m[3]) {
-      uint32_t pos = *run + lanes_below4(m[0], m[1], m[2], m[3]);
+      uint32_t pos = w.fill + lanes_below4(m[0], m[1], m[2], m[3]);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         if (keep[c]) {
-          out[pos] = make_uint2(e0 + c, bits[c]);
-          atomicAdd(&s_hist[(bits[c] & 0x7FFFFFFFu) >> 20], 1u);
+          w.stage[pos] = make_uint2(e0 + c, bits[c]);
           ++pos;
         }
       }
-      *run += (uint32_t)(__popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]));
+      w.fill += (uint32_t)(__popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]));
+      if (w.fill > kStageFlushAt) flush_rows(w, lane, false);
     }
   }
 }
@@ -305,6 +358,7 @@ template <int PASS>
 __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __restrict__ params,
                                                         ClientCtl* __restrict__ ctls, Workspace ws) {
   __shared__ uint32_t s_hist[kL1Bins];
+  __shared__ uint2 s_stage[kWavesPerBlock][kStageCap];
   const uint32_t client = blockIdx.y;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
@@ -316,47 +370,72 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __re
     tau_lo = 0;
   }
   const uint32_t d = ws.d, n_regions = ws.n_regions;
-  const float* __restrict__ U = p.update;
+  GlobalFloatPtr U = (GlobalFloatPtr)p.update;
   const uint32_t lane = lane_id();
   for (uint32_t i = threadIdx.x; i < kL1Bins; i += kBlock) s_hist[i] = 0;
   __syncthreads();
 
   uint32_t kmax = 0;
+  double sq = 0.0;
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
-  for (uint32_t region = blockIdx.x * kWavesPerBlock + wave_id(); region < n_regions; region += n_waves) {
-    const uint32_t rbase = region * kRegion;
-    const uint32_t rend = (d - rbase < kRegion) ? d : rbase + kRegion;
-    uint2* __restrict__ out = ws.cand_sparse + (size_t)client * d + rbase;
-    uint32_t run = 0;
-    double sq = 0.0;
+  FilterWave w;
+  w.stage = s_stage[wave_id()];
+  w.hist = s_hist;
+  // Software pipeline over all sub-tiles of all of this wavefront's regions: the
+  // loads of the next sub-tile (of the next region, at a region's end) are issued
+  // before the current one is processed, so the rare row stores sit behind loads
+  // that are already in flight.
+  uint32_t region = blockIdx.x * kWavesPerBlock + wave_id();
+  if (region < n_regions) {
     SubTile cur, nxt;
-    load_subtile(cur, U, rbase, lane, d);
-    for (uint32_t sbase = rbase; sbase < rend; sbase += kSubTile) {
-      const bool more = sbase + kSubTile < rend;
-      if (more) load_subtile(nxt, U, sbase + kSubTile, lane, d);
-      if (sbase + kSubTile <= d) {
-        filter_subtile<false>(cur, sbase, lane, d, tau_lo, out, &run, &sq, &kmax, s_hist);
-      } else {
-        filter_subtile<true>(cur, sbase, lane, d, tau_lo, out, &run, &sq, &kmax, s_hist);
+    uint32_t sbase = region * kRegion;
+    load_subtile(cur, U, sbase, lane, d);
+    while (true) {
+      const uint32_t rbase = region * kRegion;
+      const uint32_t rend = (d - rbase < kRegion) ? d : rbase + kRegion;
+      if (sbase == rbase) {
+        w.out = ws.cand_sparse + (size_t)client * d + rbase;
+        w.fill = 0;
+        w.run = 0;
       }
-      if (more) cur = nxt;
-    }
-    sq = wave_sum_f64(sq);
-    if (lane == 0) {
-      ws.region_cnt[(size_t)client * n_regions + region] = run;
-      ws.region_sumsq[(size_t)client * n_regions + region] = sq;
+      // where the pipeline goes next
+      const bool last_of_region = sbase + kSubTile >= rend;
+      const uint32_t next_region = last_of_region ? region + n_waves : region;
+      const uint32_t next_sbase = last_of_region ? next_region * kRegion : sbase + kSubTile;
+      const bool more = next_region < n_regions;
+      if (more) load_subtile(nxt, U, next_sbase, lane, d);
+      if (sbase + kSubTile <= d) {
+        filter_subtile<false>(cur, sbase, lane, d, tau_lo, w, &sq, &kmax);
+      } else {
+        filter_subtile<true>(cur, sbase, lane, d, tau_lo, w, &sq, &kmax);
+      }
+      if (last_of_region) {
+        flush_rows(w, lane, true);
+        const double total = wave_sum_f64(sq);
+        sq = 0.0;
+        if (lane == 0) {
+          ws.region_cnt[(size_t)client * n_regions + region] = w.run;
+          ws.region_sumsq[(size_t)client * n_regions + region] = total;
+        }
+      }
+      if (!more) break;
+      cur = nxt;
+      region = next_region;
+      sbase = next_sbase;
     }
   }
   if (kmax >= 0x7F800000u) atomicOr(ws.status, CVLC_DEV_NONFINITE);
   __syncthreads();
-  uint32_t* part = ws.hist1_part + ((size_t)client * gridDim.x + blockIdx.x) * kL1Bins;
-  for (uint32_t i = threadIdx.x; i < kL1Bins; i += kBlock) part[i] = s_hist[i];
+  for (uint32_t i = threadIdx.x; i < kL1Bins; i += kBlock) {
+    const uint32_t h = s_hist[i];
+    if (h) atomicAdd(&ctl->hist_l1[PASS][i], h);
+  }
 }
 
 // ------------------------------------------------------------------ 3. region prefix + selection level 1
 // One workgroup per client.  Turns the region counts into exclusive offsets
-// (the candidates' position-ordered numbering), then adds up the level-1
-// histograms the filter's workgroups stored and locates, for every boundary
+// (the candidates' position-ordered numbering), then reads the level-1
+// histogram the filter's workgroups accumulated and locates, for every boundary
 // Z_r, the bin holding the Z_r-th largest key and the rank left inside it.
 template <int PASS>
 __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams* __restrict__ params,
@@ -389,17 +468,8 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
     return;
   }
 
-  const uint32_t n_parts = ws.filter_blocks;
-  const uint32_t* parts = ws.hist1_part + (size_t)client * n_parts * kL1Bins;
-  // thread t owns bins 2t and 2t+1 while adding up, and reads them back from the top for the scan
-  uint2 sum = make_uint2(0u, 0u);
-  for (uint32_t b = 0; b < n_parts; ++b) {
-    const uint2 h = *reinterpret_cast<const uint2*>(parts + (size_t)b * kL1Bins + 2u * tid);
-    sum.x += h.x;
-    sum.y += h.y;
-  }
-  hist[2u * tid] = sum.x;
-  hist[2u * tid + 1] = sum.y;
+  hist[2u * tid] = ctl->hist_l1[PASS][2u * tid];
+  hist[2u * tid + 1] = ctl->hist_l1[PASS][2u * tid + 1];
   __syncthreads();
   const uint32_t top = kL1Bins - 1 - 2u * tid;
   const uint32_t h0 = hist[top], h1 = hist[top - 1];
@@ -636,15 +706,20 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
   for (uint32_t i = tid; i < used; i += kWideBlock) part[i] = S.hist[i];
 }
 
+// One workgroup per (histogram slot, client): thread t owns digit t.  The
+// partial histograms are added up, a suffix sum from the largest digit gives
+// "keys with digit >= t", and every boundary that shares the slot reads off its
+// digit and the rank left inside it.
 template <int LEVEL>
 __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientParams* __restrict__ params,
                                                                  ClientCtl* __restrict__ ctls, Workspace ws,
                                                                  uint32_t group) {
   __shared__ SlotTable slots;
-  __shared__ uint32_t s_slow[kSlotGroup];
+  __shared__ uint32_t s_ge[kDigitBins + 1];   // keys of the slot with digit >= t
+  __shared__ uint32_t s_digit[kSlotGroup], s_quota[kSlotGroup], s_need[kSlotGroup];
   __shared__ uint32_t s_found;
   __shared__ uint32_t scan_tmp[kWideWaves];
-  const uint32_t client = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+  const uint32_t slot = blockIdx.x, client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   const uint32_t r0 = group * kSlotGroup;
@@ -652,47 +727,31 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   const uint32_t nb = min(p.R - r0, kSlotGroup);
   const uint32_t n_parts = ws.sel_blocks;
   const uint32_t* parts = ws.sel_part + (size_t)client * n_parts * kSlotGroup * kDigitBins;
-  const uint2* ties = ws.tie_list + (size_t)client * kSlotGroup * kTieCap;
   if (tid == 0) build_slots(slots, ctl, r0, nb);
-  if (tid < kSlotGroup) s_slow[tid] = 0;
+  if (tid < kSlotGroup) s_need[tid] = 0;
   __syncthreads();
+  if (slot >= slots.n) return;
 
-  // one wavefront per boundary; lane l owns digits [top-15, top], top = 1023 - 16 l
-  if (wave < nb && slots.leader[wave] != kNoSlot) {
-    const uint32_t r = r0 + wave, slot = slots.leader[wave];
-    const uint32_t top = kDigitBins - 1 - 16u * lane;
-    uint32_t h[16], mine = 0;
-#pragma unroll
-    for (uint32_t i = 0; i < 16; ++i) h[i] = 0;
-    for (uint32_t b = 0; b < n_parts; ++b) {
-      const uint4* src = reinterpret_cast<const uint4*>(&parts[((size_t)b * kSlotGroup + slot) * kDigitBins + top - 15]);
-#pragma unroll
-      for (uint32_t q = 0; q < 4; ++q) {  // src[q] holds digits top-15+4q .. top-12+4q
-        const uint4 w = src[q];
-        h[15 - 4 * q] += w.x; h[14 - 4 * q] += w.y; h[13 - 4 * q] += w.z; h[12 - 4 * q] += w.w;
-      }
-    }
-#pragma unroll
-    for (uint32_t i = 0; i < 16; ++i) mine += h[i];
-    const uint32_t above = wave_incl_scan_u32(mine) - mine;
-    const uint32_t rem = ctl->sel_rem[r];
-    uint32_t need = 0, digit = 0, quota = 0;
-    const bool here = above < rem && rem <= above + mine;
-    if (here) {
-      uint32_t acc = above;
-#pragma unroll
-      for (uint32_t i = 0; i < 16; ++i) {
-        if (quota == 0 && acc + h[i] >= rem) {
-          digit = top - i;
-          quota = rem - acc;  // rank inside the digit class, 1-based
-          need = (LEVEL == 3 && quota < h[i]) ? 1u : 0u;
-        }
-        acc += h[i];
-      }
-    }
-    if (__ballot(here) == 0 && lane == 0) atomicOr(ws.status, CVLC_DEV_INTERNAL);  // histogram short of the rank
-    if (here) {
-      const uint32_t full = (slots.prefix[slot] << 10) | digit;
+  // thread t takes digit 1023 - t, so that the scan runs from the top digit down
+  const uint32_t digit = kDigitBins - 1 - tid;
+  uint32_t h = 0;
+#pragma unroll 8
+  for (uint32_t b = 0; b < n_parts; ++b) h += parts[((size_t)b * kSlotGroup + slot) * kDigitBins + digit];
+  uint32_t total;
+  const uint32_t above = block_excl_scan<kWideWaves>(h, scan_tmp, &total);  // keys with a larger digit
+  s_ge[digit] = above + h;
+  if (tid == 0) s_ge[kDigitBins] = 0;
+  __syncthreads();
+  const uint32_t prefix = slots.prefix[slot];
+  for (uint32_t b = 0; b < nb; ++b) {
+    if (slots.leader[b] != slot) continue;
+    const uint32_t r = r0 + b;
+    const uint32_t rem = ctl->sel_rem[r];  // read by every thread before the owner below rewrites it
+    if (rem > total && tid == 0) atomicOr(ws.status, CVLC_DEV_INTERNAL);  // histogram short of the rank
+    __syncthreads();
+    if (above < rem && rem <= above + h) {  // exactly one thread
+      const uint32_t quota = rem - above;   // rank inside the digit class, 1-based
+      const uint32_t full = (prefix << 10) | digit;
       if (LEVEL == 2) {
         ctl->sel_prefix[r] = full;
         ctl->sel_rem[r] = quota;
@@ -700,17 +759,24 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
         ctl->tau[r] = full;
         ctl->sel_rem[r] = quota;     // tie quota q_r
         ctl->iota[r] = 0xFFFFFFFFu;  // every member of the class is inside unless it straddles Z_r
+        s_digit[b] = digit;
+        s_quota[b] = quota;
+        s_need[b] = quota < h ? 1u : 0u;
       }
     }
-    if (LEVEL == 3) {
-      // the class of equal keys straddles the boundary: find its quota-th member in position order
-      const uint64_t who = __ballot(need != 0);
-      if (who) {
-        const uint32_t src_lane = (uint32_t)__builtin_ctzll(who);
-        const uint32_t w_digit = __shfl(digit, src_lane, 64), w_quota = __shfl(quota, src_lane, 64);
-        const uint32_t kept = ctl->tie_cnt[group][slot];
-        if (kept <= kTieCap) {
-          const uint2* list = ties + slot * kTieCap;
+  }
+  if (LEVEL == 3) {
+    __syncthreads();
+    // a class of equal keys straddles the boundary: find its quota-th member in position order
+    const uint2* list = ws.tie_list + ((size_t)client * kSlotGroup + slot) * kTieCap;
+    const uint32_t kept = ctl->tie_cnt[group][slot];
+    const uint32_t n = ctl->n_cand;
+    const uint2* __restrict__ dense = ws.cand_dense + (size_t)client * ws.d;
+    for (uint32_t b = 0; b < nb; ++b) {
+      if (!s_need[b]) continue;  // uniform
+      const uint32_t r = r0 + b, w_digit = s_digit[b], w_quota = s_quota[b];
+      if (kept <= kTieCap) {
+        if (wave == b % kWideWaves) {
           for (uint32_t e = lane; e < kept; e += kWave) {
             const uint2 me = list[e];
             if (me.y != w_digit) continue;
@@ -721,40 +787,31 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
             }
             if (before + 1 == w_quota) ctl->iota[r] = me.x;
           }
-        } else if (lane == 0) {
-          s_slow[wave] = 1;  // too many to keep aside: walk the whole candidate list below
         }
-      }
-    }
-  }
-  if (LEVEL == 3) {
-    __syncthreads();
-    const uint32_t n = ctl->n_cand;
-    const uint2* __restrict__ dense = ws.cand_dense + (size_t)client * ws.d;
-    for (uint32_t b = 0; b < nb; ++b) {
-      if (!s_slow[b]) continue;
-      const uint32_t r = r0 + b;
-      const uint32_t tau = ctl->tau[r];
-      uint32_t left = ctl->sel_rem[r];
-      __syncthreads();
-      if (tid == 0) s_found = 0;
-      __syncthreads();
-      for (uint32_t base = 0; base < n; base += kWideBlock) {
-        const uint32_t i = base + tid;
-        uint2 e = make_uint2(0u, 0xFFFFFFFFu);
-        if (i < n) e = dense[i];
-        const uint32_t hit = (i < n && (e.y & 0x7FFFFFFFu) == tau) ? 1u : 0u;
-        uint32_t tot;
-        const uint32_t rank = block_excl_scan<kWideWaves>(hit, scan_tmp, &tot);
-        if (hit && rank + 1 == left) {
-          ctl->iota[r] = e.x;
-          s_found = 1;
-        }
+      } else {
+        // too many to keep aside: walk the whole candidate list
+        const uint32_t tau = (prefix << 10) | w_digit;
+        uint32_t left = w_quota;
         __syncthreads();
-        if (s_found || tot >= left) break;
-        left -= tot;
+        if (tid == 0) s_found = 0;
+        __syncthreads();
+        for (uint32_t base = 0; base < n; base += kWideBlock) {
+          const uint32_t i = base + tid;
+          uint2 e = make_uint2(0u, 0xFFFFFFFFu);
+          if (i < n) e = dense[i];
+          const uint32_t hit = (i < n && (e.y & 0x7FFFFFFFu) == tau) ? 1u : 0u;
+          uint32_t tot;
+          const uint32_t rank = block_excl_scan<kWideWaves>(hit, scan_tmp, &tot);
+          if (hit && rank + 1 == left) {
+            ctl->iota[r] = e.x;
+            s_found = 1;
+          }
+          __syncthreads();
+          if (s_found || tot >= left) break;
+          left -= tot;
+        }
+        if (tid == 0 && !s_found) atomicOr(ws.status, CVLC_DEV_INTERNAL);
       }
-      if (tid == 0 && !s_found) atomicOr(ws.status, CVLC_DEV_INTERNAL);
     }
   }
 }
@@ -1147,6 +1204,23 @@ uint32_t sample_rank(uint32_t d, uint32_t k, uint32_t n_sampled) {
   return (uint32_t)want;
 }
 
+// Filter workgroups the current device holds at once, at most kFilterBlocksCap.
+uint32_t filter_resident_blocks() {
+  static uint32_t cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return kFilterBlocksCap / 2;
+  if (cached[dev] == 0) {
+    int cus = 0, per_cu = 0;
+    uint32_t r = kFilterBlocksCap / 2;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, filter_kernel<0>, kBlock, 0) == hipSuccess && cus > 0 &&
+        per_cu > 0)
+      r = (uint32_t)cus * (uint32_t)per_cu;
+    cached[dev] = r > kFilterBlocksCap ? kFilterBlocksCap : r;
+  }
+  return cached[dev];
+}
+
 }  // namespace
 }  // namespace cvlc
 
@@ -1179,12 +1253,11 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   ws.chunk_cnt = reinterpret_cast<uint32_t*>(base + L.chunk_cnt);
   ws.chunk_sumsq = reinterpret_cast<double*>(base + L.chunk_sumsq);
   ws.tie_list = reinterpret_cast<uint2*>(base + L.tie_list);
-  ws.hist1_part = reinterpret_cast<uint32_t*>(base + L.hist1_part);
   ws.sel_part = reinterpret_cast<uint32_t*>(base + L.sel_part);
   ws.d = d;
   ws.n_regions = L.n_regions;
   ws.max_chunks = L.max_chunks;
-  ws.filter_blocks = L.filter_blocks;
+  ws.filter_blocks = filter_blocks_per_client(L.n_regions, n, filter_resident_blocks());
   ws.sel_blocks = L.sel_blocks;
 
   // sample geometry: 64-byte pieces spread evenly; all of them when the vector is short
@@ -1234,19 +1307,19 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
 
   if (any_sampled) {
     StageScope scope(CVLC_STAGE_ENC_SAMPLE, stream);
-    hipLaunchKernelGGL(sample_hist_kernel, dim3(kSampleBlocks, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, n_s,
+    hipLaunchKernelGGL(sample_hist_kernel, dim3(kSampleBlocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, n_s,
                        n_src);
     hipLaunchKernelGGL(sample_walk_kernel, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl);
   }
   {
     StageScope scope(CVLC_STAGE_ENC_FILTER, stream);
-    hipLaunchKernelGGL(filter_kernel<0>, dim3(L.filter_blocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+    hipLaunchKernelGGL(filter_kernel<0>, dim3(ws.filter_blocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
   }
   {
     StageScope scope(CVLC_STAGE_ENC_REFILTER, stream);
     hipLaunchKernelGGL(scan_l1_kernel<0>, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
     if (any_sampled) {  // only clients whose sampled threshold kept too few do anything here
-      hipLaunchKernelGGL(filter_kernel<1>, dim3(L.filter_blocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+      hipLaunchKernelGGL(filter_kernel<1>, dim3(ws.filter_blocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
       hipLaunchKernelGGL(scan_l1_kernel<1>, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
     }
   }
@@ -1259,9 +1332,9 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
     for (uint32_t gr = 0; gr < groups; ++gr) {
       if (gr > 0)
         hipLaunchKernelGGL((select_pass_kernel<2, false>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
-      hipLaunchKernelGGL(select_walk_kernel<2>, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+      hipLaunchKernelGGL(select_walk_kernel<2>, dim3(kSlotGroup, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
       hipLaunchKernelGGL((select_pass_kernel<3, false>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
-      hipLaunchKernelGGL(select_walk_kernel<3>, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+      hipLaunchKernelGGL(select_walk_kernel<3>, dim3(kSlotGroup, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
     }
   }
   uint32_t g_chunk = (2048u + n - 1) / n;
