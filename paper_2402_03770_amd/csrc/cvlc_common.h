@@ -23,7 +23,7 @@ constexpr uint32_t kWave = 64;
 constexpr uint32_t kWavesPerBlock = kBlock / kWave;
 constexpr uint32_t kSubTile = 1024;        // coordinates one wavefront holds in registers (16 per lane)
 constexpr uint32_t kRegion = 8192;         // coordinates one wavefront filters as a unit (8 sub-tiles)
-constexpr uint32_t kChunk = 2048;          // candidates per classify/emit chunk
+constexpr uint32_t kChunkRegions = 8;      // regions per chunk: the unit of the classify/emit passes
 constexpr uint32_t kSampleBins = 4096;     // sample histogram on key >> 19
 constexpr uint32_t kSampleShift = 19;
 constexpr uint32_t kL1Bins = 2048;         // level-1 digit: key >> 20 (8 exponent + 3 mantissa bits)
@@ -58,6 +58,8 @@ struct ClientCtl {
   uint32_t n_cand;           // candidates kept by the filter pass that counts
   uint32_t refilter;         // 1: the sampled threshold kept fewer than k, the keep-all pass must run
   uint32_t pad0;
+  double tail_sumsq;         // energy of the coordinates the filter dropped
+  double seg_sumsq[32];      // energy of every coded group; entry R: candidates below the last boundary (atomic)
   uint32_t tie_cnt[kMaxGroups][16];  // kept-aside class members per (boundary group, histogram slot)
   uint32_t sel_prefix[32];   // key prefix fixed so far for boundary r (0xFFFFFFFF: Z_r = 0)
   uint32_t sel_rem[32];      // rank of the boundary element inside the prefix class, 1-based from the top

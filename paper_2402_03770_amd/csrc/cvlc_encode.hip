@@ -17,16 +17,14 @@
 //                 order; it also counts the level-1 digit (top 11 key bits) of
 //                 what it keeps and sums the squares of what it drops
 //   scan_l1       prefix over the region counts; level-1 bins of the boundaries
-//   select_pass   level 2 (and, fused, gathering the region runs into one dense
-//                 position-ordered candidate list), then level 3: LDS
-//                 histograms of the next 10 key bits of the candidates that
-//                 match a boundary's prefix
+//   select_pass   level 2, then level 3: LDS histograms of the next 10 key bits
+//                 of the candidates that match a boundary's prefix
 //   select_walk   adds up the histograms, fixes the next digit of every
 //                 boundary; after level 3 the exact boundary keys and, where a
 //                 boundary cuts a class of equal magnitudes, the position of
 //                 its last member inside the boundary
-//   classify      per chunk of candidates: group of every candidate, per-group
-//                 count, min/max/sum of squares
+//   count         per chunk (the runs of 8 consecutive regions): group of every
+//                 candidate, per-group count, min/max/sum of squares
 //   layout        prefix of the per-chunk counts, headers, statistics
 //   emit          stochastic rounding (Philox4x32-10) and bit packing
 #include <hip/hip_runtime.h>
@@ -40,11 +38,18 @@ namespace cvlc {
 namespace {
 
 // ------------------------------------------------------------------ workspace layout
+// Per-client, per-group constants of the last stages, written by the layout kernel.
+struct GroupInfo {
+  uint32_t payload[32];  // first stream word of the group's records
+  uint32_t P[32], W[32], y[32];
+  float m[32], inv[32];  // smallest value and reciprocal centroid spacing
+};
+
 struct EncodeLayout {
-  size_t status, ctl, params, region_cnt, region_off, region_sumsq, cand_sparse, cand_dense, chunk_cnt, chunk_sumsq,
+  size_t status, ctl, params, region_cnt, region_off, region_sumsq, cand_idx, cand_val, chunk_cnt, group_info,
       tie_list, sel_part, total;
   size_t zero_bytes;        // [status, params) is cleared at the start of a call
-  uint32_t n_regions, max_chunks;
+  uint32_t n_regions, n_chunks;
   uint32_t sel_blocks;      // workgroups per client in a level-2/3 selection pass
 };
 
@@ -64,7 +69,7 @@ uint32_t filter_blocks_per_client(uint32_t n_regions, uint32_t n, uint32_t resid
 EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   EncodeLayout L;
   L.n_regions = (uint32_t)(((uint64_t)d + kRegion - 1) / kRegion);
-  L.max_chunks = (uint32_t)(((uint64_t)d + kChunk - 1) / kChunk);
+  L.n_chunks = (L.n_regions + kChunkRegions - 1) / kChunkRegions;
   {
     uint32_t b = (512u + n - 1) / n;
     L.sel_blocks = b < 2 ? 2u : (b > 32 ? 32u : b);
@@ -77,10 +82,10 @@ EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   L.region_cnt = off; off = align256(off + (size_t)n * L.n_regions * sizeof(uint32_t));
   L.region_off = off; off = align256(off + (size_t)n * (L.n_regions + 1) * sizeof(uint32_t));
   L.region_sumsq = off; off = align256(off + (size_t)n * L.n_regions * sizeof(double));
-  L.cand_sparse = off; off = align256(off + (size_t)n * d * sizeof(uint2));
-  L.cand_dense = off; off = align256(off + (size_t)n * d * sizeof(uint2));
-  L.chunk_cnt = off; off = align256(off + (size_t)n * L.max_chunks * 32 * sizeof(uint32_t));
-  L.chunk_sumsq = off; off = align256(off + (size_t)n * L.max_chunks * 32 * sizeof(double));
+  L.cand_idx = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
+  L.cand_val = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
+  L.chunk_cnt = off; off = align256(off + (size_t)n * L.n_chunks * 32 * sizeof(uint32_t));
+  L.group_info = off; off = align256(off + (size_t)n * sizeof(GroupInfo));
   L.tie_list = off; off = align256(off + (size_t)n * kSlotGroup * kTieCap * sizeof(uint2));
   L.sel_part = off; off = align256(off + (size_t)n * L.sel_blocks * kSlotGroup * kDigitBins * sizeof(uint32_t));
   L.total = off;
@@ -94,13 +99,13 @@ struct Workspace {  // device pointers into the caller's workspace
   uint32_t* region_cnt;
   uint32_t* region_off;
   double* region_sumsq;
-  uint2* cand_sparse;  // (position, value bits) runs at the front of every region's slot
-  uint2* cand_dense;   // the same candidates, contiguous per client, in position order
+  uint32_t* cand_idx;  // positions of the kept coordinates: a run at the front of every region's slot
+  uint32_t* cand_val;  // their value bits, same layout
   uint32_t* chunk_cnt;
-  double* chunk_sumsq;
+  GroupInfo* group_info;
   uint2* tie_list;
   uint32_t* sel_part;
-  uint32_t d, n_regions, max_chunks, filter_blocks, sel_blocks;
+  uint32_t d, n_regions, n_chunks, filter_blocks, sel_blocks;
 };
 
 // ------------------------------------------------------------------ parameter upload
@@ -278,7 +283,8 @@ constexpr uint32_t kStageFlushAt = kStageCap - 256;  // more staged than this: f
 
 struct FilterWave {
   uint2* stage;            // this wavefront's staging rows in LDS
-  uint2* __restrict__ out; // the region's slot in global memory
+  uint32_t* __restrict__ out_idx;  // the region's slot in global memory: positions
+  uint32_t* __restrict__ out_val;  // ... and value bits
   uint32_t* hist;          // the workgroup's level-1 histogram in LDS
   uint32_t fill;           // staged entries (uniform)
   uint32_t run;            // entries already written to `out` (uniform)
@@ -293,7 +299,8 @@ __device__ __forceinline__ void flush_rows(FilterWave& w, uint32_t lane, bool al
   uint32_t g = 0;
   for (; g + kWave <= w.fill; g += kWave) {
     const uint2 e = w.stage[g + lane];
-    w.out[w.run + g + lane] = e;
+    w.out_idx[w.run + g + lane] = e.x;
+    w.out_val[w.run + g + lane] = e.y;
     atomicAdd(&w.hist[(e.y & 0x7FFFFFFFu) >> 20], 1u);
   }
   const uint32_t left = w.fill - g;  // < 64
@@ -302,7 +309,8 @@ __device__ __forceinline__ void flush_rows(FilterWave& w, uint32_t lane, bool al
     if (lane < left) e = w.stage[g + lane];
     if (all) {
       if (lane < left) {
-        w.out[w.run + g + lane] = e;
+        w.out_idx[w.run + g + lane] = e.x;
+        w.out_val[w.run + g + lane] = e.y;
         atomicAdd(&w.hist[(e.y & 0x7FFFFFFFu) >> 20], 1u);
       }
       g += left;
@@ -394,7 +402,8 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __re
       const uint32_t rbase = region * kRegion;
       const uint32_t rend = (d - rbase < kRegion) ? d : rbase + kRegion;
       if (sbase == rbase) {
-        w.out = ws.cand_sparse + (size_t)client * d + rbase;
+        w.out_idx = ws.cand_idx + (size_t)client * d + rbase;
+        w.out_val = ws.cand_val + (size_t)client * d + rbase;
         w.fill = 0;
         w.run = 0;
       }
@@ -518,11 +527,12 @@ struct SlotTable {
   uint32_t n;
 };
 
-// Slots in order of first appearance among the group's boundaries.  Run by one thread.
-__device__ void build_slots(SlotTable& st, const ClientCtl* ctl, uint32_t r0, uint32_t nb) {
+// Slots in order of first appearance among the group's boundaries, whose
+// prefixes are in pre[0..nb).  Run by one thread.
+__device__ void build_slots(SlotTable& st, const uint32_t* pre_of, uint32_t nb) {
   uint32_t ns = 0;
   for (uint32_t b = 0; b < nb; ++b) {
-    const uint32_t pre = ctl->sel_prefix[r0 + b];
+    const uint32_t pre = pre_of[b];
     uint32_t slot = kNoSlot;
     if (pre != 0xFFFFFFFFu) {
       for (uint32_t q = 0; q < ns; ++q)
@@ -543,6 +553,7 @@ struct SelectShared {
   uint32_t bin_slot[kL1Bins / 8];                // top 11 key bits -> 1 + (level 2: slot, level 3: bin id), 4 bits each
   uint32_t digit_map[kSlotGroup][kDigitBins / 32];  // level 3: second digits present per bin id
   uint32_t tie_full[kSlotGroup];                 // this workgroup has seen the slot's kept-aside list overflow
+  uint32_t pre[kSlotGroup];                      // the group's boundary prefixes
 
   __device__ __forceinline__ uint32_t bin_tag(uint32_t top11) const {
     return (bin_slot[top11 >> 3] >> ((top11 & 7u) * 4u)) & 15u;
@@ -554,11 +565,11 @@ struct SelectShared {
 static_assert(kSlotGroup <= 15, "bin tags are 4 bits wide");
 static_assert(sizeof(SelectShared) <= 65536, "SelectShared must fit the 64 KB static LDS limit");
 
-// Counts one candidate per lane (`live` lanes only).  Must be reached by all
-// lanes of the wavefront.
+// Counts one candidate per lane (`live` lanes only); idx_at points at its
+// position.  Must be reached by all lanes of the wavefront.
 template <int LEVEL>
-__device__ __forceinline__ void select_count(SelectShared& S, uint32_t key, uint32_t idx, bool live, uint32_t* tie_cnt,
-                                             uint2* __restrict__ ties) {
+__device__ __forceinline__ void select_count(SelectShared& S, uint32_t key, const uint32_t* __restrict__ idx_at,
+                                             bool live, uint32_t* tie_cnt, uint2* __restrict__ ties) {
   uint32_t q = kNoSlot;
   if (live) {
     const uint32_t tag = S.bin_tag(key >> 20);
@@ -591,28 +602,59 @@ __device__ __forceinline__ void select_count(SelectShared& S, uint32_t key, uint
       base = __builtin_amdgcn_readlane(base, leader);
       if (mine) {
         const uint32_t pos = base + lanes_below(peers);
-        if (pos < kTieCap) ties[qs * kTieCap + pos] = make_uint2(idx, key & (kDigitBins - 1));
+        if (pos < kTieCap) ties[qs * kTieCap + pos] = make_uint2(*idx_at, key & (kDigitBins - 1));  // position is read only here
       }
       todo &= ~peers;
     }
   }
 }
 
-// SPARSE: read the candidates from the filter's region runs and also copy them
-// to the dense list (first pass after a filter); otherwise read the dense list.
-template <int LEVEL, bool SPARSE>
+// ---- walking the candidates
+// A chunk is kChunkRegions consecutive regions; its candidates, in position
+// order, are the regions' runs one after the other.  start[t] is the chunk-local
+// number of the first candidate of region t's run, start[kChunkRegions] the
+// chunk's size.
+struct ChunkMap {
+  uint32_t start[kChunkRegions + 1];
+};
+
+// Filled by threads 0..kChunkRegions of the workgroup (a barrier must follow).
+__device__ __forceinline__ void load_chunk_map(ChunkMap& m, const uint32_t* __restrict__ region_off, uint32_t n_regions,
+                                               uint32_t c, uint32_t t) {
+  if (t <= kChunkRegions) {
+    const uint32_t first = c * kChunkRegions;
+    const uint32_t r = first + t < n_regions ? first + t : n_regions;
+    m.start[t] = region_off[r] - region_off[first];
+  }
+}
+
+// Index into the region-slot arrays of the chunk's i-th candidate (i < size).
+__device__ __forceinline__ uint32_t chunk_slot(const ChunkMap& m, uint32_t c, uint32_t i) {
+  static_assert(kChunkRegions == 8, "three-step search");
+  uint32_t t = (i >= m.start[4]) ? 4u : 0u;
+  t += (i >= m.start[t + 2]) ? 2u : 0u;
+  t += (i >= m.start[t + 1]) ? 1u : 0u;
+  return (c * kChunkRegions + t) * kRegion + (i - m.start[t]);
+}
+
+constexpr uint32_t kMapBatch = 16;  // chunk maps a selection workgroup holds at a time
+
+template <int LEVEL>
 __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientParams* __restrict__ params,
                                                                  ClientCtl* __restrict__ ctls, Workspace ws,
                                                                  uint32_t group) {
   __shared__ SelectShared S;
-  const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+  __shared__ ChunkMap s_map[kMapBatch];
+  static_assert(sizeof(SelectShared) + sizeof(ChunkMap) * kMapBatch <= 65536, "static LDS limit");
+  const uint32_t client = blockIdx.y, tid = threadIdx.x;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   const uint32_t r0 = group * kSlotGroup;
-  const uint32_t nb = p.R > r0 ? min(p.R - r0, kSlotGroup) : 0u;
-  if (nb == 0 && !SPARSE) return;  // this client has no boundary in the group
-  const uint32_t d = ws.d;
-  uint2* __restrict__ dense = ws.cand_dense + (size_t)client * d;
+  if (p.R <= r0) return;  // this client has no boundary in the group
+  const uint32_t nb = min(p.R - r0, kSlotGroup);
+  const uint32_t* __restrict__ val = ws.cand_val + (size_t)client * ws.d;
+  const uint32_t* __restrict__ idx = ws.cand_idx + (size_t)client * ws.d;
+  const uint32_t* __restrict__ region_off = ws.region_off + (size_t)client * (ws.n_regions + 1);
   uint2* ties = ws.tie_list + (size_t)client * kSlotGroup * kTieCap;
   uint32_t* tie_cnt = ctl->tie_cnt[group];
 
@@ -620,9 +662,10 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
   for (uint32_t i = tid; i < kL1Bins / 8; i += kWideBlock) S.bin_slot[i] = 0;
   for (uint32_t i = tid; i < kSlotGroup * (kDigitBins / 32); i += kWideBlock) (&S.digit_map[0][0])[i] = 0;
   if (tid < kSlotGroup) S.tie_full[tid] = 0;
+  if (tid < nb) S.pre[tid] = ctl->sel_prefix[r0 + tid];
   __syncthreads();
   if (tid == 0) {
-    build_slots(S.slots, ctl, r0, nb);
+    build_slots(S.slots, S.pre, nb);
     uint32_t nbins = 0;
     for (uint32_t q = 0; q < S.slots.n; ++q) {
       const uint32_t pre = S.slots.prefix[q];
@@ -635,72 +678,45 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
       }
     }
   }
-  __syncthreads();
 
-  if (SPARSE) {
-    const uint32_t n_regions = ws.n_regions;
-    const uint32_t* cnt = ws.region_cnt + (size_t)client * n_regions;
-    const uint32_t* off = ws.region_off + (size_t)client * (n_regions + 1);
-    const uint2* __restrict__ sparse = ws.cand_sparse + (size_t)client * d;
-    const uint32_t wpc = gridDim.x * kWideWaves;  // wavefronts per client
-    // a wavefront takes regions gw, gw + wpc, ...; their counts and offsets are fetched 64 at a time
-    for (uint32_t first = blockIdx.x * kWideWaves + wave; first < n_regions; first += wpc * kWave) {
-      const uint32_t mine = first + lane * wpc;
-      uint32_t c = 0, o = 0;
-      if (mine < n_regions) {
-        c = cnt[mine];
-        o = off[mine];
-      }
-      const uint32_t left = (n_regions - first + wpc - 1) / wpc;
-      const uint32_t nr = left < kWave ? left : kWave;
-      for (uint32_t l = 0; l < nr; ++l) {
-        const uint32_t rc = __builtin_amdgcn_readlane(c, l), ro = __builtin_amdgcn_readlane(o, l);
-        const uint2* __restrict__ src = sparse + (size_t)(first + l * wpc) * kRegion;
-        uint2* __restrict__ dst = dense + ro;
-        for (uint32_t b = 0; b < rc; b += kWave * 4u) {
-          uint2 e[4];
-          bool live[4];
+  // this workgroup's chunks: blockIdx.x, blockIdx.x + gridDim.x, ...; their maps are fetched kMapBatch at a time
+  const uint32_t n_chunks = ws.n_chunks;
+  for (uint32_t c0 = blockIdx.x; c0 < n_chunks; c0 += gridDim.x * kMapBatch) {
+    __syncthreads();
+    {
+      const uint32_t which = tid / 16u, t = tid % 16u;
+      const uint32_t c = c0 + which * gridDim.x;
+      if (which < kMapBatch && c < n_chunks) load_chunk_map(s_map[which], region_off, ws.n_regions, c, t);
+    }
+    __syncthreads();
+    for (uint32_t which = 0; which < kMapBatch; ++which) {
+      const uint32_t c = c0 + which * gridDim.x;
+      if (c >= n_chunks) break;
+      const ChunkMap& m = s_map[which];
+      const uint32_t size = m.start[kChunkRegions];
+      for (uint32_t base = 0; base < size; base += kWideBlock * 4u) {
+        uint32_t v[4], slot[4];
+        bool live[4];
 #pragma unroll
-          for (uint32_t u = 0; u < 4; ++u) {
-            const uint32_t i = b + u * kWave + lane;
-            live[u] = i < rc;
-            e[u] = make_uint2(0u, 0u);
-            if (live[u]) e[u] = src[i];
-          }
-#pragma unroll
-          for (uint32_t u = 0; u < 4; ++u) {
-            if (b + u * kWave >= rc) break;  // uniform
-            if (live[u]) dst[b + u * kWave + lane] = e[u];
-            if (nb) select_count<LEVEL>(S, e[u].y & 0x7FFFFFFFu, e[u].x, live[u], tie_cnt, ties);
+        for (uint32_t u = 0; u < 4; ++u) {
+          const uint32_t i = base + u * kWideBlock + tid;
+          live[u] = i < size;
+          slot[u] = 0;
+          v[u] = 0;
+          if (live[u]) {
+            slot[u] = chunk_slot(m, c, i);
+            v[u] = val[slot[u]];
           }
         }
-      }
-    }
-  } else {
-    const uint32_t n = ctl->n_cand;
-    const uint32_t span = (uint32_t)(((uint64_t)n + gridDim.x - 1) / gridDim.x);
-    const uint64_t begin64 = (uint64_t)blockIdx.x * span;
-    const uint32_t begin = (uint32_t)(begin64 < n ? begin64 : n);
-    const uint32_t end = (uint32_t)(begin64 + span < n ? begin64 + span : n);
-    for (uint32_t base = begin; base < end; base += kWideBlock * 8u) {
-      uint2 e[8];
-      bool live[8];
 #pragma unroll
-      for (uint32_t u = 0; u < 8; ++u) {
-        const uint32_t i = base + u * kWideBlock + tid;
-        live[u] = i < end;
-        e[u] = make_uint2(0u, 0u);
-        if (live[u]) e[u] = dense[i];
-      }
-#pragma unroll
-      for (uint32_t u = 0; u < 8; ++u) {
-        if (base + u * kWideBlock + wave * kWave >= end) break;  // uniform per wavefront
-        select_count<LEVEL>(S, e[u].y & 0x7FFFFFFFu, e[u].x, live[u], tie_cnt, ties);
+        for (uint32_t u = 0; u < 4; ++u) {
+          if (base + u * kWideBlock >= size) break;  // uniform
+          select_count<LEVEL>(S, v[u] & 0x7FFFFFFFu, idx + slot[u], live[u], tie_cnt, ties);
+        }
       }
     }
   }
   __syncthreads();
-  if (nb == 0) return;
   uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * kSlotGroup * kDigitBins;
   const uint32_t used = S.slots.n * kDigitBins;
   for (uint32_t i = tid; i < used; i += kWideBlock) part[i] = S.hist[i];
@@ -715,8 +731,7 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
                                                                  ClientCtl* __restrict__ ctls, Workspace ws,
                                                                  uint32_t group) {
   __shared__ SlotTable slots;
-  __shared__ uint32_t s_ge[kDigitBins + 1];   // keys of the slot with digit >= t
-  __shared__ uint32_t s_digit[kSlotGroup], s_quota[kSlotGroup], s_need[kSlotGroup];
+  __shared__ uint32_t s_digit[kSlotGroup], s_quota[kSlotGroup], s_need[kSlotGroup], s_pre[kSlotGroup];
   __shared__ uint32_t s_found;
   __shared__ uint32_t scan_tmp[kWideWaves];
   const uint32_t slot = blockIdx.x, client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
@@ -727,8 +742,10 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   const uint32_t nb = min(p.R - r0, kSlotGroup);
   const uint32_t n_parts = ws.sel_blocks;
   const uint32_t* parts = ws.sel_part + (size_t)client * n_parts * kSlotGroup * kDigitBins;
-  if (tid == 0) build_slots(slots, ctl, r0, nb);
+  if (tid < nb) s_pre[tid] = ctl->sel_prefix[r0 + tid];
   if (tid < kSlotGroup) s_need[tid] = 0;
+  __syncthreads();
+  if (tid == 0) build_slots(slots, s_pre, nb);
   __syncthreads();
   if (slot >= slots.n) return;
 
@@ -739,9 +756,6 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   for (uint32_t b = 0; b < n_parts; ++b) h += parts[((size_t)b * kSlotGroup + slot) * kDigitBins + digit];
   uint32_t total;
   const uint32_t above = block_excl_scan<kWideWaves>(h, scan_tmp, &total);  // keys with a larger digit
-  s_ge[digit] = above + h;
-  if (tid == 0) s_ge[kDigitBins] = 0;
-  __syncthreads();
   const uint32_t prefix = slots.prefix[slot];
   for (uint32_t b = 0; b < nb; ++b) {
     if (slots.leader[b] != slot) continue;
@@ -770,8 +784,9 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
     // a class of equal keys straddles the boundary: find its quota-th member in position order
     const uint2* list = ws.tie_list + ((size_t)client * kSlotGroup + slot) * kTieCap;
     const uint32_t kept = ctl->tie_cnt[group][slot];
-    const uint32_t n = ctl->n_cand;
-    const uint2* __restrict__ dense = ws.cand_dense + (size_t)client * ws.d;
+    const uint32_t* __restrict__ val = ws.cand_val + (size_t)client * ws.d;
+    const uint32_t* __restrict__ idx = ws.cand_idx + (size_t)client * ws.d;
+    const uint32_t* __restrict__ region_cnt = ws.region_cnt + (size_t)client * ws.n_regions;
     for (uint32_t b = 0; b < nb; ++b) {
       if (!s_need[b]) continue;  // uniform
       const uint32_t r = r0 + b, w_digit = s_digit[b], w_quota = s_quota[b];
@@ -789,26 +804,27 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
           }
         }
       } else {
-        // too many to keep aside: walk the whole candidate list
+        // too many to keep aside: walk all the runs in position order
         const uint32_t tau = (prefix << 10) | w_digit;
         uint32_t left = w_quota;
         __syncthreads();
         if (tid == 0) s_found = 0;
         __syncthreads();
-        for (uint32_t base = 0; base < n; base += kWideBlock) {
-          const uint32_t i = base + tid;
-          uint2 e = make_uint2(0u, 0xFFFFFFFFu);
-          if (i < n) e = dense[i];
-          const uint32_t hit = (i < n && (e.y & 0x7FFFFFFFu) == tau) ? 1u : 0u;
-          uint32_t tot;
-          const uint32_t rank = block_excl_scan<kWideWaves>(hit, scan_tmp, &tot);
-          if (hit && rank + 1 == left) {
-            ctl->iota[r] = e.x;
-            s_found = 1;
+        for (uint32_t region = 0; region < ws.n_regions && !s_found; ++region) {
+          const uint32_t cnt = region_cnt[region];
+          for (uint32_t base = 0; base < cnt; base += kWideBlock) {
+            const uint32_t i = base + tid;
+            const uint32_t hit = (i < cnt && (val[(size_t)region * kRegion + i] & 0x7FFFFFFFu) == tau) ? 1u : 0u;
+            uint32_t tot;
+            const uint32_t rank = block_excl_scan<kWideWaves>(hit, scan_tmp, &tot);
+            if (hit && rank + 1 == left) {
+              ctl->iota[r] = idx[(size_t)region * kRegion + i];
+              s_found = 1;
+            }
+            __syncthreads();
+            if (s_found) break;
+            left -= tot;
           }
-          __syncthreads();
-          if (s_found || tot >= left) break;
-          left -= tot;
         }
         if (tid == 0 && !s_found) atomicOr(ws.status, CVLC_DEV_INTERNAL);
       }
@@ -816,7 +832,7 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   }
 }
 
-// ------------------------------------------------------------------ classification
+// ------------------------------------------------------------------ 5. classification of the candidates
 struct Thresholds {  // group boundaries in LDS
   uint32_t tau[32];
   uint32_t iota[32];
@@ -832,147 +848,300 @@ __device__ __forceinline__ void load_thresholds(Thresholds& t, const ClientCtl* 
 
 // Group of a candidate, 0-based: the first boundary r whose top-Z_r set holds
 // it (key above tau_r, or equal with position <= iota_r); R if none (dropped).
-// Membership is monotone in r, so a binary search suffices.
-__device__ __forceinline__ uint32_t classify(const Thresholds& t, uint32_t R, uint32_t key, uint32_t idx) {
-  uint32_t lo = 0, hi = R;  // answer in [lo, hi]
-  while (lo < hi) {
-    const uint32_t mid = (lo + hi) >> 1;
-    const uint32_t tau = t.tau[mid];
-    const bool inside = key > tau || (key == tau && idx <= t.iota[mid]);
-    if (inside) hi = mid; else lo = mid + 1;
+// tau is non-increasing in r, so the first r with key > tau_r is the number of
+// boundaries with tau_r >= key; the thresholds are read at a uniform LDS address
+// (a broadcast) once for all of a lane's N candidates.  The position is only
+// needed (and only read) when the key equals a boundary key.
+template <uint32_t N>
+__device__ __forceinline__ void classify_keys(const Thresholds& t, uint32_t R, const uint32_t (&key)[N],
+                                              uint32_t (&grp)[N]) {
+#pragma unroll
+  for (uint32_t j = 0; j < N; ++j) grp[j] = 0;
+  for (uint32_t r = 0; r < R; ++r) {
+    const uint32_t tau = t.tau[r];
+#pragma unroll
+    for (uint32_t j = 0; j < N; ++j) grp[j] += (key[j] <= tau) ? 1u : 0u;
   }
-  return lo;
 }
 
-// ------------------------------------------------------------------ 6. classify + statistics
-// Per chunk of kChunk candidates: count, min, max, sum of squares of every
-// group (index R collects the candidates that end up dropped).  Also clears the
-// stream buffer, which the emit pass ORs records into.
-__global__ __launch_bounds__(kBlock) void classify_kernel(const ClientParams* __restrict__ params,
-                                                          ClientCtl* __restrict__ ctls, Workspace ws) {
+// Second step for a key that equals the boundary key just above its group:
+// boundaries with that key decide by position.
+__device__ __forceinline__ uint32_t classify_tie(const Thresholds& t, uint32_t key, uint32_t g,
+                                                 const uint32_t* __restrict__ idx_at) {
+  if (g > 0 && t.tau[g - 1] == key) {
+    const uint32_t idx = *idx_at;
+    while (g > 0 && t.tau[g - 1] == key && idx <= t.iota[g - 1]) --g;
+  }
+  return g;
+}
+
+constexpr uint32_t kNoGroup = 0xFFFFFFFFu;
+constexpr uint32_t kEmitBlock = 512;                    // threads of a count/emit workgroup
+constexpr uint32_t kEmitWaves = kEmitBlock / kWave;
+constexpr uint32_t kPerLane = 8;                        // candidates per lane per sweep
+constexpr uint32_t kSweep = kEmitBlock * kPerLane;      // candidates per sweep (4096)
+constexpr uint32_t kWaveSpan = kSweep / kEmitWaves;     // consecutive candidates one wavefront takes per sweep
+
+// Lanes that hold a candidate of the caller's group (5-bit group id); lanes
+// with g == kNoGroup match nobody.  Must be reached by the whole wavefront.
+__device__ __forceinline__ uint64_t same_group_lanes(uint32_t g) {
+  uint64_t same = __ballot(g != kNoGroup);
+#pragma unroll
+  for (int bit = 0; bit < 5; ++bit) {
+    const uint64_t set = __ballot((g >> bit) & 1u);
+    same &= ((g >> bit) & 1u) ? set : ~set;
+  }
+  return same;
+}
+
+// What a sweep records per candidate: its group and where it stands among the
+// candidates of the same group in its row of 64.
+__device__ __forceinline__ uint32_t row_pack(uint32_t grp, uint32_t below, uint32_t peers, bool leader) {
+  return grp | (below << 8) | (peers << 16) | (leader ? 1u << 24 : 0u);  // grp <= 31; below < 64; peers <= 64
+}
+__device__ __forceinline__ uint32_t row_group(uint32_t r) { return r & 0xFFu; }     // 0xFF: no candidate
+__device__ __forceinline__ uint32_t row_below(uint32_t r) { return (r >> 8) & 0xFFu; }
+__device__ __forceinline__ uint32_t row_peers(uint32_t r) { return (r >> 16) & 0xFFu; }
+__device__ __forceinline__ bool row_leader(uint32_t r) { return (r >> 24) & 1u; }
+constexpr uint32_t kRowNone = 0xFFu;
+
+// One sweep over a chunk: candidates [first, first + kSweep) in position order
+// (wavefront, j, lane).  Loads the value bits, classifies, and adds the
+// wavefront's group sizes to wcnt[0..R] (this wavefront's own LDS row; group R
+// collects what is dropped).  slot[j] is the candidate's place in the region-slot
+// arrays, row[j] its row_pack().
+__device__ __forceinline__ void classify_sweep(const Thresholds& thr, uint32_t R, const ChunkMap& m, uint32_t c,
+                                               uint32_t first, const uint32_t* __restrict__ val,
+                                               const uint32_t* __restrict__ idx, uint32_t (&slot)[kPerLane],
+                                               uint32_t (&v)[kPerLane], uint32_t (&row)[kPerLane],
+                                               volatile uint32_t* wcnt) {
+  const uint32_t lane = lane_id(), size = m.start[kChunkRegions];
+  const uint32_t mine = first + (threadIdx.x / kWave) * kWaveSpan + lane;
+#pragma unroll
+  for (uint32_t j = 0; j < kPerLane; ++j) {
+    const uint32_t i = mine + j * kWave;
+    slot[j] = 0;
+    v[j] = 0;
+    if (i < size) {
+      slot[j] = chunk_slot(m, c, i);
+      v[j] = val[slot[j]];
+    }
+  }
+  uint32_t key[kPerLane], grp[kPerLane];
+#pragma unroll
+  for (uint32_t j = 0; j < kPerLane; ++j) key[j] = v[j] & 0x7FFFFFFFu;
+  classify_keys<kPerLane>(thr, R, key, grp);
+#pragma unroll
+  for (uint32_t j = 0; j < kPerLane; ++j) {
+    const uint32_t i = mine + j * kWave;
+    row[j] = kRowNone;
+    if (i - lane >= size) continue;  // the whole row lies past the chunk's end (uniform)
+    const uint32_t g = i < size ? classify_tie(thr, key[j], grp[j], idx + slot[j]) : kNoGroup;
+    const uint64_t same = same_group_lanes(g);
+    if (g != kNoGroup) {
+      const uint32_t peers = (uint32_t)__popcll(same);
+      const bool leader = lane == (uint32_t)__builtin_ctzll(same);
+      row[j] = row_pack(g, lanes_below(same), peers, leader);
+      if (leader) wcnt[g] += peers;
+    }
+  }
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor(v, o, 64));
+  return v;
+}
+
+// ------------------------------------------------------------------ 6. group counts and statistics
+// One workgroup per chunk: the number of candidates of every group in the chunk
+// (for the records' places in the stream), and every group's min, max and sum
+// of squares.  Counts and statistics are kept in LDS columns private to a lane
+// id, so that the LDS atomics of one instruction never collide; the counts are
+// reduced per chunk, the statistics once.
+__global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* __restrict__ params,
+                                                           ClientCtl* __restrict__ ctls, Workspace ws) {
   __shared__ Thresholds thr;
-  __shared__ uint32_t s_cnt[32], s_max[32], s_negmin[32];
-  __shared__ double s_sq[32];
-  const uint32_t client = blockIdx.y;
+  __shared__ ChunkMap map[2];
+  __shared__ uint32_t s_cnt[33][kWave];  // group sizes of the current chunk, per lane id
+  __shared__ uint32_t s_max[33][kWave], s_negmin[33][kWave];
+  __shared__ double s_sq[33][kWave];
+  const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  const uint32_t n = ctl->n_cand, R = p.R;
-  const uint2* __restrict__ cand = ws.cand_dense + (size_t)client * ws.d;
-
-  for (uint32_t w = blockIdx.x * kBlock + threadIdx.x; w < p.total_words; w += gridDim.x * kBlock) p.stream[w] = 0;
-
+  const uint32_t R = p.R, n_chunks = ws.n_chunks;
+  const uint32_t* __restrict__ val = ws.cand_val + (size_t)client * ws.d;
+  const uint32_t* __restrict__ idx = ws.cand_idx + (size_t)client * ws.d;
+  const uint32_t* __restrict__ region_off = ws.region_off + (size_t)client * (ws.n_regions + 1);
   load_thresholds(thr, ctl, R);
-  const uint32_t n_chunks = (n + kChunk - 1) / kChunk;
-  for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+  if (blockIdx.x < n_chunks) load_chunk_map(map[0], region_off, ws.n_regions, blockIdx.x, tid);
+  for (uint32_t i = tid; i < 33 * kWave; i += kEmitBlock) {
+    (&s_max[0][0])[i] = 0;
+    (&s_negmin[0][0])[i] = 0;
+    (&s_sq[0][0])[i] = 0.0;
+  }
+  uint32_t cur = 0;
+  for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x, cur ^= 1u) {
+    for (uint32_t i = tid; i < 33 * kWave; i += kEmitBlock) (&s_cnt[0][0])[i] = 0;
     __syncthreads();
-    if (threadIdx.x < 32) { s_cnt[threadIdx.x] = 0; s_max[threadIdx.x] = 0; s_negmin[threadIdx.x] = 0; s_sq[threadIdx.x] = 0.0; }
-    __syncthreads();
-    for (uint32_t j = 0; j < kChunk / kBlock; ++j) {
-      const uint32_t i = c * kChunk + wave_id() * (kChunk / kWavesPerBlock) + j * kWave + lane_id();
-      if (i < n) {
-        const uint2 e = cand[i];
-        const float x = __uint_as_float(e.y);
-        const uint32_t g = classify(thr, R, e.y & 0x7FFFFFFFu, e.x);
-        atomicAdd(&s_cnt[g], 1u);
-        atomicAdd(&s_sq[g], (double)x * (double)x);
-        const uint32_t o = ordered_bits(x);
-        atomicMax(&s_max[g], o);
-        atomicMax(&s_negmin[g], ~o);
+    // the next chunk's map travels while this one is worked on
+    if (c + gridDim.x < n_chunks) load_chunk_map(map[cur ^ 1u], region_off, ws.n_regions, c + gridDim.x, tid);
+    const ChunkMap& m = map[cur];
+    const uint32_t size = m.start[kChunkRegions];
+    for (uint32_t first = 0; first < size; first += kSweep) {
+      if (first + wave * kWaveSpan >= size) break;  // nothing left for this wavefront (uniform)
+      const uint32_t mine = first + wave * kWaveSpan + lane;
+      uint32_t slot[kPerLane], v[kPerLane], key[kPerLane], grp[kPerLane];
+#pragma unroll
+      for (uint32_t j = 0; j < kPerLane; ++j) {
+        const uint32_t i = mine + j * kWave;
+        slot[j] = 0;
+        v[j] = 0;
+        if (i < size) {
+          slot[j] = chunk_slot(m, c, i);
+          v[j] = val[slot[j]];
+        }
+        key[j] = v[j] & 0x7FFFFFFFu;
+      }
+      classify_keys<kPerLane>(thr, R, key, grp);
+#pragma unroll
+      for (uint32_t j = 0; j < kPerLane; ++j) {
+        if (mine + j * kWave < size) {
+          const uint32_t g = classify_tie(thr, key[j], grp[j], idx + slot[j]);
+          const float x = __uint_as_float(v[j]);
+          const uint32_t o = ordered_bits(x);
+          atomicAdd(&s_cnt[g][lane], 1u);
+          atomicMax(&s_max[g][lane], o);
+          atomicMax(&s_negmin[g][lane], ~o);
+          atomicAdd(&s_sq[g][lane], (double)x * (double)x);
+        }
       }
     }
     __syncthreads();
-    if (threadIdx.x <= R) {
-      const uint32_t g = threadIdx.x;
-      const size_t slot = ((size_t)client * ws.max_chunks + c) * 32 + g;
-      ws.chunk_cnt[slot] = s_cnt[g];
-      ws.chunk_sumsq[slot] = s_sq[g];
-      if (s_cnt[g] && g < R) {
-        atomicMax(&ctl->seg_max_enc[g], s_max[g]);
-        atomicMax(&ctl->seg_negmin_enc[g], s_negmin[g]);
-      }
+    for (uint32_t g = wave; g < 32; g += kEmitWaves) {
+      const uint32_t tot = g <= R ? wave_sum_u32(s_cnt[g][lane]) : 0u;
+      if (lane == 0) ws.chunk_cnt[((size_t)client * n_chunks + c) * 32 + g] = tot;
+    }
+    __syncthreads();
+  }
+  __syncthreads();
+  // group g's columns are reduced by wavefront g mod 8; finite values never code to 0, so 0 = no member here
+  for (uint32_t g = wave; g <= R; g += kEmitWaves) {
+    const uint32_t mx = wave_max_u32(s_max[g][lane]);
+    const uint32_t ng = wave_max_u32(s_negmin[g][lane]);
+    const double sq = wave_sum_f64(s_sq[g][lane]);
+    if (lane == 0 && mx != 0) {
+      atomicMax(&ctl->seg_max_enc[g], mx);
+      atomicMax(&ctl->seg_negmin_enc[g], ng);
+      atomicAdd(&ctl->seg_sumsq[g], sq);
     }
   }
 }
 
 // ------------------------------------------------------------------ 7. layout: prefix, headers, statistics
-// One workgroup of 1024 threads per client.  Wavefront w scans the per-chunk
-// counts of groups w, w+16, ... into exclusive prefixes (in place) and adds up
-// the per-chunk sums of squares in chunk order; then the headers and the
-// statistics block are written.
-__global__ __launch_bounds__(1024) void layout_kernel(const ClientParams* __restrict__ params,
-                                                      ClientCtl* __restrict__ ctls, Workspace ws,
-                                                      cvlc_seg_stats_t* __restrict__ stats_out) {
-  __shared__ uint32_t s_total[32];
-  __shared__ double s_sq[32];
-  __shared__ double s_tail[16];
-  const uint32_t client = blockIdx.x;
+typedef uint32_t __attribute__((address_space(1))) * GlobalWordPtr;
+
+// One workgroup of 1024 threads per client.  Wavefront w turns the per-chunk
+// counts of groups w, w+16, ... into exclusive prefixes (in place), checks the
+// totals against the plan, and clears the first and the last stream word of
+// every (chunk, group) record run: those two words can be shared with the
+// neighbouring chunks, which OR their bits in; all other payload words have one
+// owner and are stored whole.  Then the headers and the statistics block.
+__global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* __restrict__ params,
+                                                            ClientCtl* __restrict__ ctls, Workspace ws,
+                                                            cvlc_seg_stats_t* __restrict__ stats_out) {
+  __shared__ double s_tail[kWideWaves];
+  __shared__ uint32_t s_payload[32];
+  const uint32_t client = blockIdx.x, tid = threadIdx.x;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  const uint32_t n = ctl->n_cand, R = p.R;
-  const uint32_t n_chunks = (n + kChunk - 1) / kChunk;
-  const uint32_t lane = lane_id(), wave = threadIdx.x / kWave;
-  uint32_t* cnt = ws.chunk_cnt + (size_t)client * ws.max_chunks * 32;
-  const double* csq = ws.chunk_sumsq + (size_t)client * ws.max_chunks * 32;
-
-  for (uint32_t g = wave; g <= R; g += 16) {
+  const uint32_t R = p.R, n_chunks = ws.n_chunks, sbits = position_bits(ws.d);
+  const uint32_t lane = lane_id(), wave = tid / kWave;
+  GlobalWordPtr stream = (GlobalWordPtr)p.stream;
+  uint32_t* cnt = ws.chunk_cnt + (size_t)client * n_chunks * 32;
+  if (tid == 0) {
+    uint32_t w = kGlobalHeaderWords + kSegHeaderWords * R;
+    for (uint32_t r = 0; r < R; ++r) {
+      s_payload[r] = w;
+      w += (uint32_t)payload_words(p.Z[r] - (r ? p.Z[r - 1] : 0u), sbits + p.y[r]);
+    }
+  }
+  __syncthreads();
+  for (uint32_t g = wave; g < R; g += kWideWaves) {
+    const uint32_t W = sbits + p.y[g];
+    const uint32_t P = p.Z[g] - (g ? p.Z[g - 1] : 0u);
     uint32_t run = 0;
-    double sq = 0.0;
     for (uint32_t c0 = 0; c0 < n_chunks; c0 += kWave) {
       const uint32_t c = c0 + lane;
       const uint32_t v = c < n_chunks ? cnt[(size_t)c * 32 + g] : 0u;
-      const double q = c < n_chunks ? csq[(size_t)c * 32 + g] : 0.0;
       const uint32_t incl = wave_incl_scan_u32(v);
-      if (c < n_chunks) cnt[(size_t)c * 32 + g] = run + incl - v;
+      const uint32_t excl = run + incl - v;
+      if (c < n_chunks) {
+        cnt[(size_t)c * 32 + g] = excl;
+        // a consistent selection never passes the planned size; the test keeps the two
+        // stores inside the group's payload even if an internal check has failed
+        if (v && excl + v <= P) {
+          const uint64_t bit0 = (uint64_t)excl * W, bit1 = (uint64_t)(excl + v) * W;
+          stream[s_payload[g] + (uint32_t)(bit0 >> 5)] = 0;
+          stream[s_payload[g] + (uint32_t)((bit1 - 1) >> 5)] = 0;
+        }
+      }
       run += __shfl(incl, 63, 64);
-      sq += wave_sum_f64(q);
     }
-    if (lane == 0) { s_total[g] = run; s_sq[g] = sq; }
+    if (lane == 0 && run != P) atomicOr(ws.status, CVLC_DEV_INTERNAL);
   }
   // energy of the coordinates the filter dropped, region by region
-  {
-    const double* rsq = ws.region_sumsq + (size_t)client * ws.n_regions;
-    double acc = 0.0;
-    for (uint32_t t = threadIdx.x; t < ws.n_regions; t += 1024) acc += rsq[t];
-    acc = wave_sum_f64(acc);
-    if (lane == 0) s_tail[wave] = acc;
-  }
+  const double* rsq = ws.region_sumsq + (size_t)client * ws.n_regions;
+  double acc = 0.0;
+  for (uint32_t t = tid; t < ws.n_regions; t += kWideBlock) acc += rsq[t];
+  acc = wave_sum_f64(acc);
+  if (lane == 0) s_tail[wave] = acc;
   __syncthreads();
 
-  uint32_t* stream = p.stream;
-  if (threadIdx.x < R) {
-    const uint32_t r = threadIdx.x;
+  if (tid < R) {
+    const uint32_t r = tid;
     const uint32_t P = p.Z[r] - (r ? p.Z[r - 1] : 0u);
-    if (s_total[r] != P) atomicOr(ws.status, CVLC_DEV_INTERNAL);
     float m = 0.0f, M = 0.0f;
     if (P > 0 && ctl->seg_max_enc[r] != 0) {
       M = from_ordered_bits(ctl->seg_max_enc[r]);
       m = from_ordered_bits(~ctl->seg_negmin_enc[r]);
+    } else if (P > 0) {
+      atomicOr(ws.status, CVLC_DEV_INTERNAL);
     }
     if (!(fabsf(M - m) <= 3.4028234664e38f)) atomicOr(ws.status, CVLC_DEV_NONFINITE);
-    uint32_t* hdr = stream + kGlobalHeaderWords + kSegHeaderWords * r;
+    GlobalWordPtr hdr = stream + kGlobalHeaderWords + kSegHeaderWords * r;
     hdr[0] = p.y[r];
     hdr[1] = P;
     hdr[2] = __float_as_uint(m);
     hdr[3] = __float_as_uint(M);
     if (stats_out) {
       cvlc_seg_stats_t* st = stats_out + (size_t)client * kStatsStride + r;
-      st->min = m; st->max = M; st->sumsq = s_sq[r]; st->count = P; st->reserved = 0;
+      st->min = m; st->max = M; st->sumsq = ctl->seg_sumsq[r]; st->count = P; st->reserved = 0;
     }
+    GroupInfo* gi = ws.group_info + client;
+    float step, inv;
+    centroid_spacing(m, M, p.y[r] == 32 ? 1u : p.y[r], &step, &inv);
+    gi->payload[r] = s_payload[r];
+    gi->P[r] = P;
+    gi->W[r] = sbits + p.y[r];
+    gi->y[r] = p.y[r];
+    gi->m[r] = m;
+    gi->inv[r] = inv;
   }
-  if (threadIdx.x == 0) {
+  if (tid == 32) {
     stream[0] = kMagic;
     stream[1] = kVersion;  // quantiser id 0 (PQ) in the upper half
     stream[2] = ws.d;
     stream[3] = R;
-    stream[4] = position_bits(ws.d);
+    stream[4] = sbits;
     stream[5] = __float_as_uint(p.B);
     stream[6] = p.client_id;
     stream[7] = p.total_words;
     if (stats_out) {
       double tail = 0.0;
-      for (int w = 0; w < 16; ++w) tail += s_tail[w];
+      for (uint32_t w = 0; w < kWideWaves; ++w) tail += s_tail[w];
       cvlc_seg_stats_t* st = stats_out + (size_t)client * kStatsStride + R;
-      st->min = 0.0f; st->max = 0.0f; st->sumsq = tail + s_sq[R]; st->count = ws.d - p.k; st->reserved = 0;
+      st->min = 0.0f; st->max = 0.0f; st->sumsq = tail + ctl->seg_sumsq[R]; st->count = ws.d - p.k; st->reserved = 0;
     }
   }
 }
@@ -983,8 +1152,9 @@ __device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint3
   uint32_t c2 = 0, c3 = 0;
 #pragma unroll
   for (int round = 0; round < 10; ++round) {
-    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+    const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
     c0 = hi1 ^ c1 ^ k0;
     c1 = lo1;
     c2 = hi0 ^ c3 ^ k1;
@@ -1012,162 +1182,199 @@ __device__ __forceinline__ uint32_t quantise(float x, float m, float inv, uint32
   return cid > last ? last : cid;
 }
 
-constexpr uint32_t kStageWords = kChunk * 2 + 2 * 32;  // every record is < 64 bits; two edge words per group
 
-__global__ __launch_bounds__(kBlock) void emit_kernel(const ClientParams* __restrict__ params,
-                                                      ClientCtl* __restrict__ ctls, Workspace ws, uint64_t seed) {
+
+constexpr uint32_t kStageWords = kSweep * 2 + 2 * 32;  // every record is < 64 bits; two edge words per group
+
+// One workgroup per chunk.  A sweep of up to 4096 candidates is classified,
+// every coded one gets its record number inside its group (members in earlier
+// chunks from the layout's prefix, then earlier sweeps, earlier wavefronts,
+// earlier rows, lower lanes), is quantised and OR-ed into an LDS image of the
+// stream words its group's run covers.  The image is then written out: the
+// chunk's first and last word of a group can be shared with a neighbouring
+// chunk and are OR-ed into the (cleared) stream; a word left unfinished by a
+// sweep is carried in LDS into the next sweep's image; all others are stored
+// whole.
+__global__ __launch_bounds__(kEmitBlock) void emit_kernel(const ClientParams* __restrict__ params,
+                                                          ClientCtl* __restrict__ ctls, Workspace ws, uint64_t seed) {
   __shared__ Thresholds thr;
+  __shared__ ChunkMap map[2];
+  __shared__ uint32_t s_run_first[2][32], s_run_last[2][32];  // the chunk's record run of every group: [first, last)
   __shared__ uint32_t s_stage[kStageWords];
-  __shared__ uint32_t s_wcnt[kWavesPerBlock][32];  // per wavefront, per group: members in this chunk
-  __shared__ volatile uint32_t s_run[kWavesPerBlock][32];
-  __shared__ uint32_t s_base[32];                  // first record index of this chunk in each group
-  __shared__ uint32_t s_lim[32];                   // one past this chunk's last record index in each group
-  __shared__ uint32_t s_P[32];                     // planned group sizes
-  __shared__ uint32_t s_word0[32];                 // first stream word (group-relative) this chunk touches
-  __shared__ uint32_t s_nwords[32];                // words this chunk touches in each group
+  __shared__ uint32_t s_wcnt[kEmitWaves][32];      // per wavefront, per group: members in this sweep, then running rank
+  __shared__ uint32_t s_base[32];                  // record number of the sweep's first member of each group
+  __shared__ uint32_t s_lim[32];                   // one past the sweep's last record number
+  __shared__ uint32_t s_word0[32];                 // first stream word (group-relative) the sweep touches
+  __shared__ uint32_t s_nwords[32];                // words the sweep touches in each group
   __shared__ uint32_t s_stage_off[33];
+  __shared__ uint32_t s_edge[32];                  // bit 0: first word is OR-ed, bit 1: last word is OR-ed, bit 2: last word is carried
+  __shared__ uint32_t s_carry[32];                 // a word the sweep before left unfinished, valid while s_has_carry
+  __shared__ uint32_t s_has_carry[32];
   __shared__ uint32_t s_payload[32];               // first stream word of each group's payload
+  __shared__ uint32_t s_P[32], s_W[32], s_y[32];
   __shared__ float s_m[32], s_inv[32];
-  __shared__ uint32_t s_W[32];
-  const uint32_t client = blockIdx.y;
+  const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  const uint32_t n = ctl->n_cand, R = p.R;
-  const uint32_t sbits = position_bits(ws.d);
-  const uint2* __restrict__ cand = ws.cand_dense + (size_t)client * ws.d;
-  uint32_t* stream = p.stream;
-  const uint32_t lane = lane_id(), wave = wave_id();
-  const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+  const uint32_t R = p.R, sbits = position_bits(ws.d), n_chunks = ws.n_chunks;
+  const uint32_t* __restrict__ val = ws.cand_val + (size_t)client * ws.d;
+  const uint32_t* __restrict__ idx = ws.cand_idx + (size_t)client * ws.d;
+  const uint32_t* __restrict__ region_off = ws.region_off + (size_t)client * (ws.n_regions + 1);
+  const uint32_t* __restrict__ chunk_cnt = ws.chunk_cnt + (size_t)client * n_chunks * 32;
+  GlobalWordPtr stream = (GlobalWordPtr)p.stream;
+  const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32), client_id = p.client_id;
+
+  // the chunk's record runs: from the layout's prefix, clamped so that every write stays inside
+  // the group's payload even if an internal check has failed
+  auto load_runs = [&](uint32_t buf, uint32_t c) {
+    if (tid < 32) {
+      uint32_t first = 0, last = 0;
+      if (tid < R) {
+        const uint32_t P = p.Z[tid] - (tid ? p.Z[tid - 1] : 0u);
+        first = chunk_cnt[(size_t)c * 32 + tid];
+        last = c + 1 < n_chunks ? chunk_cnt[(size_t)(c + 1) * 32 + tid] : P;
+        if (first > P) first = P;
+        if (last > P) last = P;
+        if (last < first) last = first;
+      }
+      s_run_first[buf][tid] = first;
+      s_run_last[buf][tid] = last;
+    }
+  };
 
   load_thresholds(thr, ctl, R);
-  if (threadIdx.x < 32) {
-    const uint32_t r = threadIdx.x;
-    if (r < R) {
-      const uint32_t* hdr = stream + kGlobalHeaderWords + kSegHeaderWords * r;  // written by the layout kernel
-      const float m = __uint_as_float(hdr[2]), M = __uint_as_float(hdr[3]);
-      float step, inv;
-      centroid_spacing(m, M, p.y[r] == 32 ? 1u : p.y[r], &step, &inv);
-      s_m[r] = m;
-      s_inv[r] = inv;
-      s_W[r] = sbits + p.y[r];
-      s_P[r] = p.Z[r] - (r ? p.Z[r - 1] : 0u);
-    }
+  if (tid < 32) {
+    const GroupInfo* gi = ws.group_info + client;
+    const bool live = tid < R;
+    s_payload[tid] = live ? gi->payload[tid] : 0u;
+    s_P[tid] = live ? gi->P[tid] : 0u;
+    s_W[tid] = live ? gi->W[tid] : 0u;
+    s_y[tid] = live ? gi->y[tid] : 0u;
+    s_m[tid] = live ? gi->m[tid] : 0.0f;
+    s_inv[tid] = live ? gi->inv[tid] : 0.0f;
   }
-  if (threadIdx.x == 0) {
-    uint32_t w = kGlobalHeaderWords + kSegHeaderWords * R;
-    for (uint32_t r = 0; r < R; ++r) {
-      s_payload[r] = w;
-      const uint32_t P = p.Z[r] - (r ? p.Z[r - 1] : 0u);
-      w += (uint32_t)payload_words(P, sbits + p.y[r]);
-    }
+  if (blockIdx.x < n_chunks) {
+    load_chunk_map(map[0], region_off, ws.n_regions, blockIdx.x, tid);
+    load_runs(0, blockIdx.x);
   }
-  const uint32_t n_chunks = (n + kChunk - 1) / kChunk;
-  for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+  uint32_t cur = 0;
+  for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x, cur ^= 1u) {
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < kWavesPerBlock * 32; i += kBlock) (&s_wcnt[0][0])[i] = 0;
-    __syncthreads();
-    // sweep 1: group of each of this thread's 8 candidates, per-wavefront group sizes
-    float x[8];
-    uint32_t pid[8], grp[8];
+    if (c + gridDim.x < n_chunks) {  // the next chunk's map and runs travel while this one is worked on
+      load_chunk_map(map[cur ^ 1u], region_off, ws.n_regions, c + gridDim.x, tid);
+      load_runs(cur ^ 1u, c + gridDim.x);
+    }
+    if (tid < 32) {
+      s_base[tid] = s_run_first[cur][tid];
+      s_has_carry[tid] = 0;
+    }
+    const ChunkMap& m = map[cur];
+    const uint32_t* run_first = s_run_first[cur];
+    const uint32_t* run_last = s_run_last[cur];
+    const uint32_t size = m.start[kChunkRegions];
+    for (uint32_t first = 0; first < size; first += kSweep) {
+      __syncthreads();
+      for (uint32_t i = tid; i < kEmitWaves * 32; i += kEmitBlock) (&s_wcnt[0][0])[i] = 0;
+      __syncthreads();
+      uint32_t slot[kPerLane], v[kPerLane], row[kPerLane];
+      volatile uint32_t* wrun = s_wcnt[wave];
+      classify_sweep(thr, R, m, c, first, val, idx, slot, v, row, wrun);
+      uint32_t pid[kPerLane];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const uint32_t i = c * kChunk + wave * (kChunk / kWavesPerBlock) + j * kWave + lane;
-      grp[j] = 0xFFFFFFFFu;
-      if (i < n) {
-        const uint2 e = cand[i];
-        x[j] = __uint_as_float(e.y);
-        pid[j] = e.x;
-        grp[j] = classify(thr, R, __float_as_uint(x[j]) & 0x7FFFFFFFu, pid[j]);
-        if (grp[j] < R) atomicAdd(&s_wcnt[wave][grp[j]], 1u);
-      }
-    }
-    __syncthreads();
-    if (threadIdx.x < 32) {
-      const uint32_t r = threadIdx.x;
-      uint32_t cnt = 0;
-      if (r < R) {
-        for (uint32_t w = 0; w < kWavesPerBlock; ++w) cnt += s_wcnt[w][r];
-        uint32_t e0 = ws.chunk_cnt[((size_t)client * ws.max_chunks + c) * 32 + r];
-        // a consistent selection never exceeds the planned size; the clamp keeps every
-        // write inside the group's payload even if an internal check has failed
-        if (e0 > s_P[r]) e0 = s_P[r];
-        if (cnt > s_P[r] - e0) cnt = s_P[r] - e0;
-        s_base[r] = e0;
-        s_lim[r] = e0 + cnt;
-        const uint64_t bit0 = (uint64_t)e0 * s_W[r], bit1 = (uint64_t)(e0 + cnt) * s_W[r];
-        s_word0[r] = (uint32_t)(bit0 >> 5);
-        s_nwords[r] = cnt ? (uint32_t)(((bit1 - 1) >> 5) - (bit0 >> 5) + 1) : 0u;
-      } else {
-        s_nwords[r] = 0;
-      }
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t off = 0;
-      for (uint32_t r = 0; r < 32; ++r) { s_stage_off[r] = off; off += s_nwords[r]; }
-      s_stage_off[32] = off;
-    }
-    __syncthreads();
-    const uint32_t staged = s_stage_off[32];
-    for (uint32_t i = threadIdx.x; i < staged; i += kBlock) s_stage[i] = 0;
-    __syncthreads();
-    // sweep 2: rank inside (group, chunk) in position order, quantise, pack into LDS.
-    // s_run[wave][g] is the number of group-g records of this chunk that precede the
-    // wavefront's current 64 candidates; it is read and advanced by the wavefront alone.
-    if (lane < 32) {
-      uint32_t before = 0;
-      for (uint32_t w = 0; w < wave; ++w) before += s_wcnt[w][lane];
-      s_run[wave][lane] = before;
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const bool coded = grp[j] < R;
-      const uint32_t g5 = grp[j] & 31u;
-      uint64_t same = __ballot(coded);  // lanes holding a coded record of the same group as this lane
-#pragma unroll
-      for (int bit = 0; bit < 5; ++bit) {
-        const uint64_t set = __ballot((g5 >> bit) & 1u);
-        same &= ((g5 >> bit) & 1u) ? set : ~set;
-      }
-      uint32_t my_rank = 0;
-      if (coded) {
-        const uint32_t start = s_run[wave][g5];
-        my_rank = start + lanes_below(same);
-        if (lane == (uint32_t)__builtin_ctzll(same)) s_run[wave][g5] = start + (uint32_t)__popcll(same);
-      }
-      if (coded && s_base[grp[j]] + my_rank < s_lim[grp[j]]) {
-        const uint32_t g = grp[j], y = p.y[g], W = s_W[g];
-        uint32_t cid;
-        if (y == 32) {
-          cid = __float_as_uint(x[j]);
-        } else {
-          const uint32_t u24 = philox_word0(pid[j], p.client_id, k0, k1) >> 8;
-          cid = quantise(x[j], s_m[g], s_inv[g], y, u24);
+      for (uint32_t j = 0; j < kPerLane; ++j) pid[j] = (row_group(row[j]) < R) ? idx[slot[j]] : 0u;
+      __syncthreads();
+      uint32_t before = 0;  // lane g of every wavefront: members of g in the sweep's earlier wavefronts
+      if (lane < 32)
+        for (uint32_t w = 0; w < wave; ++w) before += s_wcnt[w][lane];
+      if (tid < 32) {
+        const uint32_t r = tid;
+        uint32_t cnt = 0;
+        for (uint32_t w = 0; w < kEmitWaves; ++w) cnt += s_wcnt[w][r];
+        uint32_t nwords = 0, edge = 0;
+        if (r < R) {
+          const uint32_t e0 = s_base[r];
+          if (cnt > run_last[r] - e0) cnt = run_last[r] - e0;
+          s_lim[r] = e0 + cnt;
+          if (cnt) {
+            const uint64_t bit0 = (uint64_t)e0 * s_W[r], bit1 = (uint64_t)(e0 + cnt) * s_W[r];
+            s_word0[r] = (uint32_t)(bit0 >> 5);
+            nwords = (uint32_t)(((bit1 - 1) >> 5) - (bit0 >> 5) + 1);
+            // first word: the chunk's first may be shared with the chunk before (OR); later sweeps own theirs
+            if (e0 == run_first[r]) edge |= 1u;
+            // last word: the chunk's last may be shared with the chunk after (OR); an earlier sweep's
+            // unfinished last word is carried into the next sweep instead of being written
+            if (e0 + cnt == run_last[r]) edge |= 2u;
+            else if (bit1 & 31u) edge |= 4u;
+          }
         }
-        const uint64_t record = (uint64_t)pid[j] | ((uint64_t)cid << sbits);
-        const uint64_t bit = (uint64_t)(s_base[g] + my_rank) * W - (uint64_t)s_word0[g] * 32u;
-        const uint32_t w0 = s_stage_off[g] + (uint32_t)(bit >> 5), sh = (uint32_t)(bit & 31u);
-        const uint64_t lo = record << sh;
-        const uint32_t hi = sh ? (uint32_t)(record >> (64u - sh)) : 0u;
-        atomicOr(&s_stage[w0], (uint32_t)lo);
-        if (sh + W > 32u) atomicOr(&s_stage[w0 + 1], (uint32_t)(lo >> 32));
-        if (sh + W > 64u) atomicOr(&s_stage[w0 + 2], hi);
+        s_nwords[r] = nwords;
+        s_edge[r] = edge;
       }
-    }
-    __syncthreads();
-    // flush: interior words belong to this chunk alone; the two edge words of a
-    // group may be shared with neighbouring chunks and are OR-ed in.
-    for (uint32_t i = threadIdx.x; i < staged; i += kBlock) {
-      uint32_t g = 0;
-      while (i >= s_stage_off[g + 1]) ++g;
-      const uint32_t rel = i - s_stage_off[g];
-      uint32_t* dst = stream + s_payload[g] + s_word0[g] + rel;
-      const uint32_t v = s_stage[i];
-      if (rel == 0 || rel == s_nwords[g] - 1) {
-        if (v) atomicOr(dst, v);
-      } else {
-        *dst = v;
+      __syncthreads();
+      if (lane < 32) wrun[lane] = before;
+      if (tid == 0) {
+        uint32_t off = 0;
+        for (uint32_t r = 0; r < 32; ++r) { s_stage_off[r] = off; off += s_nwords[r]; }
+        s_stage_off[32] = off;
       }
+      __syncthreads();
+      const uint32_t staged = s_stage_off[32];
+      for (uint32_t i = tid; i < staged; i += kEmitBlock) s_stage[i] = 0;
+      __syncthreads();
+      if (tid < 32 && s_nwords[tid] && s_has_carry[tid]) {  // the word the sweep before left unfinished
+        s_stage[s_stage_off[tid]] = s_carry[tid];
+        s_has_carry[tid] = 0;
+      }
+      __syncthreads();
+#pragma unroll
+      for (uint32_t j = 0; j < kPerLane; ++j) {
+        const uint32_t g = row_group(row[j]);
+        if (g != kRowNone) {
+          const uint32_t start = wrun[g];
+          const uint32_t rank = start + row_below(row[j]);
+          if (row_leader(row[j])) wrun[g] = start + row_peers(row[j]);
+          if (g < R && s_base[g] + rank < s_lim[g]) {
+            const uint32_t y = s_y[g], W = s_W[g];
+            uint32_t cid;
+            if (y == 32) {
+              cid = v[j];
+            } else {
+              const uint32_t u24 = philox_word0(pid[j], client_id, k0, k1) >> 8;
+              cid = quantise(__uint_as_float(v[j]), s_m[g], s_inv[g], y, u24);
+            }
+            const uint64_t record = (uint64_t)pid[j] | ((uint64_t)cid << sbits);
+            const uint64_t bit = (uint64_t)(s_base[g] + rank) * W - (uint64_t)s_word0[g] * 32u;
+            const uint32_t w0 = s_stage_off[g] + (uint32_t)(bit >> 5), sh = (uint32_t)(bit & 31u);
+            const uint64_t lo = record << sh;
+            atomicOr(&s_stage[w0], (uint32_t)lo);
+            if (sh + W > 32u) atomicOr(&s_stage[w0 + 1], (uint32_t)(lo >> 32));
+            if (sh + W > 64u) atomicOr(&s_stage[w0 + 2], (uint32_t)(record >> (64u - sh)));
+          }
+        }
+      }
+      __syncthreads();
+      for (uint32_t i = tid; i < staged; i += kEmitBlock) {
+        uint32_t lo = 0, hi = 32;  // group whose staged words hold word i: last g with s_stage_off[g] <= i
+        while (hi - lo > 1) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (s_stage_off[mid] <= i) lo = mid; else hi = mid;
+        }
+        const uint32_t g = lo, rel = i - s_stage_off[g];
+        GlobalWordPtr dst = stream + s_payload[g] + s_word0[g] + rel;
+        const uint32_t word = s_stage[i];
+        const uint32_t edge = s_edge[g];
+        const bool is_last = rel == s_nwords[g] - 1;
+        if (is_last && (edge & 4u)) {
+          s_carry[g] = word;
+          s_has_carry[g] = 1u;
+        } else if ((rel == 0 && (edge & 1u)) || (is_last && (edge & 2u))) {
+          if (word) atomicOr((uint32_t*)dst, word);
+        } else {
+          *dst = word;
+        }
+      }
+      __syncthreads();
+      if (tid < R) s_base[tid] = s_lim[tid];
     }
   }
 }
@@ -1248,15 +1455,15 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   ws.region_cnt = reinterpret_cast<uint32_t*>(base + L.region_cnt);
   ws.region_off = reinterpret_cast<uint32_t*>(base + L.region_off);
   ws.region_sumsq = reinterpret_cast<double*>(base + L.region_sumsq);
-  ws.cand_sparse = reinterpret_cast<uint2*>(base + L.cand_sparse);
-  ws.cand_dense = reinterpret_cast<uint2*>(base + L.cand_dense);
+  ws.cand_idx = reinterpret_cast<uint32_t*>(base + L.cand_idx);
+  ws.cand_val = reinterpret_cast<uint32_t*>(base + L.cand_val);
   ws.chunk_cnt = reinterpret_cast<uint32_t*>(base + L.chunk_cnt);
-  ws.chunk_sumsq = reinterpret_cast<double*>(base + L.chunk_sumsq);
+  ws.group_info = reinterpret_cast<GroupInfo*>(base + L.group_info);
   ws.tie_list = reinterpret_cast<uint2*>(base + L.tie_list);
   ws.sel_part = reinterpret_cast<uint32_t*>(base + L.sel_part);
   ws.d = d;
   ws.n_regions = L.n_regions;
-  ws.max_chunks = L.max_chunks;
+  ws.n_chunks = L.n_chunks;
   ws.filter_blocks = filter_blocks_per_client(L.n_regions, n, filter_resident_blocks());
   ws.sel_blocks = L.sel_blocks;
 
@@ -1327,29 +1534,28 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
     StageScope scope(CVLC_STAGE_ENC_SELECT, stream);
     const dim3 grid(L.sel_blocks, n);
     const uint32_t groups = (max_R + kSlotGroup - 1) / kSlotGroup;
-    // the first pass also gathers the region runs into the dense candidate list (also when nothing is coded)
-    hipLaunchKernelGGL((select_pass_kernel<2, true>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
     for (uint32_t gr = 0; gr < groups; ++gr) {
-      if (gr > 0)
-        hipLaunchKernelGGL((select_pass_kernel<2, false>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+      hipLaunchKernelGGL(select_pass_kernel<2>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
       hipLaunchKernelGGL(select_walk_kernel<2>, dim3(kSlotGroup, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
-      hipLaunchKernelGGL((select_pass_kernel<3, false>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+      hipLaunchKernelGGL(select_pass_kernel<3>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
       hipLaunchKernelGGL(select_walk_kernel<3>, dim3(kSlotGroup, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
     }
   }
-  uint32_t g_chunk = (2048u + n - 1) / n;
-  if (g_chunk > L.max_chunks) g_chunk = L.max_chunks;
+  // count/emit workgroups per client: what the device holds at once (four and two per CU), each walking several chunks
+  uint32_t g_count = (1024u + n - 1) / n, g_emit = (512u + n - 1) / n;
+  if (g_count > L.n_chunks) g_count = L.n_chunks;
+  if (g_emit > L.n_chunks) g_emit = L.n_chunks;
   {
     StageScope scope(CVLC_STAGE_ENC_CLASSIFY, stream);
-    hipLaunchKernelGGL(classify_kernel, dim3(g_chunk, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+    hipLaunchKernelGGL(count_kernel, dim3(g_count, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws);
   }
   {
     StageScope scope(CVLC_STAGE_ENC_LAYOUT, stream);
-    hipLaunchKernelGGL(layout_kernel, dim3(n), dim3(1024), 0, stream, ws.params, ws.ctl, ws, d_stats_out);
+    hipLaunchKernelGGL(layout_kernel, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, d_stats_out);
   }
   {
     StageScope scope(CVLC_STAGE_ENC_EMIT, stream);
-    hipLaunchKernelGGL(emit_kernel, dim3(g_chunk, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws, seed);
+    hipLaunchKernelGGL(emit_kernel, dim3(g_emit, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws, seed);
   }
   return hip_check(hipGetLastError());
 }
