@@ -23,7 +23,8 @@ constexpr uint32_t kWave = 64;
 constexpr uint32_t kWavesPerBlock = kBlock / kWave;
 constexpr uint32_t kSubTile = 1024;        // coordinates one wavefront holds in registers (16 per lane)
 constexpr uint32_t kRegion = 8192;         // coordinates one wavefront filters as a unit (8 sub-tiles)
-constexpr uint32_t kChunkRegions = 8;      // regions per chunk: the unit of the classify/emit passes
+constexpr uint32_t kSpan = 512;            // candidates one wavefront classifies as a unit (8 rows of 64)
+constexpr uint32_t kChunkSpans = 8;        // spans per emit chunk (4096 candidates, one workgroup)
 constexpr uint32_t kSampleBins = 4096;     // sample histogram on key >> 19
 constexpr uint32_t kSampleShift = 19;
 constexpr uint32_t kL1Bins = 2048;         // level-1 digit: key >> 20 (8 exponent + 3 mantissa bits)

@@ -46,10 +46,10 @@ struct GroupInfo {
 };
 
 struct EncodeLayout {
-  size_t status, ctl, params, region_cnt, region_off, region_sumsq, cand_idx, cand_val, chunk_cnt, group_info,
+  size_t status, ctl, params, region_cnt, region_off, region_sumsq, cand_idx, cand_val, dense_idx, dense_val, span_cnt, group_info,
       tie_list, sel_part, total;
   size_t zero_bytes;        // [status, params) is cleared at the start of a call
-  uint32_t n_regions, n_chunks;
+  uint32_t n_regions, max_spans;
   uint32_t sel_blocks;      // workgroups per client in a level-2/3 selection pass
 };
 
@@ -69,7 +69,7 @@ uint32_t filter_blocks_per_client(uint32_t n_regions, uint32_t n, uint32_t resid
 EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   EncodeLayout L;
   L.n_regions = (uint32_t)(((uint64_t)d + kRegion - 1) / kRegion);
-  L.n_chunks = (L.n_regions + kChunkRegions - 1) / kChunkRegions;
+  L.max_spans = (uint32_t)(((uint64_t)d + kSpan - 1) / kSpan);
   {
     uint32_t b = (512u + n - 1) / n;
     L.sel_blocks = b < 2 ? 2u : (b > 32 ? 32u : b);
@@ -84,7 +84,9 @@ EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   L.region_sumsq = off; off = align256(off + (size_t)n * L.n_regions * sizeof(double));
   L.cand_idx = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
   L.cand_val = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
-  L.chunk_cnt = off; off = align256(off + (size_t)n * L.n_chunks * 32 * sizeof(uint32_t));
+  L.dense_idx = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
+  L.dense_val = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
+  L.span_cnt = off; off = align256(off + (size_t)n * (L.max_spans + 1) * 32 * sizeof(uint32_t));
   L.group_info = off; off = align256(off + (size_t)n * sizeof(GroupInfo));
   L.tie_list = off; off = align256(off + (size_t)n * kSlotGroup * kTieCap * sizeof(uint2));
   L.sel_part = off; off = align256(off + (size_t)n * L.sel_blocks * kSlotGroup * kDigitBins * sizeof(uint32_t));
@@ -101,11 +103,13 @@ struct Workspace {  // device pointers into the caller's workspace
   double* region_sumsq;
   uint32_t* cand_idx;  // positions of the kept coordinates: a run at the front of every region's slot
   uint32_t* cand_val;  // their value bits, same layout
-  uint32_t* chunk_cnt;
+  uint32_t* dense_idx; // the same candidates, contiguous per client, in position order
+  uint32_t* dense_val;
+  uint32_t* span_cnt;  // per span of 512 candidates: members of every group, then their exclusive prefix
   GroupInfo* group_info;
   uint2* tie_list;
   uint32_t* sel_part;
-  uint32_t d, n_regions, n_chunks, filter_blocks, sel_blocks;
+  uint32_t d, n_regions, max_spans, filter_blocks, sel_blocks;
 };
 
 // ------------------------------------------------------------------ parameter upload
@@ -609,55 +613,10 @@ __device__ __forceinline__ void select_count(SelectShared& S, uint32_t key, cons
   }
 }
 
-// ---- walking the candidates
-// A chunk is kChunkRegions consecutive regions; its candidates, in position
-// order, are the regions' runs one after the other.  start[t] is the chunk-local
-// number of the first candidate of region t's run, start[kChunkRegions] the
-// chunk's size.
-struct ChunkMap {
-  uint32_t start[kChunkRegions + 1];
-};
-
-// Filled by threads 0..kChunkRegions of the workgroup (a barrier must follow).
-__device__ __forceinline__ void load_chunk_map(ChunkMap& m, const uint32_t* __restrict__ region_off, uint32_t n_regions,
-                                               uint32_t c, uint32_t t) {
-  if (t <= kChunkRegions) {
-    const uint32_t first = c * kChunkRegions;
-    const uint32_t r = first + t < n_regions ? first + t : n_regions;
-    m.start[t] = region_off[r] - region_off[first];
-  }
-}
-
-// Index into the region-slot arrays of the chunk's i-th candidate (i < size).
-__device__ __forceinline__ uint32_t chunk_slot(const ChunkMap& m, uint32_t c, uint32_t i) {
-  static_assert(kChunkRegions == 8, "three-step search");
-  uint32_t t = (i >= m.start[4]) ? 4u : 0u;
-  t += (i >= m.start[t + 2]) ? 2u : 0u;
-  t += (i >= m.start[t + 1]) ? 1u : 0u;
-  return (c * kChunkRegions + t) * kRegion + (i - m.start[t]);
-}
-
-constexpr uint32_t kMapBatch = 16;  // chunk maps a selection workgroup holds at a time
-
+// Fills the workgroup's slot tables for one group of boundaries.
 template <int LEVEL>
-__global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientParams* __restrict__ params,
-                                                                 ClientCtl* __restrict__ ctls, Workspace ws,
-                                                                 uint32_t group) {
-  __shared__ SelectShared S;
-  __shared__ ChunkMap s_map[kMapBatch];
-  static_assert(sizeof(SelectShared) + sizeof(ChunkMap) * kMapBatch <= 65536, "static LDS limit");
-  const uint32_t client = blockIdx.y, tid = threadIdx.x;
-  const ClientParams& p = params[client];
-  ClientCtl* ctl = ctls + client;
-  const uint32_t r0 = group * kSlotGroup;
-  if (p.R <= r0) return;  // this client has no boundary in the group
-  const uint32_t nb = min(p.R - r0, kSlotGroup);
-  const uint32_t* __restrict__ val = ws.cand_val + (size_t)client * ws.d;
-  const uint32_t* __restrict__ idx = ws.cand_idx + (size_t)client * ws.d;
-  const uint32_t* __restrict__ region_off = ws.region_off + (size_t)client * (ws.n_regions + 1);
-  uint2* ties = ws.tie_list + (size_t)client * kSlotGroup * kTieCap;
-  uint32_t* tie_cnt = ctl->tie_cnt[group];
-
+__device__ __forceinline__ void select_setup(SelectShared& S, const ClientCtl* ctl, uint32_t r0, uint32_t nb) {
+  const uint32_t tid = threadIdx.x;
   for (uint32_t i = tid; i < kSlotGroup * kDigitBins; i += kWideBlock) S.hist[i] = 0;
   for (uint32_t i = tid; i < kL1Bins / 8; i += kWideBlock) S.bin_slot[i] = 0;
   for (uint32_t i = tid; i < kSlotGroup * (kDigitBins / 32); i += kWideBlock) (&S.digit_map[0][0])[i] = 0;
@@ -678,42 +637,111 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
       }
     }
   }
+  __syncthreads();
+}
 
-  // this workgroup's chunks: blockIdx.x, blockIdx.x + gridDim.x, ...; their maps are fetched kMapBatch at a time
-  const uint32_t n_chunks = ws.n_chunks;
-  for (uint32_t c0 = blockIdx.x; c0 < n_chunks; c0 += gridDim.x * kMapBatch) {
-    __syncthreads();
-    {
-      const uint32_t which = tid / 16u, t = tid % 16u;
-      const uint32_t c = c0 + which * gridDim.x;
-      if (which < kMapBatch && c < n_chunks) load_chunk_map(s_map[which], region_off, ws.n_regions, c, t);
+// Level 2 of the first group of boundaries, fused with the gather: every
+// wavefront takes region runs (gw, gw + wavefronts, ...), copies them to their
+// place in the dense position-ordered candidate list (region_off is the
+// exclusive prefix of the run lengths) and counts the level-2 digits on the
+// way.  The wavefronts do not wait for each other until the histogram is stored.
+__global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParams* __restrict__ params,
+                                                               ClientCtl* __restrict__ ctls, Workspace ws) {
+  __shared__ SelectShared S;
+  const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+  const ClientParams& p = params[client];
+  ClientCtl* ctl = ctls + client;
+  const uint32_t nb = min(p.R, kSlotGroup);
+  select_setup<2>(S, ctl, 0, nb);
+  const uint32_t d = ws.d, n_regions = ws.n_regions;
+  const uint32_t* __restrict__ cnt = ws.region_cnt + (size_t)client * n_regions;
+  const uint32_t* __restrict__ off = ws.region_off + (size_t)client * (n_regions + 1);
+  const uint32_t* __restrict__ src_idx = ws.cand_idx + (size_t)client * d;
+  const uint32_t* __restrict__ src_val = ws.cand_val + (size_t)client * d;
+  uint32_t* __restrict__ dst_idx = ws.dense_idx + (size_t)client * d;
+  uint32_t* __restrict__ dst_val = ws.dense_val + (size_t)client * d;
+  const uint32_t wpc = gridDim.x * kWideWaves;  // wavefronts per client
+  // the runs' lengths and offsets are fetched 64 at a time, one per lane
+  for (uint32_t first = blockIdx.x * kWideWaves + wave; first < n_regions; first += wpc * kWave) {
+    const uint32_t mine = first + lane * wpc;
+    uint32_t c = 0, o = 0;
+    if (mine < n_regions) {
+      c = cnt[mine];
+      o = off[mine];
     }
-    __syncthreads();
-    for (uint32_t which = 0; which < kMapBatch; ++which) {
-      const uint32_t c = c0 + which * gridDim.x;
-      if (c >= n_chunks) break;
-      const ChunkMap& m = s_map[which];
-      const uint32_t size = m.start[kChunkRegions];
-      for (uint32_t base = 0; base < size; base += kWideBlock * 4u) {
-        uint32_t v[4], slot[4];
-        bool live[4];
+    const uint32_t left = (n_regions - first + wpc - 1) / wpc;
+    const uint32_t nr = left < kWave ? left : kWave;
+    for (uint32_t l = 0; l < nr; ++l) {
+      const uint32_t rc = __builtin_amdgcn_readlane(c, l), ro = __builtin_amdgcn_readlane(o, l);
+      const size_t slot0 = (size_t)(first + l * wpc) * kRegion;
+      for (uint32_t b = 0; b < rc; b += kWave * 4u) {
+        uint32_t v[4], x[4];
 #pragma unroll
         for (uint32_t u = 0; u < 4; ++u) {
-          const uint32_t i = base + u * kWideBlock + tid;
-          live[u] = i < size;
-          slot[u] = 0;
+          const uint32_t i = b + u * kWave + lane;
           v[u] = 0;
-          if (live[u]) {
-            slot[u] = chunk_slot(m, c, i);
-            v[u] = val[slot[u]];
+          x[u] = 0;
+          if (i < rc) {
+            v[u] = src_val[slot0 + i];
+            x[u] = src_idx[slot0 + i];
           }
         }
 #pragma unroll
         for (uint32_t u = 0; u < 4; ++u) {
-          if (base + u * kWideBlock >= size) break;  // uniform
-          select_count<LEVEL>(S, v[u] & 0x7FFFFFFFu, idx + slot[u], live[u], tie_cnt, ties);
+          const uint32_t i = b + u * kWave + lane;
+          if (b + u * kWave >= rc) break;  // uniform
+          if (i < rc) {
+            dst_val[ro + i] = v[u];
+            dst_idx[ro + i] = x[u];
+          }
+          if (nb) select_count<2>(S, v[u] & 0x7FFFFFFFu, nullptr, i < rc, nullptr, nullptr);
         }
       }
+    }
+  }
+  __syncthreads();
+  if (nb == 0) return;
+  uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * kSlotGroup * kDigitBins;
+  const uint32_t used = S.slots.n * kDigitBins;
+  for (uint32_t i = tid; i < used; i += kWideBlock) part[i] = S.hist[i];
+}
+
+// Every other selection pass reads the dense list.
+template <int LEVEL>
+__global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientParams* __restrict__ params,
+                                                                 ClientCtl* __restrict__ ctls, Workspace ws,
+                                                                 uint32_t group) {
+  __shared__ SelectShared S;
+  const uint32_t client = blockIdx.y, tid = threadIdx.x, wave = tid / kWave;
+  const ClientParams& p = params[client];
+  ClientCtl* ctl = ctls + client;
+  const uint32_t r0 = group * kSlotGroup;
+  if (p.R <= r0) return;  // this client has no boundary in the group
+  const uint32_t nb = min(p.R - r0, kSlotGroup);
+  const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
+  const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.d;
+  uint2* ties = ws.tie_list + (size_t)client * kSlotGroup * kTieCap;
+  uint32_t* tie_cnt = ctl->tie_cnt[group];
+  select_setup<LEVEL>(S, ctl, r0, nb);
+
+  const uint32_t n = ctl->n_cand;
+  const uint32_t span = (uint32_t)(((uint64_t)n + gridDim.x - 1) / gridDim.x);
+  const uint64_t begin64 = (uint64_t)blockIdx.x * span;
+  const uint32_t begin = (uint32_t)(begin64 < n ? begin64 : n);
+  const uint32_t end = (uint32_t)(begin64 + span < n ? begin64 + span : n);
+  for (uint32_t base = begin; base < end; base += kWideBlock * 8u) {
+    uint32_t v[8];
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) {
+      const uint32_t i = base + u * kWideBlock + tid;
+      v[u] = 0;
+      if (i < end) v[u] = val[i];
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < 8; ++u) {
+      const uint32_t i = base + u * kWideBlock + tid;
+      if (base + u * kWideBlock + wave * kWave >= end) break;  // uniform per wavefront
+      select_count<LEVEL>(S, v[u] & 0x7FFFFFFFu, idx + i, i < end, tie_cnt, ties);
     }
   }
   __syncthreads();
@@ -784,9 +812,9 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
     // a class of equal keys straddles the boundary: find its quota-th member in position order
     const uint2* list = ws.tie_list + ((size_t)client * kSlotGroup + slot) * kTieCap;
     const uint32_t kept = ctl->tie_cnt[group][slot];
-    const uint32_t* __restrict__ val = ws.cand_val + (size_t)client * ws.d;
-    const uint32_t* __restrict__ idx = ws.cand_idx + (size_t)client * ws.d;
-    const uint32_t* __restrict__ region_cnt = ws.region_cnt + (size_t)client * ws.n_regions;
+    const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
+    const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.d;
+    const uint32_t n = ctl->n_cand;
     for (uint32_t b = 0; b < nb; ++b) {
       if (!s_need[b]) continue;  // uniform
       const uint32_t r = r0 + b, w_digit = s_digit[b], w_quota = s_quota[b];
@@ -804,27 +832,24 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
           }
         }
       } else {
-        // too many to keep aside: walk all the runs in position order
+        // too many to keep aside: walk the whole candidate list
         const uint32_t tau = (prefix << 10) | w_digit;
         uint32_t left = w_quota;
         __syncthreads();
         if (tid == 0) s_found = 0;
         __syncthreads();
-        for (uint32_t region = 0; region < ws.n_regions && !s_found; ++region) {
-          const uint32_t cnt = region_cnt[region];
-          for (uint32_t base = 0; base < cnt; base += kWideBlock) {
-            const uint32_t i = base + tid;
-            const uint32_t hit = (i < cnt && (val[(size_t)region * kRegion + i] & 0x7FFFFFFFu) == tau) ? 1u : 0u;
-            uint32_t tot;
-            const uint32_t rank = block_excl_scan<kWideWaves>(hit, scan_tmp, &tot);
-            if (hit && rank + 1 == left) {
-              ctl->iota[r] = idx[(size_t)region * kRegion + i];
-              s_found = 1;
-            }
-            __syncthreads();
-            if (s_found) break;
-            left -= tot;
+        for (uint32_t base = 0; base < n; base += kWideBlock) {
+          const uint32_t i = base + tid;
+          const uint32_t hit = (i < n && (val[i] & 0x7FFFFFFFu) == tau) ? 1u : 0u;
+          uint32_t tot;
+          const uint32_t rank = block_excl_scan<kWideWaves>(hit, scan_tmp, &tot);
+          if (hit && rank + 1 == left) {
+            ctl->iota[r] = idx[i];
+            s_found = 1;
           }
+          __syncthreads();
+          if (s_found || tot >= left) break;
+          left -= tot;
         }
         if (tid == 0 && !s_found) atomicOr(ws.status, CVLC_DEV_INTERNAL);
       }
@@ -876,11 +901,10 @@ __device__ __forceinline__ uint32_t classify_tie(const Thresholds& t, uint32_t k
 }
 
 constexpr uint32_t kNoGroup = 0xFFFFFFFFu;
-constexpr uint32_t kEmitBlock = 512;                    // threads of a count/emit workgroup
+constexpr uint32_t kEmitBlock = kSpan * kChunkSpans / 8u;  // threads of a count/emit workgroup: 8 candidates each
 constexpr uint32_t kEmitWaves = kEmitBlock / kWave;
-constexpr uint32_t kPerLane = 8;                        // candidates per lane per sweep
-constexpr uint32_t kSweep = kEmitBlock * kPerLane;      // candidates per sweep (4096)
-constexpr uint32_t kWaveSpan = kSweep / kEmitWaves;     // consecutive candidates one wavefront takes per sweep
+constexpr uint32_t kPerLane = kSpan / kWave;              // candidates per lane per span
+static_assert(kEmitWaves == kChunkSpans && kPerLane == 8, "one wavefront per span, eight rows of 64");
 
 // Lanes that hold a candidate of the caller's group (5-bit group id); lanes
 // with g == kNoGroup match nobody.  Must be reached by the whole wavefront.
@@ -894,135 +918,85 @@ __device__ __forceinline__ uint64_t same_group_lanes(uint32_t g) {
   return same;
 }
 
-// What a sweep records per candidate: its group and where it stands among the
-// candidates of the same group in its row of 64.
-__device__ __forceinline__ uint32_t row_pack(uint32_t grp, uint32_t below, uint32_t peers, bool leader) {
-  return grp | (below << 8) | (peers << 16) | (leader ? 1u << 24 : 0u);  // grp <= 31; below < 64; peers <= 64
-}
-__device__ __forceinline__ uint32_t row_group(uint32_t r) { return r & 0xFFu; }     // 0xFF: no candidate
-__device__ __forceinline__ uint32_t row_below(uint32_t r) { return (r >> 8) & 0xFFu; }
-__device__ __forceinline__ uint32_t row_peers(uint32_t r) { return (r >> 16) & 0xFFu; }
-__device__ __forceinline__ bool row_leader(uint32_t r) { return (r >> 24) & 1u; }
-constexpr uint32_t kRowNone = 0xFFu;
-
-// One sweep over a chunk: candidates [first, first + kSweep) in position order
-// (wavefront, j, lane).  Loads the value bits, classifies, and adds the
-// wavefront's group sizes to wcnt[0..R] (this wavefront's own LDS row; group R
-// collects what is dropped).  slot[j] is the candidate's place in the region-slot
-// arrays, row[j] its row_pack().
-__device__ __forceinline__ void classify_sweep(const Thresholds& thr, uint32_t R, const ChunkMap& m, uint32_t c,
-                                               uint32_t first, const uint32_t* __restrict__ val,
-                                               const uint32_t* __restrict__ idx, uint32_t (&slot)[kPerLane],
-                                               uint32_t (&v)[kPerLane], uint32_t (&row)[kPerLane],
-                                               volatile uint32_t* wcnt) {
-  const uint32_t lane = lane_id(), size = m.start[kChunkRegions];
-  const uint32_t mine = first + (threadIdx.x / kWave) * kWaveSpan + lane;
-#pragma unroll
-  for (uint32_t j = 0; j < kPerLane; ++j) {
-    const uint32_t i = mine + j * kWave;
-    slot[j] = 0;
-    v[j] = 0;
-    if (i < size) {
-      slot[j] = chunk_slot(m, c, i);
-      v[j] = val[slot[j]];
-    }
-  }
-  uint32_t key[kPerLane], grp[kPerLane];
-#pragma unroll
-  for (uint32_t j = 0; j < kPerLane; ++j) key[j] = v[j] & 0x7FFFFFFFu;
-  classify_keys<kPerLane>(thr, R, key, grp);
-#pragma unroll
-  for (uint32_t j = 0; j < kPerLane; ++j) {
-    const uint32_t i = mine + j * kWave;
-    row[j] = kRowNone;
-    if (i - lane >= size) continue;  // the whole row lies past the chunk's end (uniform)
-    const uint32_t g = i < size ? classify_tie(thr, key[j], grp[j], idx + slot[j]) : kNoGroup;
-    const uint64_t same = same_group_lanes(g);
-    if (g != kNoGroup) {
-      const uint32_t peers = (uint32_t)__popcll(same);
-      const bool leader = lane == (uint32_t)__builtin_ctzll(same);
-      row[j] = row_pack(g, lanes_below(same), peers, leader);
-      if (leader) wcnt[g] += peers;
-    }
-  }
-}
-
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = max(v, (uint32_t)__shfl_xor(v, o, 64));
   return v;
 }
 
+// Loads span `span` of the dense list (kPerLane candidates per lane, row j at
+// span*512 + j*64 + lane, i.e. in position order) and classifies them.
+// grp[j] = kNoGroup past the end of the list.
+__device__ __forceinline__ void classify_span(const Thresholds& thr, uint32_t R, const uint32_t* __restrict__ val,
+                                              const uint32_t* __restrict__ idx, uint32_t n, uint32_t span,
+                                              uint32_t (&v)[kPerLane], uint32_t (&grp)[kPerLane]) {
+  const uint32_t mine = span * kSpan + lane_id();
+  uint32_t key[kPerLane];
+#pragma unroll
+  for (uint32_t j = 0; j < kPerLane; ++j) {
+    const uint32_t i = mine + j * kWave;
+    v[j] = 0;
+    if (i < n) v[j] = val[i];
+    key[j] = v[j] & 0x7FFFFFFFu;
+  }
+  classify_keys<kPerLane>(thr, R, key, grp);
+#pragma unroll
+  for (uint32_t j = 0; j < kPerLane; ++j) {
+    const uint32_t i = mine + j * kWave;
+    grp[j] = i < n ? classify_tie(thr, key[j], grp[j], idx + i) : kNoGroup;
+  }
+}
+
 // ------------------------------------------------------------------ 6. group counts and statistics
-// One workgroup per chunk: the number of candidates of every group in the chunk
-// (for the records' places in the stream), and every group's min, max and sum
-// of squares.  Counts and statistics are kept in LDS columns private to a lane
-// id, so that the LDS atomics of one instruction never collide; the counts are
-// reduced per chunk, the statistics once.
+// Every wavefront takes spans of 512 candidates (gw, gw + wavefronts, ...) and
+// writes, per span, the number of members of every group (for the records'
+// places in the stream).  Min, max and sum of squares of the groups go to LDS
+// columns private to a lane id, so that the LDS atomics of one instruction never
+// collide; they are reduced once at the end.  Wavefronts do not wait for each
+// other before that.
 __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* __restrict__ params,
                                                            ClientCtl* __restrict__ ctls, Workspace ws) {
   __shared__ Thresholds thr;
-  __shared__ ChunkMap map[2];
-  __shared__ uint32_t s_cnt[33][kWave];  // group sizes of the current chunk, per lane id
   __shared__ uint32_t s_max[33][kWave], s_negmin[33][kWave];
   __shared__ double s_sq[33][kWave];
   const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  const uint32_t R = p.R, n_chunks = ws.n_chunks;
-  const uint32_t* __restrict__ val = ws.cand_val + (size_t)client * ws.d;
-  const uint32_t* __restrict__ idx = ws.cand_idx + (size_t)client * ws.d;
-  const uint32_t* __restrict__ region_off = ws.region_off + (size_t)client * (ws.n_regions + 1);
+  const uint32_t R = p.R, n = ctl->n_cand;
+  const uint32_t n_spans = (n + kSpan - 1) / kSpan;
+  const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
+  const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.d;
+  uint32_t* __restrict__ span_cnt = ws.span_cnt + (size_t)client * (ws.max_spans + 1) * 32;
   load_thresholds(thr, ctl, R);
-  if (blockIdx.x < n_chunks) load_chunk_map(map[0], region_off, ws.n_regions, blockIdx.x, tid);
   for (uint32_t i = tid; i < 33 * kWave; i += kEmitBlock) {
     (&s_max[0][0])[i] = 0;
     (&s_negmin[0][0])[i] = 0;
     (&s_sq[0][0])[i] = 0.0;
   }
-  uint32_t cur = 0;
-  for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x, cur ^= 1u) {
-    for (uint32_t i = tid; i < 33 * kWave; i += kEmitBlock) (&s_cnt[0][0])[i] = 0;
-    __syncthreads();
-    // the next chunk's map travels while this one is worked on
-    if (c + gridDim.x < n_chunks) load_chunk_map(map[cur ^ 1u], region_off, ws.n_regions, c + gridDim.x, tid);
-    const ChunkMap& m = map[cur];
-    const uint32_t size = m.start[kChunkRegions];
-    for (uint32_t first = 0; first < size; first += kSweep) {
-      if (first + wave * kWaveSpan >= size) break;  // nothing left for this wavefront (uniform)
-      const uint32_t mine = first + wave * kWaveSpan + lane;
-      uint32_t slot[kPerLane], v[kPerLane], key[kPerLane], grp[kPerLane];
+  __syncthreads();
+  for (uint32_t span = blockIdx.x * kEmitWaves + wave; span < n_spans; span += gridDim.x * kEmitWaves) {
+    uint32_t v[kPerLane], grp[kPerLane];
+    classify_span(thr, R, val, idx, n, span, v, grp);
+    // lane r ends up with the span's size of group r
+    uint32_t mine = 0;
+    for (uint32_t r = 0; r <= R; ++r) {
+      uint32_t tot = 0;
 #pragma unroll
-      for (uint32_t j = 0; j < kPerLane; ++j) {
-        const uint32_t i = mine + j * kWave;
-        slot[j] = 0;
-        v[j] = 0;
-        if (i < size) {
-          slot[j] = chunk_slot(m, c, i);
-          v[j] = val[slot[j]];
-        }
-        key[j] = v[j] & 0x7FFFFFFFu;
-      }
-      classify_keys<kPerLane>(thr, R, key, grp);
+      for (uint32_t j = 0; j < kPerLane; ++j) tot += (uint32_t)__popcll(__ballot(grp[j] == r));
+      if (lane == r) mine = tot;
+    }
+    if (lane < 32) span_cnt[(size_t)span * 32 + lane] = mine;
 #pragma unroll
-      for (uint32_t j = 0; j < kPerLane; ++j) {
-        if (mine + j * kWave < size) {
-          const uint32_t g = classify_tie(thr, key[j], grp[j], idx + slot[j]);
-          const float x = __uint_as_float(v[j]);
-          const uint32_t o = ordered_bits(x);
-          atomicAdd(&s_cnt[g][lane], 1u);
-          atomicMax(&s_max[g][lane], o);
-          atomicMax(&s_negmin[g][lane], ~o);
-          atomicAdd(&s_sq[g][lane], (double)x * (double)x);
-        }
+    for (uint32_t j = 0; j < kPerLane; ++j) {
+      const uint32_t g = grp[j];
+      if (g != kNoGroup) {
+        const float x = __uint_as_float(v[j]);
+        const uint32_t o = ordered_bits(x);
+        atomicMax(&s_max[g][lane], o);
+        atomicMax(&s_negmin[g][lane], ~o);
+        atomicAdd(&s_sq[g][lane], (double)x * (double)x);
       }
     }
-    __syncthreads();
-    for (uint32_t g = wave; g < 32; g += kEmitWaves) {
-      const uint32_t tot = g <= R ? wave_sum_u32(s_cnt[g][lane]) : 0u;
-      if (lane == 0) ws.chunk_cnt[((size_t)client * n_chunks + c) * 32 + g] = tot;
-    }
-    __syncthreads();
   }
   __syncthreads();
   // group g's columns are reduced by wavefront g mod 8; finite values never code to 0, so 0 = no member here
@@ -1041,12 +1015,13 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
 // ------------------------------------------------------------------ 7. layout: prefix, headers, statistics
 typedef uint32_t __attribute__((address_space(1))) * GlobalWordPtr;
 
-// One workgroup of 1024 threads per client.  Wavefront w turns the per-chunk
-// counts of groups w, w+16, ... into exclusive prefixes (in place), checks the
-// totals against the plan, and clears the first and the last stream word of
-// every (chunk, group) record run: those two words can be shared with the
-// neighbouring chunks, which OR their bits in; all other payload words have one
-// owner and are stored whole.  Then the headers and the statistics block.
+// One workgroup of 1024 threads per client.  Wavefront w turns the per-span
+// counts of groups w, w+16, ... into exclusive prefixes (in place; the row after
+// the last span receives the totals), checks the totals against the plan, and
+// clears the first and the last stream word of every (chunk, group) record run,
+// a chunk being 8 spans: those two words can be shared with the neighbouring
+// chunks, which OR their bits in; all other payload words have one owner and are
+// stored whole.  Then the headers and the statistics block.
 __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* __restrict__ params,
                                                             ClientCtl* __restrict__ ctls, Workspace ws,
                                                             cvlc_seg_stats_t* __restrict__ stats_out) {
@@ -1055,10 +1030,11 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
   const uint32_t client = blockIdx.x, tid = threadIdx.x;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  const uint32_t R = p.R, n_chunks = ws.n_chunks, sbits = position_bits(ws.d);
+  const uint32_t R = p.R, sbits = position_bits(ws.d);
+  const uint32_t n_spans = (ctl->n_cand + kSpan - 1) / kSpan;
   const uint32_t lane = lane_id(), wave = tid / kWave;
   GlobalWordPtr stream = (GlobalWordPtr)p.stream;
-  uint32_t* cnt = ws.chunk_cnt + (size_t)client * n_chunks * 32;
+  uint32_t* cnt = ws.span_cnt + (size_t)client * (ws.max_spans + 1) * 32;
   if (tid == 0) {
     uint32_t w = kGlobalHeaderWords + kSegHeaderWords * R;
     for (uint32_t r = 0; r < R; ++r) {
@@ -1067,28 +1043,34 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
     }
   }
   __syncthreads();
-  for (uint32_t g = wave; g < R; g += kWideWaves) {
-    const uint32_t W = sbits + p.y[g];
-    const uint32_t P = p.Z[g] - (g ? p.Z[g - 1] : 0u);
+  for (uint32_t g = wave; g < 32; g += kWideWaves) {
+    const uint32_t W = g < R ? sbits + p.y[g] : 0u;
+    const uint32_t P = g < R ? p.Z[g] - (g ? p.Z[g - 1] : 0u) : 0u;
     uint32_t run = 0;
-    for (uint32_t c0 = 0; c0 < n_chunks; c0 += kWave) {
+    for (uint32_t c0 = 0; c0 < n_spans; c0 += kWave) {  // c0 is a multiple of 64, hence of the chunk size
       const uint32_t c = c0 + lane;
-      const uint32_t v = c < n_chunks ? cnt[(size_t)c * 32 + g] : 0u;
+      const uint32_t v = c < n_spans ? cnt[(size_t)c * 32 + g] : 0u;
       const uint32_t incl = wave_incl_scan_u32(v);
       const uint32_t excl = run + incl - v;
-      if (c < n_chunks) {
+      run += __shfl(incl, 63, 64);
+      // the chunk that starts at span c ends where the chunk 8 spans on starts
+      const uint32_t next = __shfl_down(excl, kChunkSpans, 64);
+      const uint32_t chunk_end = lane + kChunkSpans < kWave ? next : run;
+      if (c < n_spans) {
         cnt[(size_t)c * 32 + g] = excl;
         // a consistent selection never passes the planned size; the test keeps the two
         // stores inside the group's payload even if an internal check has failed
-        if (v && excl + v <= P) {
-          const uint64_t bit0 = (uint64_t)excl * W, bit1 = (uint64_t)(excl + v) * W;
+        if (g < R && c % kChunkSpans == 0 && chunk_end > excl && chunk_end <= P) {
+          const uint64_t bit0 = (uint64_t)excl * W, bit1 = (uint64_t)chunk_end * W;
           stream[s_payload[g] + (uint32_t)(bit0 >> 5)] = 0;
           stream[s_payload[g] + (uint32_t)((bit1 - 1) >> 5)] = 0;
         }
       }
-      run += __shfl(incl, 63, 64);
     }
-    if (lane == 0 && run != P) atomicOr(ws.status, CVLC_DEV_INTERNAL);
+    if (lane == 0) {
+      cnt[(size_t)n_spans * 32 + g] = run;
+      if (g < R && run != P) atomicOr(ws.status, CVLC_DEV_INTERNAL);
+    }
   }
   // energy of the coordinates the filter dropped, region by region
   const double* rsq = ws.region_sumsq + (size_t)client * ws.n_regions;
@@ -1184,199 +1166,141 @@ __device__ __forceinline__ uint32_t quantise(float x, float m, float inv, uint32
 
 
 
-constexpr uint32_t kStageWords = kSweep * 2 + 2 * 32;  // every record is < 64 bits; two edge words per group
 
-// One workgroup per chunk.  A sweep of up to 4096 candidates is classified,
-// every coded one gets its record number inside its group (members in earlier
-// chunks from the layout's prefix, then earlier sweeps, earlier wavefronts,
-// earlier rows, lower lanes), is quantised and OR-ed into an LDS image of the
-// stream words its group's run covers.  The image is then written out: the
-// chunk's first and last word of a group can be shared with a neighbouring
-// chunk and are OR-ed into the (cleared) stream; a word left unfinished by a
-// sweep is carried in LDS into the next sweep's image; all others are stored
-// whole.
+constexpr uint32_t kChunkCands = kSpan * kChunkSpans;         // 4096
+constexpr uint32_t kStageWords = kChunkCands * 2 + 2 * 32;    // every record is < 64 bits; two edge words per group
+
+// One workgroup per chunk of 4096 candidates, one wavefront per span.  Every
+// coded candidate gets its record number inside its group (members in earlier
+// spans from the layout's prefix, then earlier rows, then lower lanes), is
+// quantised and OR-ed into an LDS image of the stream words its group's run
+// covers.  The image is then written out: a group's first and last word can be
+// shared with a neighbouring chunk and are OR-ed into the (cleared) stream, all
+// others are stored whole.
 __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const ClientParams* __restrict__ params,
                                                           ClientCtl* __restrict__ ctls, Workspace ws, uint64_t seed) {
   __shared__ Thresholds thr;
-  __shared__ ChunkMap map[2];
-  __shared__ uint32_t s_run_first[2][32], s_run_last[2][32];  // the chunk's record run of every group: [first, last)
   __shared__ uint32_t s_stage[kStageWords];
-  __shared__ uint32_t s_wcnt[kEmitWaves][32];      // per wavefront, per group: members in this sweep, then running rank
-  __shared__ uint32_t s_base[32];                  // record number of the sweep's first member of each group
-  __shared__ uint32_t s_lim[32];                   // one past the sweep's last record number
-  __shared__ uint32_t s_word0[32];                 // first stream word (group-relative) the sweep touches
-  __shared__ uint32_t s_nwords[32];                // words the sweep touches in each group
+  __shared__ uint32_t s_wrun[kEmitWaves][32];      // per wavefront, per group: record number of its next member
+  __shared__ uint32_t s_lim[32];                   // one past the chunk's last record number in each group
+  __shared__ uint32_t s_word0[32];                 // first stream word (group-relative) the chunk touches
+  __shared__ uint32_t s_nwords[32];                // words the chunk touches in each group
   __shared__ uint32_t s_stage_off[33];
-  __shared__ uint32_t s_edge[32];                  // bit 0: first word is OR-ed, bit 1: last word is OR-ed, bit 2: last word is carried
-  __shared__ uint32_t s_carry[32];                 // a word the sweep before left unfinished, valid while s_has_carry
-  __shared__ uint32_t s_has_carry[32];
-  __shared__ uint32_t s_payload[32];               // first stream word of each group's payload
-  __shared__ uint32_t s_P[32], s_W[32], s_y[32];
+  __shared__ uint32_t s_payload[32], s_W[32], s_y[32];
   __shared__ float s_m[32], s_inv[32];
   const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  const uint32_t R = p.R, sbits = position_bits(ws.d), n_chunks = ws.n_chunks;
-  const uint32_t* __restrict__ val = ws.cand_val + (size_t)client * ws.d;
-  const uint32_t* __restrict__ idx = ws.cand_idx + (size_t)client * ws.d;
-  const uint32_t* __restrict__ region_off = ws.region_off + (size_t)client * (ws.n_regions + 1);
-  const uint32_t* __restrict__ chunk_cnt = ws.chunk_cnt + (size_t)client * n_chunks * 32;
+  const uint32_t n = ctl->n_cand;
+  const uint32_t n_spans = (n + kSpan - 1) / kSpan;
+  const uint32_t R = p.R, sbits = position_bits(ws.d);
+  const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
+  const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.d;
+  const uint32_t* __restrict__ prefix = ws.span_cnt + (size_t)client * (ws.max_spans + 1) * 32;
   GlobalWordPtr stream = (GlobalWordPtr)p.stream;
   const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32), client_id = p.client_id;
 
-  // the chunk's record runs: from the layout's prefix, clamped so that every write stays inside
-  // the group's payload even if an internal check has failed
-  auto load_runs = [&](uint32_t buf, uint32_t c) {
-    if (tid < 32) {
-      uint32_t first = 0, last = 0;
-      if (tid < R) {
-        const uint32_t P = p.Z[tid] - (tid ? p.Z[tid - 1] : 0u);
-        first = chunk_cnt[(size_t)c * 32 + tid];
-        last = c + 1 < n_chunks ? chunk_cnt[(size_t)(c + 1) * 32 + tid] : P;
-        if (first > P) first = P;
-        if (last > P) last = P;
-        if (last < first) last = first;
-      }
-      s_run_first[buf][tid] = first;
-      s_run_last[buf][tid] = last;
-    }
-  };
-
   load_thresholds(thr, ctl, R);
-  if (tid < 32) {
+  uint32_t my_P = 0, my_W = 0;
+  if (tid < 32 && tid < R) {
     const GroupInfo* gi = ws.group_info + client;
-    const bool live = tid < R;
-    s_payload[tid] = live ? gi->payload[tid] : 0u;
-    s_P[tid] = live ? gi->P[tid] : 0u;
-    s_W[tid] = live ? gi->W[tid] : 0u;
-    s_y[tid] = live ? gi->y[tid] : 0u;
-    s_m[tid] = live ? gi->m[tid] : 0.0f;
-    s_inv[tid] = live ? gi->inv[tid] : 0.0f;
+    my_P = gi->P[tid];
+    my_W = gi->W[tid];
+    s_payload[tid] = gi->payload[tid];
+    s_y[tid] = gi->y[tid];
+    s_m[tid] = gi->m[tid];
+    s_inv[tid] = gi->inv[tid];
   }
-  if (blockIdx.x < n_chunks) {
-    load_chunk_map(map[0], region_off, ws.n_regions, blockIdx.x, tid);
-    load_runs(0, blockIdx.x);
+  for (uint32_t c = blockIdx.x; c * kChunkSpans < n_spans; c += gridDim.x) {
+  __syncthreads();  // the chunk before is written out
+  {  // every wavefront: the record numbers its span starts at
+    const uint32_t span = c * kChunkSpans + wave;
+    if (lane < 32) s_wrun[wave][lane] = span < n_spans ? prefix[(size_t)span * 32 + lane] : 0u;
   }
-  uint32_t cur = 0;
-  for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x, cur ^= 1u) {
-    __syncthreads();
-    if (c + gridDim.x < n_chunks) {  // the next chunk's map and runs travel while this one is worked on
-      load_chunk_map(map[cur ^ 1u], region_off, ws.n_regions, c + gridDim.x, tid);
-      load_runs(cur ^ 1u, c + gridDim.x);
+  if (tid < 32) {
+    const uint32_t r = tid;
+    uint32_t nwords = 0, W = 0;
+    if (r < R) {
+      const uint32_t P = my_P;
+      W = my_W;
+      // the chunk's record run of group r: [first, last), clamped so that every write stays inside
+      // the group's payload even if an internal check has failed
+      const uint32_t last_span = min((c + 1) * kChunkSpans, n_spans);
+      uint32_t first = prefix[(size_t)c * kChunkSpans * 32 + r];
+      uint32_t last = prefix[(size_t)last_span * 32 + r];
+      if (last > P) last = P;
+      if (first > last) first = last;
+      s_lim[r] = last;
+      if (last > first) {
+        const uint64_t bit0 = (uint64_t)first * W, bit1 = (uint64_t)last * W;
+        s_word0[r] = (uint32_t)(bit0 >> 5);
+        nwords = (uint32_t)(((bit1 - 1) >> 5) - (bit0 >> 5) + 1);
+      }
     }
-    if (tid < 32) {
-      s_base[tid] = s_run_first[cur][tid];
-      s_has_carry[tid] = 0;
-    }
-    const ChunkMap& m = map[cur];
-    const uint32_t* run_first = s_run_first[cur];
-    const uint32_t* run_last = s_run_last[cur];
-    const uint32_t size = m.start[kChunkRegions];
-    for (uint32_t first = 0; first < size; first += kSweep) {
-      __syncthreads();
-      for (uint32_t i = tid; i < kEmitWaves * 32; i += kEmitBlock) (&s_wcnt[0][0])[i] = 0;
-      __syncthreads();
-      uint32_t slot[kPerLane], v[kPerLane], row[kPerLane];
-      volatile uint32_t* wrun = s_wcnt[wave];
-      classify_sweep(thr, R, m, c, first, val, idx, slot, v, row, wrun);
-      uint32_t pid[kPerLane];
+    s_W[r] = W;
+    s_nwords[r] = nwords;
+    // exclusive prefix of the staged word counts over the groups
+    const uint32_t incl = wave_incl_scan_u32(nwords);
+    s_stage_off[r] = incl - nwords;
+    if (r == 31) s_stage_off[32] = incl;
+  }
+  __syncthreads();
+  const uint32_t staged = s_stage_off[32];
+  for (uint32_t i = tid; i < staged; i += kEmitBlock) s_stage[i] = 0;
+
+  uint32_t v[kPerLane], grp[kPerLane], pid[kPerLane];
+  classify_span(thr, R, val, idx, n, c * kChunkSpans + wave, v, grp);
 #pragma unroll
-      for (uint32_t j = 0; j < kPerLane; ++j) pid[j] = (row_group(row[j]) < R) ? idx[slot[j]] : 0u;
-      __syncthreads();
-      uint32_t before = 0;  // lane g of every wavefront: members of g in the sweep's earlier wavefronts
-      if (lane < 32)
-        for (uint32_t w = 0; w < wave; ++w) before += s_wcnt[w][lane];
-      if (tid < 32) {
-        const uint32_t r = tid;
-        uint32_t cnt = 0;
-        for (uint32_t w = 0; w < kEmitWaves; ++w) cnt += s_wcnt[w][r];
-        uint32_t nwords = 0, edge = 0;
-        if (r < R) {
-          const uint32_t e0 = s_base[r];
-          if (cnt > run_last[r] - e0) cnt = run_last[r] - e0;
-          s_lim[r] = e0 + cnt;
-          if (cnt) {
-            const uint64_t bit0 = (uint64_t)e0 * s_W[r], bit1 = (uint64_t)(e0 + cnt) * s_W[r];
-            s_word0[r] = (uint32_t)(bit0 >> 5);
-            nwords = (uint32_t)(((bit1 - 1) >> 5) - (bit0 >> 5) + 1);
-            // first word: the chunk's first may be shared with the chunk before (OR); later sweeps own theirs
-            if (e0 == run_first[r]) edge |= 1u;
-            // last word: the chunk's last may be shared with the chunk after (OR); an earlier sweep's
-            // unfinished last word is carried into the next sweep instead of being written
-            if (e0 + cnt == run_last[r]) edge |= 2u;
-            else if (bit1 & 31u) edge |= 4u;
-          }
-        }
-        s_nwords[r] = nwords;
-        s_edge[r] = edge;
-      }
-      __syncthreads();
-      if (lane < 32) wrun[lane] = before;
-      if (tid == 0) {
-        uint32_t off = 0;
-        for (uint32_t r = 0; r < 32; ++r) { s_stage_off[r] = off; off += s_nwords[r]; }
-        s_stage_off[32] = off;
-      }
-      __syncthreads();
-      const uint32_t staged = s_stage_off[32];
-      for (uint32_t i = tid; i < staged; i += kEmitBlock) s_stage[i] = 0;
-      __syncthreads();
-      if (tid < 32 && s_nwords[tid] && s_has_carry[tid]) {  // the word the sweep before left unfinished
-        s_stage[s_stage_off[tid]] = s_carry[tid];
-        s_has_carry[tid] = 0;
-      }
-      __syncthreads();
+  for (uint32_t j = 0; j < kPerLane; ++j) {
+    const uint32_t i = (c * kChunkSpans + wave) * kSpan + j * kWave + lane;
+    pid[j] = grp[j] < R ? idx[i] : 0u;
+  }
+  __syncthreads();
+  volatile uint32_t* wrun = s_wrun[wave];
 #pragma unroll
-      for (uint32_t j = 0; j < kPerLane; ++j) {
-        const uint32_t g = row_group(row[j]);
-        if (g != kRowNone) {
-          const uint32_t start = wrun[g];
-          const uint32_t rank = start + row_below(row[j]);
-          if (row_leader(row[j])) wrun[g] = start + row_peers(row[j]);
-          if (g < R && s_base[g] + rank < s_lim[g]) {
-            const uint32_t y = s_y[g], W = s_W[g];
-            uint32_t cid;
-            if (y == 32) {
-              cid = v[j];
-            } else {
-              const uint32_t u24 = philox_word0(pid[j], client_id, k0, k1) >> 8;
-              cid = quantise(__uint_as_float(v[j]), s_m[g], s_inv[g], y, u24);
-            }
-            const uint64_t record = (uint64_t)pid[j] | ((uint64_t)cid << sbits);
-            const uint64_t bit = (uint64_t)(s_base[g] + rank) * W - (uint64_t)s_word0[g] * 32u;
-            const uint32_t w0 = s_stage_off[g] + (uint32_t)(bit >> 5), sh = (uint32_t)(bit & 31u);
-            const uint64_t lo = record << sh;
-            atomicOr(&s_stage[w0], (uint32_t)lo);
-            if (sh + W > 32u) atomicOr(&s_stage[w0 + 1], (uint32_t)(lo >> 32));
-            if (sh + W > 64u) atomicOr(&s_stage[w0 + 2], (uint32_t)(record >> (64u - sh)));
-          }
-        }
-      }
-      __syncthreads();
-      for (uint32_t i = tid; i < staged; i += kEmitBlock) {
-        uint32_t lo = 0, hi = 32;  // group whose staged words hold word i: last g with s_stage_off[g] <= i
-        while (hi - lo > 1) {
-          const uint32_t mid = (lo + hi) >> 1;
-          if (s_stage_off[mid] <= i) lo = mid; else hi = mid;
-        }
-        const uint32_t g = lo, rel = i - s_stage_off[g];
-        GlobalWordPtr dst = stream + s_payload[g] + s_word0[g] + rel;
-        const uint32_t word = s_stage[i];
-        const uint32_t edge = s_edge[g];
-        const bool is_last = rel == s_nwords[g] - 1;
-        if (is_last && (edge & 4u)) {
-          s_carry[g] = word;
-          s_has_carry[g] = 1u;
-        } else if ((rel == 0 && (edge & 1u)) || (is_last && (edge & 2u))) {
-          if (word) atomicOr((uint32_t*)dst, word);
+  for (uint32_t j = 0; j < kPerLane; ++j) {
+    const uint32_t g = grp[j] < R ? grp[j] : kNoGroup;  // dropped candidates take no record
+    const uint64_t same = same_group_lanes(g);
+    if (g != kNoGroup) {
+      const uint32_t start = wrun[g];
+      const uint32_t e = start + lanes_below(same);
+      if (lane == (uint32_t)__builtin_ctzll(same)) wrun[g] = start + (uint32_t)__popcll(same);
+      if (e < s_lim[g]) {
+        const uint32_t y = s_y[g], W = s_W[g];
+        uint32_t cid;
+        if (y == 32) {
+          cid = v[j];
         } else {
-          *dst = word;
+          const uint32_t u24 = philox_word0(pid[j], client_id, k0, k1) >> 8;
+          cid = quantise(__uint_as_float(v[j]), s_m[g], s_inv[g], y, u24);
         }
+        const uint64_t record = (uint64_t)pid[j] | ((uint64_t)cid << sbits);
+        const uint64_t bit = (uint64_t)e * W - (uint64_t)s_word0[g] * 32u;
+        const uint32_t w0 = s_stage_off[g] + (uint32_t)(bit >> 5), sh = (uint32_t)(bit & 31u);
+        const uint64_t lo = record << sh;
+        atomicOr(&s_stage[w0], (uint32_t)lo);
+        if (sh + W > 32u) atomicOr(&s_stage[w0 + 1], (uint32_t)(lo >> 32));
+        if (sh + W > 64u) atomicOr(&s_stage[w0 + 2], (uint32_t)(record >> (64u - sh)));
       }
-      __syncthreads();
-      if (tid < R) s_base[tid] = s_lim[tid];
     }
   }
+  __syncthreads();
+  for (uint32_t i = tid; i < staged; i += kEmitBlock) {
+    uint32_t lo = 0, hi = 32;  // group whose staged words hold word i: last g with s_stage_off[g] <= i
+    while (hi - lo > 1) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (s_stage_off[mid] <= i) lo = mid; else hi = mid;
+    }
+    const uint32_t g = lo, rel = i - s_stage_off[g];
+    GlobalWordPtr dst = stream + s_payload[g] + s_word0[g] + rel;
+    const uint32_t word = s_stage[i];
+    if (rel == 0 || rel == s_nwords[g] - 1) {
+      if (word) atomicOr((uint32_t*)dst, word);
+    } else {
+      *dst = word;
+    }
+  }
+  }  // chunks
 }
 
 // ------------------------------------------------------------------ host side
@@ -1457,13 +1381,15 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   ws.region_sumsq = reinterpret_cast<double*>(base + L.region_sumsq);
   ws.cand_idx = reinterpret_cast<uint32_t*>(base + L.cand_idx);
   ws.cand_val = reinterpret_cast<uint32_t*>(base + L.cand_val);
-  ws.chunk_cnt = reinterpret_cast<uint32_t*>(base + L.chunk_cnt);
+  ws.dense_idx = reinterpret_cast<uint32_t*>(base + L.dense_idx);
+  ws.dense_val = reinterpret_cast<uint32_t*>(base + L.dense_val);
+  ws.span_cnt = reinterpret_cast<uint32_t*>(base + L.span_cnt);
   ws.group_info = reinterpret_cast<GroupInfo*>(base + L.group_info);
   ws.tie_list = reinterpret_cast<uint2*>(base + L.tie_list);
   ws.sel_part = reinterpret_cast<uint32_t*>(base + L.sel_part);
   ws.d = d;
   ws.n_regions = L.n_regions;
-  ws.n_chunks = L.n_chunks;
+  ws.max_spans = L.max_spans;
   ws.filter_blocks = filter_blocks_per_client(L.n_regions, n, filter_resident_blocks());
   ws.sel_blocks = L.sel_blocks;
 
@@ -1534,17 +1460,19 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
     StageScope scope(CVLC_STAGE_ENC_SELECT, stream);
     const dim3 grid(L.sel_blocks, n);
     const uint32_t groups = (max_R + kSlotGroup - 1) / kSlotGroup;
+    // level 2 of the first group of boundaries also builds the dense candidate list (also when nothing is coded)
+    hipLaunchKernelGGL(gather_l2_kernel, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
     for (uint32_t gr = 0; gr < groups; ++gr) {
-      hipLaunchKernelGGL(select_pass_kernel<2>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+      if (gr > 0)
+        hipLaunchKernelGGL(select_pass_kernel<2>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
       hipLaunchKernelGGL(select_walk_kernel<2>, dim3(kSlotGroup, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
       hipLaunchKernelGGL(select_pass_kernel<3>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
       hipLaunchKernelGGL(select_walk_kernel<3>, dim3(kSlotGroup, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
     }
   }
-  // count/emit workgroups per client: what the device holds at once (four and two per CU), each walking several chunks
-  uint32_t g_count = (1024u + n - 1) / n, g_emit = (512u + n - 1) / n;
-  if (g_count > L.n_chunks) g_count = L.n_chunks;
-  if (g_emit > L.n_chunks) g_emit = L.n_chunks;
+  // count: wavefronts walk the spans; about what the device holds at once (four workgroups per CU)
+  uint32_t g_count = (1024u + n - 1) / n;
+  if (g_count > (L.max_spans + kEmitWaves - 1) / kEmitWaves) g_count = (L.max_spans + kEmitWaves - 1) / kEmitWaves;
   {
     StageScope scope(CVLC_STAGE_ENC_CLASSIFY, stream);
     hipLaunchKernelGGL(count_kernel, dim3(g_count, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws);
@@ -1554,7 +1482,11 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
     hipLaunchKernelGGL(layout_kernel, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, d_stats_out);
   }
   {
+    // emit: workgroups walk the chunks; about what the device holds at once (three per CU)
     StageScope scope(CVLC_STAGE_ENC_EMIT, stream);
+    uint32_t g_emit = (768u + n - 1) / n;
+    const uint32_t max_chunks = (L.max_spans + kChunkSpans - 1) / kChunkSpans;
+    if (g_emit > max_chunks) g_emit = max_chunks;
     hipLaunchKernelGGL(emit_kernel, dim3(g_emit, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws, seed);
   }
   return hip_check(hipGetLastError());
