@@ -113,6 +113,26 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
   return v;
 }
 
+// Exclusive prefix sum of one value per thread over a workgroup of NW
+// wavefronts, in thread order; *total receives the sum.  `scratch` holds NW words.
+template <uint32_t NW>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
+  const uint32_t incl = wave_incl_scan_u32(v);
+  const uint32_t wave = threadIdx.x / kWave;
+  __syncthreads();
+  if (lane_id() == kWave - 1) scratch[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0, sum = 0;
+#pragma unroll
+  for (uint32_t w = 0; w < NW; ++w) {
+    const uint32_t t = scratch[w];
+    if (w < wave) before += t;
+    sum += t;
+  }
+  *total = sum;
+  return before + incl - v;
+}
+
 // hist[bin] += 1 for every lane with `active`, using one LDS atomic per distinct
 // bin in the wavefront (lanes that share a bin elect the lowest one).  Must be
 // reached by all lanes of the wavefront.  `bin` must fit in NBITS bits.

@@ -7,7 +7,10 @@
 // slice of every list that falls into its tile, accumulates in LDS in fp64 and
 // writes the tile once; nothing is scattered into global memory.
 //   parse_headers  validate headers, build one descriptor per list
-//   tile_table     for every list, the first record of every output tile
+//   compact_lists  the non-empty lists, numbered consecutively, with the
+//                  tile_table work items they need
+//   tile_table     one streaming pass over all records: for every list, the
+//                  first record of every output tile (and the order/range checks)
 //   decode_tiles   fused decode + accumulate + single write of each tile
 #include <hip/hip_runtime.h>
 
@@ -19,8 +22,27 @@
 namespace cvlc {
 namespace {
 
+constexpr uint32_t kListsPerClient = 32;   // descriptor slots per client (CVLC_MAX_CODED used)
+constexpr uint32_t kTabChunk = 2048;       // records per tile_table work item
+constexpr uint32_t kTabWords = kTabChunk / 32u * 63u + 8u;  // words such a chunk can span, plus the record before it
+constexpr uint32_t kListBatch = 512;       // lists a decode workgroup handles per sweep
+
+struct CompactDesc {  // one non-empty (client, group) record list, 32 bytes
+  const uint32_t* payload;
+  double weight;  // w_i
+  uint32_t P;
+  uint32_t wsy;   // W | s << 8 | y << 16
+  float m, step;
+};
+static_assert(sizeof(CompactDesc) == 32, "CompactDesc is copied to LDS as two 16-byte pieces");
+
+struct DecodeCtl {  // written by compact_lists
+  uint32_t n_active;  // non-empty lists
+  uint32_t n_items;   // tile_table work items in all
+};
+
 struct DecodeLayout {
-  size_t status, streams, desc, table, total;
+  size_t status, ctl, streams, desc, cdesc, item_start, table, total;
   uint32_t n_tiles, n_lists;
 };
 
@@ -37,11 +59,14 @@ struct StreamArg {  // per-stream inputs, uploaded through kernel arguments
 DecodeLayout decode_layout(uint32_t d, uint32_t n) {
   DecodeLayout L;
   L.n_tiles = (uint32_t)(((uint64_t)d + kDecTile - 1) / kDecTile);
-  L.n_lists = n * CVLC_MAX_CODED;
+  L.n_lists = n * kListsPerClient;
   size_t off = 0;
   L.status = off; off = align256(off + 256);
+  L.ctl = off; off = align256(off + sizeof(DecodeCtl));
   L.streams = off; off = align256(off + (size_t)n * sizeof(StreamArg));
   L.desc = off; off = align256(off + (size_t)L.n_lists * sizeof(ListDesc));
+  L.cdesc = off; off = align256(off + (size_t)L.n_lists * sizeof(CompactDesc));
+  L.item_start = off; off = align256(off + ((size_t)L.n_lists + 1) * sizeof(uint32_t));
   L.table = off; off = align256(off + (size_t)(L.n_tiles + 1) * L.n_lists * sizeof(uint32_t));
   L.total = off;
   return L;
@@ -59,8 +84,8 @@ __global__ void upload_kernel(uint32_t* dst, UploadChunk c) {
 
 // Bits [bit, bit + W) of a little-endian word array, W <= 63.  Reads the three
 // words the field can touch; `n_words` bounds the reads.
-__device__ __forceinline__ uint64_t read_bits(const uint32_t* __restrict__ words, uint64_t n_words, uint64_t bit,
-                                              uint32_t W) {
+template <typename WordPtr>
+__device__ __forceinline__ uint64_t read_bits(WordPtr words, uint64_t n_words, uint64_t bit, uint32_t W) {
   const uint64_t w = bit >> 5;
   const uint32_t sh = (uint32_t)(bit & 31u);
   const uint64_t a = words[w];
@@ -81,7 +106,7 @@ __global__ __launch_bounds__(64) void parse_headers_kernel(const StreamArg* __re
   const uint32_t client = blockIdx.x, t = threadIdx.x;
   const StreamArg sa = streams[client];
   const uint32_t* w = sa.words;
-  ListDesc* out = descs + (size_t)client * CVLC_MAX_CODED;
+  ListDesc* out = descs + (size_t)client * kListsPerClient;
   if (t == 0) {
     bool ok = sa.n_words >= kGlobalHeaderWords;
     uint32_t R = 0, s = 0;
@@ -113,7 +138,7 @@ __global__ __launch_bounds__(64) void parse_headers_kernel(const StreamArg* __re
     if (!ok) atomicOr(status, CVLC_DEV_STREAM);
   }
   __syncthreads();
-  if (t < CVLC_MAX_CODED) {
+  if (t < kListsPerClient) {
     ListDesc ld;
     ld.payload = nullptr; ld.weight = 0.0; ld.P = 0; ld.W = 0; ld.s = 0; ld.y = 0; ld.m = 0.0f; ld.step = 0.0f;
     if (s_ok && t < w[3]) {
@@ -135,76 +160,285 @@ __global__ __launch_bounds__(64) void parse_headers_kernel(const StreamArg* __re
   }
 }
 
-// ------------------------------------------------------------------ 2. tile table
-// table[t][list] = index of the first record of `list` whose position lies in
-// output tile t or later; row n_tiles holds the list length.  Thread e compares
-// the tiles of records e-1 and e and fills the rows in between.
-__global__ __launch_bounds__(kBlock) void tile_table_kernel(const ListDesc* __restrict__ descs, uint32_t* table,
-                                                            uint32_t d, uint32_t n_tiles, uint32_t n_lists,
-                                                            uint32_t* status) {
-  const uint32_t list = blockIdx.y;
-  const ListDesc ld = descs[list];
-  if (ld.P == 0) return;
-  const uint64_t n_words = payload_words(ld.P, ld.W);
-  const uint64_t pid_mask = (1ull << ld.s) - 1ull;
-  bool bad = false;
-  for (uint32_t e = blockIdx.x * kBlock + threadIdx.x; e < ld.P; e += gridDim.x * kBlock) {
-    const uint32_t pid = (uint32_t)(read_bits(ld.payload, n_words, (uint64_t)e * ld.W, ld.W) & pid_mask);
-    int64_t t_prev = -1;
-    if (e > 0) {
-      const uint32_t prev = (uint32_t)(read_bits(ld.payload, n_words, (uint64_t)(e - 1) * ld.W, ld.W) & pid_mask);
-      bad |= prev >= pid;  // positions must ascend strictly
-      t_prev = prev < d ? (int64_t)(prev / kDecTile) : (int64_t)n_tiles;
+// ------------------------------------------------------------------ 1b. the non-empty lists
+// One workgroup.  Lists with records are numbered in (client, group) order;
+// item_start is the exclusive prefix of their tile_table work items.
+__global__ __launch_bounds__(1024) void compact_lists_kernel(const ListDesc* __restrict__ descs, uint32_t n_lists,
+                                                             CompactDesc* __restrict__ cdesc,
+                                                             uint32_t* __restrict__ item_start, DecodeCtl* ctl) {
+  __shared__ uint32_t scan_tmp[16];
+  const uint32_t tid = threadIdx.x;
+  uint32_t lists_before = 0, items_before = 0;
+  for (uint32_t base = 0; base < n_lists; base += 1024) {
+    const uint32_t l = base + tid;
+    ListDesc ld;
+    ld.P = 0;
+    if (l < n_lists) ld = descs[l];
+    const uint32_t live = ld.P > 0 ? 1u : 0u;
+    const uint32_t items = (ld.P + kTabChunk - 1) / kTabChunk;
+    uint32_t tot_l, tot_i;
+    const uint32_t pos = lists_before + block_excl_scan<16>(live, scan_tmp, &tot_l);
+    const uint32_t first = items_before + block_excl_scan<16>(items, scan_tmp, &tot_i);
+    if (live) {
+      CompactDesc c;
+      c.payload = ld.payload; c.weight = ld.weight; c.P = ld.P; c.wsy = ld.W | (ld.s << 8) | (ld.y << 16);
+      c.m = ld.m; c.step = ld.step;
+      cdesc[pos] = c;
+      item_start[pos] = first;
     }
-    bad |= pid >= d;
-    const int64_t t_cur = pid < d ? (int64_t)(pid / kDecTile) : (int64_t)n_tiles;
-    for (int64_t t = t_prev + 1; t <= t_cur && t <= (int64_t)n_tiles; ++t) table[(size_t)t * n_lists + list] = e;
-    if (e == ld.P - 1)
-      for (int64_t t = t_cur + 1; t <= (int64_t)n_tiles; ++t) table[(size_t)t * n_lists + list] = ld.P;
+    lists_before += tot_l;
+    items_before += tot_i;
+  }
+  if (tid == 0) {
+    item_start[lists_before] = items_before;
+    ctl->n_active = lists_before;
+    ctl->n_items = items_before;
+  }
+}
+
+// ------------------------------------------------------------------ 2. tile table
+// table[list][t] = index of the first record of `list` whose position lies in
+// output tile t or later; entry n_tiles holds the list length.  (List-major: a
+// list's entries are written in ascending t by neighbouring threads.)  A work
+// item is a run of kTabChunk records of one list: its stream words are brought
+// into LDS with coalesced loads, then thread e compares the tiles of records e-1
+// and e and fills the entries in between.
+typedef const uint32_t __attribute__((address_space(1))) * GlobalConstWordPtr;
+
+// Bits [bit, bit + W) of an LDS word array, bit < 2^32, W <= 63.
+__device__ __forceinline__ uint64_t lds_bits(const uint32_t* words, uint32_t n_words, uint32_t bit, uint32_t W) {
+  const uint32_t w = bit >> 5, sh = bit & 31u;
+  const uint64_t a = words[w];
+  const uint64_t b = (w + 1 < n_words) ? words[w + 1] : 0u;
+  uint64_t v = (a | (b << 32)) >> sh;
+  if (sh + W > 64u) v |= (uint64_t)words[min(w + 2, n_words - 1)] << (64u - sh);
+  return v & ((1ull << W) - 1ull);
+}
+
+__global__ __launch_bounds__(kBlock) void tile_table_kernel(const CompactDesc* __restrict__ cdesc,
+                                                            const uint32_t* __restrict__ item_start,
+                                                            const DecodeCtl* __restrict__ ctl, uint32_t* table,
+                                                            uint32_t d, uint32_t n_tiles, uint32_t* status) {
+  constexpr uint32_t kStartCache = 2048;
+  __shared__ uint32_t s_words[kTabWords];
+  __shared__ uint32_t s_start[kStartCache];
+  const uint32_t tid = threadIdx.x, lane = lane_id();
+  const uint32_t n_active = ctl->n_active, n_items = ctl->n_items;
+  const bool cached = n_active <= kStartCache;
+  if (cached)
+    for (uint32_t i = tid; i < n_active; i += kBlock) s_start[i] = item_start[i];
+  __syncthreads();
+  bool bad = false;
+  for (uint32_t q = blockIdx.x; q < n_items; q += gridDim.x) {
+    uint32_t a = 0, b = n_active;  // the list that owns item q: last list with item_start <= q (uniform)
+    while (b - a > 1) {
+      const uint32_t mid = (a + b) >> 1;
+      const uint32_t v = cached ? s_start[mid] : item_start[mid];
+      if (v <= q) a = mid; else b = mid;
+    }
+    const uint32_t list = a;
+    const CompactDesc ld = cdesc[list];
+    const uint32_t W = ld.wsy & 0xFFu, s = (ld.wsy >> 8) & 0xFFu;
+    const uint32_t e0 = (q - item_start[list]) * kTabChunk;
+    const uint32_t cnt = min(ld.P - e0, kTabChunk);
+    // words that hold records e0-1 (if any) .. e0+cnt-1
+    const uint32_t e_lo = e0 ? e0 - 1 : 0;
+    const uint64_t bit_lo = (uint64_t)e_lo * W, bit_hi = (uint64_t)(e0 + cnt) * W;
+    const uint64_t w_lo = bit_lo >> 5;
+    const uint32_t nw = (uint32_t)(((bit_hi + 31u) >> 5) - w_lo);
+    const uint32_t bit_base = (uint32_t)(bit_lo - (w_lo << 5));  // bit of record e_lo inside s_words
+    GlobalConstWordPtr src = (GlobalConstWordPtr)ld.payload + w_lo;
+    __syncthreads();  // the item before is done with s_words
+    for (uint32_t i = tid; i < nw; i += kBlock) s_words[i] = src[i];
+    __syncthreads();
+    const uint32_t pid_mask = s >= 32 ? 0xFFFFFFFFu : (1u << s) - 1u;
+    uint32_t* row = table + (size_t)list * (n_tiles + 1);
+    for (uint32_t j0 = 0; j0 < cnt; j0 += kBlock) {  // uniform trip count: the shuffle below needs the whole wavefront
+      const uint32_t j = j0 + tid;
+      const bool live = j < cnt;
+      const uint32_t e = e0 + j;
+      uint32_t pid = 0;
+      if (live) pid = (uint32_t)lds_bits(s_words, nw, bit_base + (e - e_lo) * W, W) & pid_mask;
+      uint32_t prev = __shfl_up(pid, 1, 64);  // the record before mine sits in the lane below
+      if (live && lane == 0 && e > 0) prev = (uint32_t)lds_bits(s_words, nw, bit_base + (e - 1 - e_lo) * W, W) & pid_mask;
+      // entries (tile of record e-1, tile of record e] point at e; past the last record they hold P
+      uint32_t t_first = 1, t_cur = 0, tail_first = 1, tail_last = 0;
+      if (live) {
+        t_first = 0;
+        if (e > 0) {
+          bad |= prev >= pid;  // positions must ascend strictly
+          t_first = (prev < d ? prev / kDecTile : n_tiles) + 1;
+        }
+        bad |= pid >= d;
+        t_cur = pid < d ? pid / kDecTile : n_tiles;
+        if (e == ld.P - 1) {
+          tail_first = t_cur + 1;
+          tail_last = n_tiles;
+        }
+      }
+      // short runs of entries are written by the lane that found them, long ones (the stretch before a
+      // list's first record, after its last, or across a region it skips) by the whole wavefront
+      constexpr uint32_t kLong = 16;
+      const bool long_run = t_cur >= t_first && t_cur - t_first >= kLong;
+      const bool long_tail = tail_last >= tail_first;
+      if (t_cur >= t_first && !long_run)
+        for (uint32_t t = t_first; t <= t_cur; ++t) row[t] = e;
+      uint64_t todo = __ballot(long_run);
+      while (todo) {
+        const uint32_t src = (uint32_t)__builtin_ctzll(todo);
+        const uint32_t a0 = __builtin_amdgcn_readlane(t_first, src), a1 = __builtin_amdgcn_readlane(t_cur, src);
+        const uint32_t val = __builtin_amdgcn_readlane(e, src);
+        for (uint32_t t = a0 + lane; t <= a1; t += kWave) row[t] = val;
+        todo &= todo - 1;
+      }
+      todo = __ballot(long_tail);
+      while (todo) {
+        const uint32_t src = (uint32_t)__builtin_ctzll(todo);
+        const uint32_t a0 = __builtin_amdgcn_readlane(tail_first, src), a1 = __builtin_amdgcn_readlane(tail_last, src);
+        for (uint32_t t = a0 + lane; t <= a1; t += kWave) row[t] = ld.P;
+        todo &= todo - 1;
+      }
+    }
   }
   if (bad) atomicOr(status, CVLC_DEV_STREAM);
 }
 
 // ------------------------------------------------------------------ 3. fused decode + accumulate
-__global__ __launch_bounds__(kBlock) void decode_tiles_kernel(const ListDesc* __restrict__ descs,
+// Workgroups walk the output tiles (b, b + workgroups, ...), so that at any time
+// neighbouring tiles are in flight and the stream lines they share are fetched
+// from HBM once.  The records of a tile, over all lists, are numbered
+// 0..total-1 list by list (an exclusive scan of the slice lengths); thread
+// q mod 256 decodes record q, so the work is even however the records are
+// spread over the lists.  List descriptors sit in LDS.
+struct DecodeShared {
+  double acc[kDecTile];
+  uint4 desc[kListBatch][2];      // CompactDesc, as loaded
+  uint32_t begin[kListBatch];     // first record of the list's slice
+  uint32_t first[kListBatch + 1]; // number of the slice's first record in the tile
+};
+
+constexpr uint32_t kDecBlock = 512;  // threads of a decode workgroup
+
+__global__ __launch_bounds__(kDecBlock, 3) void decode_tiles_kernel(const CompactDesc* __restrict__ cdesc,
+                                                              const DecodeCtl* __restrict__ ctl,
                                                               const uint32_t* __restrict__ table, float* out,
-                                                              uint32_t d, uint32_t n_tiles, uint32_t n_lists,
-                                                              uint32_t accumulate, uint32_t* status) {
-  __shared__ double acc[kDecTile];
-  const uint32_t tile = blockIdx.x;
-  const uint32_t lo = tile * kDecTile;
-  for (uint32_t i = threadIdx.x; i < kDecTile; i += kBlock) acc[i] = 0.0;
-  __syncthreads();
+                                                              uint32_t d, uint32_t n_tiles, uint32_t accumulate,
+                                                              uint32_t* status) {
+  __shared__ DecodeShared S;
+  __shared__ uint32_t scan_tmp[kDecBlock / kWave];
+  const uint32_t tid = threadIdx.x;
+  const uint32_t n_active = ctl->n_active;
+  const bool one_batch = n_active <= kListBatch;
   bool bad = false;
-  for (uint32_t list = threadIdx.x; list < n_lists; list += kBlock) {
-    uint32_t begin = table[(size_t)tile * n_lists + list];
-    uint32_t end = table[(size_t)(tile + 1) * n_lists + list];
-    const ListDesc ld = descs[list];
-    if (ld.P == 0) continue;
-    if (begin > ld.P) begin = ld.P;  // table rows of a malformed list may hold anything
-    if (end > ld.P) end = ld.P;
-    if (end <= begin) continue;
-    const uint64_t n_words = payload_words(ld.P, ld.W);
-    const uint64_t pid_mask = (1ull << ld.s) - 1ull;
-    for (uint32_t e = begin; e < end; ++e) {
-      const uint64_t rec = read_bits(ld.payload, n_words, (uint64_t)e * ld.W, ld.W);
-      const uint32_t pid = (uint32_t)(rec & pid_mask);
-      const uint32_t cid = (uint32_t)(rec >> ld.s);
-      if (pid < lo || pid - lo >= kDecTile || pid >= d) { bad = true; continue; }
-      const float xhat = ld.y == 32 ? __uint_as_float(cid) : __fmaf_rn((float)cid, ld.step, ld.m);
-      atomicAdd(&acc[pid - lo], ld.weight * (double)xhat);
+  auto load_descs = [&](uint32_t l0, uint32_t nl) {
+    const uint4* src = reinterpret_cast<const uint4*>(cdesc + l0);
+    for (uint32_t i = tid; i < nl * 2u; i += kDecBlock) (&S.desc[0][0])[i] = src[i];
+  };
+  if (one_batch) load_descs(0, n_active);
+  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const uint32_t lo = tile * kDecTile;
+    __syncthreads();  // the tile before is written out; the descriptors are in place
+    for (uint32_t i = tid; i < kDecTile; i += kDecBlock) S.acc[i] = 0.0;
+    for (uint32_t l0 = 0; l0 < n_active; l0 += kListBatch) {
+      const uint32_t nl = min(n_active - l0, kListBatch);
+      if (!one_batch) {
+        __syncthreads();
+        load_descs(l0, nl);
+        __syncthreads();
+      }
+      // slice of every list of the batch: [begin, end) from two neighbouring table entries
+      constexpr uint32_t per = kListBatch / kDecBlock;
+      uint32_t len[per], mine = 0;
+#pragma unroll
+      for (uint32_t u = 0; u < per; ++u) {
+        const uint32_t li = tid * per + u;  // consecutive lists per thread: the scan below is in list order
+        len[u] = 0;
+        if (li < nl) {
+          const uint32_t P = S.desc[li][1].x;
+          const uint32_t* row = table + (size_t)(l0 + li) * (n_tiles + 1) + tile;
+          uint32_t begin = row[0], end = row[1];
+          if (begin > P) begin = P;  // table entries of a malformed list may hold anything
+          if (end > P) end = P;
+          if (end > begin) len[u] = end - begin;
+          S.begin[li] = begin;
+        }
+        mine += len[u];
+      }
+      uint32_t total;
+      uint32_t before = block_excl_scan<kDecBlock / kWave>(mine, scan_tmp, &total);
+#pragma unroll
+      for (uint32_t u = 0; u < per; ++u) {
+        const uint32_t li = tid * per + u;
+        if (li < nl) S.first[li] = before;
+        before += len[u];
+      }
+      if (tid == 0) S.first[nl] = total;
+      __syncthreads();
+      // eight records per thread at a time: searches and descriptors from LDS, then all
+      // record loads together, so that their latencies overlap
+      constexpr uint32_t kUnroll = 8;
+      for (uint32_t q0 = tid; q0 < total; q0 += kDecBlock * kUnroll) {
+        uint32_t li_of[kUnroll], sh_of[kUnroll];
+        uint64_t a_of[kUnroll];
+        uint32_t b_of[kUnroll];
+        bool live[kUnroll];
+#pragma unroll
+        for (uint32_t u = 0; u < kUnroll; ++u) {
+          const uint32_t q = q0 + u * kDecBlock;
+          live[u] = q < total;
+          uint32_t a = 0, b = nl;  // last list with first <= q (lists with no record in the tile are skipped over)
+          while (b - a > 1) {
+            const uint32_t mid = (a + b) >> 1;
+            if (S.first[mid] <= q) a = mid; else b = mid;
+          }
+          li_of[u] = a;
+          a_of[u] = 0;
+          b_of[u] = 0;
+          sh_of[u] = 0;
+          if (live[u]) {
+            const uint4 d0 = S.desc[a][0], d1 = S.desc[a][1];
+            GlobalConstWordPtr pay = (GlobalConstWordPtr)(((uint64_t)d0.y << 32) | d0.x);
+            const uint32_t P = d1.x, W = d1.y & 0xFFu;
+            const uint64_t n_words = payload_words(P, W);
+            const uint32_t e = S.begin[a] + (q - S.first[a]);
+            const uint64_t bit = (uint64_t)e * W;
+            const uint64_t w = bit >> 5;
+            sh_of[u] = (uint32_t)(bit & 31u);
+            // two words always exist or the second reads as 0; the third only when the record reaches it
+            const uint32_t w0 = pay[w];
+            const uint32_t w1 = (w + 1 < n_words) ? pay[w + 1] : 0u;
+            a_of[u] = ((uint64_t)w1 << 32) | w0;
+            if (sh_of[u] + W > 64u) b_of[u] = pay[w + 2];  // inside the payload: the record's last bit lies there
+          }
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < kUnroll; ++u) {
+          if (!live[u]) continue;
+          const uint4 d0 = S.desc[li_of[u]][0], d1 = S.desc[li_of[u]][1];
+          const uint32_t W = d1.y & 0xFFu, s = (d1.y >> 8) & 0xFFu, y = (d1.y >> 16) & 0xFFu;
+          const double weight = __hiloint2double((int)d0.w, (int)d0.z);
+          uint64_t rec = a_of[u] >> sh_of[u];
+          if (sh_of[u] + W > 64u) rec |= (uint64_t)b_of[u] << (64u - sh_of[u]);
+          rec &= (1ull << W) - 1ull;
+          const uint32_t pid = (uint32_t)(rec & ((1ull << s) - 1ull));
+          const uint32_t cid = (uint32_t)(rec >> s);
+          if (pid < lo || pid - lo >= kDecTile || pid >= d) { bad = true; continue; }
+          const float xhat = y == 32 ? __uint_as_float(cid) : __fmaf_rn((float)cid, __uint_as_float(d1.w), __uint_as_float(d1.z));
+          atomicAdd(&S.acc[pid - lo], weight * (double)xhat);
+        }
+      }
+    }
+    __syncthreads();
+    for (uint32_t i = tid; i < kDecTile; i += kDecBlock) {
+      const uint32_t j = lo + i;
+      if (j < d) {
+        double v = S.acc[i];
+        if (accumulate) v += (double)out[j];
+        out[j] = (float)v;
+      }
     }
   }
   if (bad) atomicOr(status, CVLC_DEV_STREAM);
-  __syncthreads();
-  for (uint32_t i = threadIdx.x; i < kDecTile; i += kBlock) {
-    const uint32_t j = lo + i;
-    if (j < d) {
-      double v = acc[i];
-      if (accumulate) v += (double)out[j];
-      out[j] = (float)v;
-    }
-  }
 }
 
 }  // namespace
@@ -222,6 +456,7 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
                           size_t ws_bytes, void* hip_stream) {
   using namespace cvlc;
   if (!d_out || d < 1 || d > 0x7FFFFFFFu || !d_workspace) return CVLC_ERR_ARG;
+  if (n > 65535u) return CVLC_ERR_ARG;  // streams index the grid's y dimension
   if (n > 0 && (!d_streams || !stream_bytes)) return CVLC_ERR_ARG;
   if (reinterpret_cast<uintptr_t>(d_workspace) % 256u || reinterpret_cast<uintptr_t>(d_out) % 4u) return CVLC_ERR_ARG;
   for (uint32_t i = 0; i < n; ++i) {
@@ -235,11 +470,14 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
   uint32_t* status = reinterpret_cast<uint32_t*>(base + L.status);
   StreamArg* sargs = reinterpret_cast<StreamArg*>(base + L.streams);
   ListDesc* descs = reinterpret_cast<ListDesc*>(base + L.desc);
+  CompactDesc* cdesc = reinterpret_cast<CompactDesc*>(base + L.cdesc);
+  uint32_t* item_start = reinterpret_cast<uint32_t*>(base + L.item_start);
+  DecodeCtl* ctl = reinterpret_cast<DecodeCtl*>(base + L.ctl);
   uint32_t* table = reinterpret_cast<uint32_t*>(base + L.table);
-  const uint32_t n_lists = n * CVLC_MAX_CODED;
+  const uint32_t n_lists = n * kListsPerClient;
 
   profile_mark(CVLC_STAGE_DEC_SETUP, true, stream);
-  int rc = hip_check(hipMemsetAsync(status, 0, 256, stream));
+  int rc = hip_check(hipMemsetAsync(status, 0, L.streams, stream));  // status word and list counts (n = 0: no lists)
   if (rc) return rc;
   if (n > 0) {
     constexpr uint32_t words_per = sizeof(StreamArg) / 4u;
@@ -261,17 +499,20 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
       hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(sargs), chunk);
     }
     hipLaunchKernelGGL(parse_headers_kernel, dim3(n), dim3(64), 0, stream, sargs, descs, d, n, status);
+    hipLaunchKernelGGL(compact_lists_kernel, dim3(1), dim3(1024), 0, stream, descs, n_lists, cdesc, item_start, ctl);
   }
   profile_mark(CVLC_STAGE_DEC_SETUP, false, stream);
   if (n > 0) {
     StageScope scope(CVLC_STAGE_DEC_TABLE, stream);
-    hipLaunchKernelGGL(tile_table_kernel, dim3(8, n_lists), dim3(kBlock), 0, stream, descs, table, d, L.n_tiles,
-                       n_lists, status);
+    // the number of work items is only known on the device: 2048 workgroups (eight per CU) walk them
+    hipLaunchKernelGGL(tile_table_kernel, dim3(2048), dim3(kBlock), 0, stream, cdesc, item_start, ctl, table, d,
+                       L.n_tiles, status);
   }
   {
     StageScope scope(CVLC_STAGE_DEC_TILES, stream);
-    hipLaunchKernelGGL(decode_tiles_kernel, dim3(L.n_tiles), dim3(kBlock), 0, stream, descs, table, d_out, d,
-                       L.n_tiles, n_lists, flags & CVLC_DECODE_ACCUMULATE, status);
+    const uint32_t g = L.n_tiles < 768u ? L.n_tiles : 768u;  // three workgroups per CU
+    hipLaunchKernelGGL(decode_tiles_kernel, dim3(g), dim3(kDecBlock), 0, stream, cdesc, ctl, table, d_out, d, L.n_tiles,
+                       flags & CVLC_DECODE_ACCUMULATE, status);
   }
   return hip_check(hipGetLastError());
 }

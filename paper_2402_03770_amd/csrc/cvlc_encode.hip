@@ -124,26 +124,6 @@ __global__ void upload_kernel(uint32_t* dst, UploadChunk c) {
 }
 
 // ------------------------------------------------------------------ small device helpers
-// Exclusive prefix sum of one value per thread over a workgroup of NW
-// wavefronts, in thread order; *total receives the sum.  `scratch` holds NW words.
-template <uint32_t NW>
-__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
-  const uint32_t incl = wave_incl_scan_u32(v);
-  const uint32_t wave = threadIdx.x / kWave;
-  __syncthreads();
-  if (lane_id() == kWave - 1) scratch[wave] = incl;
-  __syncthreads();
-  uint32_t before = 0, sum = 0;
-#pragma unroll
-  for (uint32_t w = 0; w < NW; ++w) {
-    const uint32_t t = scratch[w];
-    if (w < wave) before += t;
-    sum += t;
-  }
-  *total = sum;
-  return before + incl - v;
-}
-
 // Number of set bits of the four masks in lanes below the caller's.
 __device__ __forceinline__ uint32_t lanes_below4(uint64_t m0, uint64_t m1, uint64_t m2, uint64_t m3) {
   uint32_t acc = __builtin_amdgcn_mbcnt_lo((uint32_t)m0, 0u);
