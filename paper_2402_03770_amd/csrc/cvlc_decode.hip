@@ -319,7 +319,7 @@ struct DecodeShared {
 
 constexpr uint32_t kDecBlock = 512;  // threads of a decode workgroup
 
-__global__ __launch_bounds__(kDecBlock, 3) void decode_tiles_kernel(const CompactDesc* __restrict__ cdesc,
+__global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const CompactDesc* __restrict__ cdesc,
                                                               const DecodeCtl* __restrict__ ctl,
                                                               const uint32_t* __restrict__ table, float* out,
                                                               uint32_t d, uint32_t n_tiles, uint32_t accumulate,

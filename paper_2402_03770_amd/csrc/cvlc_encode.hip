@@ -641,6 +641,24 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
   uint32_t* __restrict__ dst_idx = ws.dense_idx + (size_t)client * d;
   uint32_t* __restrict__ dst_val = ws.dense_val + (size_t)client * d;
   const uint32_t wpc = gridDim.x * kWideWaves;  // wavefronts per client
+  // One-step software pipeline: the loads of a step (up to 256 entries of a run) are issued before the
+  // stores of the step before, so that a wavefront never waits for a store's acknowledgement with
+  // nothing in flight (loads and stores share one outstanding-operation counter).
+  bool have = false;
+  uint32_t pv[4], px[4], p_rc = 0, p_ro = 0, p_b = 0;
+  auto retire = [&]() {
+    if (!have) return;
+#pragma unroll
+    for (uint32_t u = 0; u < 4; ++u) {
+      const uint32_t i = p_b + u * kWave + lane;
+      if (p_b + u * kWave >= p_rc) break;  // uniform
+      if (i < p_rc) {
+        dst_val[p_ro + i] = pv[u];
+        dst_idx[p_ro + i] = px[u];
+      }
+      if (nb) select_count<2>(S, pv[u] & 0x7FFFFFFFu, nullptr, i < p_rc, nullptr, nullptr);
+    }
+  };
   // the runs' lengths and offsets are fetched 64 at a time, one per lane
   for (uint32_t first = blockIdx.x * kWideWaves + wave; first < n_regions; first += wpc * kWave) {
     const uint32_t mine = first + lane * wpc;
@@ -666,19 +684,20 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
             x[u] = src_idx[slot0 + i];
           }
         }
+        retire();
 #pragma unroll
         for (uint32_t u = 0; u < 4; ++u) {
-          const uint32_t i = b + u * kWave + lane;
-          if (b + u * kWave >= rc) break;  // uniform
-          if (i < rc) {
-            dst_val[ro + i] = v[u];
-            dst_idx[ro + i] = x[u];
-          }
-          if (nb) select_count<2>(S, v[u] & 0x7FFFFFFFu, nullptr, i < rc, nullptr, nullptr);
+          pv[u] = v[u];
+          px[u] = x[u];
         }
+        p_rc = rc;
+        p_ro = ro;
+        p_b = b;
+        have = true;
       }
     }
   }
+  retire();
   __syncthreads();
   if (nb == 0) return;
   uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * kSlotGroup * kDigitBins;
@@ -742,7 +761,8 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   __shared__ uint32_t s_digit[kSlotGroup], s_quota[kSlotGroup], s_need[kSlotGroup], s_pre[kSlotGroup];
   __shared__ uint32_t s_found;
   __shared__ uint32_t scan_tmp[kWideWaves];
-  const uint32_t slot = blockIdx.x, client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+  __shared__ uint2 s_list[LEVEL == 3 ? kTieCap : 1];
+  const uint32_t slot = blockIdx.x, client = blockIdx.y, tid = threadIdx.x;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   const uint32_t r0 = group * kSlotGroup;
@@ -799,17 +819,19 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
       if (!s_need[b]) continue;  // uniform
       const uint32_t r = r0 + b, w_digit = s_digit[b], w_quota = s_quota[b];
       if (kept <= kTieCap) {
-        if (wave == b % kWideWaves) {
-          for (uint32_t e = lane; e < kept; e += kWave) {
-            const uint2 me = list[e];
-            if (me.y != w_digit) continue;
-            uint32_t before = 0;
-            for (uint32_t o = 0; o < kept; ++o) {
-              const uint2 other = list[o];
-              before += (other.y == w_digit && other.x < me.x) ? 1u : 0u;
-            }
-            if (before + 1 == w_quota) ctl->iota[r] = me.x;
+        // position-order rank of every kept-aside member of the class, all threads, list in LDS
+        __syncthreads();
+        for (uint32_t e = tid; e < kept; e += kWideBlock) s_list[e] = list[e];
+        __syncthreads();
+        for (uint32_t e = tid; e < kept; e += kWideBlock) {
+          const uint2 me = s_list[e];
+          if (me.y != w_digit) continue;
+          uint32_t before = 0;
+          for (uint32_t o = 0; o < kept; ++o) {
+            const uint2 other = s_list[o];
+            before += (other.y == w_digit && other.x < me.x) ? 1u : 0u;
           }
+          if (before + 1 == w_quota) ctl->iota[r] = me.x;
         }
       } else {
         // too many to keep aside: walk the whole candidate list
@@ -1015,41 +1037,55 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
   const uint32_t lane = lane_id(), wave = tid / kWave;
   GlobalWordPtr stream = (GlobalWordPtr)p.stream;
   uint32_t* cnt = ws.span_cnt + (size_t)client * (ws.max_spans + 1) * 32;
-  if (tid == 0) {
-    uint32_t w = kGlobalHeaderWords + kSegHeaderWords * R;
-    for (uint32_t r = 0; r < R; ++r) {
-      s_payload[r] = w;
-      w += (uint32_t)payload_words(p.Z[r] - (r ? p.Z[r - 1] : 0u), sbits + p.y[r]);
-    }
+  if (tid < 32) {  // first stream word of every group's records: exclusive prefix of the payload sizes
+    uint32_t words = 0;
+    if (tid < R) words = (uint32_t)payload_words(p.Z[tid] - (tid ? p.Z[tid - 1] : 0u), sbits + p.y[tid]);
+    const uint32_t incl = wave_incl_scan_u32(words);
+    s_payload[tid] = kGlobalHeaderWords + kSegHeaderWords * R + incl - words;
   }
   __syncthreads();
+  constexpr uint32_t kBatches = 8;  // 64-span batches loaded together
   for (uint32_t g = wave; g < 32; g += kWideWaves) {
     const uint32_t W = g < R ? sbits + p.y[g] : 0u;
     const uint32_t P = g < R ? p.Z[g] - (g ? p.Z[g - 1] : 0u) : 0u;
     uint32_t run = 0;
-    for (uint32_t c0 = 0; c0 < n_spans; c0 += kWave) {  // c0 is a multiple of 64, hence of the chunk size
-      const uint32_t c = c0 + lane;
-      const uint32_t v = c < n_spans ? cnt[(size_t)c * 32 + g] : 0u;
-      const uint32_t incl = wave_incl_scan_u32(v);
-      const uint32_t excl = run + incl - v;
-      run += __shfl(incl, 63, 64);
-      // the chunk that starts at span c ends where the chunk 8 spans on starts
-      const uint32_t next = __shfl_down(excl, kChunkSpans, 64);
-      const uint32_t chunk_end = lane + kChunkSpans < kWave ? next : run;
-      if (c < n_spans) {
-        cnt[(size_t)c * 32 + g] = excl;
-        // a consistent selection never passes the planned size; the test keeps the two
-        // stores inside the group's payload even if an internal check has failed
-        if (g < R && c % kChunkSpans == 0 && chunk_end > excl && chunk_end <= P) {
-          const uint64_t bit0 = (uint64_t)excl * W, bit1 = (uint64_t)chunk_end * W;
-          stream[s_payload[g] + (uint32_t)(bit0 >> 5)] = 0;
-          stream[s_payload[g] + (uint32_t)((bit1 - 1) >> 5)] = 0;
+    if (g >= R) {  // no records: the prefix of these columns is never read, only cleared
+      for (uint32_t c = lane; c <= n_spans; c += kWave) cnt[(size_t)c * 32 + g] = 0;
+      continue;
+    }
+    for (uint32_t c00 = 0; c00 < n_spans; c00 += kWave * kBatches) {
+      uint32_t vs[kBatches];
+#pragma unroll
+      for (uint32_t u = 0; u < kBatches; ++u) {
+        const uint32_t c = c00 + u * kWave + lane;
+        vs[u] = c < n_spans ? cnt[(size_t)c * 32 + g] : 0u;
+      }
+#pragma unroll
+      for (uint32_t u = 0; u < kBatches; ++u) {
+        const uint32_t c = c00 + u * kWave + lane;  // the batch starts at a multiple of 64, hence of the chunk size
+        if (c00 + u * kWave >= n_spans) break;      // uniform
+        const uint32_t v = vs[u];
+        const uint32_t incl = wave_incl_scan_u32(v);
+        const uint32_t excl = run + incl - v;
+        run += __shfl(incl, 63, 64);
+        // the chunk that starts at span c ends where the chunk 8 spans on starts
+        const uint32_t next = __shfl_down(excl, kChunkSpans, 64);
+        const uint32_t chunk_end = lane + kChunkSpans < kWave ? next : run;
+        if (c < n_spans) {
+          cnt[(size_t)c * 32 + g] = excl;
+          // a consistent selection never passes the planned size; the test keeps the two
+          // stores inside the group's payload even if an internal check has failed
+          if (c % kChunkSpans == 0 && chunk_end > excl && chunk_end <= P) {
+            const uint64_t bit0 = (uint64_t)excl * W, bit1 = (uint64_t)chunk_end * W;
+            stream[s_payload[g] + (uint32_t)(bit0 >> 5)] = 0;
+            stream[s_payload[g] + (uint32_t)((bit1 - 1) >> 5)] = 0;
+          }
         }
       }
     }
     if (lane == 0) {
       cnt[(size_t)n_spans * 32 + g] = run;
-      if (g < R && run != P) atomicOr(ws.status, CVLC_DEV_INTERNAL);
+      if (run != P) atomicOr(ws.status, CVLC_DEV_INTERNAL);
     }
   }
   // energy of the coordinates the filter dropped, region by region
