@@ -155,12 +155,13 @@ enum {
   CVLC_STAGE_ENC_SETUP = 0,    /* clear scratch, upload per-client parameters   */
   CVLC_STAGE_ENC_SAMPLE = 1,   /* sample histogram -> candidate threshold       */
   CVLC_STAGE_ENC_FILTER = 2,   /* the full pass over the update vectors         */
-  CVLC_STAGE_ENC_REFILTER = 3, /* second full pass, only if the sample misjudged */
-  CVLC_STAGE_ENC_SELECT = 4,   /* exact boundary keys + ties                    */
+  CVLC_STAGE_ENC_REFILTER = 3, /* prefix of the kept runs, level-1 boundaries;  */
+                               /* keep-all second pass if the sample misjudged  */
+  CVLC_STAGE_ENC_SELECT = 4,   /* dense candidate list, exact boundary keys, ties */
   CVLC_STAGE_ENC_CLASSIFY = 5, /* group counts and statistics                   */
-  CVLC_STAGE_ENC_LAYOUT = 6,   /* prefix sums, headers                          */
+  CVLC_STAGE_ENC_LAYOUT = 6,   /* prefix sums, headers, statistics block        */
   CVLC_STAGE_ENC_EMIT = 7,     /* quantise + pack                               */
-  CVLC_STAGE_DEC_SETUP = 8,    /* upload + header parsing                       */
+  CVLC_STAGE_DEC_SETUP = 8,    /* upload, header parsing, list numbering        */
   CVLC_STAGE_DEC_TABLE = 9,    /* per-list tile boundaries                      */
   CVLC_STAGE_DEC_TILES = 10,   /* fused decode + accumulate                     */
   CVLC_PROFILE_STAGES = 11

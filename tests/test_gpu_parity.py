@@ -211,6 +211,50 @@ def test_workloads_at_oracle_friendly_sizes(cfg, d, n):
     check_decode(refs, d)
 
 
+# --------------------------------------------------------------------------- the encoder's internal fallbacks
+def test_sample_that_misjudges_the_threshold():
+    """The encoder places its candidate threshold from a strided sample of 64-byte pieces.
+    Here exactly the sampled pieces hold large values and everything else small ones, so the
+    sampled threshold keeps far fewer than k coordinates and the keep-all pass has to run."""
+    d = 2_000_000
+    rng = np.random.default_rng(5)
+    U = (rng.standard_normal(d) * 1e-4).astype(np.float32)
+    n_src, n_s = d // 16, 16384
+    pieces = (np.arange(n_s, dtype=np.int64) * n_src) // n_s
+    for off in range(16):
+        U[pieces * 16 + off] = (rng.standard_normal(n_s) * 10.0).astype(np.float32)
+    p = orc.plan_manual(d, [8, 4, 2], [50_000, 100_000, 150_000])   # k = 300 000 > the 262 144 large values
+    refs, _ = check_encode([U], [p], 21, [3])
+    check_decode(refs, d)
+
+
+def test_values_rounded_to_few_mantissa_bits():
+    """Updates that were computed in a very short format: thousands of coordinates share each
+    magnitude, so every boundary cuts through a large class of equal keys."""
+    d = 400_000
+    U = syn.update_vector(2, 3, d=d)
+    U = (U.view(np.uint32) & np.uint32(0xFFF00000)).view(np.float32).copy()   # keep 3 mantissa bits
+    p = orc.plan_manual(d, [8, 6, 4, 2], [4_000, 12_000, 30_000, 50_000])
+    refs, _ = check_encode([U], [p], 77, [6])
+    check_decode(refs, d)
+
+
+def test_repeatable_and_without_statistics():
+    d = 120_000
+    host = [syn.update_vector(3, c, d=d) for c in range(3)]
+    plans = [orc.plan_alg1(d, d, 5, -0.6)] * 3
+    a, _, sa, streams = gpu_encode(host, plans, 4, [0, 1, 2], want_stats=False)
+    b, _, sb, _ = gpu_encode(host, plans, 4, [0, 1, 2], want_stats=True)
+    assert sa == 0 and sb == 0
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    out1, st1 = gpu_decode(streams, d)
+    out2, st2 = gpu_decode(streams, d)
+    assert st1 == 0 and st2 == 0
+    # the order of the fp64 additions may differ between runs; the rounded sums may differ in the last place at most
+    assert np.allclose(out1, out2, rtol=2e-7, atol=0.0)
+
+
 # --------------------------------------------------------------------------- decode / aggregate specifics
 def test_decode_accumulate_mode_and_empty_batch():
     d = 90_000
