@@ -58,7 +58,7 @@ struct ClientCtl {
   uint32_t tau_lo;           // candidate threshold key from the sample (0: keep every coordinate)
   uint32_t n_cand;           // candidates kept by the filter pass that counts
   uint32_t refilter;         // 1: the sampled threshold kept fewer than k, the keep-all pass must run
-  uint32_t pad0;
+  uint32_t n_nz;             // regions that kept at least one coordinate
   double tail_sumsq;         // energy of the coordinates the filter dropped
   double seg_sumsq[32];      // energy of every coded group; entry R: candidates below the last boundary (atomic)
   uint32_t tie_cnt[kMaxGroups][16];  // kept-aside class members per (boundary group, histogram slot)

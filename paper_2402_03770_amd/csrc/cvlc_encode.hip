@@ -46,7 +46,7 @@ struct GroupInfo {
 };
 
 struct EncodeLayout {
-  size_t status, ctl, params, region_cnt, region_off, region_sumsq, cand_idx, cand_val, dense_idx, dense_val, span_cnt, group_info,
+  size_t status, ctl, params, region_cnt, region_off, region_sumsq, cand_idx, cand_val, dense_idx, dense_val, nz_off, nz_run, span_first, span_cnt, group_info,
       tie_list, sel_part, total;
   size_t zero_bytes;        // [status, params) is cleared at the start of a call
   uint32_t n_regions, max_spans;
@@ -86,6 +86,9 @@ EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   L.cand_val = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
   L.dense_idx = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
   L.dense_val = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
+  L.nz_off = off; off = align256(off + (size_t)n * (L.n_regions + 1) * sizeof(uint32_t));
+  L.nz_run = off; off = align256(off + (size_t)n * (L.n_regions + 1) * sizeof(uint32_t));
+  L.span_first = off; off = align256(off + (size_t)n * (L.max_spans + 1) * sizeof(uint32_t));
   L.span_cnt = off; off = align256(off + (size_t)n * (L.max_spans + 1) * 32 * sizeof(uint32_t));
   L.group_info = off; off = align256(off + (size_t)n * sizeof(GroupInfo));
   L.tie_list = off; off = align256(off + (size_t)n * kSlotGroup * kTieCap * sizeof(uint2));
@@ -105,6 +108,9 @@ struct Workspace {  // device pointers into the caller's workspace
   uint32_t* cand_val;  // their value bits, same layout
   uint32_t* dense_idx; // the same candidates, contiguous per client, in position order
   uint32_t* dense_val;
+  uint32_t* nz_off;      // the non-empty runs in position order: number of the run's first candidate ...
+  uint32_t* nz_run;      // ... and its region; entry n_nz of nz_off holds the number of candidates
+  uint32_t* span_first;  // index (into the non-empty runs) of the run that holds candidate 512 s, per span s
   uint32_t* span_cnt;  // per span of 512 candidates: members of every group, then their exclusive prefix
   GroupInfo* group_info;
   uint2* tie_list;
@@ -427,7 +433,9 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __re
 
 // ------------------------------------------------------------------ 3. region prefix + selection level 1
 // One workgroup per client.  Turns the region counts into exclusive offsets
-// (the candidates' position-ordered numbering), then reads the level-1
+// and lists the non-empty runs with the number of their first candidate (the
+// candidates' position-ordered numbering; the gather works in spans of 512
+// candidates, and the run holding every span's first candidate is noted), then reads the level-1
 // histogram the filter's workgroups accumulated and locates, for every boundary
 // Z_r, the bin holding the Z_r-th largest key and the rank left inside it.
 template <int PASS>
@@ -443,18 +451,34 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
   const uint32_t n_regions = ws.n_regions;
   const uint32_t* cnt = ws.region_cnt + (size_t)client * n_regions;
   uint32_t* off = ws.region_off + (size_t)client * (n_regions + 1);
-  uint32_t run = 0;
+  uint32_t* nz_off = ws.nz_off + (size_t)client * (n_regions + 1);
+  uint32_t* nz_run = ws.nz_run + (size_t)client * (n_regions + 1);
+  uint32_t* span_first = ws.span_first + (size_t)client * (ws.max_spans + 1);
+  uint32_t run = 0, n_nz = 0;
   for (uint32_t base = 0; base < n_regions; base += kWideBlock) {
     const uint32_t j = base + tid;
     const uint32_t v = j < n_regions ? cnt[j] : 0u;
-    uint32_t tot;
+    uint32_t tot, tot_nz;
     const uint32_t excl = block_excl_scan<kWideWaves>(v, scan_tmp, &tot);
-    if (j < n_regions) off[j] = run + excl;
+    const uint32_t q = n_nz + block_excl_scan<kWideWaves>(v ? 1u : 0u, scan_tmp, &tot_nz);
+    if (j < n_regions) {
+      off[j] = run + excl;
+      if (v) {
+        const uint32_t begin = run + excl, end = begin + v;
+        nz_off[q] = begin;
+        nz_run[q] = j;
+        // spans whose first candidate lies in this run
+        for (uint32_t sp = (begin + kSpan - 1) / kSpan; (uint64_t)sp * kSpan < end; ++sp) span_first[sp] = q;
+      }
+    }
     run += tot;
+    n_nz += tot_nz;
   }
   if (tid == 0) {
     off[n_regions] = run;
+    nz_off[n_nz] = run;
     ctl->n_cand = run;
+    ctl->n_nz = n_nz;
   }
   if (PASS == 0 && run < p.k) {  // the sample misjudged the threshold: everything is redone by pass 1
     if (tid == 0) ctl->refilter = 1u;
@@ -593,6 +617,82 @@ __device__ __forceinline__ void select_count(SelectShared& S, uint32_t key, cons
   }
 }
 
+// ---- walking the filter's output in position order
+constexpr uint32_t kNoGroup = 0xFFFFFFFFu;
+constexpr uint32_t kEmitBlock = kSpan * kChunkSpans / 8u;  // threads of a count/emit workgroup: 8 candidates each
+constexpr uint32_t kEmitWaves = kEmitBlock / kWave;
+constexpr uint32_t kPerLane = kSpan / kWave;              // candidates per lane per span
+static_assert(kEmitWaves == kChunkSpans && kPerLane == 8, "one wavefront per span, eight rows of 64");
+
+// The candidates of one client in position order, as the filter left them:
+// candidate i is entry i - nz_off[q] of the run of region nz_run[q], q the last
+// non-empty run with nz_off[q] <= i.
+struct CandView {
+  const uint32_t* __restrict__ val;         // region slots: value bits
+  const uint32_t* __restrict__ idx;         // region slots: positions
+  const uint32_t* __restrict__ nz_off;      // n_nz + 1 entries, the last = n
+  const uint32_t* __restrict__ nz_run;
+  const uint32_t* __restrict__ span_first;  // q of candidate 512 s
+  uint32_t n_nz, n;
+};
+
+__device__ __forceinline__ CandView cand_view(const Workspace& ws, const ClientCtl* ctl, uint32_t client) {
+  CandView view;
+  view.val = ws.cand_val + (size_t)client * ws.d;
+  view.idx = ws.cand_idx + (size_t)client * ws.d;
+  view.nz_off = ws.nz_off + (size_t)client * (ws.n_regions + 1);
+  view.nz_run = ws.nz_run + (size_t)client * (ws.n_regions + 1);
+  view.span_first = ws.span_first + (size_t)client * (ws.max_spans + 1);
+  view.n_nz = ctl->n_nz;
+  view.n = ctl->n_cand;
+  return view;
+}
+
+// Places of the candidates of span `span` in the region slots: row j of the
+// span is candidate span*512 + j*64 + lane.  The runs that follow the span's
+// first one are fetched 64 at a time, one per lane; every run that starts
+// inside the span moves the rows at or after its first candidate on to it.
+__device__ __forceinline__ void span_slots(const CandView& cv, uint32_t span, uint32_t (&slot)[kPerLane]) {
+  const uint32_t lane = lane_id();
+  const uint32_t begin = span * kSpan;
+  const uint32_t end = min(begin + kSpan, cv.n);
+  uint32_t base = cv.span_first[span];
+  uint32_t wo = cv.nz_off[min(base + lane, cv.n_nz)];
+  uint32_t wr = cv.nz_run[min(base + lane, cv.n_nz)];  // entry n_nz is never selected: its offset is n >= end
+  uint32_t run_of[kPerLane], off_of[kPerLane];
+  const uint32_t off0 = __builtin_amdgcn_readlane(wo, 0), run0 = __builtin_amdgcn_readlane(wr, 0);
+#pragma unroll
+  for (uint32_t j = 0; j < kPerLane; ++j) {
+    run_of[j] = run0;
+    off_of[j] = off0;
+  }
+  while (true) {
+    uint32_t t = 1;
+    for (; t < kWave; ++t) {
+      const uint32_t ot = __builtin_amdgcn_readlane(wo, t);
+      if (ot >= end) break;
+      const uint32_t rt = __builtin_amdgcn_readlane(wr, t);
+#pragma unroll
+      for (uint32_t j = 0; j < kPerLane; ++j) {
+        const uint32_t i = begin + j * kWave + lane;
+        if (i >= ot) {
+          run_of[j] = rt;
+          off_of[j] = ot;
+        }
+      }
+    }
+    if (t < kWave) break;
+    base += kWave - 1;  // entry 63 of this window is entry 0 of the next
+    wo = cv.nz_off[min(base + lane, cv.n_nz)];
+    wr = cv.nz_run[min(base + lane, cv.n_nz)];
+  }
+#pragma unroll
+  for (uint32_t j = 0; j < kPerLane; ++j) {
+    const uint32_t i = begin + j * kWave + lane;
+    slot[j] = run_of[j] * kRegion + (i - off_of[j]);  // meaningless for i >= n, never used there
+  }
+}
+
 // Fills the workgroup's slot tables for one group of boundaries.
 template <int LEVEL>
 __device__ __forceinline__ void select_setup(SelectShared& S, const ClientCtl* ctl, uint32_t r0, uint32_t nb) {
@@ -621,10 +721,11 @@ __device__ __forceinline__ void select_setup(SelectShared& S, const ClientCtl* c
 }
 
 // Level 2 of the first group of boundaries, fused with the gather: every
-// wavefront takes region runs (gw, gw + wavefronts, ...), copies them to their
-// place in the dense position-ordered candidate list (region_off is the
-// exclusive prefix of the run lengths) and counts the level-2 digits on the
-// way.  The wavefronts do not wait for each other until the histogram is stored.
+// wavefront takes spans of 512 candidates (gw, gw + wavefronts, ...), collects
+// them from the region runs they lie in, stores them at their place in the
+// dense position-ordered candidate list and counts the level-2 digits on the
+// way.  Every span is the same amount of work wherever its candidates lie.
+// The wavefronts do not wait for each other until the histogram is stored.
 __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParams* __restrict__ params,
                                                                ClientCtl* __restrict__ ctls, Workspace ws) {
   __shared__ SelectShared S;
@@ -633,71 +734,34 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
   ClientCtl* ctl = ctls + client;
   const uint32_t nb = min(p.R, kSlotGroup);
   select_setup<2>(S, ctl, 0, nb);
-  const uint32_t d = ws.d, n_regions = ws.n_regions;
-  const uint32_t* __restrict__ cnt = ws.region_cnt + (size_t)client * n_regions;
-  const uint32_t* __restrict__ off = ws.region_off + (size_t)client * (n_regions + 1);
-  const uint32_t* __restrict__ src_idx = ws.cand_idx + (size_t)client * d;
-  const uint32_t* __restrict__ src_val = ws.cand_val + (size_t)client * d;
-  uint32_t* __restrict__ dst_idx = ws.dense_idx + (size_t)client * d;
-  uint32_t* __restrict__ dst_val = ws.dense_val + (size_t)client * d;
-  const uint32_t wpc = gridDim.x * kWideWaves;  // wavefronts per client
-  // One-step software pipeline: the loads of a step (up to 256 entries of a run) are issued before the
-  // stores of the step before, so that a wavefront never waits for a store's acknowledgement with
-  // nothing in flight (loads and stores share one outstanding-operation counter).
-  bool have = false;
-  uint32_t pv[4], px[4], p_rc = 0, p_ro = 0, p_b = 0;
-  auto retire = [&]() {
-    if (!have) return;
+  const CandView cv = cand_view(ws, ctl, client);
+  uint32_t* __restrict__ dst_idx = ws.dense_idx + (size_t)client * ws.d;
+  uint32_t* __restrict__ dst_val = ws.dense_val + (size_t)client * ws.d;
+  const uint32_t n_spans = (cv.n + kSpan - 1) / kSpan;
+  for (uint32_t span = blockIdx.x * kWideWaves + wave; span < n_spans; span += gridDim.x * kWideWaves) {
+    uint32_t slot[kPerLane], v[kPerLane], x[kPerLane];
+    span_slots(cv, span, slot);
 #pragma unroll
-    for (uint32_t u = 0; u < 4; ++u) {
-      const uint32_t i = p_b + u * kWave + lane;
-      if (p_b + u * kWave >= p_rc) break;  // uniform
-      if (i < p_rc) {
-        dst_val[p_ro + i] = pv[u];
-        dst_idx[p_ro + i] = px[u];
+    for (uint32_t j = 0; j < kPerLane; ++j) {
+      const uint32_t i = span * kSpan + j * kWave + lane;
+      v[j] = 0;
+      x[j] = 0;
+      if (i < cv.n) {
+        v[j] = cv.val[slot[j]];
+        x[j] = cv.idx[slot[j]];
       }
-      if (nb) select_count<2>(S, pv[u] & 0x7FFFFFFFu, nullptr, i < p_rc, nullptr, nullptr);
     }
-  };
-  // the runs' lengths and offsets are fetched 64 at a time, one per lane
-  for (uint32_t first = blockIdx.x * kWideWaves + wave; first < n_regions; first += wpc * kWave) {
-    const uint32_t mine = first + lane * wpc;
-    uint32_t c = 0, o = 0;
-    if (mine < n_regions) {
-      c = cnt[mine];
-      o = off[mine];
-    }
-    const uint32_t left = (n_regions - first + wpc - 1) / wpc;
-    const uint32_t nr = left < kWave ? left : kWave;
-    for (uint32_t l = 0; l < nr; ++l) {
-      const uint32_t rc = __builtin_amdgcn_readlane(c, l), ro = __builtin_amdgcn_readlane(o, l);
-      const size_t slot0 = (size_t)(first + l * wpc) * kRegion;
-      for (uint32_t b = 0; b < rc; b += kWave * 4u) {
-        uint32_t v[4], x[4];
 #pragma unroll
-        for (uint32_t u = 0; u < 4; ++u) {
-          const uint32_t i = b + u * kWave + lane;
-          v[u] = 0;
-          x[u] = 0;
-          if (i < rc) {
-            v[u] = src_val[slot0 + i];
-            x[u] = src_idx[slot0 + i];
-          }
-        }
-        retire();
-#pragma unroll
-        for (uint32_t u = 0; u < 4; ++u) {
-          pv[u] = v[u];
-          px[u] = x[u];
-        }
-        p_rc = rc;
-        p_ro = ro;
-        p_b = b;
-        have = true;
+    for (uint32_t j = 0; j < kPerLane; ++j) {
+      const uint32_t i = span * kSpan + j * kWave + lane;
+      if (i - lane >= cv.n) break;  // uniform
+      if (i < cv.n) {
+        dst_val[i] = v[j];
+        dst_idx[i] = x[j];
       }
+      if (nb) select_count<2>(S, v[j] & 0x7FFFFFFFu, nullptr, i < cv.n, nullptr, nullptr);
     }
   }
-  retire();
   __syncthreads();
   if (nb == 0) return;
   uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * kSlotGroup * kDigitBins;
@@ -901,12 +965,6 @@ __device__ __forceinline__ uint32_t classify_tie(const Thresholds& t, uint32_t k
   }
   return g;
 }
-
-constexpr uint32_t kNoGroup = 0xFFFFFFFFu;
-constexpr uint32_t kEmitBlock = kSpan * kChunkSpans / 8u;  // threads of a count/emit workgroup: 8 candidates each
-constexpr uint32_t kEmitWaves = kEmitBlock / kWave;
-constexpr uint32_t kPerLane = kSpan / kWave;              // candidates per lane per span
-static_assert(kEmitWaves == kChunkSpans && kPerLane == 8, "one wavefront per span, eight rows of 64");
 
 // Lanes that hold a candidate of the caller's group (5-bit group id); lanes
 // with g == kNoGroup match nobody.  Must be reached by the whole wavefront.
@@ -1399,6 +1457,9 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   ws.cand_val = reinterpret_cast<uint32_t*>(base + L.cand_val);
   ws.dense_idx = reinterpret_cast<uint32_t*>(base + L.dense_idx);
   ws.dense_val = reinterpret_cast<uint32_t*>(base + L.dense_val);
+  ws.nz_off = reinterpret_cast<uint32_t*>(base + L.nz_off);
+  ws.nz_run = reinterpret_cast<uint32_t*>(base + L.nz_run);
+  ws.span_first = reinterpret_cast<uint32_t*>(base + L.span_first);
   ws.span_cnt = reinterpret_cast<uint32_t*>(base + L.span_cnt);
   ws.group_info = reinterpret_cast<GroupInfo*>(base + L.group_info);
   ws.tie_list = reinterpret_cast<uint2*>(base + L.tie_list);
