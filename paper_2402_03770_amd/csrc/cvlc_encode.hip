@@ -1075,9 +1075,9 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
 // ------------------------------------------------------------------ 7. layout: prefix, headers, statistics
 typedef uint32_t __attribute__((address_space(1))) * GlobalWordPtr;
 
-// One workgroup of 1024 threads per client.  Wavefront w turns the per-span
-// counts of groups w, w+16, ... into exclusive prefixes (in place; the row after
-// the last span receives the totals), checks the totals against the plan, and
+// One workgroup of 1024 threads per client.  Turns the per-span counts of the
+// groups into exclusive prefixes (in place; the row after the last span
+// receives the totals), checks the totals against the plan, and
 // clears the first and the last stream word of every (chunk, group) record run,
 // a chunk being 8 spans: those two words can be shared with the neighbouring
 // chunks, which OR their bits in; all other payload words have one owner and are
@@ -1087,6 +1087,7 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
                                                             cvlc_seg_stats_t* __restrict__ stats_out) {
   __shared__ double s_tail[kWideWaves];
   __shared__ uint32_t s_payload[32];
+  __shared__ uint32_t s_tot[kWideWaves][32];
   const uint32_t client = blockIdx.x, tid = threadIdx.x;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
@@ -1102,49 +1103,73 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
     s_payload[tid] = kGlobalHeaderWords + kSegHeaderWords * R + incl - words;
   }
   __syncthreads();
-  constexpr uint32_t kBatches = 8;  // 64-span batches loaded together
-  for (uint32_t g = wave; g < 32; g += kWideWaves) {
-    const uint32_t W = g < R ? sbits + p.y[g] : 0u;
-    const uint32_t P = g < R ? p.Z[g] - (g ? p.Z[g - 1] : 0u) : 0u;
-    uint32_t run = 0;
-    if (g >= R) {  // no records: the prefix of these columns is never read, only cleared
-      for (uint32_t c = lane; c <= n_spans; c += kWave) cnt[(size_t)c * 32 + g] = 0;
-      continue;
-    }
-    for (uint32_t c00 = 0; c00 < n_spans; c00 += kWave * kBatches) {
-      uint32_t vs[kBatches];
+  // Exclusive prefix of the per-span counts over the spans, per group, in place.
+  // Wavefront w takes a contiguous range of spans (a whole number of chunks); a
+  // lane takes group (lane & 31) of every second span, so that one load covers
+  // two whole rows of the table.
+  const uint32_t g = lane & 31u, half = lane >> 5;
+  const uint32_t W = g < R ? sbits + p.y[g] : 0u;
+  const uint32_t P = g < R ? p.Z[g] - (g ? p.Z[g - 1] : 0u) : 0u;
+  const uint32_t per_wave = (((n_spans + kWideWaves - 1) / kWideWaves + kChunkSpans - 1) / kChunkSpans) * kChunkSpans;
+  const uint32_t s0 = min(wave * per_wave, n_spans), s1 = min(s0 + per_wave, n_spans);
+  constexpr uint32_t kBatch = 8;  // loads in flight per lane
+  {
+    uint32_t acc = 0;
+    for (uint32_t c = s0; c < s1; c += 2 * kBatch) {
+      uint32_t vs[kBatch];
 #pragma unroll
-      for (uint32_t u = 0; u < kBatches; ++u) {
-        const uint32_t c = c00 + u * kWave + lane;
-        vs[u] = c < n_spans ? cnt[(size_t)c * 32 + g] : 0u;
+      for (uint32_t u = 0; u < kBatch; ++u) {
+        const uint32_t cc = c + 2 * u + half;
+        vs[u] = cc < s1 ? cnt[(size_t)cc * 32 + g] : 0u;
       }
 #pragma unroll
-      for (uint32_t u = 0; u < kBatches; ++u) {
-        const uint32_t c = c00 + u * kWave + lane;  // the batch starts at a multiple of 64, hence of the chunk size
-        if (c00 + u * kWave >= n_spans) break;      // uniform
-        const uint32_t v = vs[u];
-        const uint32_t incl = wave_incl_scan_u32(v);
-        const uint32_t excl = run + incl - v;
-        run += __shfl(incl, 63, 64);
-        // the chunk that starts at span c ends where the chunk 8 spans on starts
-        const uint32_t next = __shfl_down(excl, kChunkSpans, 64);
-        const uint32_t chunk_end = lane + kChunkSpans < kWave ? next : run;
-        if (c < n_spans) {
-          cnt[(size_t)c * 32 + g] = excl;
-          // a consistent selection never passes the planned size; the test keeps the two
-          // stores inside the group's payload even if an internal check has failed
-          if (c % kChunkSpans == 0 && chunk_end > excl && chunk_end <= P) {
-            const uint64_t bit0 = (uint64_t)excl * W, bit1 = (uint64_t)chunk_end * W;
-            stream[s_payload[g] + (uint32_t)(bit0 >> 5)] = 0;
-            stream[s_payload[g] + (uint32_t)((bit1 - 1) >> 5)] = 0;
-          }
-        }
+      for (uint32_t u = 0; u < kBatch; ++u) acc += vs[u];
+    }
+    acc += __shfl_xor(acc, 32, 64);
+    if (half == 0) s_tot[wave][g] = acc;
+  }
+  __syncthreads();
+  uint32_t run = 0, total = 0;
+  for (uint32_t w = 0; w < kWideWaves; ++w) {
+    const uint32_t t = s_tot[w][g];
+    if (w < wave) run += t;
+    total += t;
+  }
+  // The first and the last word of a (chunk, group) record run [b, e); a consistent selection
+  // never passes the planned size, and the test keeps the two stores inside the group's
+  // payload even if an internal check has failed.
+  auto clear_edges = [&](uint32_t b, uint32_t e) {
+    if (half == 0 && e > b && e <= P) {
+      const uint64_t bit0 = (uint64_t)b * W, bit1 = (uint64_t)e * W;
+      stream[s_payload[g] + (uint32_t)(bit0 >> 5)] = 0;
+      stream[s_payload[g] + (uint32_t)((bit1 - 1) >> 5)] = 0;
+    }
+  };
+  uint32_t chunk_begin = run;
+  for (uint32_t c = s0; c < s1; c += 2 * kBatch) {
+    uint32_t vs[kBatch];
+#pragma unroll
+    for (uint32_t u = 0; u < kBatch; ++u) {
+      const uint32_t cc = c + 2 * u + half;
+      vs[u] = cc < s1 ? cnt[(size_t)cc * 32 + g] : 0u;
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < kBatch; ++u) {
+      const uint32_t cp = c + 2 * u;  // the pair's first span
+      if (cp >= s1) break;            // uniform
+      if (cp % kChunkSpans == 0 && cp > s0) {
+        clear_edges(chunk_begin, run);
+        chunk_begin = run;
       }
+      const uint32_t v = vs[u], other = __shfl_xor(v, 32, 64);
+      if (cp + half < s1) cnt[(size_t)(cp + half) * 32 + g] = half ? run + other : run;
+      run += v + other;
     }
-    if (lane == 0) {
-      cnt[(size_t)n_spans * 32 + g] = run;
-      if (run != P) atomicOr(ws.status, CVLC_DEV_INTERNAL);
-    }
+  }
+  if (s1 > s0) clear_edges(chunk_begin, run);
+  if (wave == 0 && half == 0) {
+    cnt[(size_t)n_spans * 32 + g] = total;
+    if (g < R && total != P) atomicOr(ws.status, CVLC_DEV_INTERNAL);
   }
   // energy of the coordinates the filter dropped, region by region
   const double* rsq = ws.region_sumsq + (size_t)client * ws.n_regions;
