@@ -62,8 +62,8 @@ struct ClientCtl {
   double tail_sumsq;         // energy of the coordinates the filter dropped
   double seg_sumsq[32];      // energy of every coded group; entry R: candidates below the last boundary (atomic)
   uint32_t tie_cnt[kMaxGroups][16];  // kept-aside class members per (boundary group, histogram slot)
-  uint32_t sel_prefix[32];   // key prefix fixed so far for boundary r (0xFFFFFFFF: Z_r = 0)
-  uint32_t sel_rem[32];      // rank of the boundary element inside the prefix class, 1-based from the top
+  uint32_t sel_prefix[2][32];  // key prefix of boundary r after level 1 (11 bits) and level 2 (21 bits); 0xFFFFFFFF: Z_r = 0
+  uint32_t sel_rem[2][32];     // rank of the boundary element inside that prefix class, 1-based from the top
   uint32_t tau[32];          // Z_r-th largest key (0xFFFFFFFF: Z_r = 0)
   uint32_t iota[32];         // largest index among the key == tau_r coordinates inside the top Z_r
   uint32_t seg_max_enc[32];  // max over the group of ordered(x); 0 = empty

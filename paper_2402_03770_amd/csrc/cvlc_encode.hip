@@ -510,8 +510,8 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
         rem = Z - (incl[lo] - hist[lo]);
       }
     }
-    ctl->sel_prefix[tid] = pre;
-    ctl->sel_rem[tid] = rem;
+    ctl->sel_prefix[0][tid] = pre;
+    ctl->sel_rem[0][tid] = rem;
     ctl->tau[tid] = 0xFFFFFFFFu;  // boundaries with Z_r = 0 keep "nothing inside"
     ctl->iota[tid] = 0u;
   }
@@ -535,24 +535,36 @@ struct SlotTable {
   uint32_t n;
 };
 
-// Slots in order of first appearance among the group's boundaries, whose
-// prefixes are in pre[0..nb).  Run by one thread.
-__device__ void build_slots(SlotTable& st, const uint32_t* pre_of, uint32_t nb) {
-  uint32_t ns = 0;
-  for (uint32_t b = 0; b < nb; ++b) {
-    const uint32_t pre = pre_of[b];
-    uint32_t slot = kNoSlot;
-    if (pre != 0xFFFFFFFFu) {
-      for (uint32_t q = 0; q < ns; ++q)
-        if (st.prefix[q] == pre) slot = q;
-      if (slot == kNoSlot) {
-        slot = ns++;
-        st.prefix[slot] = pre;
-      }
-    }
-    st.leader[b] = slot;
+// Lane of the first of the lanes 0..kSlotGroup-1 that are `valid` and hold the
+// caller's value (the caller's own lane if none is earlier).  Whole wavefront;
+// the result means something for valid lanes below kSlotGroup only.
+__device__ __forceinline__ uint32_t first_equal_lane(uint32_t value, bool valid) {
+  const uint64_t vmask = __ballot(valid);
+  const uint32_t lane = lane_id();
+  uint32_t first = lane;
+#pragma unroll
+  for (int j = (int)kSlotGroup - 1; j >= 0; --j) {
+    const uint32_t vj = __builtin_amdgcn_readlane(value, j);
+    if (((vmask >> j) & 1u) && (uint32_t)j < lane && vj == value) first = (uint32_t)j;
   }
-  st.n = ns;
+  return first;
+}
+
+// Slots in order of first appearance among the group's boundaries.  Run by one
+// whole wavefront whose lane b < nb holds boundary b's prefix.  Returns the
+// caller's slot (kNoSlot: Z_r = 0 or no boundary) and whether it opens it.
+__device__ __forceinline__ uint32_t build_slots(SlotTable& st, uint32_t pre, uint32_t nb, bool* opens) {
+  const uint32_t lane = lane_id();
+  const bool valid = lane < nb && pre != 0xFFFFFFFFu;
+  const uint32_t first = first_equal_lane(pre, valid);
+  const bool leader = valid && first == lane;
+  const uint64_t leaders = __ballot(leader);
+  const uint32_t slot = valid ? (uint32_t)__popcll(leaders & ((1ull << first) - 1ull)) : kNoSlot;
+  if (leader) st.prefix[slot] = pre;
+  if (lane < kSlotGroup) st.leader[lane] = slot;
+  if (lane == 0) st.n = (uint32_t)__popcll(leaders);
+  *opens = leader;
+  return slot;
 }
 
 struct SelectShared {
@@ -561,13 +573,12 @@ struct SelectShared {
   uint32_t bin_slot[kL1Bins / 8];                // top 11 key bits -> 1 + (level 2: slot, level 3: bin id), 4 bits each
   uint32_t digit_map[kSlotGroup][kDigitBins / 32];  // level 3: second digits present per bin id
   uint32_t tie_full[kSlotGroup];                 // this workgroup has seen the slot's kept-aside list overflow
-  uint32_t pre[kSlotGroup];                      // the group's boundary prefixes
 
   __device__ __forceinline__ uint32_t bin_tag(uint32_t top11) const {
     return (bin_slot[top11 >> 3] >> ((top11 & 7u) * 4u)) & 15u;
   }
-  __device__ __forceinline__ void set_bin_tag(uint32_t top11, uint32_t tag) {  // single thread, tag <= 15
-    bin_slot[top11 >> 3] |= tag << ((top11 & 7u) * 4u);
+  __device__ __forceinline__ void set_bin_tag(uint32_t top11, uint32_t tag) {  // once per top11, tag <= 15
+    atomicOr(&bin_slot[top11 >> 3], tag << ((top11 & 7u) * 4u));
   }
 };
 static_assert(kSlotGroup <= 15, "bin tags are 4 bits wide");
@@ -701,19 +712,23 @@ __device__ __forceinline__ void select_setup(SelectShared& S, const ClientCtl* c
   for (uint32_t i = tid; i < kL1Bins / 8; i += kWideBlock) S.bin_slot[i] = 0;
   for (uint32_t i = tid; i < kSlotGroup * (kDigitBins / 32); i += kWideBlock) (&S.digit_map[0][0])[i] = 0;
   if (tid < kSlotGroup) S.tie_full[tid] = 0;
-  if (tid < nb) S.pre[tid] = ctl->sel_prefix[r0 + tid];
+  uint32_t pre = 0xFFFFFFFFu;
+  if (tid < nb) pre = ctl->sel_prefix[LEVEL - 2][r0 + tid];
   __syncthreads();
-  if (tid == 0) {
-    build_slots(S.slots, S.pre, nb);
-    uint32_t nbins = 0;
-    for (uint32_t q = 0; q < S.slots.n; ++q) {
-      const uint32_t pre = S.slots.prefix[q];
-      if (LEVEL == 2) {
-        S.set_bin_tag(pre, q + 1);
-      } else {
-        const uint32_t top11 = pre >> 10, second = pre & (kDigitBins - 1);
-        if (S.bin_tag(top11) == 0) S.set_bin_tag(top11, ++nbins);
-        S.digit_map[S.bin_tag(top11) - 1][second >> 5] |= 1u << (second & 31u);
+  if (tid < kWave) {  // the first wavefront, lane b = boundary b
+    bool opens;
+    const uint32_t slot = build_slots(S.slots, pre, nb, &opens);
+    if (LEVEL == 2) {
+      if (opens) S.set_bin_tag(pre, slot + 1);
+    } else {
+      // the slots' top 11 bits are numbered in order of first appearance as well
+      const uint32_t top11 = pre >> 10, second = pre & (kDigitBins - 1);
+      const uint32_t first = first_equal_lane(top11, opens);
+      const uint64_t bin_openers = __ballot(opens && first == tid);
+      if (opens) {
+        const uint32_t bin = (uint32_t)__popcll(bin_openers & ((1ull << first) - 1ull));
+        if (first == tid) S.set_bin_tag(top11, bin + 1);
+        atomicOr(&S.digit_map[bin][second >> 5], 1u << (second & 31u));
       }
     }
   }
@@ -822,7 +837,7 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
                                                                  ClientCtl* __restrict__ ctls, Workspace ws,
                                                                  uint32_t group) {
   __shared__ SlotTable slots;
-  __shared__ uint32_t s_digit[kSlotGroup], s_quota[kSlotGroup], s_need[kSlotGroup], s_pre[kSlotGroup];
+  __shared__ uint32_t s_digit[kSlotGroup], s_quota[kSlotGroup], s_need[kSlotGroup], s_rem[kSlotGroup];
   __shared__ uint32_t s_found;
   __shared__ uint32_t scan_tmp[kWideWaves];
   __shared__ uint2 s_list[LEVEL == 3 ? kTieCap : 1];
@@ -834,36 +849,47 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   const uint32_t nb = min(p.R - r0, kSlotGroup);
   const uint32_t n_parts = ws.sel_blocks;
   const uint32_t* parts = ws.sel_part + (size_t)client * n_parts * kSlotGroup * kDigitBins;
-  if (tid < nb) s_pre[tid] = ctl->sel_prefix[r0 + tid];
-  if (tid < kSlotGroup) s_need[tid] = 0;
-  __syncthreads();
-  if (tid == 0) build_slots(slots, s_pre, nb);
-  __syncthreads();
-  if (slot >= slots.n) return;
-
-  // thread t takes digit 1023 - t, so that the scan runs from the top digit down
+  // Everything the walk reads from global memory is requested here, before the
+  // first wait.  Thread t takes digit 1023 - t, so that the scan runs from the top
+  // digit down; a slot past the last one in use adds up stale partials for nothing.
+  uint32_t pre = 0xFFFFFFFFu, rem_in = 0;
+  if (tid < nb) {
+    pre = ctl->sel_prefix[LEVEL - 2][r0 + tid];
+    rem_in = ctl->sel_rem[LEVEL - 2][r0 + tid];
+    // the level's results go to arrays of their own: other workgroups of this launch may still have to read its inputs
+    if (LEVEL == 2 && slot == 0 && pre == 0xFFFFFFFFu) ctl->sel_prefix[1][r0 + tid] = pre;
+  }
+  const uint32_t kept = LEVEL == 3 ? ctl->tie_cnt[group][slot] : 0u;
   const uint32_t digit = kDigitBins - 1 - tid;
   uint32_t h = 0;
 #pragma unroll 8
   for (uint32_t b = 0; b < n_parts; ++b) h += parts[((size_t)b * kSlotGroup + slot) * kDigitBins + digit];
+  if (tid < kSlotGroup) {
+    s_need[tid] = 0;
+    s_rem[tid] = rem_in;
+  }
+  if (tid < kWave) {
+    bool opens;
+    build_slots(slots, pre, nb, &opens);
+  }
+  __syncthreads();
+  if (slot >= slots.n) return;
   uint32_t total;
   const uint32_t above = block_excl_scan<kWideWaves>(h, scan_tmp, &total);  // keys with a larger digit
   const uint32_t prefix = slots.prefix[slot];
   for (uint32_t b = 0; b < nb; ++b) {
     if (slots.leader[b] != slot) continue;
     const uint32_t r = r0 + b;
-    const uint32_t rem = ctl->sel_rem[r];  // read by every thread before the owner below rewrites it
+    const uint32_t rem = s_rem[b];
     if (rem > total && tid == 0) atomicOr(ws.status, CVLC_DEV_INTERNAL);  // histogram short of the rank
-    __syncthreads();
     if (above < rem && rem <= above + h) {  // exactly one thread
       const uint32_t quota = rem - above;   // rank inside the digit class, 1-based
       const uint32_t full = (prefix << 10) | digit;
       if (LEVEL == 2) {
-        ctl->sel_prefix[r] = full;
-        ctl->sel_rem[r] = quota;
+        ctl->sel_prefix[1][r] = full;
+        ctl->sel_rem[1][r] = quota;
       } else {
         ctl->tau[r] = full;
-        ctl->sel_rem[r] = quota;     // tie quota q_r
         ctl->iota[r] = 0xFFFFFFFFu;  // every member of the class is inside unless it straddles Z_r
         s_digit[b] = digit;
         s_quota[b] = quota;
@@ -875,7 +901,6 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
     __syncthreads();
     // a class of equal keys straddles the boundary: find its quota-th member in position order
     const uint2* list = ws.tie_list + ((size_t)client * kSlotGroup + slot) * kTieCap;
-    const uint32_t kept = ctl->tie_cnt[group][slot];
     const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
     const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.d;
     const uint32_t n = ctl->n_cand;
