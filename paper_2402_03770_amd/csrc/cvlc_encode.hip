@@ -278,6 +278,7 @@ struct FilterWave {
   uint32_t* hist;          // the workgroup's level-1 histogram in LDS
   uint32_t fill;           // staged entries (uniform)
   uint32_t run;            // entries already written to `out` (uniform)
+  uint32_t nonfinite;      // a kept key was Inf or NaN (per lane)
 };
 
 // LDS accesses of one wavefront complete in order; this keeps the compiler from
@@ -292,6 +293,7 @@ __device__ __forceinline__ void flush_rows(FilterWave& w, uint32_t lane, bool al
     w.out_idx[w.run + g + lane] = e.x;
     w.out_val[w.run + g + lane] = e.y;
     atomicAdd(&w.hist[(e.y & 0x7FFFFFFFu) >> 20], 1u);
+    w.nonfinite |= (e.y & 0x7FFFFFFFu) >= 0x7F800000u ? 1u : 0u;
   }
   const uint32_t left = w.fill - g;  // < 64
   if (left) {
@@ -302,6 +304,7 @@ __device__ __forceinline__ void flush_rows(FilterWave& w, uint32_t lane, bool al
         w.out_idx[w.run + g + lane] = e.x;
         w.out_val[w.run + g + lane] = e.y;
         atomicAdd(&w.hist[(e.y & 0x7FFFFFFFu) >> 20], 1u);
+        w.nonfinite |= (e.y & 0x7FFFFFFFu) >= 0x7F800000u ? 1u : 0u;
       }
       g += left;
     } else if (g) {  // move the partial row to the front
@@ -315,10 +318,11 @@ __device__ __forceinline__ void flush_rows(FilterWave& w, uint32_t lane, bool al
 }
 
 // Stages the coordinates of one sub-tile whose key reaches tau_lo, in position
-// order.  The squares of the others go to *sq; *kmax tracks the largest key seen.
+// order.  The squares of the others go to *sq.  Inf and NaN have the largest
+// keys, so they are always among the kept ones, where flush_rows sees them.
 template <bool TAIL>
 __device__ __forceinline__ void filter_subtile(const SubTile& t, uint32_t sbase, uint32_t lane, uint32_t d,
-                                               uint32_t tau_lo, FilterWave& w, double* sq, uint32_t* kmax) {
+                                               uint32_t tau_lo, FilterWave& w, double* sq) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const uint32_t e0 = sbase + j * 256u + lane * 4u;
@@ -329,7 +333,6 @@ __device__ __forceinline__ void filter_subtile(const SubTile& t, uint32_t sbase,
     for (int c = 0; c < 4; ++c) {
       bits[c] = __float_as_uint(t.v[j][c]);
       const uint32_t key = bits[c] & 0x7FFFFFFFu;
-      *kmax = max(*kmax, key);
       keep[c] = key >= tau_lo && (!TAIL || e0 + c < d);
       m[c] = __ballot(keep[c]);
       const double dropped = (double)(keep[c] ? 0.0f : t.v[j][c]);  // coordinates past d were loaded as 0
@@ -373,12 +376,12 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __re
   for (uint32_t i = threadIdx.x; i < kL1Bins; i += kBlock) s_hist[i] = 0;
   __syncthreads();
 
-  uint32_t kmax = 0;
   double sq = 0.0;
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
   FilterWave w;
   w.stage = s_stage[wave_id()];
   w.hist = s_hist;
+  w.nonfinite = 0;
   // Software pipeline over all sub-tiles of all of this wavefront's regions: the
   // loads of the next sub-tile (of the next region, at a region's end) are issued
   // before the current one is processed, so the rare row stores sit behind loads
@@ -404,9 +407,9 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __re
       const bool more = next_region < n_regions;
       if (more) load_subtile(nxt, U, next_sbase, lane, d);
       if (sbase + kSubTile <= d) {
-        filter_subtile<false>(cur, sbase, lane, d, tau_lo, w, &sq, &kmax);
+        filter_subtile<false>(cur, sbase, lane, d, tau_lo, w, &sq);
       } else {
-        filter_subtile<true>(cur, sbase, lane, d, tau_lo, w, &sq, &kmax);
+        filter_subtile<true>(cur, sbase, lane, d, tau_lo, w, &sq);
       }
       if (last_of_region) {
         flush_rows(w, lane, true);
@@ -423,7 +426,8 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __re
       sbase = next_sbase;
     }
   }
-  if (kmax >= 0x7F800000u) atomicOr(ws.status, CVLC_DEV_NONFINITE);
+  // a threshold in the Inf/NaN range can only come from a sample that held such values
+  if (w.nonfinite || tau_lo > 0x7F800000u) atomicOr(ws.status, CVLC_DEV_NONFINITE);
   __syncthreads();
   for (uint32_t i = threadIdx.x; i < kL1Bins; i += kBlock) {
     const uint32_t h = s_hist[i];

@@ -202,6 +202,18 @@ def test_batch_with_mixed_plans():
     check_decode(refs, d, weights=[0.5, -1.0, 2.0, 0.25, 1.0, 1e-3])
 
 
+def test_more_clients_than_the_chip_holds_workgroups_for():
+    """96 clients: the per-(slot, client) launches are then larger than one resident set of workgroups, so
+    workgroups that start late run after others of the same launch have finished."""
+    d, n = 40_000, 96
+    host, plans = [], []
+    for c in range(n):
+        host.append(syn.update_vector(3 if c % 3 else 2, 1000 + c, d=d))
+        plans.append(orc.plan_alg1(d, int(d * (0.5 + 0.02 * (c % 11))), [15, 31, 4][c % 3], -0.6))
+    refs, _ = check_encode(host, plans, 5, list(range(n)))
+    check_decode(refs, d)
+
+
 @pytest.mark.parametrize("cfg,d,n", [(2, 1_200_000, 8), (3, 700_001, 4), (4, 1_000_000, 4), (5, 800_000, 3)])
 def test_workloads_at_oracle_friendly_sizes(cfg, d, n):
     w = syn.WORKLOADS[cfg]
