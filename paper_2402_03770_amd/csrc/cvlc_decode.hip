@@ -374,51 +374,49 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
       }
       if (tid == 0) S.first[nl] = total;
       __syncthreads();
-      // eight records per thread at a time: searches and descriptors from LDS, then all
-      // record loads together, so that their latencies overlap
-      constexpr uint32_t kUnroll = 8;
+      // Six records per thread at a time: searches and descriptors from LDS, then all
+      // record loads together, so that their latencies overlap.  Nothing in the first
+      // half branches (a thread past the end works on the last record again, a record
+      // near the end of its payload reads the last word twice), so that no load has
+      // to be waited for before the next one is issued.
+      constexpr uint32_t kUnroll = 6;
+      uint32_t steps = 0;  // binary search steps that settle any list index below nl
+      while ((1u << steps) < nl) ++steps;
       for (uint32_t q0 = tid; q0 < total; q0 += kDecBlock * kUnroll) {
-        uint32_t li_of[kUnroll], sh_of[kUnroll];
-        uint64_t a_of[kUnroll];
-        uint32_t b_of[kUnroll];
-        bool live[kUnroll];
+        uint32_t at_of[kUnroll], w0_of[kUnroll], w1_of[kUnroll], w2_of[kUnroll];  // at: list << 8 | flags | shift
 #pragma unroll
         for (uint32_t u = 0; u < kUnroll; ++u) {
-          const uint32_t q = q0 + u * kDecBlock;
-          live[u] = q < total;
+          const uint32_t q = min(q0 + u * kDecBlock, total - 1u);
           uint32_t a = 0, b = nl;  // last list with first <= q (lists with no record in the tile are skipped over)
-          while (b - a > 1) {
+          for (uint32_t it = 0; it < steps; ++it) {
             const uint32_t mid = (a + b) >> 1;
-            if (S.first[mid] <= q) a = mid; else b = mid;
+            const bool take = S.first[mid] <= q;  // mid == a once b - a <= 1: nothing moves any more
+            a = take ? mid : a;
+            b = take ? b : mid;
           }
-          li_of[u] = a;
-          a_of[u] = 0;
-          b_of[u] = 0;
-          sh_of[u] = 0;
-          if (live[u]) {
-            const uint4 d0 = S.desc[a][0], d1 = S.desc[a][1];
-            GlobalConstWordPtr pay = (GlobalConstWordPtr)(((uint64_t)d0.y << 32) | d0.x);
-            const uint32_t P = d1.x, W = d1.y & 0xFFu;
-            const uint64_t n_words = payload_words(P, W);
-            const uint32_t e = S.begin[a] + (q - S.first[a]);
-            const uint64_t bit = (uint64_t)e * W;
-            const uint64_t w = bit >> 5;
-            sh_of[u] = (uint32_t)(bit & 31u);
-            // two words always exist or the second reads as 0; the third only when the record reaches it
-            const uint32_t w0 = pay[w];
-            const uint32_t w1 = (w + 1 < n_words) ? pay[w + 1] : 0u;
-            a_of[u] = ((uint64_t)w1 << 32) | w0;
-            if (sh_of[u] + W > 64u) b_of[u] = pay[w + 2];  // inside the payload: the record's last bit lies there
-          }
+          const uint4 d0 = S.desc[a][0], d1 = S.desc[a][1];
+          GlobalConstWordPtr pay = (GlobalConstWordPtr)(((uint64_t)d0.y << 32) | d0.x);
+          const uint32_t P = d1.x, W = d1.y & 0xFFu;
+          const uint32_t last_word = (uint32_t)payload_words(P, W) - 1u;  // P >= 1; sizes were checked against 2^32 words
+          const uint32_t e = S.begin[a] + (q - S.first[a]);
+          const uint64_t bit = (uint64_t)e * W;
+          const uint32_t w = (uint32_t)(bit >> 5);
+          at_of[u] = (a << 8) | (uint32_t)(bit & 31u);
+          w0_of[u] = pay[w];
+          w1_of[u] = pay[min(w + 1u, last_word)];
+          w2_of[u] = pay[min(w + 2u, last_word)];
+          if (w + 1u > last_word) at_of[u] |= 0x80u;  // the second word does not exist: reads as 0
         }
 #pragma unroll
         for (uint32_t u = 0; u < kUnroll; ++u) {
-          if (!live[u]) continue;
-          const uint4 d0 = S.desc[li_of[u]][0], d1 = S.desc[li_of[u]][1];
+          if (q0 + u * kDecBlock >= total) continue;
+          const uint4 d0 = S.desc[at_of[u] >> 8][0], d1 = S.desc[at_of[u] >> 8][1];
           const uint32_t W = d1.y & 0xFFu, s = (d1.y >> 8) & 0xFFu, y = (d1.y >> 16) & 0xFFu;
           const double weight = __hiloint2double((int)d0.w, (int)d0.z);
-          uint64_t rec = a_of[u] >> sh_of[u];
-          if (sh_of[u] + W > 64u) rec |= (uint64_t)b_of[u] << (64u - sh_of[u]);
+          const uint32_t sh = at_of[u] & 31u;
+          const uint32_t w1 = (at_of[u] & 0x80u) ? 0u : w1_of[u];
+          uint64_t rec = (((uint64_t)w1 << 32) | w0_of[u]) >> sh;
+          if (sh + W > 64u) rec |= (uint64_t)w2_of[u] << (64u - sh);  // the record's last bit lies in the third word
           rec &= (1ull << W) - 1ull;
           const uint32_t pid = (uint32_t)(rec & ((1ull << s) - 1ull));
           const uint32_t cid = (uint32_t)(rec >> s);
