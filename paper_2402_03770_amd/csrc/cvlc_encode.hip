@@ -1021,13 +1021,15 @@ __device__ __forceinline__ void classify_span(const Thresholds& thr, uint32_t R,
                                               uint32_t (&v)[kPerLane], uint32_t (&grp)[kPerLane]) {
   const uint32_t mine = span * kSpan + lane_id();
   uint32_t key[kPerLane];
+  // no branch around the loads (a lane past the end reads the last candidate again): all eight are in
+  // flight before the first is waited for
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) {
     const uint32_t i = mine + j * kWave;
-    v[j] = 0;
-    if (i < n) v[j] = val[i];
-    key[j] = v[j] & 0x7FFFFFFFu;
+    v[j] = val[min(i, n - 1u)];
   }
+#pragma unroll
+  for (uint32_t j = 0; j < kPerLane; ++j) key[j] = v[j] & 0x7FFFFFFFu;
   classify_keys<kPerLane>(thr, R, key, grp);
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) {
@@ -1305,7 +1307,7 @@ constexpr uint32_t kStageWords = kChunkCands * 2 + 2 * 32;    // every record is
 // covers.  The image is then written out: a group's first and last word can be
 // shared with a neighbouring chunk and are OR-ed into the (cleared) stream, all
 // others are stored whole.
-__global__ __launch_bounds__(kEmitBlock) void emit_kernel(const ClientParams* __restrict__ params,
+__global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams* __restrict__ params,
                                                           ClientCtl* __restrict__ ctls, Workspace ws, uint64_t seed) {
   __shared__ Thresholds thr;
   __shared__ uint32_t s_stage[kStageWords];
@@ -1379,9 +1381,9 @@ __global__ __launch_bounds__(kEmitBlock) void emit_kernel(const ClientParams* __
   uint32_t v[kPerLane], grp[kPerLane], pid[kPerLane];
   classify_span(thr, R, val, idx, n, c * kChunkSpans + wave, v, grp);
 #pragma unroll
-  for (uint32_t j = 0; j < kPerLane; ++j) {
+  for (uint32_t j = 0; j < kPerLane; ++j) {  // unconditional, so that the loads overlap
     const uint32_t i = (c * kChunkSpans + wave) * kSpan + j * kWave + lane;
-    pid[j] = grp[j] < R ? idx[i] : 0u;
+    pid[j] = idx[min(i, n - 1u)];
   }
   __syncthreads();
   volatile uint32_t* wrun = s_wrun[wave];
