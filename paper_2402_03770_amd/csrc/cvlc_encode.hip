@@ -1386,15 +1386,18 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
     pid[j] = idx[min(i, n - 1u)];
   }
   __syncthreads();
-  volatile uint32_t* wrun = s_wrun[wave];
+  uint32_t* wrun = s_wrun[wave];  // touched by this wavefront only; its LDS accesses complete in order
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) {
     const uint32_t g = grp[j] < R ? grp[j] : kNoGroup;  // dropped candidates take no record
     const uint64_t same = same_group_lanes(g);
+    uint32_t start = 0;
+    if (g != kNoGroup) start = wrun[g];
+    wave_lds_fence();
+    if (g != kNoGroup && lane == (uint32_t)__builtin_ctzll(same)) wrun[g] = start + (uint32_t)__popcll(same);
+    wave_lds_fence();
     if (g != kNoGroup) {
-      const uint32_t start = wrun[g];
       const uint32_t e = start + lanes_below(same);
-      if (lane == (uint32_t)__builtin_ctzll(same)) wrun[g] = start + (uint32_t)__popcll(same);
       if (e < s_lim[g]) {
         const uint32_t y = s_y[g], W = s_W[g];
         uint32_t cid;
