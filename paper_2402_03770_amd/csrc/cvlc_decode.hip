@@ -215,6 +215,18 @@ __device__ __forceinline__ uint64_t lds_bits(const uint32_t* words, uint32_t n_w
   return v & ((1ull << W) - 1ull);
 }
 
+// What a work item needs from its list, and where its records sit.
+struct TabItem {
+  GlobalConstWordPtr src;  // first word brought into LDS
+  uint32_t list, P, W, s;
+  uint32_t e0, cnt;        // records e0 .. e0+cnt-1
+  uint32_t e_lo;           // e0 - 1 (the record before, whose tile the first comparison needs), or 0
+  uint32_t nw;             // words that hold records e_lo .. e0+cnt-1
+  uint32_t bit_base;       // bit of record e_lo inside the first word
+};
+
+constexpr uint32_t kTabRegs = (kTabWords + kBlock - 1) / kBlock;  // stream words a thread carries for the next item
+
 __global__ __launch_bounds__(kBlock) void tile_table_kernel(const CompactDesc* __restrict__ cdesc,
                                                             const uint32_t* __restrict__ item_start,
                                                             const DecodeCtl* __restrict__ ctl, uint32_t* table,
@@ -228,31 +240,80 @@ __global__ __launch_bounds__(kBlock) void tile_table_kernel(const CompactDesc* _
   if (cached)
     for (uint32_t i = tid; i < n_active; i += kBlock) s_start[i] = item_start[i];
   __syncthreads();
-  bool bad = false;
-  for (uint32_t q = blockIdx.x; q < n_items; q += gridDim.x) {
-    uint32_t a = 0, b = n_active;  // the list that owns item q: last list with item_start <= q (uniform)
-    while (b - a > 1) {
-      const uint32_t mid = (a + b) >> 1;
-      const uint32_t v = cached ? s_start[mid] : item_start[mid];
-      if (v <= q) a = mid; else b = mid;
+  // The items of a workgroup (b, b + workgroups, ...) go through a pipeline two deep: while item i is
+  // worked on from LDS, the stream words of item i+1 are on their way into registers and the list
+  // descriptor of item i+2 is on its way as well, so that no step waits for a whole memory round trip.
+  struct Located {
+    uint4 d0, d1;  // the list's CompactDesc as loaded
+    uint32_t list, first_item;
+  };
+  auto locate = [&](uint32_t q) {
+    Located L;
+    L.d0 = make_uint4(0u, 0u, 0u, 0u);
+    L.d1 = L.d0;
+    L.list = 0;
+    L.first_item = 0;
+    if (q < n_items) {
+      uint32_t a = 0, b = n_active;  // the list that owns item q: last list with item_start <= q (uniform)
+      while (b - a > 1) {
+        const uint32_t mid = (a + b) >> 1;
+        const uint32_t v = cached ? s_start[mid] : item_start[mid];
+        if (v <= q) a = mid; else b = mid;
+      }
+      L.list = a;
+      L.first_item = cached ? s_start[a] : item_start[a];
+      const uint4* src = reinterpret_cast<const uint4*>(cdesc + a);
+      L.d0 = src[0];
+      L.d1 = src[1];
     }
-    const uint32_t list = a;
-    const CompactDesc ld = cdesc[list];
-    const uint32_t W = ld.wsy & 0xFFu, s = (ld.wsy >> 8) & 0xFFu;
-    const uint32_t e0 = (q - item_start[list]) * kTabChunk;
-    const uint32_t cnt = min(ld.P - e0, kTabChunk);
-    // words that hold records e0-1 (if any) .. e0+cnt-1
-    const uint32_t e_lo = e0 ? e0 - 1 : 0;
-    const uint64_t bit_lo = (uint64_t)e_lo * W, bit_hi = (uint64_t)(e0 + cnt) * W;
+    return L;
+  };
+  auto geometry = [&](const Located& L, uint32_t q) {
+    TabItem it;
+    it.list = L.list;
+    it.P = L.d1.x;
+    it.W = L.d1.y & 0xFFu;
+    it.s = (L.d1.y >> 8) & 0xFFu;
+    it.e0 = (q - L.first_item) * kTabChunk;
+    it.cnt = min(it.P - it.e0, kTabChunk);
+    it.e_lo = it.e0 ? it.e0 - 1 : 0;
+    const uint64_t bit_lo = (uint64_t)it.e_lo * it.W, bit_hi = (uint64_t)(it.e0 + it.cnt) * it.W;
     const uint64_t w_lo = bit_lo >> 5;
-    const uint32_t nw = (uint32_t)(((bit_hi + 31u) >> 5) - w_lo);
-    const uint32_t bit_base = (uint32_t)(bit_lo - (w_lo << 5));  // bit of record e_lo inside s_words
-    GlobalConstWordPtr src = (GlobalConstWordPtr)ld.payload + w_lo;
+    it.nw = (uint32_t)(((bit_hi + 31u) >> 5) - w_lo);
+    it.bit_base = (uint32_t)(bit_lo - (w_lo << 5));
+    it.src = (GlobalConstWordPtr)(((uint64_t)L.d0.y << 32) | L.d0.x) + w_lo;
+    return it;
+  };
+  uint32_t regs[kTabRegs];
+  auto request_words = [&](const TabItem& it) {  // no branches: a thread past the end reads the last word again
+#pragma unroll
+    for (uint32_t k = 0; k < kTabRegs; ++k) regs[k] = it.src[min(tid + k * kBlock, it.nw - 1u)];
+  };
+
+  bool bad = false;
+  uint32_t q = blockIdx.x;
+  const uint32_t stride = gridDim.x;
+  if (q >= n_items) return;
+  TabItem cur = geometry(locate(q), q);
+  Located next_loc = locate(q + stride);
+  request_words(cur);
+  for (; q < n_items; q += stride) {
     __syncthreads();  // the item before is done with s_words
-    for (uint32_t i = tid; i < nw; i += kBlock) s_words[i] = src[i];
+#pragma unroll
+    for (uint32_t k = 0; k < kTabRegs; ++k)
+      if (tid + k * kBlock < cur.nw) s_words[tid + k * kBlock] = regs[k];
     __syncthreads();
+    TabItem nxt = cur;
+    const bool more = q + stride < n_items;
+    if (more) {  // uniform
+      nxt = geometry(next_loc, q + stride);
+      request_words(nxt);
+      next_loc = locate(q + 2 * stride);
+    }
+    const TabItem& ld = cur;
+    const uint32_t W = ld.W, s = ld.s, e0 = ld.e0, cnt = ld.cnt, e_lo = ld.e_lo, nw = ld.nw, bit_base = ld.bit_base;
     const uint32_t pid_mask = s >= 32 ? 0xFFFFFFFFu : (1u << s) - 1u;
-    uint32_t* row = table + (size_t)list * (n_tiles + 1);
+    uint32_t* row = table + (size_t)ld.list * (n_tiles + 1);
     for (uint32_t j0 = 0; j0 < cnt; j0 += kBlock) {  // uniform trip count: the shuffle below needs the whole wavefront
       const uint32_t j = j0 + tid;
       const bool live = j < cnt;
@@ -299,6 +360,7 @@ __global__ __launch_bounds__(kBlock) void tile_table_kernel(const CompactDesc* _
         todo &= todo - 1;
       }
     }
+    cur = nxt;
   }
   if (bad) atomicOr(status, CVLC_DEV_STREAM);
 }

@@ -159,7 +159,7 @@ constexpr uint32_t kWideWaves = kWideBlock / kWave;
 // non-empty bins to the client's histogram.
 __global__ __launch_bounds__(kBlock) void sample_hist_kernel(const ClientParams* __restrict__ params,
                                                              ClientCtl* __restrict__ ctls, uint32_t n_s,
-                                                             uint32_t n_src) {
+                                                             uint64_t piece_step) {
   __shared__ uint32_t hist[kSampleBins];
   const uint32_t client = blockIdx.y;
   const ClientParams& p = params[client];
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kBlock) void sample_hist_kernel(const ClientParams*
       v[u] = Float4V{0.0f, 0.0f, 0.0f, 0.0f};
       if (live[u]) {
         const uint32_t j = q >> 2, part = q & 3u;
-        const uint64_t piece = (uint64_t)j * n_src / n_s;
+        const uint64_t piece = ((uint64_t)j * piece_step) >> 32;  // piece_step = 2^32 * pieces / n_s, rounded down
         v[u] = src[piece * 4u + part];
       }
     }
@@ -1576,8 +1576,9 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
 
   if (any_sampled) {
     StageScope scope(CVLC_STAGE_ENC_SAMPLE, stream);
+    // n_src < 2^28 and n_s <= 2^14: the step is below 2^60 / n_s and j * step below 2^60
     hipLaunchKernelGGL(sample_hist_kernel, dim3(kSampleBlocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, n_s,
-                       n_src);
+                       n_s ? ((uint64_t)n_src << 32) / n_s : 0u);
     hipLaunchKernelGGL(sample_walk_kernel, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl);
   }
   {
