@@ -956,31 +956,35 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
 struct Thresholds {  // group boundaries in LDS
   uint32_t tau[32];
   uint32_t iota[32];
+  uint32_t cut[32];  // key < cut[r]  <=>  key <= tau[r] for r < R; 0 (never) for r >= R
 };
 
 __device__ __forceinline__ void load_thresholds(Thresholds& t, const ClientCtl* ctl, uint32_t R) {
   if (threadIdx.x < 32) {
     const bool live = threadIdx.x < R;
-    t.tau[threadIdx.x] = live ? ctl->tau[threadIdx.x] : 0xFFFFFFFFu;
+    const uint32_t tau = live ? ctl->tau[threadIdx.x] : 0xFFFFFFFFu;
+    t.tau[threadIdx.x] = tau;
     t.iota[threadIdx.x] = live ? ctl->iota[threadIdx.x] : 0u;
+    t.cut[threadIdx.x] = live ? (tau == 0xFFFFFFFFu ? tau : tau + 1u) : 0u;  // keys stay below 2^31
   }
 }
 
 // Group of a candidate, 0-based: the first boundary r whose top-Z_r set holds
 // it (key above tau_r, or equal with position <= iota_r); R if none (dropped).
-// tau is non-increasing in r, so the first r with key > tau_r is the number of
-// boundaries with tau_r >= key; the thresholds are read at a uniform LDS address
-// (a broadcast) once for all of a lane's N candidates.  The position is only
-// needed (and only read) when the key equals a boundary key.
+// tau is non-increasing in r, so "key <= tau_r" holds for the first g boundaries
+// and for no later one, g being the number of boundaries with tau_r >= key: a
+// binary search over the boundaries (entries past R never hold) finds it in
+// log2 R probes per candidate.  The position is only needed (and only read)
+// when the key equals a boundary key.
 template <uint32_t N>
 __device__ __forceinline__ void classify_keys(const Thresholds& t, uint32_t R, const uint32_t (&key)[N],
                                               uint32_t (&grp)[N]) {
 #pragma unroll
   for (uint32_t j = 0; j < N; ++j) grp[j] = 0;
-  for (uint32_t r = 0; r < R; ++r) {
-    const uint32_t tau = t.tau[r];
+  // largest power of two <= R: the probes reach entry 2 * top - 2 <= 30 at most, the result 2 * top - 1 >= R
+  for (uint32_t step = R ? 1u << (31 - __builtin_clz(R)) : 0u; step; step >>= 1) {
 #pragma unroll
-    for (uint32_t j = 0; j < N; ++j) grp[j] += (key[j] <= tau) ? 1u : 0u;
+    for (uint32_t j = 0; j < N; ++j) grp[j] += key[j] < t.cut[grp[j] + step - 1u] ? step : 0u;
   }
 }
 
@@ -1050,6 +1054,7 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
   __shared__ Thresholds thr;
   __shared__ uint32_t s_max[33][kWave], s_negmin[33][kWave];
   __shared__ double s_sq[33][kWave];
+  __shared__ uint32_t s_cnt[kEmitWaves][32];
   const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
@@ -1059,6 +1064,7 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
   const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.d;
   uint32_t* __restrict__ span_cnt = ws.span_cnt + (size_t)client * (ws.max_spans + 1) * 32;
   load_thresholds(thr, ctl, R);
+  if (tid < kEmitWaves * 32) (&s_cnt[0][0])[tid] = 0;
   for (uint32_t i = tid; i < 33 * kWave; i += kEmitBlock) {
     (&s_max[0][0])[i] = 0;
     (&s_negmin[0][0])[i] = 0;
@@ -1068,15 +1074,16 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
   for (uint32_t span = blockIdx.x * kEmitWaves + wave; span < n_spans; span += gridDim.x * kEmitWaves) {
     uint32_t v[kPerLane], grp[kPerLane];
     classify_span(thr, R, val, idx, n, span, v, grp);
-    // lane r ends up with the span's size of group r
-    uint32_t mine = 0;
-    for (uint32_t r = 0; r <= R; ++r) {
-      uint32_t tot = 0;
+    // the span's size of every group, counted in a row of LDS words private to the wavefront
 #pragma unroll
-      for (uint32_t j = 0; j < kPerLane; ++j) tot += (uint32_t)__popcll(__ballot(grp[j] == r));
-      if (lane == r) mine = tot;
+    for (uint32_t j = 0; j < kPerLane; ++j)
+      if (grp[j] != kNoGroup) atomicAdd(&s_cnt[wave][grp[j]], 1u);
+    wave_lds_fence();
+    if (lane < 32) {
+      span_cnt[(size_t)span * 32 + lane] = s_cnt[wave][lane];
+      s_cnt[wave][lane] = 0;
     }
-    if (lane < 32) span_cnt[(size_t)span * 32 + lane] = mine;
+    wave_lds_fence();
 #pragma unroll
     for (uint32_t j = 0; j < kPerLane; ++j) {
       const uint32_t g = grp[j];
