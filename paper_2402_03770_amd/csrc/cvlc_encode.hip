@@ -82,7 +82,7 @@ EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   L.region_cnt = off; off = align256(off + (size_t)n * L.n_regions * sizeof(uint32_t));
   L.region_off = off; off = align256(off + (size_t)n * (L.n_regions + 1) * sizeof(uint32_t));
   L.region_sumsq = off; off = align256(off + (size_t)n * L.n_regions * sizeof(double));
-  L.cand_idx = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
+  L.cand_idx = off; off = align256(off + (size_t)n * d * sizeof(uint16_t));
   L.cand_val = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
   L.dense_idx = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
   L.dense_val = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
@@ -104,7 +104,7 @@ struct Workspace {  // device pointers into the caller's workspace
   uint32_t* region_cnt;
   uint32_t* region_off;
   double* region_sumsq;
-  uint32_t* cand_idx;  // positions of the kept coordinates: a run at the front of every region's slot
+  uint16_t* cand_idx;  // positions of the kept coordinates inside their region: a run at the front of every region's slot
   uint32_t* cand_val;  // their value bits, same layout
   uint32_t* dense_idx; // the same candidates, contiguous per client, in position order
   uint32_t* dense_val;
@@ -271,9 +271,11 @@ __device__ __forceinline__ void load_subtile(SubTile& t, GlobalFloatPtr U, uint3
 constexpr uint32_t kStageCap = 448;
 constexpr uint32_t kStageFlushAt = kStageCap - 256;  // more staged than this: flush
 
+static_assert(kRegion <= 65536 && (kRegion & (kRegion - 1)) == 0, "positions inside a region are kept in 16 bits");
+
 struct FilterWave {
   uint2* stage;            // this wavefront's staging rows in LDS
-  uint32_t* __restrict__ out_idx;  // the region's slot in global memory: positions
+  uint16_t* __restrict__ out_idx;  // the region's slot in global memory: positions inside the region (13 bits)
   uint32_t* __restrict__ out_val;  // ... and value bits
   uint32_t* hist;          // the workgroup's level-1 histogram in LDS
   uint32_t fill;           // staged entries (uniform)
@@ -290,7 +292,7 @@ __device__ __forceinline__ void flush_rows(FilterWave& w, uint32_t lane, bool al
   uint32_t g = 0;
   for (; g + kWave <= w.fill; g += kWave) {
     const uint2 e = w.stage[g + lane];
-    w.out_idx[w.run + g + lane] = e.x;
+    w.out_idx[w.run + g + lane] = (uint16_t)(e.x & (kRegion - 1u));
     w.out_val[w.run + g + lane] = e.y;
     atomicAdd(&w.hist[(e.y & 0x7FFFFFFFu) >> 20], 1u);
     w.nonfinite |= (e.y & 0x7FFFFFFFu) >= 0x7F800000u ? 1u : 0u;
@@ -301,7 +303,7 @@ __device__ __forceinline__ void flush_rows(FilterWave& w, uint32_t lane, bool al
     if (lane < left) e = w.stage[g + lane];
     if (all) {
       if (lane < left) {
-        w.out_idx[w.run + g + lane] = e.x;
+        w.out_idx[w.run + g + lane] = (uint16_t)(e.x & (kRegion - 1u));
         w.out_val[w.run + g + lane] = e.y;
         atomicAdd(&w.hist[(e.y & 0x7FFFFFFFu) >> 20], 1u);
         w.nonfinite |= (e.y & 0x7FFFFFFFu) >= 0x7F800000u ? 1u : 0u;
@@ -644,7 +646,7 @@ static_assert(kEmitWaves == kChunkSpans && kPerLane == 8, "one wavefront per spa
 // non-empty run with nz_off[q] <= i.
 struct CandView {
   const uint32_t* __restrict__ val;         // region slots: value bits
-  const uint32_t* __restrict__ idx;         // region slots: positions
+  const uint16_t* __restrict__ idx;         // region slots: positions inside the region
   const uint32_t* __restrict__ nz_off;      // n_nz + 1 entries, the last = n
   const uint32_t* __restrict__ nz_run;
   const uint32_t* __restrict__ span_first;  // q of candidate 512 s
@@ -767,7 +769,7 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
       x[j] = 0;
       if (i < cv.n) {
         v[j] = cv.val[slot[j]];
-        x[j] = cv.idx[slot[j]];
+        x[j] = (slot[j] & ~(kRegion - 1u)) + cv.idx[slot[j]];  // a slot starts where its region starts
       }
     }
 #pragma unroll
@@ -1519,7 +1521,7 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   ws.region_cnt = reinterpret_cast<uint32_t*>(base + L.region_cnt);
   ws.region_off = reinterpret_cast<uint32_t*>(base + L.region_off);
   ws.region_sumsq = reinterpret_cast<double*>(base + L.region_sumsq);
-  ws.cand_idx = reinterpret_cast<uint32_t*>(base + L.cand_idx);
+  ws.cand_idx = reinterpret_cast<uint16_t*>(base + L.cand_idx);
   ws.cand_val = reinterpret_cast<uint32_t*>(base + L.cand_val);
   ws.dense_idx = reinterpret_cast<uint32_t*>(base + L.dense_idx);
   ws.dense_val = reinterpret_cast<uint32_t*>(base + L.dense_val);
