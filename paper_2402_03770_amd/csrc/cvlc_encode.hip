@@ -47,7 +47,7 @@ struct GroupInfo {
 
 struct EncodeLayout {
   size_t status, ctl, params, region_cnt, region_off, region_sumsq, cand_idx, cand_val, dense_idx, dense_val, nz_off, nz_run, span_first, span_cnt, group_info,
-      tie_list, sel_part, total;
+      tie_list, sel_part, l3_hist, total;
   size_t zero_bytes;        // [status, params) is cleared at the start of a call
   uint32_t n_regions, max_spans;
   uint32_t sel_blocks;      // workgroups per client in a level-2/3 selection pass
@@ -77,6 +77,7 @@ EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   size_t off = 0;
   L.status = off; off = align256(off + 256);
   L.ctl = off; off = align256(off + (size_t)n * sizeof(ClientCtl));
+  L.l3_hist = off; off = align256(off + (size_t)n * kSlotGroup * kDigitBins * sizeof(uint32_t));
   L.zero_bytes = off;
   L.params = off; off = align256(off + (size_t)n * sizeof(ClientParams));
   L.region_cnt = off; off = align256(off + (size_t)n * L.n_regions * sizeof(uint32_t));
@@ -115,6 +116,7 @@ struct Workspace {  // device pointers into the caller's workspace
   GroupInfo* group_info;
   uint2* tie_list;
   uint32_t* sel_part;
+  uint32_t* l3_hist;   // level-3 digit counts per (client, slot), zero between uses
   uint32_t d, n_regions, max_spans, filter_blocks, sel_blocks;
 };
 
@@ -829,9 +831,19 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
     }
   }
   __syncthreads();
-  uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * kSlotGroup * kDigitBins;
   const uint32_t used = S.slots.n * kDigitBins;
-  for (uint32_t i = tid; i < used; i += kWideBlock) part[i] = S.hist[i];
+  if (LEVEL == 3) {
+    // a handful of candidates per slot share a boundary's 21-bit prefix (more only among heavy ties):
+    // the few non-empty counters are added straight to the client's table
+    uint32_t* table = ws.l3_hist + (size_t)client * kSlotGroup * kDigitBins;
+    for (uint32_t i = tid; i < used; i += kWideBlock) {
+      const uint32_t h = S.hist[i];
+      if (h) atomicAdd(&table[i], h);
+    }
+  } else {
+    uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * kSlotGroup * kDigitBins;
+    for (uint32_t i = tid; i < used; i += kWideBlock) part[i] = S.hist[i];
+  }
 }
 
 // One workgroup per (histogram slot, client): thread t owns digit t.  The
@@ -868,8 +880,14 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   const uint32_t kept = LEVEL == 3 ? ctl->tie_cnt[group][slot] : 0u;
   const uint32_t digit = kDigitBins - 1 - tid;
   uint32_t h = 0;
+  if (LEVEL == 3) {  // one table per client; left cleared for the next group of boundaries or the next call
+    uint32_t* mine = ws.l3_hist + ((size_t)client * kSlotGroup + slot) * kDigitBins + digit;
+    h = *mine;
+    *mine = 0;
+  } else {
 #pragma unroll 8
-  for (uint32_t b = 0; b < n_parts; ++b) h += parts[((size_t)b * kSlotGroup + slot) * kDigitBins + digit];
+    for (uint32_t b = 0; b < n_parts; ++b) h += parts[((size_t)b * kSlotGroup + slot) * kDigitBins + digit];
+  }
   if (tid < kSlotGroup) {
     s_need[tid] = 0;
     s_rem[tid] = rem_in;
@@ -1532,6 +1550,7 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   ws.group_info = reinterpret_cast<GroupInfo*>(base + L.group_info);
   ws.tie_list = reinterpret_cast<uint2*>(base + L.tie_list);
   ws.sel_part = reinterpret_cast<uint32_t*>(base + L.sel_part);
+  ws.l3_hist = reinterpret_cast<uint32_t*>(base + L.l3_hist);
   ws.d = d;
   ws.n_regions = L.n_regions;
   ws.max_spans = L.max_spans;
