@@ -78,8 +78,14 @@ struct UploadChunk {
   uint32_t data[kUploadWords];
 };
 
-__global__ void upload_kernel(uint32_t* dst, UploadChunk c) {
-  for (uint32_t i = threadIdx.x; i < c.n_words; i += blockDim.x) dst[c.dst_word + i] = c.data[i];
+// Workgroup 0 writes the chunk's words; all workgroups clear zero_n16 16-byte
+// pieces from `zero` on (the call's state that starts at zero, in the call's
+// first launch; a plain kernel, so that a caller may capture the call in a graph).
+__global__ __launch_bounds__(256) void upload_kernel(uint32_t* dst, UploadChunk c, uint4* zero, uint32_t zero_n16) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < zero_n16; i += gridDim.x * blockDim.x)
+    zero[i] = make_uint4(0u, 0u, 0u, 0u);
+  if (blockIdx.x == 0)
+    for (uint32_t i = threadIdx.x; i < c.n_words; i += blockDim.x) dst[c.dst_word + i] = c.data[i];
 }
 
 // Bits [bit, bit + W) of a little-endian word array, W <= 63.  Reads the three
@@ -97,62 +103,73 @@ __device__ __forceinline__ uint64_t read_bits(WordPtr words, uint64_t n_words, u
 }
 
 // ------------------------------------------------------------------ 1. headers
-// One workgroup (64 threads) per stream.  A stream that fails any check
+// One wavefront per stream; lane r reads and checks the header of group r, so
+// that the group headers are fetched together.  A stream that fails any check
 // contributes nothing: all its lists are marked empty and the status bit is set.
+typedef const uint32_t __attribute__((address_space(1))) * GlobalConstWordPtr;
+
+__device__ __forceinline__ uint64_t wave_incl_scan_u64(uint64_t v) {
+  const uint32_t lane = lane_id();
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t lo = __shfl_up((uint32_t)v, o, 64), hi = __shfl_up((uint32_t)(v >> 32), o, 64);
+    if (lane >= (uint32_t)o) v += ((uint64_t)hi << 32) | lo;
+  }
+  return v;
+}
+
 __global__ __launch_bounds__(64) void parse_headers_kernel(const StreamArg* __restrict__ streams, ListDesc* descs,
                                                            uint32_t d, uint32_t n, uint32_t* status) {
-  __shared__ uint32_t s_ok;
-  __shared__ uint64_t s_payload[CVLC_MAX_CODED];
   const uint32_t client = blockIdx.x, t = threadIdx.x;
   const StreamArg sa = streams[client];
-  const uint32_t* w = sa.words;
+  GlobalConstWordPtr w = (GlobalConstWordPtr)sa.words;
   ListDesc* out = descs + (size_t)client * kListsPerClient;
-  if (t == 0) {
-    bool ok = sa.n_words >= kGlobalHeaderWords;
-    uint32_t R = 0, s = 0;
-    if (ok) {
-      R = w[3];
-      s = w[4];
-      const float B = __uint_as_float(w[5]);
-      ok = w[0] == kMagic && w[1] == kVersion && w[2] == d && R <= CVLC_MAX_CODED && s == position_bits(d) &&
-           B > 0.0f && fabsf(B) <= 3.4028234664e38f;
-    }
-    uint64_t pos = kGlobalHeaderWords + (uint64_t)kSegHeaderWords * R;
-    ok = ok && sa.n_words >= pos;
-    if (ok) {
-      uint64_t k = 0;
-      for (uint32_t r = 0; r < R; ++r) {
-        const uint32_t* h = w + kGlobalHeaderWords + kSegHeaderWords * r;
-        const uint32_t y = h[0], P = h[1];
-        const float m = __uint_as_float(h[2]), M = __uint_as_float(h[3]);
-        ok = ok && code_len_supported(y) && fabsf(m) <= 3.4028234664e38f && fabsf(M) <= 3.4028234664e38f &&
-             fabsf(M - m) <= 3.4028234664e38f;
-        if (!ok) break;
-        k += P;
-        s_payload[r] = pos;
-        pos += payload_words(P, s + y);
-      }
-      ok = ok && k <= d && pos == w[7] && sa.n_words >= pos;
-    }
-    s_ok = ok ? 1u : 0u;
-    if (!ok) atomicOr(status, CVLC_DEV_STREAM);
+  bool ok = sa.n_words >= kGlobalHeaderWords;  // everything about `ok` is uniform over the wavefront
+  uint32_t g[kGlobalHeaderWords] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (ok) {
+#pragma unroll
+    for (uint32_t i = 0; i < kGlobalHeaderWords; ++i) g[i] = w[i];
   }
-  __syncthreads();
+  const uint32_t R = g[3], s = g[4];
+  const float B = __uint_as_float(g[5]);
+  ok = ok && g[0] == kMagic && g[1] == kVersion && g[2] == d && R <= CVLC_MAX_CODED && s == position_bits(d) &&
+       B > 0.0f && fabsf(B) <= 3.4028234664e38f;
+  const uint64_t first_payload = kGlobalHeaderWords + (uint64_t)kSegHeaderWords * R;
+  ok = ok && sa.n_words >= first_payload;
+  const bool mine = ok && t < R;
+  uint32_t y = 0, P = 0;
+  float m = 0.0f, M = 0.0f;
+  if (mine) {
+    GlobalConstWordPtr h = w + kGlobalHeaderWords + kSegHeaderWords * t;
+    y = h[0];
+    P = h[1];
+    m = __uint_as_float(h[2]);
+    M = __uint_as_float(h[3]);
+  }
+  const bool header_ok = !mine || (code_len_supported(y) && fabsf(m) <= 3.4028234664e38f &&
+                                   fabsf(M) <= 3.4028234664e38f && fabsf(M - m) <= 3.4028234664e38f);
+  ok = ok && __ballot(header_ok) == ~0ull;
+  // where every group's records start, and what the stream must add up to (sizes of groups with a bad header
+  // do not matter: the stream is rejected)
+  const uint64_t words = mine && header_ok ? payload_words(P, s + y) : 0u;
+  const uint64_t incl = wave_incl_scan_u64(words);
+  const uint64_t k_incl = wave_incl_scan_u64(mine ? P : 0u);
+  const uint64_t total = first_payload + (((uint64_t)__shfl((uint32_t)(incl >> 32), 63, 64) << 32) | __shfl((uint32_t)incl, 63, 64));
+  const uint64_t k = ((uint64_t)__shfl((uint32_t)(k_incl >> 32), 63, 64) << 32) | __shfl((uint32_t)k_incl, 63, 64);
+  ok = ok && k <= d && total == g[7] && sa.n_words >= total;
+  if (!ok && t == 0) atomicOr(status, CVLC_DEV_STREAM);
   if (t < kListsPerClient) {
     ListDesc ld;
     ld.payload = nullptr; ld.weight = 0.0; ld.P = 0; ld.W = 0; ld.s = 0; ld.y = 0; ld.m = 0.0f; ld.step = 0.0f;
-    if (s_ok && t < w[3]) {
-      const uint32_t* h = w + kGlobalHeaderWords + kSegHeaderWords * t;
-      const uint32_t y = h[0];
-      const float m = __uint_as_float(h[2]), M = __uint_as_float(h[3]);
+    if (ok && t < R) {
       float step = 0.0f, inv = 0.0f;
       if (y != 32) centroid_spacing(m, M, y, &step, &inv);
-      ld.payload = w + s_payload[t];
-      ld.weight = sa.has_weight ? sa.weight : 1.0 / ((double)n * (double)__uint_as_float(w[5]));
-      ld.P = h[1];
-      ld.s = w[4];
+      ld.payload = sa.words + (first_payload + incl - words);
+      ld.weight = sa.has_weight ? sa.weight : 1.0 / ((double)n * (double)B);
+      ld.P = P;
+      ld.s = s;
       ld.y = y;
-      ld.W = w[4] + y;
+      ld.W = s + y;
       ld.m = m;
       ld.step = step;
     }
@@ -203,7 +220,6 @@ __global__ __launch_bounds__(1024) void compact_lists_kernel(const ListDesc* __r
 // item is a run of kTabChunk records of one list: its stream words are brought
 // into LDS with coalesced loads, then thread e compares the tiles of records e-1
 // and e and fills the entries in between.
-typedef const uint32_t __attribute__((address_space(1))) * GlobalConstWordPtr;
 
 // Bits [bit, bit + W) of an LDS word array, bit < 2^32, W <= 63.
 __device__ __forceinline__ uint64_t lds_bits(const uint32_t* words, uint32_t n_words, uint32_t bit, uint32_t W) {
@@ -537,8 +553,8 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
   const uint32_t n_lists = n * kListsPerClient;
 
   profile_mark(CVLC_STAGE_DEC_SETUP, true, stream);
-  int rc = hip_check(hipMemsetAsync(status, 0, L.streams, stream));  // status word and list counts (n = 0: no lists)
-  if (rc) return rc;
+  // the status word and the list counts start every call at zero (n = 0: no lists)
+  uint32_t zero_n16 = (uint32_t)(L.streams / 16u);
   if (n > 0) {
     constexpr uint32_t words_per = sizeof(StreamArg) / 4u;
     const uint32_t per_chunk = kUploadWords / words_per;
@@ -556,10 +572,19 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
         sa.pad = 0;
         std::memcpy(&chunk.data[i * words_per], &sa, sizeof(sa));
       }
-      hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(sargs), chunk);
+      const uint32_t blocks = zero_n16 ? (zero_n16 + 1023u) / 1024u : 1u;
+      hipLaunchKernelGGL(upload_kernel, dim3(blocks < 512u ? blocks : 512u), dim3(256), 0, stream,
+                         reinterpret_cast<uint32_t*>(sargs), chunk, reinterpret_cast<uint4*>(status), zero_n16);
+      zero_n16 = 0;  // cleared by the first launch
     }
     hipLaunchKernelGGL(parse_headers_kernel, dim3(n), dim3(64), 0, stream, sargs, descs, d, n, status);
     hipLaunchKernelGGL(compact_lists_kernel, dim3(1), dim3(1024), 0, stream, descs, n_lists, cdesc, item_start, ctl);
+  } else {
+    UploadChunk chunk;
+    chunk.n_words = 0;
+    chunk.dst_word = 0;
+    hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(sargs), chunk,
+                       reinterpret_cast<uint4*>(status), zero_n16);
   }
   profile_mark(CVLC_STAGE_DEC_SETUP, false, stream);
   if (n > 0) {

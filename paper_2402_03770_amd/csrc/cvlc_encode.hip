@@ -127,8 +127,14 @@ struct UploadChunk {
   uint32_t data[kUploadWords];
 };
 
-__global__ void upload_kernel(uint32_t* dst, UploadChunk c) {
-  for (uint32_t i = threadIdx.x; i < c.n_words; i += blockDim.x) dst[c.dst_word + i] = c.data[i];
+// Workgroup 0 writes the chunk's words; all workgroups clear zero_n16 16-byte
+// pieces from `zero` on (the call's state that starts at zero, in the call's
+// first launch; a plain kernel, so that a caller may capture the call in a graph).
+__global__ __launch_bounds__(256) void upload_kernel(uint32_t* dst, UploadChunk c, uint4* zero, uint32_t zero_n16) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < zero_n16; i += gridDim.x * blockDim.x)
+    zero[i] = make_uint4(0u, 0u, 0u, 0u);
+  if (blockIdx.x == 0)
+    for (uint32_t i = threadIdx.x; i < c.n_words; i += blockDim.x) dst[c.dst_word + i] = c.data[i];
 }
 
 // ------------------------------------------------------------------ small device helpers
@@ -1562,7 +1568,8 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   const uint32_t n_s = n_src < kSampleChunksMax ? n_src : kSampleChunksMax;
 
   profile_mark(CVLC_STAGE_ENC_SETUP, true, stream);
-  if ((rc = hip_check(hipMemsetAsync(base + L.status, 0, L.zero_bytes, stream)))) return rc;
+  // the status word, the control blocks and the level-3 table start every call at zero
+  uint32_t zero_n16 = (uint32_t)(L.zero_bytes / 16u);  // n <= 65535 clients: below 2^32 pieces
 
   // per-client parameters, shipped as kernel arguments
   uint32_t max_R = 0;
@@ -1597,7 +1604,11 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
         if (pl.n_coded > max_R) max_R = pl.n_coded;
         std::memcpy(&chunk.data[i * words_per], &cp, sizeof(cp));
       }
-      hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(ws.params), chunk);
+      const uint32_t blocks = zero_n16 ? (zero_n16 + 1023u) / 1024u : 1u;
+      hipLaunchKernelGGL(upload_kernel, dim3(blocks < 512u ? blocks : 512u), dim3(256), 0, stream,
+                         reinterpret_cast<uint32_t*>(ws.params), chunk, reinterpret_cast<uint4*>(base + L.status),
+                         zero_n16);
+      zero_n16 = 0;  // cleared by the first launch
     }
   }
   profile_mark(CVLC_STAGE_ENC_SETUP, false, stream);
