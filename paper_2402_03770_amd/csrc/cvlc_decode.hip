@@ -243,7 +243,7 @@ struct TabItem {
 
 constexpr uint32_t kTabRegs = (kTabWords + kBlock - 1) / kBlock;  // stream words a thread carries for the next item
 
-__global__ __launch_bounds__(kBlock) void tile_table_kernel(const CompactDesc* __restrict__ cdesc,
+__global__ __launch_bounds__(kBlock, 6) void tile_table_kernel(const CompactDesc* __restrict__ cdesc,
                                                             const uint32_t* __restrict__ item_start,
                                                             const DecodeCtl* __restrict__ ctl, uint32_t* table,
                                                             uint32_t d, uint32_t n_tiles, uint32_t* status) {
@@ -330,14 +330,23 @@ __global__ __launch_bounds__(kBlock) void tile_table_kernel(const CompactDesc* _
     const uint32_t W = ld.W, s = ld.s, e0 = ld.e0, cnt = ld.cnt, e_lo = ld.e_lo, nw = ld.nw, bit_base = ld.bit_base;
     const uint32_t pid_mask = s >= 32 ? 0xFFFFFFFFu : (1u << s) - 1u;
     uint32_t* row = table + (size_t)ld.list * (n_tiles + 1);
-    for (uint32_t j0 = 0; j0 < cnt; j0 += kBlock) {  // uniform trip count: the shuffle below needs the whole wavefront
-      const uint32_t j = j0 + tid;
-      const bool live = j < cnt;
+    // a wavefront takes a contiguous quarter of the item's records, 64 at a time: the record before lane 0's
+    // is then the one lane 63 held a turn earlier, except at the start of the quarter
+    const uint32_t per_wave = ((cnt + kWavesPerBlock * kWave - 1) / (kWavesPerBlock * kWave)) * kWave;
+    const uint32_t j_begin = (tid / kWave) * per_wave;
+    const uint32_t j_end = min(j_begin + per_wave, cnt);
+    uint32_t carry = 0;
+    if (j_begin < j_end && e0 + j_begin > 0)
+      carry = (uint32_t)lds_bits(s_words, nw, bit_base + (e0 + j_begin - 1 - e_lo) * W, W) & pid_mask;  // uniform
+    for (uint32_t j0 = j_begin; j0 < j_end; j0 += kWave) {  // uniform per wavefront: the shuffles need all lanes
+      const uint32_t j = j0 + lane;
+      const bool live = j < j_end;
       const uint32_t e = e0 + j;
       uint32_t pid = 0;
       if (live) pid = (uint32_t)lds_bits(s_words, nw, bit_base + (e - e_lo) * W, W) & pid_mask;
       uint32_t prev = __shfl_up(pid, 1, 64);  // the record before mine sits in the lane below
-      if (live && lane == 0 && e > 0) prev = (uint32_t)lds_bits(s_words, nw, bit_base + (e - 1 - e_lo) * W, W) & pid_mask;
+      if (lane == 0) prev = carry;
+      carry = __shfl(pid, kWave - 1, 64);
       // entries (tile of record e-1, tile of record e] point at e; past the last record they hold P
       uint32_t t_first = 1, t_cur = 0, tail_first = 1, tail_last = 0;
       if (live) {
