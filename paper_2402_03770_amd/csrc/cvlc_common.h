@@ -25,8 +25,8 @@ constexpr uint32_t kSubTile = 1024;        // coordinates one wavefront holds in
 constexpr uint32_t kRegion = 8192;         // coordinates one wavefront filters as a unit (8 sub-tiles)
 constexpr uint32_t kSpan = 512;            // candidates one wavefront classifies as a unit (8 rows of 64)
 constexpr uint32_t kChunkSpans = 8;        // spans per emit chunk (4096 candidates, one workgroup)
-constexpr uint32_t kSampleBins = 4096;     // sample histogram on key >> 19
-constexpr uint32_t kSampleShift = 19;
+constexpr uint32_t kSampleBins = 8192;     // sample histogram on key >> 18 (8 exponent + 5 mantissa bits)
+constexpr uint32_t kSampleShift = 18;
 constexpr uint32_t kL1Bins = 2048;         // level-1 digit: key >> 20 (8 exponent + 3 mantissa bits)
 constexpr uint32_t kDigitBins = 1024;      // level-2 and level-3 digits: 10 bits each
 constexpr uint32_t kSlotGroup = 15;        // boundaries refined per level-2/3 launch (60 KB of LDS)

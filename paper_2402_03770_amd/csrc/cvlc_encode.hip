@@ -162,7 +162,7 @@ constexpr uint32_t kWideWaves = kWideBlock / kWave;
 
 // ------------------------------------------------------------------ 1. sample histogram
 // Reads n_s 64-byte pieces spread evenly over the vector and histograms the
-// magnitude keys on their top 12 bits.  kSampleBlocks workgroups per client each
+// magnitude keys on their top 13 bits.  kSampleBlocks workgroups per client each
 // take a slice of the pieces, issue their loads eight deep, and add their
 // non-empty bins to the client's histogram.
 __global__ __launch_bounds__(kBlock) void sample_hist_kernel(const ClientParams* __restrict__ params,
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(kWideBlock) void sample_walk_kernel(const ClientPar
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   if (p.sample_rank == 0) return;
-  // thread t owns the 4 bins [top-3, top], top = 4095 - 4 t
+  // thread t owns `per` bins ending at top = kSampleBins - 1 - per * t, largest keys first
   constexpr uint32_t per = kSampleBins / kWideBlock;
   const uint32_t top = kSampleBins - 1 - per * threadIdx.x;
   uint32_t h[per], mine = 0;
