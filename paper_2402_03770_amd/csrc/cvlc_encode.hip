@@ -953,25 +953,46 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
           if (before + 1 == w_quota) ctl->iota[r] = me.x;
         }
       } else {
-        // too many to keep aside: walk the whole candidate list
+        // too many to keep aside: walk the whole candidate list.  Every wavefront counts the members
+        // of the class in a contiguous sixteenth of the list; the one whose share holds the
+        // quota-th member then walks it again, row by row.  No workgroup barrier inside the walks.
         const uint32_t tau = (prefix << 10) | w_digit;
-        uint32_t left = w_quota;
+        const uint32_t lane = lane_id(), wave = tid / kWave;
+        const uint32_t share = ((n + kWideBlock - 1) / kWideBlock) * kWave;  // a multiple of 64
+        const uint32_t w_begin = min(wave * share, n), w_end = min(w_begin + share, n);
         __syncthreads();
         if (tid == 0) s_found = 0;
-        __syncthreads();
-        for (uint32_t base = 0; base < n; base += kWideBlock) {
-          const uint32_t i = base + tid;
-          const uint32_t hit = (i < n && (val[i] & 0x7FFFFFFFu) == tau) ? 1u : 0u;
-          uint32_t tot;
-          const uint32_t rank = block_excl_scan<kWideWaves>(hit, scan_tmp, &tot);
-          if (hit && rank + 1 == left) {
-            ctl->iota[r] = idx[i];
-            s_found = 1;
-          }
-          __syncthreads();
-          if (s_found || tot >= left) break;
-          left -= tot;
+        uint32_t mine = 0;
+        for (uint32_t base = w_begin; base < w_end; base += kWave * 8u) {
+          uint32_t v[8];
+#pragma unroll
+          for (uint32_t u = 0; u < 8; ++u) v[u] = val[min(base + u * kWave + lane, n - 1u)];
+#pragma unroll
+          for (uint32_t u = 0; u < 8; ++u)
+            mine += (uint32_t)__popcll(__ballot(base + u * kWave + lane < w_end && (v[u] & 0x7FFFFFFFu) == tau));
         }
+        if (lane == 0) scan_tmp[wave] = mine;
+        __syncthreads();
+        uint32_t before = 0;
+        for (uint32_t w = 0; w < wave; ++w) before += scan_tmp[w];
+        if (before < w_quota && w_quota <= before + mine) {  // uniform per wavefront: exactly one takes this
+          uint32_t left = w_quota - before;
+          for (uint32_t base = w_begin; base < w_end; base += kWave) {
+            const uint32_t i = base + lane;
+            const bool hit = i < w_end && (val[min(i, n - 1u)] & 0x7FFFFFFFu) == tau;
+            const uint64_t m = __ballot(hit);
+            const uint32_t c = (uint32_t)__popcll(m);
+            if (left <= c) {
+              if (hit && lanes_below(m) + 1u == left) {
+                ctl->iota[r] = idx[i];
+                s_found = 1;
+              }
+              break;
+            }
+            left -= c;
+          }
+        }
+        __syncthreads();
         if (tid == 0 && !s_found) atomicOr(ws.status, CVLC_DEV_INTERNAL);
       }
     }
