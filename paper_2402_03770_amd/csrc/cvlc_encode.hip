@@ -1354,6 +1354,14 @@ __device__ __forceinline__ uint32_t quantise(float x, float m, float inv, uint32
 constexpr uint32_t kChunkCands = kSpan * kChunkSpans;         // 4096
 constexpr uint32_t kStageWords = kChunkCands * 2 + 2 * 32;    // every record is < 64 bits; two edge words per group
 
+struct alignas(16) EmitGroup {  // per (chunk, group)
+  uint32_t first, lim;   // the chunk's record run [first, lim) of the group
+  uint32_t W, y;
+  float m, inv;
+  uint32_t stage_bit;    // bit of record `first` in the workgroup's staged image of the stream
+  uint32_t pad;
+};
+
 // One workgroup per chunk of 4096 candidates, one wavefront per span.  Every
 // coded candidate gets its record number inside its group (members in earlier
 // spans from the layout's prefix, then earlier rows, then lower lanes), is
@@ -1366,12 +1374,11 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
   __shared__ Thresholds thr;
   __shared__ uint32_t s_stage[kStageWords];
   __shared__ uint32_t s_wrun[kEmitWaves][32];      // per wavefront, per group: record number of its next member
-  __shared__ uint32_t s_lim[32];                   // one past the chunk's last record number in each group
+  __shared__ EmitGroup s_grp[32];                  // what a record of the group needs, read as two 16-byte pieces
   __shared__ uint32_t s_word0[32];                 // first stream word (group-relative) the chunk touches
   __shared__ uint32_t s_nwords[32];                // words the chunk touches in each group
   __shared__ uint32_t s_stage_off[33];
-  __shared__ uint32_t s_payload[32], s_W[32], s_y[32];
-  __shared__ float s_m[32], s_inv[32];
+  __shared__ uint32_t s_payload[32];
   const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
@@ -1385,15 +1392,16 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
   const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32), client_id = p.client_id;
 
   load_thresholds(thr, ctl, R);
-  uint32_t my_P = 0, my_W = 0;
+  uint32_t my_P = 0, my_W = 0, my_y = 0;
+  float my_m = 0.0f, my_inv = 0.0f;
   if (tid < 32 && tid < R) {
     const GroupInfo* gi = ws.group_info + client;
     my_P = gi->P[tid];
     my_W = gi->W[tid];
+    my_y = gi->y[tid];
+    my_m = gi->m[tid];
+    my_inv = gi->inv[tid];
     s_payload[tid] = gi->payload[tid];
-    s_y[tid] = gi->y[tid];
-    s_m[tid] = gi->m[tid];
-    s_inv[tid] = gi->inv[tid];
   }
   for (uint32_t c = blockIdx.x; c * kChunkSpans < n_spans; c += gridDim.x) {
   __syncthreads();  // the chunk before is written out
@@ -1403,30 +1411,39 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
   }
   if (tid < 32) {
     const uint32_t r = tid;
-    uint32_t nwords = 0, W = 0;
+    uint32_t nwords = 0, W = 0, first = 0, last = 0, bit_in_word = 0;
     if (r < R) {
       const uint32_t P = my_P;
       W = my_W;
       // the chunk's record run of group r: [first, last), clamped so that every write stays inside
       // the group's payload even if an internal check has failed
       const uint32_t last_span = min((c + 1) * kChunkSpans, n_spans);
-      uint32_t first = prefix[(size_t)c * kChunkSpans * 32 + r];
-      uint32_t last = prefix[(size_t)last_span * 32 + r];
+      first = prefix[(size_t)c * kChunkSpans * 32 + r];
+      last = prefix[(size_t)last_span * 32 + r];
       if (last > P) last = P;
       if (first > last) first = last;
-      s_lim[r] = last;
       if (last > first) {
         const uint64_t bit0 = (uint64_t)first * W, bit1 = (uint64_t)last * W;
         s_word0[r] = (uint32_t)(bit0 >> 5);
+        bit_in_word = (uint32_t)(bit0 & 31u);
         nwords = (uint32_t)(((bit1 - 1) >> 5) - (bit0 >> 5) + 1);
       }
     }
-    s_W[r] = W;
     s_nwords[r] = nwords;
     // exclusive prefix of the staged word counts over the groups
     const uint32_t incl = wave_incl_scan_u32(nwords);
     s_stage_off[r] = incl - nwords;
     if (r == 31) s_stage_off[32] = incl;
+    EmitGroup eg;
+    eg.first = first;
+    eg.lim = last;
+    eg.W = W;
+    eg.y = my_y;
+    eg.m = my_m;
+    eg.inv = my_inv;
+    eg.stage_bit = (incl - nwords) * 32u + bit_in_word;  // bit of record `first` in the staged image
+    eg.pad = 0;
+    s_grp[r] = eg;
   }
   __syncthreads();
   const uint32_t staged = s_stage_off[32];
@@ -1452,18 +1469,20 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
     wave_lds_fence();
     if (g != kNoGroup) {
       const uint32_t e = start + lanes_below(same);
-      if (e < s_lim[g]) {
-        const uint32_t y = s_y[g], W = s_W[g];
+      const EmitGroup eg = s_grp[g];
+      if (e < eg.lim) {
+        const uint32_t y = eg.y, W = eg.W;
         uint32_t cid;
         if (y == 32) {
           cid = v[j];
         } else {
           const uint32_t u24 = philox_word0(pid[j], client_id, k0, k1) >> 8;
-          cid = quantise(__uint_as_float(v[j]), s_m[g], s_inv[g], y, u24);
+          cid = quantise(__uint_as_float(v[j]), eg.m, eg.inv, y, u24);
         }
         const uint64_t record = (uint64_t)pid[j] | ((uint64_t)cid << sbits);
-        const uint64_t bit = (uint64_t)e * W - (uint64_t)s_word0[g] * 32u;
-        const uint32_t w0 = s_stage_off[g] + (uint32_t)(bit >> 5), sh = (uint32_t)(bit & 31u);
+        // a chunk's run of a group is at most 4096 records of at most 63 bits: 32 bits hold the offset
+        const uint32_t bit = eg.stage_bit + (e - eg.first) * W;
+        const uint32_t w0 = bit >> 5, sh = bit & 31u;
         const uint64_t lo = record << sh;
         atomicOr(&s_stage[w0], (uint32_t)lo);
         if (sh + W > 32u) atomicOr(&s_stage[w0 + 1], (uint32_t)(lo >> 32));
