@@ -350,3 +350,81 @@ def test_full_size_32_clients(cfg):
     ref = orc.decode_aggregate(ref_streams, d)
     tol = 1e-5 * abs_terms(ref_streams, d)
     assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= tol)
+
+
+# --------------------------------------------------------------------------- vectors the oracle cannot sort in test time
+@pytest.mark.parametrize("d,ys,counts", [
+    (300_000_007, [12, 8, 2], [2_000_003, 3_000_000, 5_000_001]),      # 29 position bits, records of 41, 37, 31 bits
+    (2**31 - 1, [32, 12, 1], [1_000_001, 4_000_000, 7_000_003]),        # the largest d the ABI takes: 63, 43, 32 bits
+])
+def test_properties_at_sizes_beyond_the_oracle(d, ys, counts):
+    """The oracle's sort would take minutes at these sizes, so the encoder is checked through what must
+    hold at any size: the records the oracle's parser reads back are the top-k coordinates, in position
+    order inside magnitude-ordered groups; the headers hold the groups' exact min and max; every
+    reconstruction lies within one centroid spacing of its value (exactly on it for 32-bit codes); and
+    the library's decode of the stream equals the oracle's decode of the same stream bit for bit.
+    Records wider than 33 bits span three stream words."""
+    k = sum(counts)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(2402_03770)
+    U = torch.randn(d, dtype=torch.float32, device=DEV, generator=gen)
+    # 1000 "layers" of different scale, as in the benchmark workload
+    scale = 10.0 ** (torch.rand(1000, device=DEV, generator=gen) * 3.0 - 5.0)
+    U *= scale.repeat_interleave((d + 999) // 1000)[:d]
+    del scale
+    plan = cv.plan_manual(d, ys, counts)
+    stream = cv.new_stream_buffer(plan, DEV)
+    stream.fill_(-1)
+    ws = cv.new_workspace(cv.encode_workspace_bytes(d, 1), DEV)
+    cv.encode_batch([plan], [U], 77, [5], [stream], ws)
+    assert cv.device_status(ws) == 0
+    del ws
+    words = stream.cpu().numpy().view(np.uint32)[: plan.stream_bytes // 4]
+
+    pid, cid, seg = orc.unpack(words, d)
+    assert pid.size == k
+    bounds = np.concatenate([[0], np.cumsum(counts)])
+    pid_dev = torch.from_numpy(pid.astype(np.int64)).to(DEV)
+    kept = U[pid_dev]
+    mag = kept.abs()
+    lowest_above = None
+    headers = []
+    for r in range(len(ys)):
+        a, b = int(bounds[r]), int(bounds[r + 1])
+        assert np.all(seg[a:b] == r + 1)
+        assert np.all(np.diff(pid[a:b].astype(np.int64)) > 0), f"group {r}: positions must ascend"
+        assert int(pid[a:b].max()) < d
+        g = mag[a:b]
+        if lowest_above is not None:
+            assert float(g.max()) <= lowest_above, "groups must be ordered by magnitude"
+        lowest_above = float(g.min())
+        # header: exact min and max of the group's values
+        h = words[8 + 4 * r: 12 + 4 * r]
+        assert int(h[0]) == ys[r] and int(h[1]) == counts[r]
+        m, M = h[2:3].view(np.float32)[0], h[3:4].view(np.float32)[0]
+        assert m == float(kept[a:b].min()) and M == float(kept[a:b].max())
+        headers.append((float(m), float(M)))
+    # the kept set is the top k: nothing outside it is larger than its smallest member
+    tau = float(mag.min())
+    n_gt = int((U.abs() > tau).sum())
+    n_ge = int((U.abs() >= tau).sum())
+    assert n_gt == int((mag > tau).sum()) and n_gt < k <= n_ge
+
+    out = torch.full((d,), float("nan"), dtype=torch.float32, device=DEV)
+    dws = cv.new_workspace(cv.decode_workspace_bytes(d, 1), DEV)
+    cv.decode_aggregate([stream], out, dws)
+    assert cv.device_status(dws) == 0
+    xhat = out[pid_dev]
+    for r in range(len(ys)):
+        a, b = int(bounds[r]), int(bounds[r + 1])
+        m, M = headers[r]
+        err = float((xhat[a:b].double() - kept[a:b].double()).abs().max())
+        if ys[r] == 32:
+            assert err == 0.0
+        else:
+            assert err <= (M - m) / (2 ** ys[r] - 1) * (1 + 1e-5)
+    assert int((out != 0).sum()) <= k
+    del U, kept, mag, xhat, pid_dev
+    ref = orc.decode_aggregate([words], d)
+    got = out.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), "single-client decode is bit exact"
