@@ -9,24 +9,33 @@
 // position.  Launch chain per batch of clients (no kernel waits on another
 // workgroup and none needs a memory fence; every dependency is a kernel
 // boundary):
-//   sample_hist   strided sample of |U| -> histogram of the top 12 key bits
+//   upload        per-client parameters as kernel arguments; clears the
+//                 call's control blocks
+//   sample_hist   strided sample of |U| -> histogram of the top 13 key bits
 //   sample_walk   conservative candidate threshold tau_lo from that histogram
 //   filter        the one full pass over U.  Every wavefront owns regions of
 //                 8192 consecutive coordinates and writes the coordinates with
 //                 key >= tau_lo to the front of the region's slot, in position
 //                 order; it also counts the level-1 digit (top 11 key bits) of
 //                 what it keeps and sums the squares of what it drops
-//   scan_l1       prefix over the region counts; level-1 bins of the boundaries
-//   select_pass   level 2, then level 3: LDS histograms of the next 10 key bits
-//                 of the candidates that match a boundary's prefix
+//   scan_l1       prefix over the region counts, list of the non-empty runs;
+//                 level-1 bins of the boundaries (filter and scan run a second
+//                 time, keeping everything, for a client whose sample misjudged)
+//   gather_l2     copies the runs into one dense, position-ordered candidate
+//                 list, spans of 512 candidates per wavefront, and histograms
+//                 level 2 (the next 10 key bits) of the first 15 boundaries
+//   select_pass   level 3 (and level 2 of further groups of 15 boundaries):
+//                 LDS histograms of the next 10 key bits of the candidates that
+//                 match a boundary's prefix
 //   select_walk   adds up the histograms, fixes the next digit of every
 //                 boundary; after level 3 the exact boundary keys and, where a
 //                 boundary cuts a class of equal magnitudes, the position of
 //                 its last member inside the boundary
-//   count         per chunk (the runs of 8 consecutive regions): group of every
-//                 candidate, per-group count, min/max/sum of squares
-//   layout        prefix of the per-chunk counts, headers, statistics
-//   emit          stochastic rounding (Philox4x32-10) and bit packing
+//   count         per span: group of every candidate, per-group count,
+//                 min/max/sum of squares
+//   layout        prefix of the per-span counts, headers, statistics
+//   emit          per chunk of 8 spans: stochastic rounding (Philox4x32-10)
+//                 and bit packing
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -46,7 +55,7 @@ struct GroupInfo {
 };
 
 struct EncodeLayout {
-  size_t status, ctl, params, region_cnt, region_off, region_sumsq, cand_idx, cand_val, dense_idx, dense_val, nz_off, nz_run, span_first, span_cnt, group_info,
+  size_t status, ctl, params, region_cnt, region_sumsq, cand_idx, cand_val, dense_idx, dense_val, nz_off, nz_run, span_first, span_cnt, group_info,
       tie_list, sel_part, l3_hist, total;
   size_t zero_bytes;        // [status, params) is cleared at the start of a call
   uint32_t n_regions, max_spans;
@@ -81,7 +90,6 @@ EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   L.zero_bytes = off;
   L.params = off; off = align256(off + (size_t)n * sizeof(ClientParams));
   L.region_cnt = off; off = align256(off + (size_t)n * L.n_regions * sizeof(uint32_t));
-  L.region_off = off; off = align256(off + (size_t)n * (L.n_regions + 1) * sizeof(uint32_t));
   L.region_sumsq = off; off = align256(off + (size_t)n * L.n_regions * sizeof(double));
   L.cand_idx = off; off = align256(off + (size_t)n * d * sizeof(uint16_t));
   L.cand_val = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
@@ -103,7 +111,6 @@ struct Workspace {  // device pointers into the caller's workspace
   ClientParams* params;
   ClientCtl* ctl;
   uint32_t* region_cnt;
-  uint32_t* region_off;
   double* region_sumsq;
   uint16_t* cand_idx;  // positions of the kept coordinates inside their region: a run at the front of every region's slot
   uint32_t* cand_val;  // their value bits, same layout
@@ -464,7 +471,6 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
   if (PASS == 1 && !ctl->refilter) return;
   const uint32_t n_regions = ws.n_regions;
   const uint32_t* cnt = ws.region_cnt + (size_t)client * n_regions;
-  uint32_t* off = ws.region_off + (size_t)client * (n_regions + 1);
   uint32_t* nz_off = ws.nz_off + (size_t)client * (n_regions + 1);
   uint32_t* nz_run = ws.nz_run + (size_t)client * (n_regions + 1);
   uint32_t* span_first = ws.span_first + (size_t)client * (ws.max_spans + 1);
@@ -476,7 +482,6 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
     const uint32_t excl = block_excl_scan<kWideWaves>(v, scan_tmp, &tot);
     const uint32_t q = n_nz + block_excl_scan<kWideWaves>(v ? 1u : 0u, scan_tmp, &tot_nz);
     if (j < n_regions) {
-      off[j] = run + excl;
       if (v) {
         const uint32_t begin = run + excl, end = begin + v;
         nz_off[q] = begin;
@@ -489,7 +494,6 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
     n_nz += tot_nz;
   }
   if (tid == 0) {
-    off[n_regions] = run;
     nz_off[n_nz] = run;
     ctl->n_cand = run;
     ctl->n_nz = n_nz;
@@ -1583,7 +1587,6 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   ws.params = reinterpret_cast<ClientParams*>(base + L.params);
   ws.ctl = reinterpret_cast<ClientCtl*>(base + L.ctl);
   ws.region_cnt = reinterpret_cast<uint32_t*>(base + L.region_cnt);
-  ws.region_off = reinterpret_cast<uint32_t*>(base + L.region_off);
   ws.region_sumsq = reinterpret_cast<double*>(base + L.region_sumsq);
   ws.cand_idx = reinterpret_cast<uint16_t*>(base + L.cand_idx);
   ws.cand_val = reinterpret_cast<uint32_t*>(base + L.cand_val);
