@@ -114,7 +114,7 @@ struct Workspace {  // device pointers into the caller's workspace
   double* region_sumsq;
   uint16_t* cand_idx;  // positions of the kept coordinates inside their region: a run at the front of every region's slot
   uint32_t* cand_val;  // their value bits, same layout
-  uint32_t* dense_idx; // the same candidates, contiguous per client, in position order
+  uint32_t* dense_idx; // the same candidates, contiguous per client, in position order: positions (read by emit only)
   uint32_t* dense_val;
   uint32_t* nz_off;      // the non-empty runs in position order: number of the run's first candidate ...
   uint32_t* nz_run;      // ... and its region; entry n_nz of nz_off holds the number of candidates
@@ -602,10 +602,11 @@ struct SelectShared {
 static_assert(kSlotGroup <= 15, "bin tags are 4 bits wide");
 static_assert(sizeof(SelectShared) <= 65536, "SelectShared must fit the 64 KB static LDS limit");
 
-// Counts one candidate per lane (`live` lanes only); idx_at points at its
-// position.  Must be reached by all lanes of the wavefront.
+// Counts one candidate per lane (`live` lanes only); dense_i is its number in the
+// position-ordered candidate list (which ranks equal keys just as positions do).
+// Must be reached by all lanes of the wavefront.
 template <int LEVEL>
-__device__ __forceinline__ void select_count(SelectShared& S, uint32_t key, const uint32_t* __restrict__ idx_at,
+__device__ __forceinline__ void select_count(SelectShared& S, uint32_t key, uint32_t dense_i,
                                              bool live, uint32_t* tie_cnt, uint2* __restrict__ ties) {
   uint32_t q = kNoSlot;
   if (live) {
@@ -639,7 +640,7 @@ __device__ __forceinline__ void select_count(SelectShared& S, uint32_t key, cons
       base = __builtin_amdgcn_readlane(base, leader);
       if (mine) {
         const uint32_t pos = base + lanes_below(peers);
-        if (pos < kTieCap) ties[qs * kTieCap + pos] = make_uint2(*idx_at, key & (kDigitBins - 1));  // position is read only here
+        if (pos < kTieCap) ties[qs * kTieCap + pos] = make_uint2(dense_i, key & (kDigitBins - 1));
       }
       todo &= ~peers;
     }
@@ -681,33 +682,38 @@ __device__ __forceinline__ CandView cand_view(const Workspace& ws, const ClientC
 // span is candidate span*512 + j*64 + lane.  The runs that follow the span's
 // first one are fetched 64 at a time, one per lane; every run that starts
 // inside the span moves the rows at or after its first candidate on to it.
-__device__ __forceinline__ void span_slots(const CandView& cv, uint32_t span, uint32_t (&slot)[kPerLane]) {
+struct SpanWindow {  // the first 64 runs at or after a span's first candidate, one per lane
+  uint32_t base, wo, wr;
+};
+
+__device__ __forceinline__ SpanWindow span_window(const CandView& cv, uint32_t span) {
+  SpanWindow w;
+  w.base = cv.span_first[span];
+  w.wo = cv.nz_off[min(w.base + lane_id(), cv.n_nz)];
+  w.wr = cv.nz_run[min(w.base + lane_id(), cv.n_nz)];  // entry n_nz is never selected: its offset is n >= end
+  return w;
+}
+
+__device__ __forceinline__ void span_slots(const CandView& cv, uint32_t span, const SpanWindow& win,
+                                           uint32_t (&slot)[kPerLane]) {
   const uint32_t lane = lane_id();
   const uint32_t begin = span * kSpan;
   const uint32_t end = min(begin + kSpan, cv.n);
-  uint32_t base = cv.span_first[span];
-  uint32_t wo = cv.nz_off[min(base + lane, cv.n_nz)];
-  uint32_t wr = cv.nz_run[min(base + lane, cv.n_nz)];  // entry n_nz is never selected: its offset is n >= end
-  uint32_t run_of[kPerLane], off_of[kPerLane];
-  const uint32_t off0 = __builtin_amdgcn_readlane(wo, 0), run0 = __builtin_amdgcn_readlane(wr, 0);
+  uint32_t base = win.base, wo = win.wo, wr = win.wr;
+  // slot of candidate i in run (region r, first candidate o): r * kRegion + (i - o); kept as i + shift
+  const uint32_t shift0 = __builtin_amdgcn_readlane(wr, 0) * kRegion - __builtin_amdgcn_readlane(wo, 0);
 #pragma unroll
-  for (uint32_t j = 0; j < kPerLane; ++j) {
-    run_of[j] = run0;
-    off_of[j] = off0;
-  }
+  for (uint32_t j = 0; j < kPerLane; ++j) slot[j] = shift0;
   while (true) {
     uint32_t t = 1;
     for (; t < kWave; ++t) {
       const uint32_t ot = __builtin_amdgcn_readlane(wo, t);
       if (ot >= end) break;
-      const uint32_t rt = __builtin_amdgcn_readlane(wr, t);
+      const uint32_t shift = __builtin_amdgcn_readlane(wr, t) * kRegion - ot;
 #pragma unroll
       for (uint32_t j = 0; j < kPerLane; ++j) {
         const uint32_t i = begin + j * kWave + lane;
-        if (i >= ot) {
-          run_of[j] = rt;
-          off_of[j] = ot;
-        }
+        if (i >= ot) slot[j] = shift;
       }
     }
     if (t < kWave) break;
@@ -716,10 +722,7 @@ __device__ __forceinline__ void span_slots(const CandView& cv, uint32_t span, ui
     wr = cv.nz_run[min(base + lane, cv.n_nz)];
   }
 #pragma unroll
-  for (uint32_t j = 0; j < kPerLane; ++j) {
-    const uint32_t i = begin + j * kWave + lane;
-    slot[j] = run_of[j] * kRegion + (i - off_of[j]);  // meaningless for i >= n, never used there
-  }
+  for (uint32_t j = 0; j < kPerLane; ++j) slot[j] += begin + j * kWave + lane;  // meaningless for i >= n, never used there
 }
 
 // Fills the workgroup's slot tables for one group of boundaries.
@@ -773,7 +776,7 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
   const uint32_t n_spans = (cv.n + kSpan - 1) / kSpan;
   for (uint32_t span = blockIdx.x * kWideWaves + wave; span < n_spans; span += gridDim.x * kWideWaves) {
     uint32_t slot[kPerLane], v[kPerLane], x[kPerLane];
-    span_slots(cv, span, slot);
+    span_slots(cv, span, span_window(cv, span), slot);
 #pragma unroll
     for (uint32_t j = 0; j < kPerLane; ++j) {
       const uint32_t i = span * kSpan + j * kWave + lane;
@@ -792,7 +795,7 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
         dst_val[i] = v[j];
         dst_idx[i] = x[j];
       }
-      if (nb) select_count<2>(S, v[j] & 0x7FFFFFFFu, nullptr, i < cv.n, nullptr, nullptr);
+      if (nb) select_count<2>(S, v[j] & 0x7FFFFFFFu, 0u, i < cv.n, nullptr, nullptr);
     }
   }
   __syncthreads();
@@ -815,7 +818,6 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
   if (p.R <= r0) return;  // this client has no boundary in the group
   const uint32_t nb = min(p.R - r0, kSlotGroup);
   const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
-  const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.d;
   uint2* ties = ws.tie_list + (size_t)client * kSlotGroup * kTieCap;
   uint32_t* tie_cnt = ctl->tie_cnt[group];
   select_setup<LEVEL>(S, ctl, r0, nb);
@@ -837,7 +839,7 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
     for (uint32_t u = 0; u < 8; ++u) {
       const uint32_t i = base + u * kWideBlock + tid;
       if (base + u * kWideBlock + wave * kWave >= end) break;  // uniform per wavefront
-      select_count<LEVEL>(S, v[u] & 0x7FFFFFFFu, idx + i, i < end, tie_cnt, ties);
+      select_count<LEVEL>(S, v[u] & 0x7FFFFFFFu, i, i < end, tie_cnt, ties);
     }
   }
   __syncthreads();
@@ -936,7 +938,6 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
     // a class of equal keys straddles the boundary: find its quota-th member in position order
     const uint2* list = ws.tie_list + ((size_t)client * kSlotGroup + slot) * kTieCap;
     const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
-    const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.d;
     const uint32_t n = ctl->n_cand;
     for (uint32_t b = 0; b < nb; ++b) {
       if (!s_need[b]) continue;  // uniform
@@ -988,7 +989,7 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
             const uint32_t c = (uint32_t)__popcll(m);
             if (left <= c) {
               if (hit && lanes_below(m) + 1u == left) {
-                ctl->iota[r] = idx[i];
+                ctl->iota[r] = i;
                 s_found = 1;
               }
               break;
@@ -1021,7 +1022,7 @@ __device__ __forceinline__ void load_thresholds(Thresholds& t, const ClientCtl* 
 }
 
 // Group of a candidate, 0-based: the first boundary r whose top-Z_r set holds
-// it (key above tau_r, or equal with position <= iota_r); R if none (dropped).
+// it (key above tau_r, or equal and not after candidate iota_r); R if none (dropped).
 // tau is non-increasing in r, so "key <= tau_r" holds for the first g boundaries
 // and for no later one, g being the number of boundaries with tau_r >= key: a
 // binary search over the boundaries (entries past R never hold) finds it in
@@ -1040,13 +1041,10 @@ __device__ __forceinline__ void classify_keys(const Thresholds& t, uint32_t R, c
 }
 
 // Second step for a key that equals the boundary key just above its group:
-// boundaries with that key decide by position.
-__device__ __forceinline__ uint32_t classify_tie(const Thresholds& t, uint32_t key, uint32_t g,
-                                                 const uint32_t* __restrict__ idx_at) {
-  if (g > 0 && t.tau[g - 1] == key) {
-    const uint32_t idx = *idx_at;
-    while (g > 0 && t.tau[g - 1] == key && idx <= t.iota[g - 1]) --g;
-  }
+// boundaries with that key decide by position, i.e. by the candidate's number
+// in the position-ordered list against that of the last member inside.
+__device__ __forceinline__ uint32_t classify_tie(const Thresholds& t, uint32_t key, uint32_t g, uint32_t dense_i) {
+  while (g > 0 && t.tau[g - 1] == key && dense_i <= t.iota[g - 1]) --g;
   return g;
 }
 
@@ -1072,8 +1070,8 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 // span*512 + j*64 + lane, i.e. in position order) and classifies them.
 // grp[j] = kNoGroup past the end of the list.
 __device__ __forceinline__ void classify_span(const Thresholds& thr, uint32_t R, const uint32_t* __restrict__ val,
-                                              const uint32_t* __restrict__ idx, uint32_t n, uint32_t span,
-                                              uint32_t (&v)[kPerLane], uint32_t (&grp)[kPerLane]) {
+                                              uint32_t n, uint32_t span, uint32_t (&v)[kPerLane],
+                                              uint32_t (&grp)[kPerLane]) {
   const uint32_t mine = span * kSpan + lane_id();
   uint32_t key[kPerLane];
   // no branch around the loads (a lane past the end reads the last candidate again): all eight are in
@@ -1089,7 +1087,7 @@ __device__ __forceinline__ void classify_span(const Thresholds& thr, uint32_t R,
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) {
     const uint32_t i = mine + j * kWave;
-    grp[j] = i < n ? classify_tie(thr, key[j], grp[j], idx + i) : kNoGroup;
+    grp[j] = i < n ? classify_tie(thr, key[j], grp[j], i) : kNoGroup;
   }
 }
 
@@ -1112,7 +1110,6 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
   const uint32_t R = p.R, n = ctl->n_cand;
   const uint32_t n_spans = (n + kSpan - 1) / kSpan;
   const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
-  const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.d;
   uint32_t* __restrict__ span_cnt = ws.span_cnt + (size_t)client * (ws.max_spans + 1) * 32;
   load_thresholds(thr, ctl, R);
   if (tid < kEmitWaves * 32) (&s_cnt[0][0])[tid] = 0;
@@ -1124,7 +1121,7 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
   __syncthreads();
   for (uint32_t span = blockIdx.x * kEmitWaves + wave; span < n_spans; span += gridDim.x * kEmitWaves) {
     uint32_t v[kPerLane], grp[kPerLane];
-    classify_span(thr, R, val, idx, n, span, v, grp);
+    classify_span(thr, R, val, n, span, v, grp);
     // the span's size of every group, counted in a row of LDS words private to the wavefront
 #pragma unroll
     for (uint32_t j = 0; j < kPerLane; ++j)
@@ -1454,7 +1451,7 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
   for (uint32_t i = tid; i < staged; i += kEmitBlock) s_stage[i] = 0;
 
   uint32_t v[kPerLane], grp[kPerLane], pid[kPerLane];
-  classify_span(thr, R, val, idx, n, c * kChunkSpans + wave, v, grp);
+  classify_span(thr, R, val, n, c * kChunkSpans + wave, v, grp);
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) {  // unconditional, so that the loads overlap
     const uint32_t i = (c * kChunkSpans + wave) * kSpan + j * kWave + lane;
