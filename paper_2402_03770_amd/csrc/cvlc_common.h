@@ -65,7 +65,7 @@ struct ClientCtl {
   uint32_t sel_prefix[2][32];  // key prefix of boundary r after level 1 (11 bits) and level 2 (21 bits); 0xFFFFFFFF: Z_r = 0
   uint32_t sel_rem[2][32];     // rank of the boundary element inside that prefix class, 1-based from the top
   uint32_t tau[32];          // Z_r-th largest key (0xFFFFFFFF: Z_r = 0)
-  uint32_t iota[32];         // largest index among the key == tau_r coordinates inside the top Z_r
+  uint32_t iota[32];         // last of the key == tau_r candidates inside the top Z_r, by its number in the position-ordered list
   uint32_t seg_max_enc[32];  // max over the group of ordered(x); 0 = empty
   uint32_t seg_negmin_enc[32];  // max over the group of ~ordered(x); 0 = empty
   uint32_t hist_sample[kSampleBins];  // sample histogram, accumulated with device-wide atomics
