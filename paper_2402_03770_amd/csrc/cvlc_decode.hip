@@ -24,7 +24,7 @@ namespace {
 
 constexpr uint32_t kListsPerClient = 32;   // descriptor slots per client (CVLC_MAX_CODED used)
 constexpr uint32_t kTabChunk = 2048;       // records per tile_table work item
-constexpr uint32_t kTabWords = kTabChunk / 32u * 63u + 8u;  // words such a chunk can span, plus the record before it
+constexpr uint32_t kTabWords = kTabChunk / 32u * 63u + 8u;  // words such a chunk can span, plus the record before it, plus one
 constexpr uint32_t kListBatch = 512;       // lists a decode workgroup handles per sweep
 
 struct CompactDesc {  // one non-empty (client, group) record list, 32 bytes
@@ -221,16 +221,6 @@ __global__ __launch_bounds__(1024) void compact_lists_kernel(const ListDesc* __r
 // into LDS with coalesced loads, then thread e compares the tiles of records e-1
 // and e and fills the entries in between.
 
-// Bits [bit, bit + W) of an LDS word array, bit < 2^32, W <= 63.
-__device__ __forceinline__ uint64_t lds_bits(const uint32_t* words, uint32_t n_words, uint32_t bit, uint32_t W) {
-  const uint32_t w = bit >> 5, sh = bit & 31u;
-  const uint64_t a = words[w];
-  const uint64_t b = (w + 1 < n_words) ? words[w + 1] : 0u;
-  uint64_t v = (a | (b << 32)) >> sh;
-  if (sh + W > 64u) v |= (uint64_t)words[min(w + 2, n_words - 1)] << (64u - sh);
-  return v & ((1ull << W) - 1ull);
-}
-
 // What a work item needs from its list, and where its records sit.
 struct TabItem {
   GlobalConstWordPtr src;  // first word brought into LDS
@@ -242,6 +232,13 @@ struct TabItem {
 };
 
 constexpr uint32_t kTabRegs = (kTabWords + kBlock - 1) / kBlock;  // stream words a thread carries for the next item
+
+// Position field of the record whose first bit is `bit` of an LDS word array: its s <= 31 low bits lie in
+// at most two words, whatever the record's width.  The word after must exist in the array (not in the data).
+__device__ __forceinline__ uint32_t lds_pid(const uint32_t* words, uint32_t bit, uint32_t pid_mask) {
+  const uint32_t w = bit >> 5;
+  return __builtin_amdgcn_alignbit(words[w + 1], words[w], bit & 31u) & pid_mask;
+}
 
 __global__ __launch_bounds__(kBlock, 6) void tile_table_kernel(const CompactDesc* __restrict__ cdesc,
                                                             const uint32_t* __restrict__ item_start,
@@ -327,7 +324,7 @@ __global__ __launch_bounds__(kBlock, 6) void tile_table_kernel(const CompactDesc
       next_loc = locate(q + 2 * stride);
     }
     const TabItem& ld = cur;
-    const uint32_t W = ld.W, s = ld.s, e0 = ld.e0, cnt = ld.cnt, e_lo = ld.e_lo, nw = ld.nw, bit_base = ld.bit_base;
+    const uint32_t W = ld.W, s = ld.s, e0 = ld.e0, cnt = ld.cnt, e_lo = ld.e_lo, bit_base = ld.bit_base;
     const uint32_t pid_mask = s >= 32 ? 0xFFFFFFFFu : (1u << s) - 1u;
     uint32_t* row = table + (size_t)ld.list * (n_tiles + 1);
     // a wavefront takes a contiguous quarter of the item's records, 64 at a time: the record before lane 0's
@@ -337,13 +334,13 @@ __global__ __launch_bounds__(kBlock, 6) void tile_table_kernel(const CompactDesc
     const uint32_t j_end = min(j_begin + per_wave, cnt);
     uint32_t carry = 0;
     if (j_begin < j_end && e0 + j_begin > 0)
-      carry = (uint32_t)lds_bits(s_words, nw, bit_base + (e0 + j_begin - 1 - e_lo) * W, W) & pid_mask;  // uniform
+      carry = lds_pid(s_words, bit_base + (e0 + j_begin - 1 - e_lo) * W, pid_mask);  // uniform
     for (uint32_t j0 = j_begin; j0 < j_end; j0 += kWave) {  // uniform per wavefront: the shuffles need all lanes
       const uint32_t j = j0 + lane;
       const bool live = j < j_end;
       const uint32_t e = e0 + j;
-      uint32_t pid = 0;
-      if (live) pid = (uint32_t)lds_bits(s_words, nw, bit_base + (e - e_lo) * W, W) & pid_mask;
+      // no branch here: a lane past the end reads the last record again
+      const uint32_t pid = lds_pid(s_words, bit_base + (min(e, e0 + cnt - 1u) - e_lo) * W, pid_mask);
       uint32_t prev = __shfl_up(pid, 1, 64);  // the record before mine sits in the lane below
       if (lane == 0) prev = carry;
       carry = __shfl(pid, kWave - 1, 64);
