@@ -468,16 +468,27 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
       while ((1u << steps) < nl) ++steps;
       for (uint32_t q0 = tid; q0 < total; q0 += kDecBlock * kUnroll) {
         uint32_t at_of[kUnroll], w0_of[kUnroll], w1_of[kUnroll], w2_of[kUnroll];  // at: list << 8 | flags | shift
+        // the six searches advance together, one LDS round trip per step for all of them
+        uint32_t lo_of[kUnroll], hi_of[kUnroll];
+#pragma unroll
+        for (uint32_t u = 0; u < kUnroll; ++u) {
+          lo_of[u] = 0;   // last list with first <= q (lists with no record in the tile are skipped over)
+          hi_of[u] = nl;
+        }
+        for (uint32_t it = 0; it < steps; ++it) {
+#pragma unroll
+          for (uint32_t u = 0; u < kUnroll; ++u) {
+            const uint32_t q = min(q0 + u * kDecBlock, total - 1u);
+            const uint32_t mid = (lo_of[u] + hi_of[u]) >> 1;
+            const bool take = S.first[mid] <= q;  // mid == lo once hi - lo <= 1: nothing moves any more
+            lo_of[u] = take ? mid : lo_of[u];
+            hi_of[u] = take ? hi_of[u] : mid;
+          }
+        }
 #pragma unroll
         for (uint32_t u = 0; u < kUnroll; ++u) {
           const uint32_t q = min(q0 + u * kDecBlock, total - 1u);
-          uint32_t a = 0, b = nl;  // last list with first <= q (lists with no record in the tile are skipped over)
-          for (uint32_t it = 0; it < steps; ++it) {
-            const uint32_t mid = (a + b) >> 1;
-            const bool take = S.first[mid] <= q;  // mid == a once b - a <= 1: nothing moves any more
-            a = take ? mid : a;
-            b = take ? b : mid;
-          }
+          const uint32_t a = lo_of[u];
           const uint4 d0 = S.desc[a][0], d1 = S.desc[a][1];
           GlobalConstWordPtr pay = (GlobalConstWordPtr)(((uint64_t)d0.y << 32) | d0.x);
           const uint32_t P = d1.x, W = d1.y & 0xFFu;
