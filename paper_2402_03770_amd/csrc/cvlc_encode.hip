@@ -1492,19 +1492,18 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
     }
   }
   __syncthreads();
-  for (uint32_t i = tid; i < staged; i += kEmitBlock) {
-    uint32_t lo = 0, hi = 32;  // group whose staged words hold word i: last g with s_stage_off[g] <= i
-    while (hi - lo > 1) {
-      const uint32_t mid = (lo + hi) >> 1;
-      if (s_stage_off[mid] <= i) lo = mid; else hi = mid;
-    }
-    const uint32_t g = lo, rel = i - s_stage_off[g];
-    GlobalWordPtr dst = stream + s_payload[g] + s_word0[g] + rel;
-    const uint32_t word = s_stage[i];
-    if (rel == 0 || rel == s_nwords[g] - 1) {
-      if (word) atomicOr((uint32_t*)dst, word);
-    } else {
-      *dst = word;
+  // group by group (the loop bounds are uniform), thread t the t-th, t+512-th, ... word of the group's run
+  for (uint32_t g = 0; g < R; ++g) {
+    const uint32_t nwords = s_nwords[g];
+    const uint32_t* staged_words = s_stage + s_stage_off[g];
+    GlobalWordPtr dst = stream + s_payload[g] + s_word0[g];
+    for (uint32_t rel = tid; rel < nwords; rel += kEmitBlock) {
+      const uint32_t word = staged_words[rel];
+      if (rel == 0 || rel == nwords - 1) {
+        if (word) atomicOr((uint32_t*)(dst + rel), word);
+      } else {
+        dst[rel] = word;
+      }
     }
   }
   }  // chunks
