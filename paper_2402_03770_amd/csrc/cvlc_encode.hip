@@ -128,20 +128,37 @@ struct Workspace {  // device pointers into the caller's workspace
 };
 
 // ------------------------------------------------------------------ parameter upload
+// The per-client parameter blocks travel as kernel arguments (no pinned memory,
+// no synchronisation).  Clients of a batch mostly share a plan, so a chunk holds
+// every distinct block once, with pointers and client id left out ("template"),
+// and six words per client: update pointer, stream pointer, client id, template.
 constexpr uint32_t kUploadWords = 960;
+constexpr uint32_t kParamWords = sizeof(ClientParams) / 4u;
+constexpr uint32_t kRefWords = 6;
+static_assert(sizeof(ClientParams) % 4 == 0 && offsetof(ClientParams, update) == 0 &&
+                  offsetof(ClientParams, stream) == 8 && offsetof(ClientParams, client_id) == 16,
+              "the upload kernel patches words 0..4 of a parameter block");
 struct UploadChunk {
-  uint32_t n_words, dst_word;
-  uint32_t data[kUploadWords];
+  uint32_t n_clients, first_client, n_templates, pad;
+  uint32_t data[kUploadWords];  // n_templates parameter blocks, then n_clients references
 };
 
-// Workgroup 0 writes the chunk's words; all workgroups clear zero_n16 16-byte
-// pieces from `zero` on (the call's state that starts at zero, in the call's
-// first launch; a plain kernel, so that a caller may capture the call in a graph).
+// Workgroup 0 expands the chunk into the clients' parameter blocks; all
+// workgroups clear zero_n16 16-byte pieces from `zero` on (the call's state that
+// starts at zero, in the call's first launch; a plain kernel, so that a caller
+// may capture the call in a graph).
 __global__ __launch_bounds__(256) void upload_kernel(uint32_t* dst, UploadChunk c, uint4* zero, uint32_t zero_n16) {
   for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < zero_n16; i += gridDim.x * blockDim.x)
     zero[i] = make_uint4(0u, 0u, 0u, 0u);
-  if (blockIdx.x == 0)
-    for (uint32_t i = threadIdx.x; i < c.n_words; i += blockDim.x) dst[c.dst_word + i] = c.data[i];
+  if (blockIdx.x == 0) {
+    const uint32_t* refs = c.data + c.n_templates * kParamWords;
+    for (uint32_t i = threadIdx.x; i < c.n_clients * kParamWords; i += blockDim.x) {
+      const uint32_t client = i / kParamWords, w = i % kParamWords;
+      const uint32_t* ref = refs + client * kRefWords;
+      const uint32_t v = w < 5 ? ref[w] : c.data[ref[5] * kParamWords + w];
+      dst[(size_t)(c.first_client + client) * kParamWords + w] = v;
+    }
+  }
 }
 
 // ------------------------------------------------------------------ small device helpers
@@ -1614,41 +1631,65 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   uint32_t max_R = 0;
   bool any_sampled = false;
   {
-    constexpr uint32_t words_per = sizeof(ClientParams) / 4u;
-    const uint32_t per_chunk = kUploadWords / words_per;
     UploadChunk chunk;
-    for (uint32_t first = 0; first < n; first += per_chunk) {
-      const uint32_t cnt = (n - first < per_chunk) ? n - first : per_chunk;
-      chunk.n_words = cnt * words_per;
-      chunk.dst_word = first * words_per;
-      for (uint32_t i = 0; i < cnt; ++i) {
-        const cvlc_plan_t& pl = plans[first + i];
-        ClientParams cp;
-        std::memset(&cp, 0, sizeof(cp));
-        cp.update = d_updates[first + i];
-        cp.stream = static_cast<uint32_t*>(d_streams_out[first + i]);
-        cp.client_id = client_ids[first + i];
-        cp.R = pl.n_coded;
-        cp.total_words = (uint32_t)(pl.total_bits / 32u);
-        cp.B = pl.B;
-        uint32_t z = 0;
-        for (uint32_t r = 0; r < pl.n_coded; ++r) {
-          z += pl.count[r];
-          cp.Z[r] = z;
-          cp.y[r] = (uint8_t)pl.code_len[r];
-        }
-        cp.k = z;
-        cp.sample_rank = sample_rank(d, z, n_s * 16u);
-        any_sampled |= cp.sample_rank != 0;
-        if (pl.n_coded > max_R) max_R = pl.n_coded;
-        std::memcpy(&chunk.data[i * words_per], &cp, sizeof(cp));
-      }
+    chunk.n_clients = 0;
+    chunk.first_client = 0;
+    chunk.n_templates = 0;
+    chunk.pad = 0;
+    uint32_t refs[kUploadWords];  // the chunk's references, appended behind its templates when it is sent
+    auto send = [&]() {
+      std::memcpy(&chunk.data[chunk.n_templates * kParamWords], refs, (size_t)chunk.n_clients * kRefWords * 4u);
       const uint32_t blocks = zero_n16 ? (zero_n16 + 1023u) / 1024u : 1u;
       hipLaunchKernelGGL(upload_kernel, dim3(blocks < 512u ? blocks : 512u), dim3(256), 0, stream,
                          reinterpret_cast<uint32_t*>(ws.params), chunk, reinterpret_cast<uint4*>(base + L.status),
                          zero_n16);
       zero_n16 = 0;  // cleared by the first launch
+      chunk.first_client += chunk.n_clients;
+      chunk.n_clients = 0;
+      chunk.n_templates = 0;
+    };
+    for (uint32_t i = 0; i < n; ++i) {
+      const cvlc_plan_t& pl = plans[i];
+      ClientParams cp;
+      std::memset(&cp, 0, sizeof(cp));  // pointers and client id stay out of the template
+      cp.R = pl.n_coded;
+      cp.total_words = (uint32_t)(pl.total_bits / 32u);
+      cp.B = pl.B;
+      uint32_t z = 0;
+      for (uint32_t r = 0; r < pl.n_coded; ++r) {
+        z += pl.count[r];
+        cp.Z[r] = z;
+        cp.y[r] = (uint8_t)pl.code_len[r];
+      }
+      cp.k = z;
+      cp.sample_rank = sample_rank(d, z, n_s * 16u);
+      any_sampled |= cp.sample_rank != 0;
+      if (pl.n_coded > max_R) max_R = pl.n_coded;
+      for (int attempt = 0; attempt < 2; ++attempt) {
+        uint32_t t = 0;
+        while (t < chunk.n_templates && std::memcmp(&chunk.data[t * kParamWords], &cp, sizeof(cp)) != 0) ++t;
+        const uint32_t templates = t == chunk.n_templates ? t + 1 : chunk.n_templates;
+        if (templates * kParamWords + (chunk.n_clients + 1) * kRefWords > kUploadWords) {
+          send();  // no room: this client opens the next chunk (which always has room for one)
+          continue;
+        }
+        if (t == chunk.n_templates) {
+          std::memcpy(&chunk.data[t * kParamWords], &cp, sizeof(cp));
+          chunk.n_templates = templates;
+        }
+        uint32_t* ref = refs + chunk.n_clients * kRefWords;
+        const uint64_t up = reinterpret_cast<uint64_t>(d_updates[i]), sp = reinterpret_cast<uint64_t>(d_streams_out[i]);
+        ref[0] = (uint32_t)up;
+        ref[1] = (uint32_t)(up >> 32);
+        ref[2] = (uint32_t)sp;
+        ref[3] = (uint32_t)(sp >> 32);
+        ref[4] = client_ids[i];
+        ref[5] = t;
+        ++chunk.n_clients;
+        break;
+      }
     }
+    if (chunk.n_clients) send();
   }
   profile_mark(CVLC_STAGE_ENC_SETUP, false, stream);
 
