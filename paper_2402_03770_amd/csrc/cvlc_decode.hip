@@ -42,13 +42,13 @@ struct DecodeCtl {  // written by compact_lists
 };
 
 struct DecodeLayout {
-  size_t status, ctl, streams, desc, cdesc, item_start, table, total;
+  size_t status, ctl, stream_bad, desc, cdesc, item_start, table, total;
   uint32_t n_tiles, n_lists;
 };
 
 size_t align256(size_t v) { return (v + 255u) & ~(size_t)255u; }
 
-struct StreamArg {  // per-stream inputs, uploaded through kernel arguments
+struct StreamArg {  // per-stream inputs, passed as kernel arguments
   const uint32_t* words;
   uint64_t n_words;
   double weight;
@@ -63,7 +63,7 @@ DecodeLayout decode_layout(uint32_t d, uint32_t n) {
   size_t off = 0;
   L.status = off; off = align256(off + 256);
   L.ctl = off; off = align256(off + sizeof(DecodeCtl));
-  L.streams = off; off = align256(off + (size_t)n * sizeof(StreamArg));
+  L.stream_bad = off; off = align256(off + (size_t)n * sizeof(uint32_t));
   L.desc = off; off = align256(off + (size_t)L.n_lists * sizeof(ListDesc));
   L.cdesc = off; off = align256(off + (size_t)L.n_lists * sizeof(CompactDesc));
   L.item_start = off; off = align256(off + ((size_t)L.n_lists + 1) * sizeof(uint32_t));
@@ -72,21 +72,14 @@ DecodeLayout decode_layout(uint32_t d, uint32_t n) {
   return L;
 }
 
-constexpr uint32_t kUploadWords = 960;
-struct UploadChunk {
-  uint32_t n_words, dst_word;
-  uint32_t data[kUploadWords];
+// The streams' pointers, sizes and weights travel as kernel arguments of the
+// header pass (no pinned memory, no synchronisation), up to kParseStreams a launch.
+constexpr uint32_t kParseStreams = 112;
+struct ParseChunk {
+  uint32_t first, count, pad[2];
+  StreamArg args[kParseStreams];
 };
-
-// Workgroup 0 writes the chunk's words; all workgroups clear zero_n16 16-byte
-// pieces from `zero` on (the call's state that starts at zero, in the call's
-// first launch; a plain kernel, so that a caller may capture the call in a graph).
-__global__ __launch_bounds__(256) void upload_kernel(uint32_t* dst, UploadChunk c, uint4* zero, uint32_t zero_n16) {
-  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < zero_n16; i += gridDim.x * blockDim.x)
-    zero[i] = make_uint4(0u, 0u, 0u, 0u);
-  if (blockIdx.x == 0)
-    for (uint32_t i = threadIdx.x; i < c.n_words; i += blockDim.x) dst[c.dst_word + i] = c.data[i];
-}
+static_assert(sizeof(ParseChunk) <= 3800, "kernel arguments are limited to 4 KB");
 
 // Bits [bit, bit + W) of a little-endian word array, W <= 63.  Reads the three
 // words the field can touch; `n_words` bounds the reads.
@@ -118,10 +111,10 @@ __device__ __forceinline__ uint64_t wave_incl_scan_u64(uint64_t v) {
   return v;
 }
 
-__global__ __launch_bounds__(64) void parse_headers_kernel(const StreamArg* __restrict__ streams, ListDesc* descs,
-                                                           uint32_t d, uint32_t n, uint32_t* status) {
-  const uint32_t client = blockIdx.x, t = threadIdx.x;
-  const StreamArg sa = streams[client];
+__global__ __launch_bounds__(64) void parse_headers_kernel(ParseChunk chunk, ListDesc* descs, uint32_t d, uint32_t n,
+                                                           uint32_t* __restrict__ stream_bad) {
+  const uint32_t client = chunk.first + blockIdx.x, t = threadIdx.x;
+  const StreamArg sa = chunk.args[blockIdx.x];
   GlobalConstWordPtr w = (GlobalConstWordPtr)sa.words;
   ListDesc* out = descs + (size_t)client * kListsPerClient;
   bool ok = sa.n_words >= kGlobalHeaderWords;  // everything about `ok` is uniform over the wavefront
@@ -157,7 +150,7 @@ __global__ __launch_bounds__(64) void parse_headers_kernel(const StreamArg* __re
   const uint64_t total = first_payload + (((uint64_t)__shfl((uint32_t)(incl >> 32), 63, 64) << 32) | __shfl((uint32_t)incl, 63, 64));
   const uint64_t k = ((uint64_t)__shfl((uint32_t)(k_incl >> 32), 63, 64) << 32) | __shfl((uint32_t)k_incl, 63, 64);
   ok = ok && k <= d && total == g[7] && sa.n_words >= total;
-  if (!ok && t == 0) atomicOr(status, CVLC_DEV_STREAM);
+  if (t == 0) stream_bad[client] = ok ? 0u : 1u;  // gathered into the status word by the next kernel
   if (t < kListsPerClient) {
     ListDesc ld;
     ld.payload = nullptr; ld.weight = 0.0; ld.P = 0; ld.W = 0; ld.s = 0; ld.y = 0; ld.m = 0.0f; ld.step = 0.0f;
@@ -182,9 +175,16 @@ __global__ __launch_bounds__(64) void parse_headers_kernel(const StreamArg* __re
 // item_start is the exclusive prefix of their tile_table work items.
 __global__ __launch_bounds__(1024) void compact_lists_kernel(const ListDesc* __restrict__ descs, uint32_t n_lists,
                                                              CompactDesc* __restrict__ cdesc,
-                                                             uint32_t* __restrict__ item_start, DecodeCtl* ctl) {
+                                                             uint32_t* __restrict__ item_start, DecodeCtl* ctl,
+                                                             const uint32_t* __restrict__ stream_bad, uint32_t n,
+                                                             uint32_t* status) {
   __shared__ uint32_t scan_tmp[16];
   const uint32_t tid = threadIdx.x;
+  // the call's status word starts here: set if any stream failed its header checks
+  uint32_t any_bad = 0;
+  for (uint32_t i = tid; i < n; i += 1024) any_bad |= stream_bad[i];
+  any_bad = __syncthreads_or((int)any_bad) ? 1u : 0u;
+  if (tid == 0) *status = any_bad ? CVLC_DEV_STREAM : 0u;
   uint32_t lists_before = 0, items_before = 0;
   for (uint32_t base = 0; base < n_lists; base += 1024) {
     const uint32_t l = base + tid;
@@ -561,7 +561,7 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
   const DecodeLayout L = decode_layout(d, n < 1 ? 1 : n);
   char* base = static_cast<char*>(d_workspace);
   uint32_t* status = reinterpret_cast<uint32_t*>(base + L.status);
-  StreamArg* sargs = reinterpret_cast<StreamArg*>(base + L.streams);
+  uint32_t* stream_bad = reinterpret_cast<uint32_t*>(base + L.stream_bad);
   ListDesc* descs = reinterpret_cast<ListDesc*>(base + L.desc);
   CompactDesc* cdesc = reinterpret_cast<CompactDesc*>(base + L.cdesc);
   uint32_t* item_start = reinterpret_cast<uint32_t*>(base + L.item_start);
@@ -570,38 +570,25 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
   const uint32_t n_lists = n * kListsPerClient;
 
   profile_mark(CVLC_STAGE_DEC_SETUP, true, stream);
-  // the status word and the list counts start every call at zero (n = 0: no lists)
-  uint32_t zero_n16 = (uint32_t)(L.streams / 16u);
-  if (n > 0) {
-    constexpr uint32_t words_per = sizeof(StreamArg) / 4u;
-    const uint32_t per_chunk = kUploadWords / words_per;
-    UploadChunk chunk;
-    for (uint32_t first = 0; first < n; first += per_chunk) {
-      const uint32_t cnt = (n - first < per_chunk) ? n - first : per_chunk;
-      chunk.n_words = cnt * words_per;
-      chunk.dst_word = first * words_per;
-      for (uint32_t i = 0; i < cnt; ++i) {
-        StreamArg sa;
+  {
+    ParseChunk chunk;
+    chunk.pad[0] = chunk.pad[1] = 0;
+    for (uint32_t first = 0; first < n; first += kParseStreams) {
+      chunk.first = first;
+      chunk.count = (n - first < kParseStreams) ? n - first : kParseStreams;
+      for (uint32_t i = 0; i < chunk.count; ++i) {
+        StreamArg& sa = chunk.args[i];
         sa.words = static_cast<const uint32_t*>(d_streams[first + i]);
         sa.n_words = stream_bytes[first + i] / 4u;
         sa.weight = weights ? (double)weights[first + i] : 0.0;
         sa.has_weight = weights ? 1u : 0u;
         sa.pad = 0;
-        std::memcpy(&chunk.data[i * words_per], &sa, sizeof(sa));
       }
-      const uint32_t blocks = zero_n16 ? (zero_n16 + 1023u) / 1024u : 1u;
-      hipLaunchKernelGGL(upload_kernel, dim3(blocks < 512u ? blocks : 512u), dim3(256), 0, stream,
-                         reinterpret_cast<uint32_t*>(sargs), chunk, reinterpret_cast<uint4*>(status), zero_n16);
-      zero_n16 = 0;  // cleared by the first launch
+      hipLaunchKernelGGL(parse_headers_kernel, dim3(chunk.count), dim3(64), 0, stream, chunk, descs, d, n, stream_bad);
     }
-    hipLaunchKernelGGL(parse_headers_kernel, dim3(n), dim3(64), 0, stream, sargs, descs, d, n, status);
-    hipLaunchKernelGGL(compact_lists_kernel, dim3(1), dim3(1024), 0, stream, descs, n_lists, cdesc, item_start, ctl);
-  } else {
-    UploadChunk chunk;
-    chunk.n_words = 0;
-    chunk.dst_word = 0;
-    hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(sargs), chunk,
-                       reinterpret_cast<uint4*>(status), zero_n16);
+    // also for n = 0: writes the (empty) list counts and the status word
+    hipLaunchKernelGGL(compact_lists_kernel, dim3(1), dim3(1024), 0, stream, descs, n_lists, cdesc, item_start, ctl,
+                       stream_bad, n, status);
   }
   profile_mark(CVLC_STAGE_DEC_SETUP, false, stream);
   if (n > 0) {
