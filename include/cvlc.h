@@ -141,12 +141,39 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
                           const float* weights, float* d_out, uint32_t d, uint32_t flags,
                           void* d_workspace, size_t ws_bytes, void* hip_stream);
 
+/* Ranks at which Definition 1's power law is fitted: 1, 2, 4, ... (powers of two
+ * below d) and d itself, ascending.  Writes them to ranks_out (CVLC_FIT_RANKS_MAX
+ * entries, may be NULL) and returns how many there are (0 for d = 0). */
+#define CVLC_FIT_RANKS_MAX 32u
+uint32_t cvlc_fit_ranks(uint32_t d, uint32_t* ranks_out);
+
+/* Scratch bytes cvlc_fit_alpha needs for n_clients vectors (independent of d). */
+size_t cvlc_fit_workspace_bytes(uint32_t n_clients);
+
+/* GPU.  First step of Algorithm 1: the decay exponent alpha_i of Definition 1
+ * for each of n update vectors, |U{l}| ~ phi * l^alpha with U{l} the l-th
+ * largest magnitude.  alpha is the ordinary-least-squares slope of ln|U{l}| on
+ * ln l over the ranks of cvlc_fit_ranks(d), ranks whose magnitude is zero left
+ * out; fewer than two usable ranks give alpha = -1.  The magnitudes are exact
+ * order statistics of the whole vector (three counting passes over it).
+ *   d_updates[i]  host array of device pointers, each d fp32, 16-byte aligned
+ *   d_alpha_out   device, n doubles
+ *   d_keys_out    device or NULL: n * CVLC_FIT_RANKS_MAX words; word j of client
+ *                 i = fp32 bit pattern (sign cleared) of the magnitude at the
+ *                 j-th fitted rank, 0 beyond the last rank
+ *   d_workspace   device, 256-byte aligned, ws_bytes >= cvlc_fit_workspace_bytes(n)
+ * A NaN or Inf in a vector sets CVLC_DEV_NONFINITE in the workspace's status
+ * word (cvlc_device_status); that vector's outputs are then meaningless.
+ * Calls that share a workspace must not overlap in time. */
+int cvlc_fit_alpha(uint32_t n, const float* const* d_updates, uint32_t d, double* d_alpha_out,
+                   uint32_t* d_keys_out, void* d_workspace, size_t ws_bytes, void* hip_stream);
+
 /* Waits for hip_stream and copies the workspace's device status word to
  * *status_out (0 = clean, else CVLC_DEV_* bits). */
 int cvlc_device_status(const void* d_workspace, void* hip_stream, uint32_t* status_out);
 
 /* Profiling aid (not part of the hot path).  Between cvlc_profile_start and
- * cvlc_profile_stop every cvlc_encode_batch / cvlc_decode_aggregate call of this
+ * cvlc_profile_stop every cvlc_encode_batch / cvlc_decode_aggregate / cvlc_fit_alpha call of this
  * process brackets the stages selected in stage_mask (bit i = stage i) with a
  * pair of HIP events on the call's stream.  cvlc_profile_stop waits for those
  * events and returns, per stage, the summed elapsed milliseconds and the number
@@ -161,10 +188,11 @@ enum {
   CVLC_STAGE_ENC_CLASSIFY = 5, /* group counts and statistics                   */
   CVLC_STAGE_ENC_LAYOUT = 6,   /* prefix sums, headers, statistics block        */
   CVLC_STAGE_ENC_EMIT = 7,     /* quantise + pack                               */
-  CVLC_STAGE_DEC_SETUP = 8,    /* upload, header parsing, list numbering        */
+  CVLC_STAGE_DEC_SETUP = 8,    /* header parsing, list numbering                */
   CVLC_STAGE_DEC_TABLE = 9,    /* per-list tile boundaries                      */
   CVLC_STAGE_DEC_TILES = 10,   /* fused decode + accumulate                     */
-  CVLC_PROFILE_STAGES = 11
+  CVLC_STAGE_FIT_ALPHA = 11,   /* cvlc_fit_alpha, the whole call                */
+  CVLC_PROFILE_STAGES = 12
 };
 int cvlc_profile_start(uint32_t stage_mask);
 int cvlc_profile_stop(float* ms_per_stage, uint32_t* brackets_per_stage);

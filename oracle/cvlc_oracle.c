@@ -680,24 +680,41 @@ int64_t orc_unpack(const uint32_t* stream, uint64_t nwords, uint32_t d, uint32_t
   return k;
 }
 
-/* alpha of Definition 1: least-squares slope of ln|U{l}| against ln l at the
- * ranks l = 1, 2, 4, ... and l = d, skipping zero magnitudes. */
-int orc_fit_alpha(const float* U, uint32_t d, double* alpha_out) {
+/* The points of the fit of Definition 1's exponent: ranks l = 1, 2, 4, ... and
+ * l = d, ascending, with the fp32 bit pattern (sign cleared) of the l-th largest
+ * magnitude U{l} at each.  Both arrays hold up to 32 entries. */
+int orc_fit_points(const float* U, uint32_t d, uint32_t* ranks_out, uint32_t* keys_out, uint32_t* n_out) {
   uint32_t* order = (uint32_t*)malloc((size_t)d * sizeof(uint32_t));
   if (!order) return ORC_ERR_ARG;
   int rc = orc_rank(U, d, order);
   if (rc) { free(order); return rc; }
-  double sx = 0, sy = 0, sxx = 0, sxy = 0; int n = 0;
+  uint32_t n = 0;
   for (uint64_t l = 1;; l *= 2) {
     if (l > d) l = d;
-    double mag = fabs((double)U[order[l - 1]]);
-    if (mag > 0.0) {
-      double x = log((double)l), yv = log(mag);
-      sx += x; sy += yv; sxx += x * x; sxy += x * yv; ++n;
-    }
+    ranks_out[n] = (uint32_t)l;
+    keys_out[n] = f2u(U[order[l - 1]]) & 0x7FFFFFFFu;
+    ++n;
     if (l == d) break;
   }
   free(order);
+  *n_out = n;
+  return ORC_OK;
+}
+
+/* alpha of Definition 1: least-squares slope of ln|U{l}| against ln l at the
+ * ranks l = 1, 2, 4, ... and l = d, skipping zero magnitudes. */
+int orc_fit_alpha(const float* U, uint32_t d, double* alpha_out) {
+  uint32_t ranks[32], keys[32], np = 0;
+  int rc = orc_fit_points(U, d, ranks, keys, &np);
+  if (rc) return rc;
+  double sx = 0, sy = 0, sxx = 0, sxy = 0; int n = 0;
+  for (uint32_t j = 0; j < np; ++j) {
+    double mag = (double)u2f(keys[j]);
+    if (mag > 0.0) {
+      double x = log((double)ranks[j]), yv = log(mag);
+      sx += x; sy += yv; sxx += x * x; sxy += x * yv; ++n;
+    }
+  }
   if (n < 2) { *alpha_out = -1.0; return ORC_OK; }
   *alpha_out = ((double)n * sxy - sx * sy) / ((double)n * sxx - sx * sx);
   return ORC_OK;

@@ -84,6 +84,7 @@ def lib() -> C.CDLL:
         L.orc_unpack.argtypes = [u32p, C.c_uint64, C.c_uint32, u32p, u32p, u32p]
         L.orc_unpack.restype = C.c_int64
         L.orc_fit_alpha.argtypes = [f32p, C.c_uint32, C.POINTER(C.c_double)]
+        L.orc_fit_points.argtypes = [f32p, C.c_uint32, u32p, u32p, u32p]
         _lib = L
     return _lib
 
@@ -235,6 +236,15 @@ def unpack(stream: np.ndarray, d: int) -> Tuple[np.ndarray, np.ndarray, np.ndarr
     if k < 0:
         raise OracleError(int(k), "unpack")
     return pid[:k], cid[:k], seg[:k]
+
+
+def fit_points(U: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """(ranks, magnitude bit patterns) at which Definition 1's exponent is fitted."""
+    ranks = np.zeros(32, dtype=np.uint32)
+    keys = np.zeros(32, dtype=np.uint32)
+    n = C.c_uint32(0)
+    _check(lib().orc_fit_points(_f32(U), U.size, _u32(ranks), _u32(keys), C.byref(n)), "fit_points")
+    return ranks[: n.value].copy(), keys[: n.value].copy()
 
 
 def fit_alpha(U: np.ndarray) -> float:

@@ -14,6 +14,7 @@ MAX_CODED = 31
 STATS_STRIDE = 32
 DEV_NONFINITE, DEV_STREAM, DEV_INTERNAL = 1, 2, 4
 DECODE_ACCUMULATE = 1
+FIT_RANKS_MAX = 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcvlc.so")
@@ -87,6 +88,11 @@ def lib() -> C.CDLL:
         L.cvlc_decode_aggregate.argtypes = [C.c_uint32, C.POINTER(vp), szp, C.POINTER(C.c_float), vp, C.c_uint32,
                                             C.c_uint32, vp, C.c_size_t, vp]
         L.cvlc_device_status.argtypes = [vp, vp, u32p]
+        L.cvlc_fit_ranks.argtypes = [C.c_uint32, u32p]
+        L.cvlc_fit_ranks.restype = C.c_uint32
+        L.cvlc_fit_workspace_bytes.argtypes = [C.c_uint32]
+        L.cvlc_fit_workspace_bytes.restype = C.c_size_t
+        L.cvlc_fit_alpha.argtypes = [C.c_uint32, C.POINTER(vp), C.c_uint32, vp, vp, vp, C.c_size_t, vp]
         L.cvlc_profile_start.argtypes = [C.c_uint32]
         L.cvlc_profile_stop.argtypes = [C.POINTER(C.c_float), u32p]
         L.cvlc_status_string.argtypes = [C.c_int]
@@ -153,6 +159,17 @@ def decode_workspace_bytes(d: int, n_clients: int) -> int:
     return int(lib().cvlc_decode_workspace_bytes(d, n_clients))
 
 
+def fit_ranks(d: int) -> List[int]:
+    """cvlc_fit_ranks: the ranks at which cvlc_fit_alpha reads the magnitudes."""
+    out = (C.c_uint32 * FIT_RANKS_MAX)()
+    n = int(lib().cvlc_fit_ranks(d, out))
+    return [int(out[j]) for j in range(n)]
+
+
+def fit_workspace_bytes(n_clients: int) -> int:
+    return int(lib().cvlc_fit_workspace_bytes(n_clients))
+
+
 # ----------------------------------------------------------------------------- device side
 def new_workspace(n_bytes: int, device="cuda") -> torch.Tensor:
     return torch.empty(max(int(n_bytes), 256), dtype=torch.uint8, device=device)
@@ -205,6 +222,18 @@ def decode_aggregate(streams: Sequence[torch.Tensor], out: torch.Tensor, workspa
                                        workspace.numel(), _stream_handle()), "cvlc_decode_aggregate")
 
 
+def fit_alpha(updates: Sequence[torch.Tensor], alpha_out: torch.Tensor, workspace: torch.Tensor,
+              keys_out: Optional[torch.Tensor] = None) -> None:
+    """cvlc_fit_alpha on the current stream.  `alpha_out` is a float64 device tensor of n entries,
+    `keys_out` an optional int32 device tensor of n * FIT_RANKS_MAX entries."""
+    n = len(updates)
+    vp = C.c_void_p
+    upd = (vp * max(n, 1))(*[u.data_ptr() for u in updates])
+    d = updates[0].numel() if n else 0
+    _check(lib().cvlc_fit_alpha(n, upd, d, alpha_out.data_ptr(), keys_out.data_ptr() if keys_out is not None else None,
+                                workspace.data_ptr(), workspace.numel(), _stream_handle()), "cvlc_fit_alpha")
+
+
 def device_status(workspace: torch.Tensor) -> int:
     """cvlc_device_status: waits for the current stream, returns the CVLC_DEV_* bits."""
     st = C.c_uint32(0)
@@ -221,7 +250,7 @@ def read_stats(stats_out: torch.Tensor, client: int, n_coded: int) -> List[SegSt
 
 
 PROFILE_STAGES = ["enc_setup", "enc_sample", "enc_filter", "enc_refilter", "enc_select", "enc_classify",
-                  "enc_layout", "enc_emit", "dec_setup", "dec_table", "dec_tiles"]
+                  "enc_layout", "enc_emit", "dec_setup", "dec_table", "dec_tiles", "fit_alpha"]
 
 
 def profile_start(stages: Sequence[str] = tuple(PROFILE_STAGES)) -> None:

@@ -322,6 +322,86 @@ def test_non_finite_update_sets_status():
             orc.encode(U, p, 1, 0)
 
 
+# --------------------------------------------------------------------------- power-law exponent (Algorithm 1, first step)
+def gpu_fit_alpha(host_updates):
+    n = len(host_updates)
+    updates = [torch.from_numpy(u).to(DEV) for u in host_updates]
+    alpha = torch.full((n,), float("nan"), dtype=torch.float64, device=DEV)
+    keys = torch.full((n * cv.FIT_RANKS_MAX,), -1, dtype=torch.int32, device=DEV)
+    ws = cv.new_workspace(cv.fit_workspace_bytes(n), DEV)
+    ws.fill_(0xA5)  # the call must clear what it counts in
+    cv.fit_alpha(updates, alpha, ws, keys)
+    status = cv.device_status(ws)
+    return alpha.cpu().numpy(), keys.cpu().numpy().view(np.uint32).reshape(n, cv.FIT_RANKS_MAX), status
+
+
+def check_fit(host_updates):
+    """Magnitudes at the fitted ranks bit for bit; the slope to 1e-11 (fp64 on both
+    sides, but two implementations of log)."""
+    alpha, keys, status = gpu_fit_alpha(host_updates)
+    assert status == 0
+    for c, u in enumerate(host_updates):
+        ranks, ref_keys = orc.fit_points(u)
+        assert ranks.tolist() == cv.fit_ranks(u.size)
+        assert keys[c, : ranks.size].tolist() == ref_keys.tolist(), f"client {c}"
+        assert not keys[c, ranks.size:].any()
+        assert alpha[c] == pytest.approx(orc.fit_alpha(u), rel=1e-11, abs=1e-11), f"client {c}"
+    return alpha
+
+
+def test_fit_alpha_on_the_workload_distributions():
+    check_fit([syn.update_vector(1, 0)])
+    check_fit([syn.update_vector(2, c, d=300_001) for c in range(8)])
+    check_fit([syn.update_vector(3, c, d=1_000_003) for c in range(5)])
+    check_fit([syn.update_vector(4, c, d=250_000) for c in range(3)])
+
+
+@pytest.mark.parametrize("kind", ["all_equal", "all_equal_mixed_sign", "two_valued", "few_levels",
+                                  "zeros_and_denormals", "all_zero"])
+def test_fit_alpha_on_colliding_magnitudes(kind):
+    """Ranks that fall into one class at every radix level, zeros and denormals at the low ranks."""
+    check_fit([syn.tie_heavy_vector(kind, 70_001, seed=1)])
+    check_fit([syn.tie_heavy_vector(kind, 16_384, seed=3), syn.tie_heavy_vector(kind, 16_384, seed=4)])
+
+
+def test_fit_alpha_tiny_and_ragged_lengths():
+    rng = np.random.default_rng(11)
+    for d in (1, 2, 3, 4, 5, 7, 8, 63, 4095, 4096, 4097, 16_385, 65_539):
+        check_fit([(rng.standard_normal(d) * 10.0 ** rng.uniform(-6, 2, d)).astype(np.float32)])
+
+
+def test_fit_alpha_recovers_a_power_law_and_feeds_the_planner():
+    """Definition 1 in closed form: magnitudes l^alpha in shuffled order give alpha back;
+    Algorithm 1 run with the fitted exponent yields the plan the oracle's planner makes from it."""
+    d = 1 << 20
+    rng = np.random.default_rng(5)
+    vecs = []
+    for a in (-0.3, -0.6, -0.9):
+        mags = (np.arange(1, d + 1, dtype=np.float64) ** a).astype(np.float32)
+        vecs.append((mags * rng.choice([-1.0, 1.0], d)).astype(np.float32)[rng.permutation(d)])
+    alpha = check_fit(vecs)
+    assert np.allclose(alpha, [-0.3, -0.6, -0.9], atol=1e-3)
+    for a in alpha:
+        pg = cv.plan(d, d, n_coded=6, alpha=float(a))
+        po = orc.plan_alg1(d, d, 6, float(a))
+        assert pg.counts() == po.counts() and pg.code_lens() == po.code_len() and pg.total_bits == po.total_bits
+
+
+def test_fit_alpha_more_clients_than_one_upload_holds():
+    """600 short vectors: the pointer table travels in two launches, one workgroup per client."""
+    rng = np.random.default_rng(13)
+    check_fit([(rng.standard_t(3, 5000) * 1e-3).astype(np.float32) for _ in range(600)])
+
+
+def test_fit_alpha_flags_non_finite_input():
+    U = syn.update_vector(1, 0).copy()
+    U[777] = np.float32("inf")
+    _, _, status = gpu_fit_alpha([U])
+    assert status & cv.DEV_NONFINITE
+    with pytest.raises(orc.OracleError):
+        orc.fit_points(U)
+
+
 # --------------------------------------------------------------------------- full benchmark size
 def _parallel(fn, items, workers=12):
     with ThreadPoolExecutor(max_workers=workers) as ex:
@@ -350,6 +430,18 @@ def test_full_size_32_clients(cfg):
     ref = orc.decode_aggregate(ref_streams, d)
     tol = 1e-5 * abs_terms(ref_streams, d)
     assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= tol)
+
+
+def test_fit_alpha_full_size_32_clients():
+    """The benchmark's launch configuration of the exponent fit: 32 clients, d = 11.2M."""
+    w = syn.WORKLOADS[3]
+    host = _parallel(lambda c: syn.update_vector(3, c), range(w.n_clients), workers=8)
+    alpha, keys, status = gpu_fit_alpha(host)
+    assert status == 0
+    refs = _parallel(lambda c: (orc.fit_points(host[c]), orc.fit_alpha(host[c])), range(w.n_clients))
+    for c, ((ranks, ref_keys), ref_alpha) in enumerate(refs):
+        assert keys[c, : ranks.size].tolist() == ref_keys.tolist(), f"client {c}"
+        assert alpha[c] == pytest.approx(ref_alpha, rel=1e-11, abs=1e-11)
 
 
 # --------------------------------------------------------------------------- vectors the oracle cannot sort in test time

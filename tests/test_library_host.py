@@ -102,3 +102,25 @@ def test_argument_errors_are_returned_before_any_launch():
     assert lib.cvlc_decode_aggregate(1, streams, sizes, None, None, 1000, 0, vp(ws), dws, None) == -1
     assert lib.cvlc_decode_aggregate(1, streams, sizes, None, vp(0x3000), 1000, 0, vp(ws), dws - 1, None) == -4
     assert cv.status_string(-4) == "buffer too small"
+
+
+def test_fit_ranks_and_argument_errors():
+    """The ranks of the power-law fit (doubling ranks, then d) and cvlc_fit_alpha's host-side checks."""
+    for d in (1, 2, 3, 4, 5, 1000, 65536, 11_200_000, 2**31 - 1):
+        want = [1 << j for j in range(32) if (1 << j) < d] + [d]
+        assert cv.fit_ranks(d) == want and len(want) <= cv.FIT_RANKS_MAX
+    assert cv.lib().cvlc_fit_ranks(0, None) == 0
+    assert cv.lib().cvlc_fit_ranks(1000, None) == 11
+    lib = cv.lib()
+    vp = C.c_void_p
+    ws_bytes = cv.fit_workspace_bytes(2)
+    assert ws_bytes > cv.fit_workspace_bytes(1) > 0
+    ptrs = (vp * 2)(0x1000, 0x2000)
+    call = lambda n, p, d, a, w, wsz: lib.cvlc_fit_alpha(n, p, d, vp(a), None, vp(w), wsz, None)
+    assert call(0, ptrs, 1000, 0x3000, 0x10000, ws_bytes) == -1
+    assert call(2, ptrs, 0, 0x3000, 0x10000, ws_bytes) == -1
+    assert call(2, ptrs, 1000, None, 0x10000, ws_bytes) == -1
+    assert call(2, ptrs, 1000, 0x3000, 0x10008, ws_bytes) == -1     # workspace not 256-byte aligned
+    assert call(2, ptrs, 1000, 0x3000, 0x10000, ws_bytes - 1) == -4
+    assert call(2, (vp * 2)(0x1000, 0x2004), 1000, 0x3000, 0x10000, ws_bytes) == -1  # vector not 16-byte aligned
+    assert call(2, (vp * 2)(0x1000, None), 1000, 0x3000, 0x10000, ws_bytes) == -1

@@ -476,3 +476,31 @@ def test_alpha_fit_recovers_a_power_law():
         rng = np.random.default_rng(1)
         U = (mags * rng.choice([-1.0, 1.0], d)).astype(np.float32)[rng.permutation(d)]
         assert abs(orc.fit_alpha(U) - alpha) < 1e-3
+
+
+def test_fit_points_are_order_statistics_at_doubling_ranks():
+    """Definition 1 speaks of the l-th largest magnitude: the points of the fit are a
+    library sort's entries at l = 1, 2, 4, ... and l = d, whatever d's residue."""
+    rng = np.random.default_rng(7)
+    for d in (1, 2, 3, 5, 64, 1000, 4097, 65536):
+        U = (rng.standard_t(3, d) * 10.0 ** rng.uniform(-5, -2, d)).astype(np.float32)
+        U[rng.integers(0, d, d // 7)] = 0.0                       # zeros and ties are ordinary input
+        U[rng.integers(0, d, d // 9)] = np.float32(1e-3)
+        ranks, keys = orc.fit_points(U)
+        want = [1 << j for j in range(32) if (1 << j) < d] + [d]
+        assert ranks.tolist() == want
+        desc = np.sort(np.abs(U).view(np.uint32))[::-1]
+        assert keys.tolist() == [int(desc[l - 1]) for l in want]
+
+
+def test_alpha_fit_special_cases():
+    """Closed forms: a constant vector has slope 0; two usable points give the slope
+    between them; fewer than two usable points give the stated default -1."""
+    assert orc.fit_alpha(np.full(1000, -2.5, dtype=np.float32)) == pytest.approx(0.0, abs=1e-15)
+    U = np.array([8.0, -2.0], dtype=np.float32)                   # ranks 1 and 2
+    assert orc.fit_alpha(U) == pytest.approx(math.log(2.0 / 8.0) / math.log(2.0), rel=1e-14)
+    assert orc.fit_alpha(np.array([3.0], dtype=np.float32)) == -1.0
+    assert orc.fit_alpha(np.zeros(100, dtype=np.float32)) == -1.0
+    U = np.zeros(100, dtype=np.float32)
+    U[17] = 4.0; U[3] = -1.0                                      # ranks 1, 2 usable, 4 ... 100 are zeros
+    assert orc.fit_alpha(U) == pytest.approx(-2.0, rel=1e-14)
