@@ -172,6 +172,18 @@ def main() -> int:
 
     t_enc = timed(encode, args.steps)
     t_dec = timed(decode, args.steps)
+
+    # outside the step: Algorithm 1's exponent fit, which a planner runs once per round before encoding
+    fit_ws = cv.new_workspace(cv.fit_workspace_bytes(n), dev)
+    alpha = torch.empty(n, dtype=torch.float64, device=dev)
+
+    def fit():
+        cv.fit_alpha(updates, alpha, fit_ws)
+
+    for _ in range(args.warmup):
+        fit()
+    t_fit = timed(fit, args.steps)
+    assert cv.device_status(fit_ws) == 0
     assert cv.device_status(enc_ws) == 0 and cv.device_status(dec_ws) == 0
 
     if args.stages:
@@ -202,6 +214,9 @@ def main() -> int:
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(),
                      "launch_ms": filter_ms},
     }
+    result["fit_alpha"] = {"ms": t_fit * 1e3, "g_coords_s": n * d / t_fit / 1e9, "algorithmic_gb": 4.0 * n * d / 1e9,
+                           "hbm_frac": 4.0 * n * d / t_fit / 1e9 / HBM_PEAK_GBS, "passes_over_input": 3,
+                           "in_step": False}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(host, w, d)
     print(json.dumps(result))

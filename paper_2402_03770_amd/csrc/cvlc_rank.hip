@@ -300,16 +300,22 @@ __global__ __launch_bounds__(kRankBlock) void rank_walk_kernel(RankCtl* __restri
   // level 3: s_prefix holds the keys
   if (keys_out && threadIdx.x < kRanksMax)
     keys_out[(size_t)blockIdx.x * kRanksMax + threadIdx.x] = threadIdx.x < ranks.n ? s_prefix[threadIdx.x] : 0u;
+  // ordinary least squares of ln(magnitude) on ln(rank): the logarithms side by side,
+  // the sums by one thread with the ranks in ascending order
+  __shared__ double s_x[kRanksMax], s_y[kRanksMax];
+  if (threadIdx.x < ranks.n) {
+    const double mag = (double)__uint_as_float(s_prefix[threadIdx.x]);
+    s_x[threadIdx.x] = log((double)ranks.rank[threadIdx.x]);
+    s_y[threadIdx.x] = mag > 0.0 ? log(mag) : 0.0;
+  }
+  __syncthreads();
   if (threadIdx.x == 0) {
-    // ordinary least squares of ln(magnitude) on ln(rank), ranks taken in ascending order
     double sx = 0.0, sy = 0.0, sxx = 0.0, sxy = 0.0;
     uint32_t m = 0;
     for (uint32_t j = 0; j < ranks.n; ++j) {
-      const double mag = (double)__uint_as_float(s_prefix[j]);
-      if (mag > 0.0) {
-        const double x = log((double)ranks.rank[j]), y = log(mag);
-        sx += x; sy += y; sxx += x * x; sxy += x * y; ++m;
-      }
+      if (s_prefix[j] == 0u) continue;  // a zero magnitude has no logarithm
+      const double x = s_x[j], y = s_y[j];
+      sx += x; sy += y; sxx += x * x; sxy += x * y; ++m;
     }
     alpha_out[blockIdx.x] = m < 2 ? -1.0 : ((double)m * sxy - sx * sy) / ((double)m * sxx - sx * sx);
   }
