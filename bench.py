@@ -9,6 +9,7 @@ line; `value` counts the input coordinates (clients x d) a step accounts for.
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -133,7 +134,7 @@ def main() -> int:
     enc_ws = cv.new_workspace(cv.encode_workspace_bytes(d, n), dev)
     dec_ws = cv.new_workspace(cv.decode_workspace_bytes(d, n), dev)
     out = torch.empty(d, dtype=torch.float32, device=dev)
-    stats = torch.zeros(n * cv.STATS_STRIDE * 24, dtype=torch.uint8, device=dev)   # cvlc_seg_stats_t is 24 bytes
+    stats = torch.zeros(n * cv.STATS_STRIDE * ctypes.sizeof(cv.SegStats), dtype=torch.uint8, device=dev)
     ids = list(range(n))
     stream_bytes = sum(p.stream_bytes for p in plans)
 

@@ -63,12 +63,18 @@ typedef struct cvlc_plan_t {
 
 /* Per-group statistics returned by the encoder: entries 0..R-1 are the coded
  * groups, entry R the sparsified tail (min = max = 0 there; its sumsq is the
- * sparsification error energy of Proposition 1's first term). */
+ * sparsification error energy of Proposition 1's first term).
+ * errsq is the error energy of this draw after quantisation and scaling,
+ * sum over the group of (xtilde/B - x)^2 with xtilde the centroid value the
+ * parameter server will read: the left side of Lemma 1.  It is filled for the
+ * coded groups only when CVLC_ENCODE_ERROR_STATS is set (else 0); the tail is
+ * dropped whole, so its errsq always equals its sumsq. */
 typedef struct cvlc_seg_stats_t {
   float min, max;
   double sumsq;
   uint32_t count;
   uint32_t reserved;
+  double errsq;
 } cvlc_seg_stats_t;
 
 /* s = ceil(log2 d), at least 1 (Sec. IV-C, below Eq. (2)). */
@@ -96,6 +102,18 @@ uint64_t cvlc_plan_total_bits(const cvlc_plan_t* plan);
 /* CPU.  gamma of Eq. (5) for the plan under exponent alpha. */
 double cvlc_plan_gamma(const cvlc_plan_t* plan, double alpha);
 
+/* CPU.  Scale factor for the next round (footnote to Proposition 1: the exact
+ * B is max_r Q(P_r, y_r) + 1, taken from the previous round's plan), with PQ's
+ * Q(P, y) = P / (2^y - 1)^2 of the appendix case study; raw 32-bit and empty
+ * groups contribute 0.  Returns 1 for a NULL plan. */
+double cvlc_plan_next_scale(const cvlc_plan_t* plan);
+
+/* CPU.  ||Uhat - U||^2 / ||U||^2 of one encoded vector, the quantity that
+ * Propositions 1 and 2 bound by gamma, from a HOST copy of that client's
+ * statistics entries (n_coded groups, then the tail) written by an encode with
+ * CVLC_ENCODE_ERROR_STATS.  0 for an all-zero vector. */
+double cvlc_stats_gamma(const cvlc_seg_stats_t* stats, uint32_t n_coded);
+
 /* Bytes a stream buffer must hold for this plan (= total_bits / 8). */
 size_t cvlc_stream_capacity(const cvlc_plan_t* plan);
 
@@ -114,17 +132,21 @@ size_t cvlc_decode_workspace_bytes(uint32_t d, uint32_t n_clients);
  *                    least capacities[i] >= cvlc_stream_capacity(&plans[i]) bytes
  *   d_workspace      device, 256-byte aligned, ws_bytes >= cvlc_encode_workspace_bytes(d, n)
  *   d_stats_out      device or NULL: n * CVLC_STATS_STRIDE cvlc_seg_stats_t
+ *   flags            CVLC_ENCODE_ERROR_STATS: also measure every coded group's
+ *                    error energy (errsq; needs d_stats_out, else CVLC_ERR_ARG);
+ *                    the stream does not depend on it
  * The stream is bit-identical for identical (update, plan, seed, client id).
  * Calls that share a workspace must not overlap in time. */
+#define CVLC_ENCODE_ERROR_STATS 1u
 int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* d_updates,
                       uint64_t seed, const uint32_t* client_ids, void* const* d_streams_out,
                       const size_t* capacities, void* d_workspace, size_t ws_bytes,
-                      cvlc_seg_stats_t* d_stats_out, void* hip_stream);
+                      cvlc_seg_stats_t* d_stats_out, uint32_t flags, void* hip_stream);
 
 /* GPU.  One client; same as cvlc_encode_batch with n = 1. */
 int cvlc_encode(const cvlc_plan_t* plan, const float* d_update, uint64_t seed, uint32_t client_id,
                 void* d_stream_out, size_t capacity, void* d_workspace, size_t ws_bytes,
-                cvlc_seg_stats_t* d_stats_out, void* hip_stream);
+                cvlc_seg_stats_t* d_stats_out, uint32_t flags, void* hip_stream);
 
 /* GPU.  Parameter-server side (Sec. III step 3 with the scaling of Sec. IV-B):
  * d_out[j] = sum_i w_i * xhat_{i,j}, xhat the centroid value stored for

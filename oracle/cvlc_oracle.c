@@ -78,6 +78,9 @@ typedef struct {
   double sumsq;   /* sum of squares of the group's original values            */
   uint32_t count;
   uint32_t pad;
+  double errsq;   /* sum over the group of (xtilde/B - x)^2: the left side of */
+                  /* Lemma 1 for this draw; the tail is dropped whole, so its */
+                  /* errsq equals its sumsq                                    */
 } orc_seg_stats;
 
 /* ------------------------------------------------------------------------- */
@@ -564,18 +567,22 @@ int orc_encode(const float* U, const orc_plan* p, uint64_t seed, uint32_t client
     if (P > 0 && !isfinite(M - m)) { free(order); return ORC_ERR_NONFINITE; }
     uint32_t* hdr = words_out + ORC_GLOBAL_HEADER_WORDS + ORC_SEG_HEADER_WORDS * r;
     hdr[0] = y; hdr[1] = P; hdr[2] = f2u(m); hdr[3] = f2u(M);
-    if (stats_out) {
-      stats_out[r].min = m; stats_out[r].max = M; stats_out[r].sumsq = sumsq;
-      stats_out[r].count = P; stats_out[r].pad = 0;
-    }
     uint32_t* seg_words = words_out + payload_word;
+    double inv_B = 1.0 / (double)p->B; /* the scaling operation of Sec. IV-B: Uhat = Utilde / B */
+    double errsq = 0.0;
     for (uint32_t e = 0; e < P; ++e) {
       uint32_t i = members[e];
       uint32_t cid = orc_quantise(U[i], m, M, y, orc_u24(seed, client, i));
+      double err = (double)orc_dequantise(cid, m, M, y) * inv_B - (double)U[i];
+      errsq += err * err;
       uint64_t record = (uint64_t)i | ((uint64_t)cid << s);
       put_bits(seg_words, (uint64_t)e * W, record, W);
       if (seg_out) seg_out[i] = r + 1;
       if (cid_out) cid_out[i] = cid;
+    }
+    if (stats_out) {
+      stats_out[r].min = m; stats_out[r].max = M; stats_out[r].sumsq = sumsq;
+      stats_out[r].count = P; stats_out[r].pad = 0; stats_out[r].errsq = errsq;
     }
     payload_word += seg_payload_words(P, W);
     l += P;
@@ -584,7 +591,7 @@ int orc_encode(const float* U, const orc_plan* p, uint64_t seed, uint32_t client
     double sumsq = 0.0;
     for (uint64_t t = l; t < d; ++t) { double x = U[order[t]]; sumsq += x * x; }
     stats_out[R].min = 0.0f; stats_out[R].max = 0.0f; stats_out[R].sumsq = sumsq;
-    stats_out[R].count = (uint32_t)(d - l); stats_out[R].pad = 0;
+    stats_out[R].count = (uint32_t)(d - l); stats_out[R].pad = 0; stats_out[R].errsq = sumsq;
   }
   free(order);
   return ORC_OK;
@@ -678,6 +685,29 @@ int64_t orc_unpack(const uint32_t* stream, uint64_t nwords, uint32_t d, uint32_t
     }
   }
   return k;
+}
+
+/* Scale factor for the next round (footnote to Proposition 1): max over the
+ * coded groups of Q(P_r, y_r), plus 1, with PQ's quantisation error
+ * Q(P, y) = P / (2^y - 1)^2 (appendix case study); a raw 32-bit group has no
+ * quantisation error. */
+double orc_next_scale(const orc_plan* p) {
+  double worst = 0.0;
+  for (uint32_t r = 0; r < p->R; ++r) {
+    if (p->y[r] == 32 || p->P[r] == 0) continue;
+    double levels = (double)(((uint64_t)1 << p->y[r]) - 1u);
+    double Q = (double)p->P[r] / (levels * levels);
+    if (Q > worst) worst = Q;
+  }
+  return worst + 1.0;
+}
+
+/* ||Uhat - U||^2 / ||U||^2 of one encoded vector from its statistics block (R
+ * coded groups, then the tail): the quantity Propositions 1 and 2 bound by gamma. */
+double orc_empirical_gamma(const orc_seg_stats* stats, uint32_t R) {
+  double err = 0.0, all = 0.0;
+  for (uint32_t r = 0; r <= R; ++r) { err += stats[r].errsq; all += stats[r].sumsq; }
+  return all > 0.0 ? err / all : 0.0;
 }
 
 /* The points of the fit of Definition 1's exponent: ranks l = 1, 2, 4, ... and

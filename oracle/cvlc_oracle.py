@@ -41,7 +41,7 @@ class Plan(C.Structure):
 
 class SegStats(C.Structure):
     _fields_ = [("min", C.c_float), ("max", C.c_float), ("sumsq", C.c_double),
-                ("count", C.c_uint32), ("pad", C.c_uint32)]
+                ("count", C.c_uint32), ("pad", C.c_uint32), ("errsq", C.c_double)]
 
 
 class OracleError(RuntimeError):
@@ -84,6 +84,10 @@ def lib() -> C.CDLL:
         L.orc_unpack.argtypes = [u32p, C.c_uint64, C.c_uint32, u32p, u32p, u32p]
         L.orc_unpack.restype = C.c_int64
         L.orc_fit_alpha.argtypes = [f32p, C.c_uint32, C.POINTER(C.c_double)]
+        L.orc_next_scale.argtypes = [C.POINTER(Plan)]
+        L.orc_next_scale.restype = C.c_double
+        L.orc_empirical_gamma.argtypes = [C.POINTER(SegStats), C.c_uint32]
+        L.orc_empirical_gamma.restype = C.c_double
         L.orc_fit_points.argtypes = [f32p, C.c_uint32, u32p, u32p, u32p]
         _lib = L
     return _lib
@@ -236,6 +240,17 @@ def unpack(stream: np.ndarray, d: int) -> Tuple[np.ndarray, np.ndarray, np.ndarr
     if k < 0:
         raise OracleError(int(k), "unpack")
     return pid[:k], cid[:k], seg[:k]
+
+
+def next_scale(plan: Plan) -> float:
+    """B for the next round: max_r Q(P_r, y_r) + 1 (footnote to Proposition 1)."""
+    return float(lib().orc_next_scale(C.byref(plan)))
+
+
+def empirical_gamma(stats: Sequence[SegStats], R: int) -> float:
+    """||Uhat - U||^2 / ||U||^2 from an encode's statistics block."""
+    arr = (SegStats * (R + 1))(*stats[: R + 1])
+    return float(lib().orc_empirical_gamma(arr, R))
 
 
 def fit_points(U: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:

@@ -52,6 +52,7 @@ struct GroupInfo {
   uint32_t payload[32];  // first stream word of the group's records
   uint32_t P[32], W[32], y[32];
   float m[32], inv[32];  // smallest value and reciprocal centroid spacing
+  float step[32];        // centroid spacing, as the decoder derives it from the header
 };
 
 struct EncodeLayout {
@@ -1301,6 +1302,7 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
     if (stats_out) {
       cvlc_seg_stats_t* st = stats_out + (size_t)client * kStatsStride + r;
       st->min = m; st->max = M; st->sumsq = ctl->seg_sumsq[r]; st->count = P; st->reserved = 0;
+      st->errsq = 0.0;  // the pack kernel adds the group's error energy when asked to
     }
     GroupInfo* gi = ws.group_info + client;
     float step, inv;
@@ -1311,6 +1313,7 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
     gi->y[r] = p.y[r];
     gi->m[r] = m;
     gi->inv[r] = inv;
+    gi->step[r] = step;
   }
   if (tid == 32) {
     stream[0] = kMagic;
@@ -1326,6 +1329,7 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
       for (uint32_t w = 0; w < kWideWaves; ++w) tail += s_tail[w];
       cvlc_seg_stats_t* st = stats_out + (size_t)client * kStatsStride + R;
       st->min = 0.0f; st->max = 0.0f; st->sumsq = tail + ctl->seg_sumsq[R]; st->count = ws.d - p.k; st->reserved = 0;
+      st->errsq = st->sumsq;  // dropped whole
     }
   }
 }
@@ -1377,7 +1381,7 @@ struct alignas(16) EmitGroup {  // per (chunk, group)
   uint32_t W, y;
   float m, inv;
   uint32_t stage_bit;    // bit of record `first` in the workgroup's staged image of the stream
-  uint32_t pad;
+  float step;            // centroid spacing (only read when the error energy is measured)
 };
 
 // One workgroup per chunk of 4096 candidates, one wavefront per span.  Every
@@ -1387,9 +1391,15 @@ struct alignas(16) EmitGroup {  // per (chunk, group)
 // covers.  The image is then written out: a group's first and last word can be
 // shared with a neighbouring chunk and are OR-ed into the (cleared) stream, all
 // others are stored whole.
+// ERR: every record also adds (xtilde / B - x)^2 to its group's error energy in
+// the statistics block (Lemma 1's left side for this draw), xtilde being the
+// centroid value the decoder will compute from the header.
+template <bool ERR>
 __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams* __restrict__ params,
-                                                          ClientCtl* __restrict__ ctls, Workspace ws, uint64_t seed) {
+                                                          ClientCtl* __restrict__ ctls, Workspace ws, uint64_t seed,
+                                                          cvlc_seg_stats_t* __restrict__ stats_out) {
   __shared__ Thresholds thr;
+  __shared__ double s_err[ERR ? kEmitWaves : 1][32];  // per wavefront, per group
   __shared__ uint32_t s_stage[kStageWords];
   __shared__ uint32_t s_wrun[kEmitWaves][32];      // per wavefront, per group: record number of its next member
   __shared__ EmitGroup s_grp[32];                  // what a record of the group needs, read as two 16-byte pieces
@@ -1411,7 +1421,7 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
 
   load_thresholds(thr, ctl, R);
   uint32_t my_P = 0, my_W = 0, my_y = 0;
-  float my_m = 0.0f, my_inv = 0.0f;
+  float my_m = 0.0f, my_inv = 0.0f, my_step = 0.0f;
   if (tid < 32 && tid < R) {
     const GroupInfo* gi = ws.group_info + client;
     my_P = gi->P[tid];
@@ -1419,8 +1429,11 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
     my_y = gi->y[tid];
     my_m = gi->m[tid];
     my_inv = gi->inv[tid];
+    my_step = gi->step[tid];
     s_payload[tid] = gi->payload[tid];
   }
+  const double inv_B = ERR ? 1.0 / (double)p.B : 0.0;  // the scaling operation of Sec. IV-B
+  if (ERR && lane < 32) s_err[wave][lane] = 0.0;       // touched by this wavefront only until the end
   for (uint32_t c = blockIdx.x; c * kChunkSpans < n_spans; c += gridDim.x) {
   __syncthreads();  // the chunk before is written out
   {  // every wavefront: the record numbers its span starts at
@@ -1460,7 +1473,7 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
     eg.m = my_m;
     eg.inv = my_inv;
     eg.stage_bit = (incl - nwords) * 32u + bit_in_word;  // bit of record `first` in the staged image
-    eg.pad = 0;
+    eg.step = my_step;
     s_grp[r] = eg;
   }
   __syncthreads();
@@ -1497,6 +1510,12 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
           const uint32_t u24 = philox_word0(pid[j], client_id, k0, k1) >> 8;
           cid = quantise(__uint_as_float(v[j]), eg.m, eg.inv, y, u24);
         }
+        if (ERR) {
+          const float x = __uint_as_float(v[j]);
+          const float xt = y == 32 ? x : __fmaf_rn((float)cid, eg.step, eg.m);
+          const double err = (double)xt * inv_B - (double)x;
+          atomicAdd(&s_err[wave][g], err * err);
+        }
         const uint64_t record = (uint64_t)pid[j] | ((uint64_t)cid << sbits);
         // a chunk's run of a group is at most 4096 records of at most 63 bits: 32 bits hold the offset
         const uint32_t bit = eg.stage_bit + (e - eg.first) * W;
@@ -1524,6 +1543,14 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
     }
   }
   }  // chunks
+  if (ERR) {
+    __syncthreads();
+    if (tid < R) {
+      double sum = 0.0;
+      for (uint32_t w = 0; w < kEmitWaves; ++w) sum += s_err[w][tid];
+      if (sum != 0.0) atomicAdd(&stats_out[(size_t)client * kStatsStride + tid].errsq, sum);
+    }
+  }
 }
 
 // ------------------------------------------------------------------ host side
@@ -1587,10 +1614,13 @@ size_t cvlc_encode_workspace_bytes(uint32_t d, uint32_t n_clients) {
 
 int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* d_updates, uint64_t seed,
                       const uint32_t* client_ids, void* const* d_streams_out, const size_t* capacities,
-                      void* d_workspace, size_t ws_bytes, cvlc_seg_stats_t* d_stats_out, void* hip_stream) {
+                      void* d_workspace, size_t ws_bytes, cvlc_seg_stats_t* d_stats_out, uint32_t flags,
+                      void* hip_stream) {
   using namespace cvlc;
   int rc = validate_batch(n, plans, d_updates, client_ids, d_streams_out, capacities, d_workspace, ws_bytes);
   if (rc) return rc;
+  if (flags & ~CVLC_ENCODE_ERROR_STATS) return CVLC_ERR_ARG;
+  if ((flags & CVLC_ENCODE_ERROR_STATS) && !d_stats_out) return CVLC_ERR_ARG;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const uint32_t d = plans[0].d;
   const EncodeLayout L = encode_layout(d, n);
@@ -1743,19 +1773,24 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
     uint32_t g_emit = (768u + n - 1) / n;
     const uint32_t max_chunks = (L.max_spans + kChunkSpans - 1) / kChunkSpans;
     if (g_emit > max_chunks) g_emit = max_chunks;
-    hipLaunchKernelGGL(emit_kernel, dim3(g_emit, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws, seed);
+    if (flags & CVLC_ENCODE_ERROR_STATS)
+      hipLaunchKernelGGL(emit_kernel<true>, dim3(g_emit, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws, seed,
+                         d_stats_out);
+    else
+      hipLaunchKernelGGL(emit_kernel<false>, dim3(g_emit, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws, seed,
+                         d_stats_out);
   }
   return hip_check(hipGetLastError());
 }
 
 int cvlc_encode(const cvlc_plan_t* plan, const float* d_update, uint64_t seed, uint32_t client_id,
                 void* d_stream_out, size_t capacity, void* d_workspace, size_t ws_bytes,
-                cvlc_seg_stats_t* d_stats_out, void* hip_stream) {
+                cvlc_seg_stats_t* d_stats_out, uint32_t flags, void* hip_stream) {
   if (!plan) return CVLC_ERR_ARG;
   const float* updates[1] = {d_update};
   void* streams[1] = {d_stream_out};
   return cvlc_encode_batch(1, plan, updates, seed, &client_id, streams, &capacity, d_workspace, ws_bytes,
-                           d_stats_out, hip_stream);
+                           d_stats_out, flags, hip_stream);
 }
 
 int cvlc_device_status(const void* d_workspace, void* hip_stream, uint32_t* status_out) {

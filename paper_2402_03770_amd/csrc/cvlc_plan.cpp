@@ -268,6 +268,31 @@ double cvlc_plan_gamma(const cvlc_plan_t* p, double alpha) {
   return gamma_integer(p->d, p->n_coded, p->count, p->code_len, alpha, (double)p->B);
 }
 
+double cvlc_plan_next_scale(const cvlc_plan_t* plan) {
+  double worst = 0.0;
+  if (plan) {
+    const uint32_t R = plan->n_coded < CVLC_MAX_CODED ? plan->n_coded : CVLC_MAX_CODED;
+    for (uint32_t r = 0; r < R; ++r) {
+      const uint32_t y = plan->code_len[r];
+      if (y == 0 || y >= 32 || plan->count[r] == 0) continue;  // raw values carry no quantisation error
+      const double top = (double)((1ull << y) - 1ull);
+      const double Q = (double)plan->count[r] / (top * top);
+      if (Q > worst) worst = Q;
+    }
+  }
+  return worst + 1.0;
+}
+
+double cvlc_stats_gamma(const cvlc_seg_stats_t* stats, uint32_t n_coded) {
+  if (!stats || n_coded > CVLC_MAX_CODED) return 0.0;
+  double err = 0.0, all = 0.0;
+  for (uint32_t r = 0; r <= n_coded; ++r) {
+    err += stats[r].errsq;
+    all += stats[r].sumsq;
+  }
+  return all > 0.0 ? err / all : 0.0;
+}
+
 size_t cvlc_stream_capacity(const cvlc_plan_t* p) { return p ? (size_t)(p->total_bits / 8u) : 0; }
 
 int cvlc_plan(uint32_t d, uint64_t budget_bits, uint32_t n_coded, const uint32_t* code_len,

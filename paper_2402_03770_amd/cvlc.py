@@ -14,6 +14,7 @@ MAX_CODED = 31
 STATS_STRIDE = 32
 DEV_NONFINITE, DEV_STREAM, DEV_INTERNAL = 1, 2, 4
 DECODE_ACCUMULATE = 1
+ENCODE_ERROR_STATS = 1
 FIT_RANKS_MAX = 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -46,7 +47,7 @@ class Plan(C.Structure):
 class SegStats(C.Structure):
     """cvlc_seg_stats_t"""
     _fields_ = [("min", C.c_float), ("max", C.c_float), ("sumsq", C.c_double),
-                ("count", C.c_uint32), ("reserved", C.c_uint32)]
+                ("count", C.c_uint32), ("reserved", C.c_uint32), ("errsq", C.c_double)]
 
 
 class CvlcError(RuntimeError):
@@ -83,8 +84,13 @@ def lib() -> C.CDLL:
         L.cvlc_decode_workspace_bytes.argtypes = [C.c_uint32, C.c_uint32]
         L.cvlc_decode_workspace_bytes.restype = C.c_size_t
         L.cvlc_encode_batch.argtypes = [C.c_uint32, C.POINTER(Plan), C.POINTER(vp), C.c_uint64, u32p, C.POINTER(vp),
-                                        szp, vp, C.c_size_t, vp, vp]
-        L.cvlc_encode.argtypes = [C.POINTER(Plan), vp, C.c_uint64, C.c_uint32, vp, C.c_size_t, vp, C.c_size_t, vp, vp]
+                                        szp, vp, C.c_size_t, vp, C.c_uint32, vp]
+        L.cvlc_encode.argtypes = [C.POINTER(Plan), vp, C.c_uint64, C.c_uint32, vp, C.c_size_t, vp, C.c_size_t, vp,
+                                  C.c_uint32, vp]
+        L.cvlc_plan_next_scale.argtypes = [C.POINTER(Plan)]
+        L.cvlc_plan_next_scale.restype = C.c_double
+        L.cvlc_stats_gamma.argtypes = [C.POINTER(SegStats), C.c_uint32]
+        L.cvlc_stats_gamma.restype = C.c_double
         L.cvlc_decode_aggregate.argtypes = [C.c_uint32, C.POINTER(vp), szp, C.POINTER(C.c_float), vp, C.c_uint32,
                                             C.c_uint32, vp, C.c_size_t, vp]
         L.cvlc_device_status.argtypes = [vp, vp, u32p]
@@ -147,6 +153,17 @@ def plan_gamma(p: Plan, alpha: float) -> float:
     return float(lib().cvlc_plan_gamma(C.byref(p), alpha))
 
 
+def plan_next_scale(p: Plan) -> float:
+    """cvlc_plan_next_scale: B for the next round from this round's plan."""
+    return float(lib().cvlc_plan_next_scale(C.byref(p)))
+
+
+def stats_gamma(stats: Sequence[SegStats], n_coded: int) -> float:
+    """cvlc_stats_gamma over one client's entries as read_stats returns them."""
+    arr = (SegStats * (n_coded + 1))(*stats[: n_coded + 1])
+    return float(lib().cvlc_stats_gamma(arr, n_coded))
+
+
 def stream_capacity(p: Plan) -> int:
     return int(lib().cvlc_stream_capacity(C.byref(p)))
 
@@ -181,10 +198,10 @@ def new_stream_buffer(p: Plan, device="cuda") -> torch.Tensor:
 
 def encode_batch(plans: Sequence[Plan], updates: Sequence[torch.Tensor], seed: int, client_ids: Sequence[int],
                  streams_out: Sequence[torch.Tensor], workspace: torch.Tensor,
-                 stats_out: Optional[torch.Tensor] = None) -> None:
+                 stats_out: Optional[torch.Tensor] = None, error_stats: bool = False) -> None:
     """cvlc_encode_batch on the current stream.  `streams_out[i]` is an int32/uint8 device
     tensor of at least plan.stream_bytes; `stats_out` an optional uint8 device tensor of
-    n * STATS_STRIDE * sizeof(SegStats) bytes."""
+    n * STATS_STRIDE * sizeof(SegStats) bytes; `error_stats` sets CVLC_ENCODE_ERROR_STATS."""
     n = len(plans)
     vp = C.c_void_p
     plan_arr = (Plan * n)(*plans)
@@ -194,16 +211,16 @@ def encode_batch(plans: Sequence[Plan], updates: Sequence[torch.Tensor], seed: i
     caps = (C.c_size_t * n)(*[s.numel() * s.element_size() for s in streams_out])
     _check(lib().cvlc_encode_batch(n, plan_arr, upd, seed, ids, outs, caps, workspace.data_ptr(),
                                    workspace.numel(), stats_out.data_ptr() if stats_out is not None else None,
-                                   _stream_handle()), "cvlc_encode_batch")
+                                   ENCODE_ERROR_STATS if error_stats else 0, _stream_handle()), "cvlc_encode_batch")
 
 
 def encode(p: Plan, update: torch.Tensor, seed: int, client_id: int, stream_out: torch.Tensor,
-           workspace: torch.Tensor, stats_out: Optional[torch.Tensor] = None) -> None:
+           workspace: torch.Tensor, stats_out: Optional[torch.Tensor] = None, error_stats: bool = False) -> None:
     """cvlc_encode on the current stream."""
     _check(lib().cvlc_encode(C.byref(p), update.data_ptr(), seed, client_id, stream_out.data_ptr(),
                              stream_out.numel() * stream_out.element_size(), workspace.data_ptr(), workspace.numel(),
-                             stats_out.data_ptr() if stats_out is not None else None, _stream_handle()),
-           "cvlc_encode")
+                             stats_out.data_ptr() if stats_out is not None else None,
+                             ENCODE_ERROR_STATS if error_stats else 0, _stream_handle()), "cvlc_encode")
 
 
 def decode_aggregate(streams: Sequence[torch.Tensor], out: torch.Tensor, workspace: torch.Tensor,

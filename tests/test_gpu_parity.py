@@ -27,7 +27,7 @@ def to_lib_plan(po: orc.Plan) -> cv.Plan:
     return cv.plan_manual(po.d, po.code_len(), po.counts(), B=float(po.B))
 
 
-def gpu_encode(host_updates, oracle_plans, seed, client_ids, want_stats=True):
+def gpu_encode(host_updates, oracle_plans, seed, client_ids, want_stats=True, error_stats=False):
     n = len(host_updates)
     d = host_updates[0].size
     plans = [to_lib_plan(p) for p in oracle_plans]
@@ -37,7 +37,7 @@ def gpu_encode(host_updates, oracle_plans, seed, client_ids, want_stats=True):
         s.fill_(-1)  # the encoder must overwrite every word
     ws = cv.new_workspace(cv.encode_workspace_bytes(d, n), DEV)
     stats = torch.zeros(n * cv.STATS_STRIDE * C.sizeof(cv.SegStats), dtype=torch.uint8, device=DEV) if want_stats else None
-    cv.encode_batch(plans, updates, seed, client_ids, streams, ws, stats)
+    cv.encode_batch(plans, updates, seed, client_ids, streams, ws, stats, error_stats=error_stats)
     status = cv.device_status(ws)
     words = [s.cpu().numpy().view(np.uint32)[: p.stream_bytes // 4] for s, p in zip(streams, plans)]
     st = [cv.read_stats(stats, c, plans[c].n_coded) for c in range(n)] if want_stats else None
@@ -52,12 +52,16 @@ def assert_stream_equal(got, ref, what=""):
                              f"{got[bad[0]]:#x} != {ref[bad[0]]:#x}")
 
 
-def assert_stats_close(got, ref, R):
+def assert_stats_close(got, ref, R, error_stats=False):
     for r in range(R + 1):
         assert got[r].count == ref[r].count, r
         assert np.float32(got[r].min).view(np.uint32) == np.float32(ref[r].min).view(np.uint32), r
         assert np.float32(got[r].max).view(np.uint32) == np.float32(ref[r].max).view(np.uint32), r
         assert got[r].sumsq == pytest.approx(ref[r].sumsq, rel=1e-6, abs=1e-300), r
+        if error_stats or r == R:   # every term is computed alike on both sides; only the order of the fp64 sum differs
+            assert got[r].errsq == pytest.approx(ref[r].errsq, rel=1e-6, abs=1e-300), r
+        else:
+            assert got[r].errsq == 0.0, r
 
 
 def check_encode(host_updates, oracle_plans, seed, client_ids):
@@ -320,6 +324,40 @@ def test_non_finite_update_sets_status():
         assert status & cv.DEV_NONFINITE
         with pytest.raises(orc.OracleError):
             orc.encode(U, p, 1, 0)
+
+
+# --------------------------------------------------------------------------- error energy, scale factor across rounds
+def test_error_statistics_and_the_scale_factor_carried_across_rounds():
+    """Round t uses B from round t-1's plan (footnote to Proposition 1); the encoder reports the
+    error energy of quantisation + scaling per group (Lemma 1's left side), from which the
+    empirical gamma follows; the parameter server divides by B."""
+    d, n, seed = 300_007, 3, 99
+    host = [syn.update_vector(3, c, d=d) for c in range(n)]
+    host[2] = syn.tie_heavy_vector("few_levels", d, seed=2)
+    B = 1.0
+    for rnd in range(2):
+        plans = [orc.plan_manual(d, [32, 10, 4, 2, 1], [500, 3000, 6000, 9000, 12000], B=B),
+                 orc.plan_alg1(d, d, 6, -0.6, B=B),
+                 orc.plan_manual(d, [5, 1], [10_000, 20_001], B=B)]
+        words, stats, status, streams = gpu_encode(host, plans, seed + rnd, [4, 5, 6], error_stats=True)
+        assert status == 0
+        plain, plain_stats, _, _ = gpu_encode(host, plans, seed + rnd, [4, 5, 6])
+        for c in range(n):
+            ref = orc.encode(host[c], plans[c], seed + rnd, 4 + c)
+            assert_stream_equal(words[c], ref.words, f"round {rnd} client {c}")
+            assert_stream_equal(plain[c], ref.words, f"round {rnd} client {c}, no error statistics")
+            assert_stats_close(stats[c], ref.stats, plans[c].R, error_stats=True)
+            assert_stats_close(plain_stats[c], ref.stats, plans[c].R)
+            assert cv.stats_gamma(stats[c], plans[c].R) == pytest.approx(orc.empirical_gamma(ref.stats, plans[c].R), rel=1e-6)
+        got, status = gpu_decode(streams, d)
+        assert status == 0
+        ref_words = [orc.encode(host[c], plans[c], seed + rnd, 4 + c).words for c in range(n)]
+        ref = orc.decode_aggregate(ref_words, d)
+        assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= 1e-5 * abs_terms(ref_words, d))
+        nxt = [cv.plan_next_scale(to_lib_plan(p)) for p in plans]
+        assert nxt == [orc.next_scale(p) for p in plans]
+        B = float(np.float32(max(nxt)))   # one factor for the round, as the paper's constant B
+    assert B > 1.0
 
 
 # --------------------------------------------------------------------------- power-law exponent (Algorithm 1, first step)

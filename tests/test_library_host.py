@@ -84,7 +84,7 @@ def test_argument_errors_are_returned_before_any_launch():
     good_ws = cv.encode_workspace_bytes(1000, 1)
     assert good_ws > 0 and cv.encode_workspace_bytes(1000, 2) > good_ws
     upd, out, ws = 0x1000, 0x2000, 0x10000
-    call = lambda u, o, cap, w, wsz: lib.cvlc_encode(C.byref(p), vp(u), 1, 0, vp(o), cap, vp(w), wsz, None, None)
+    call = lambda u, o, cap, w, wsz: lib.cvlc_encode(C.byref(p), vp(u), 1, 0, vp(o), cap, vp(w), wsz, None, 0, None)
     assert call(None, out, 4096, ws, good_ws) == -1
     assert call(upd + 4, out, 4096, ws, good_ws) == -1          # update not 16-byte aligned
     assert call(upd, out + 2, 4096, ws, good_ws) == -1          # stream not 4-byte aligned
@@ -93,7 +93,9 @@ def test_argument_errors_are_returned_before_any_launch():
     assert call(upd, out, 4096, ws + 8, good_ws) == -1          # workspace not 256-byte aligned
     bad = cv.Plan.from_buffer_copy(p)
     bad.total_bits += 32
-    assert lib.cvlc_encode(C.byref(bad), vp(upd), 1, 0, vp(out), 4096, vp(ws), good_ws, None, None) == -2
+    assert lib.cvlc_encode(C.byref(bad), vp(upd), 1, 0, vp(out), 4096, vp(ws), good_ws, None, 0, None) == -2
+    assert lib.cvlc_encode(C.byref(p), vp(upd), 1, 0, vp(out), 4096, vp(ws), good_ws, None, 1, None) == -1   # error statistics need a statistics block
+    assert lib.cvlc_encode(C.byref(p), vp(upd), 1, 0, vp(out), 4096, vp(ws), good_ws, vp(0x4000), 2, None) == -1  # unknown flag
     streams = (vp * 1)(out)
     sizes = (C.c_size_t * 1)(16)
     dws = cv.decode_workspace_bytes(1000, 1)
@@ -124,3 +126,19 @@ def test_fit_ranks_and_argument_errors():
     assert call(2, ptrs, 1000, 0x3000, 0x10000, ws_bytes - 1) == -4
     assert call(2, (vp * 2)(0x1000, 0x2004), 1000, 0x3000, 0x10000, ws_bytes) == -1  # vector not 16-byte aligned
     assert call(2, (vp * 2)(0x1000, None), 1000, 0x3000, 0x10000, ws_bytes) == -1
+
+
+def test_next_scale_and_stats_gamma_match_the_oracle():
+    rng = np.random.default_rng(23)
+    for _ in range(40):
+        d = int(rng.integers(1000, 2_000_000))
+        R = int(rng.integers(1, 9))
+        y = sorted(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 32], size=R).tolist(), reverse=True)
+        budget = int(d * rng.uniform(0.2, 2.0)) + 256 + 200 * R
+        pg, po = cv.plan(d, budget, code_len=y), orc.plan_budget(d, budget, y)
+        assert cv.plan_next_scale(pg) == orc.next_scale(po)
+        gs = [cv.SegStats(0.0, 0.0, float(rng.uniform(0, 5)), 1, 0, float(rng.uniform(0, 1))) for _ in range(R + 1)]
+        os_ = [orc.SegStats(g.min, g.max, g.sumsq, g.count, 0, g.errsq) for g in gs]
+        assert cv.stats_gamma(gs, R) == orc.empirical_gamma(os_, R)
+    assert cv.stats_gamma([cv.SegStats()] * 2, 1) == 0.0
+    assert C.sizeof(cv.SegStats) == C.sizeof(orc.SegStats) == 32

@@ -504,3 +504,88 @@ def test_alpha_fit_special_cases():
     U = np.zeros(100, dtype=np.float32)
     U[17] = 4.0; U[3] = -1.0                                      # ranks 1, 2 usable, 4 ... 100 are zeros
     assert orc.fit_alpha(U) == pytest.approx(-2.0, rel=1e-14)
+
+
+def _records(U, plan, enc):
+    """(group index 0-based, position, reconstructed value) of every record of an encoded
+    stream, through the parser and the single-value dequantiser."""
+    pid, cid, seg = orc.unpack(enc.words, plan.d)
+    xhat = np.array([orc.dequantise(int(c), enc.stats[int(g) - 1].min, enc.stats[int(g) - 1].max,
+                                    plan.code_len()[int(g) - 1]) for c, g in zip(cid, seg)], dtype=np.float32)
+    return seg.astype(np.int64) - 1, pid.astype(np.int64), xhat
+
+
+@pytest.mark.parametrize("B", [1.0, 2.5])
+def test_error_energy_is_the_squared_distance_to_the_scaled_reconstruction(B):
+    """Sec. IV-B: Uhat = Utilde / B.  The error energy the encoder reports per group equals
+    the squared distance between the group's values and their reconstructions read back
+    from the stream; the tail is dropped whole."""
+    d = 6000
+    U = syn.update_vector(3, 1, d=d)
+    plan = orc.plan_manual(d, [32, 9, 3, 1], [40, 300, 900, 1500], B=B)
+    enc = orc.encode(U, plan, 77, 5)
+    grp, pid, xhat = _records(U, plan, enc)
+    x = U.astype(np.float64)
+    for r in range(plan.R):
+        sel = grp == r
+        want = float(np.sum((xhat[sel].astype(np.float64) / B - x[pid[sel]]) ** 2))
+        assert enc.stats[r].errsq == pytest.approx(want, rel=1e-12, abs=1e-300), r
+    assert enc.stats[0].errsq == pytest.approx((1.0 - 1.0 / B) ** 2 * enc.stats[0].sumsq, rel=1e-12)  # raw group
+    kept = np.zeros(d, dtype=bool)
+    kept[pid] = True
+    assert enc.stats[plan.R].errsq == enc.stats[plan.R].sumsq == pytest.approx(float(np.sum(x[~kept] ** 2)), rel=1e-12)
+
+
+def test_empirical_gamma_is_the_relative_error_of_the_decoded_vector():
+    """The left side of Propositions 1 and 2: ||Uhat - U||^2 / ||U||^2, with Uhat the
+    parameter server's reconstruction (B = 1, one client: the decoder returns it exactly)."""
+    for cfg, d in ((1, 5000), (3, 20000)):
+        U = syn.update_vector(cfg, 2, d=d)
+        plan = orc.plan_alg1(d, 2 * d, 4, -0.6)
+        enc = orc.encode(U, plan, 3, 2)
+        Uhat = orc.decode_aggregate([enc.words], d).astype(np.float64)
+        x = U.astype(np.float64)
+        want = float(np.sum((Uhat - x) ** 2) / np.sum(x ** 2))
+        assert orc.empirical_gamma(enc.stats, plan.R) == pytest.approx(want, rel=1e-10)
+        assert 0.0 < want < 1.0
+    zeros = np.zeros(100, dtype=np.float32)
+    enc = orc.encode(zeros, orc.plan_manual(100, [4], [10]), 1, 0)
+    assert orc.empirical_gamma(enc.stats, 1) == 0.0
+
+
+def test_error_energy_obeys_lemma_1():
+    """Lemma 1 per group: E||Uhat - Ubar||^2 <= (Q + (B-1)^2) / B^2 ||Ubar||^2 with PQ's
+    Q(P, y) = P / (2^y - 1)^2, and step (a) of its proof: the expectation splits into the
+    quantisation error over B^2 plus (1 - 1/B)^2 ||Ubar||^2 (the rounding is unbiased)."""
+    d, B, seeds = 3000, 3.0, 300
+    U = syn.update_vector(1, 0, d=d)
+    ys, Ps = [6, 3, 1], [200, 500, 800]
+    scaled = orc.plan_manual(d, ys, Ps, B=B)
+    plain = orc.plan_manual(d, ys, Ps, B=1.0)
+    err_b = np.zeros((seeds, 3))
+    err_1 = np.zeros((seeds, 3))
+    for s in range(seeds):
+        eb, e1 = orc.encode(U, scaled, 1000 + s, 0), orc.encode(U, plain, 1000 + s, 0)
+        err_b[s] = [eb.stats[r].errsq for r in range(3)]
+        err_1[s] = [e1.stats[r].errsq for r in range(3)]
+    energy = np.array([eb.stats[r].sumsq for r in range(3)])
+    for r in range(3):
+        Q = Ps[r] / (2 ** ys[r] - 1) ** 2
+        assert err_b[:, r].max() <= (Q + (B - 1) ** 2) / B ** 2 * energy[r]
+        split = err_1[:, r].mean() / B ** 2 + (1 - 1 / B) ** 2 * energy[r]
+        spread = err_b[:, r].std() / math.sqrt(seeds)
+        assert abs(err_b[:, r].mean() - split) <= 5 * spread + 1e-9 * split
+
+
+def test_next_round_scale_factor():
+    """Footnote to Proposition 1: B = max_r Q(P_r, y_r) + 1, with PQ's Q of the appendix."""
+    p = orc.plan_manual(11_200_000, [16, 8, 6, 4, 3, 2, 1], [19995, 24994, 26660, 28564, 29622, 30761, 31992])
+    assert orc.next_scale(p) == pytest.approx(31992 / 1.0 + 1.0, rel=1e-15)          # the 1-bit group dominates
+    p = orc.plan_manual(100_000, [8, 4], [100, 28564])
+    assert orc.next_scale(p) == pytest.approx(28564 / 225.0 + 1.0, rel=1e-15)
+    assert orc.next_scale(orc.plan_manual(1000, [32], [100])) == 1.0                  # raw values: no quantisation error
+    assert orc.next_scale(orc.plan_manual(1000, [8, 2], [0, 0])) == 1.0
+    for R in (1, 5):                                                                  # Proposition 1's condition B > (Q+1)/2
+        q = orc.plan_alg1(500_000, 400_000, R, -0.7)
+        Bn = orc.next_scale(q)
+        assert all(Bn > (P / (2 ** y - 1) ** 2 + 1) / 2 for P, y in zip(q.counts(), q.code_len()) if y != 32)
