@@ -70,7 +70,7 @@ typedef struct {
   uint32_t P[ORC_MAX_R]; /* number of updates in group r                       */
   uint64_t total_bits;   /* exact stream size in bits                          */
   float B;               /* scale factor of Lemma 1                            */
-  uint32_t quant;        /* 0 = PQ                                             */
+  uint32_t quant;        /* 0 = PQ, 1 = QSGD                                   */
 } orc_plan;
 
 typedef struct {
@@ -152,11 +152,12 @@ int orc_plan_validate(const orc_plan* p) {
   if (p->d < 1 || p->d > 0x7FFFFFFFu) return ORC_ERR_PLAN;
   if (p->R > ORC_MAX_R) return ORC_ERR_PLAN;
   if (p->s != orc_s_bits(p->d)) return ORC_ERR_PLAN;
-  if (p->quant != 0) return ORC_ERR_PLAN;
+  if (p->quant > 1) return ORC_ERR_PLAN;
   if (!(p->B > 0.0f) || !isfinite(p->B)) return ORC_ERR_PLAN;
   uint64_t k = 0;
   for (uint32_t r = 0; r < p->R; ++r) {
     if (!code_len_ok(p->y[r])) return ORC_ERR_PLAN;
+    if (p->quant == 1 && p->y[r] < 2) return ORC_ERR_PLAN; /* a sign bit and at least one level bit */
     if (r > 0 && p->y[r] > p->y[r - 1]) return ORC_ERR_PLAN;
     k += p->P[r];
   }
@@ -254,8 +255,17 @@ static double energy_share(double a, double b, double d, double beta) {
 
 /* gamma of Eq. (5) for real-valued group sizes P_r with y_r = u/P_r - s, or,
  * when y_int is given, for those integer code lengths. */
+/* QSGD's quantisation error (appendix case study): min(P/s^2, sqrt(P)/s), with
+ * s the number of levels above zero that y bits hold beside the sign. */
+static double q_qsgd(double P, double y) {
+  if (!(y > 1.0)) return INFINITY;
+  double levels = exp2(y - 1.0) - 1.0;
+  double a = P / (levels * levels), b = sqrt(P) / levels;
+  return a < b ? a : b;
+}
+
 static double gamma_eq5(uint32_t d, uint32_t R, const double* P, const uint32_t* y_int, double u,
-                        uint32_t s, double beta, double B) {
+                        uint32_t s, double beta, double B, uint32_t quant) {
   double invB2 = 1.0 / (B * B);
   double invBc = 1.0 - 1.0 / B; /* 1/B + 1/B_c = 1 */
   double k = 0.0;
@@ -266,7 +276,8 @@ static double gamma_eq5(uint32_t d, uint32_t R, const double* P, const uint32_t*
     double Z = Zprev + P[r];
     if (P[r] > 0.0) {
       double y = y_int ? (double)y_int[r] : u / P[r] - (double)s;
-      g += (q_pq(P[r], y) * invB2 + invBc * invBc) * energy_share(Z, Zprev, (double)d, beta);
+      double Q = quant == 1 ? q_qsgd(P[r], y) : q_pq(P[r], y);
+      g += (Q * invB2 + invBc * invBc) * energy_share(Z, Zprev, (double)d, beta);
     }
     Zprev = Z;
   }
@@ -276,7 +287,7 @@ static double gamma_eq5(uint32_t d, uint32_t R, const double* P, const uint32_t*
 double orc_gamma(const orc_plan* p, double alpha) {
   double P[ORC_MAX_R];
   for (uint32_t r = 0; r < p->R; ++r) P[r] = (double)p->P[r];
-  return gamma_eq5(p->d, p->R, P, p->y, 0.0, p->s, 2.0 * alpha + 1.0, (double)p->B);
+  return gamma_eq5(p->d, p->R, P, p->y, 0.0, p->s, 2.0 * alpha + 1.0, (double)p->B, p->quant);
 }
 
 /* f(X, P_{r-1}, P_r) of Eq. (6) as a function of P_r, with Z_{r-2} and X fixed. */
@@ -379,7 +390,7 @@ int orc_plan_alg1(uint32_t d, uint64_t budget_bits, uint32_t R, double alpha, fl
     double Pd[ORC_MAX_R];
     integerise(d, R, P, u, s, y, Pi);
     for (uint32_t r = 0; r < R; ++r) Pd[r] = (double)Pi[r];
-    double gam = gamma_eq5(d, R, Pd, y, u, s, beta, (double)B);
+    double gam = gamma_eq5(d, R, Pd, y, u, s, beta, (double)B, 0);
     if (gam < best) {
       best = gam;
       for (uint32_t r = 0; r < R; ++r) { out->y[r] = y[r]; out->P[r] = Pi[r]; }
@@ -489,6 +500,104 @@ float orc_dequantise(uint32_t cid, float m, float M, uint32_t y) {
 }
 
 /* ------------------------------------------------------------------------- */
+/* QSGD (Alistarh et al., NeurIPS'17) as the second quantiser of Sec. IV-D:   */
+/* the magnitude relative to the group's l2-norm is rounded at random to one  */
+/* of the levels 0, 1/s, ..., 1 (up with probability equal to the fractional  */
+/* position, so the value is unbiased) and sent with the sign.  The y bits of */
+/* a record's code hold the sign in the top bit and the level below it, so    */
+/* there are s = 2^(y-1) - 1 levels above zero.                               */
+/* ------------------------------------------------------------------------- */
+
+/* The norm that goes into the header must come out the same whatever order a
+ * machine adds the squares in, so it is defined without floating-point sums:
+ * S = sum of x_i^2 as an exact number, and the norm is the smallest fp32 value
+ * n with n*n >= S (so no |x_i| exceeds it).  S is kept as a fixed-point number
+ * in units of 2^-298 (the square of the smallest denormal) in 32-bit limbs. */
+#define QN_LIMBS 20 /* bits 0 .. 639: squares reach bit 2*(127+149)+48 = 600, 2^31 of them 631 */
+
+static void qn_add_square(uint64_t* limb, float x) {
+  uint32_t b = f2u(x) & 0x7FFFFFFFu;
+  uint32_t e = b >> 23, frac = b & 0x7FFFFFu;
+  uint64_t m = e ? (frac | 0x800000u) : frac; /* |x| = m * 2^(q-149), q below */
+  uint32_t q = e ? e - 1 : 0;
+  uint64_t sq = m * m;                         /* < 2^48, worth sq * 2^(2q) units */
+  uint32_t off = 2 * q, word = off / 32, sh = off % 32;
+  limb[word] += (sq << sh) & 0xFFFFFFFFu;      /* the three 32-bit pieces of sq << sh (< 2^80) */
+  limb[word + 1] += (sq >> (32 - sh)) & 0xFFFFFFFFu;
+  limb[word + 2] += sh ? (sq >> (64 - sh)) : 0;
+}
+
+static void qn_carry(uint64_t* limb) { /* every limb below 2^32 afterwards */
+  uint64_t carry = 0;
+  for (int i = 0; i < QN_LIMBS; ++i) {
+    uint64_t v = limb[i] + carry;
+    limb[i] = v & 0xFFFFFFFFu;
+    carry = v >> 32;
+  }
+}
+
+/* n*n >= S for the fp32 bit pattern `key` (finite, sign clear), S in carried limbs. */
+static int qn_square_reaches(uint32_t key, const uint64_t* S) {
+  uint64_t sq[QN_LIMBS];
+  memset(sq, 0, sizeof(sq));
+  qn_add_square(sq, u2f(key));
+  qn_carry(sq);
+  for (int i = QN_LIMBS - 1; i >= 0; --i)
+    if (sq[i] != S[i]) return sq[i] > S[i];
+  return 1;
+}
+
+int orc_qsgd_norm(const float* x, uint32_t n, float* norm_out) {
+  uint64_t S[QN_LIMBS];
+  memset(S, 0, sizeof(S));
+  for (uint32_t i = 0; i < n; ++i) {
+    if (!isfinite(x[i])) return ORC_ERR_NONFINITE;
+    qn_add_square(S, x[i]);
+  }
+  qn_carry(S);
+  if (!qn_square_reaches(0x7F7FFFFFu, S)) return ORC_ERR_NONFINITE; /* the norm overflows fp32 */
+  uint32_t lo = 0, hi = 0x7F7FFFFFu; /* smallest key whose square reaches S; squares grow with the key */
+  while (lo < hi) {
+    uint32_t mid = lo + (hi - lo) / 2;
+    if (qn_square_reaches(mid, S)) hi = mid; else lo = mid + 1;
+  }
+  *norm_out = u2f(lo);
+  return ORC_OK;
+}
+
+static uint32_t qsgd_levels(uint32_t y) { return ((uint32_t)1 << (y - 1)) - 1u; }
+
+/* CID of x in a group with l2-norm `norm` at y bits: position t = |x| * (s/norm)
+ * in fp32 (s/norm one correctly rounded division per group), lower level
+ * floor(t), one up with probability t - floor(t) resolved against the 24-bit
+ * uniform; the sign bit sits above the level.  y = 32 keeps the raw bits. */
+uint32_t orc_quantise_qsgd(float x, float norm, uint32_t y, uint32_t u24) {
+  if (y == 32) return f2u(x);
+  float s = (float)qsgd_levels(y);
+  float inv = norm > 0.0f ? s / norm : 0.0f;
+  float t = fabsf(x) * inv;
+  if (!(t > 0.0f)) t = 0.0f;
+  if (t > s) t = s;
+  float fl = floorf(t);
+  uint32_t level = (uint32_t)fl;
+  float p = t - fl;
+  uint32_t thr = (uint32_t)(p * 16777216.0f);
+  level += (u24 < thr) ? 1u : 0u;
+  if (level > qsgd_levels(y)) level = qsgd_levels(y);
+  return level | ((f2u(x) >> 31) << (y - 1));
+}
+
+/* Value of a CID: sign * level * (norm/s), the spacing one correctly rounded
+ * division, the product one rounding. */
+float orc_dequantise_qsgd(uint32_t cid, float norm, uint32_t y) {
+  if (y == 32) return u2f(cid);
+  float s = (float)qsgd_levels(y);
+  float step = norm > 0.0f ? norm / s : 0.0f;
+  float v = (float)(cid & qsgd_levels(y)) * step;
+  return ((cid >> (y - 1)) & 1u) ? -v : v;
+}
+
+/* ------------------------------------------------------------------------- */
 /* bit stream                                                                 */
 /* ------------------------------------------------------------------------- */
 
@@ -565,15 +674,28 @@ int orc_encode(const float* U, const orc_plan* p, uint64_t seed, uint32_t client
       sumsq += (double)x * (double)x;
     }
     if (P > 0 && !isfinite(M - m)) { free(order); return ORC_ERR_NONFINITE; }
+    float norm = 0.0f;
+    if (p->quant == 1) { /* centroid distribution of QSGD: the group's l2-norm (Sec. IV-D) */
+      float* vals = (float*)malloc((size_t)(P ? P : 1) * sizeof(float));
+      if (!vals) { free(order); return ORC_ERR_ARG; }
+      for (uint32_t e = 0; e < P; ++e) vals[e] = U[members[e]];
+      rc = orc_qsgd_norm(vals, P, &norm);
+      free(vals);
+      if (rc) { free(order); return rc; }
+    }
     uint32_t* hdr = words_out + ORC_GLOBAL_HEADER_WORDS + ORC_SEG_HEADER_WORDS * r;
-    hdr[0] = y; hdr[1] = P; hdr[2] = f2u(m); hdr[3] = f2u(M);
+    hdr[0] = y; hdr[1] = P;
+    if (p->quant == 1) { hdr[2] = f2u(norm); hdr[3] = 0; }
+    else { hdr[2] = f2u(m); hdr[3] = f2u(M); }
     uint32_t* seg_words = words_out + payload_word;
     double inv_B = 1.0 / (double)p->B; /* the scaling operation of Sec. IV-B: Uhat = Utilde / B */
     double errsq = 0.0;
     for (uint32_t e = 0; e < P; ++e) {
       uint32_t i = members[e];
-      uint32_t cid = orc_quantise(U[i], m, M, y, orc_u24(seed, client, i));
-      double err = (double)orc_dequantise(cid, m, M, y) * inv_B - (double)U[i];
+      uint32_t u24 = orc_u24(seed, client, i);
+      uint32_t cid = p->quant == 1 ? orc_quantise_qsgd(U[i], norm, y, u24) : orc_quantise(U[i], m, M, y, u24);
+      float xt = p->quant == 1 ? orc_dequantise_qsgd(cid, norm, y) : orc_dequantise(cid, m, M, y);
+      double err = (double)xt * inv_B - (double)U[i];
       errsq += err * err;
       uint64_t record = (uint64_t)i | ((uint64_t)cid << s);
       put_bits(seg_words, (uint64_t)e * W, record, W);
@@ -599,7 +721,7 @@ int orc_encode(const float* U, const orc_plan* p, uint64_t seed, uint32_t client
 
 /* Parse and check one stream's headers. */
 typedef struct {
-  uint32_t d, R, s, client;
+  uint32_t d, R, s, client, quant;
   float B;
   uint32_t y[ORC_MAX_R], P[ORC_MAX_R];
   float m[ORC_MAX_R], M[ORC_MAX_R];
@@ -609,7 +731,8 @@ typedef struct {
 
 static int parse_header(const uint32_t* w, uint64_t nwords, uint32_t d_expected, orc_header* h) {
   if (nwords < ORC_GLOBAL_HEADER_WORDS) return ORC_ERR_STREAM;
-  if (w[0] != ORC_MAGIC || (w[1] & 0xFFFFu) != ORC_VERSION || (w[1] >> 16) != 0) return ORC_ERR_STREAM;
+  if (w[0] != ORC_MAGIC || (w[1] & 0xFFFFu) != ORC_VERSION || (w[1] >> 16) > 1) return ORC_ERR_STREAM;
+  h->quant = w[1] >> 16;
   h->d = w[2]; h->R = w[3]; h->s = w[4]; h->B = u2f(w[5]); h->client = w[6]; h->total_words = w[7];
   if (h->d != d_expected || h->R > ORC_MAX_R || h->s != orc_s_bits(h->d)) return ORC_ERR_STREAM;
   if (!(h->B > 0.0f) || !isfinite(h->B)) return ORC_ERR_STREAM;
@@ -620,6 +743,7 @@ static int parse_header(const uint32_t* w, uint64_t nwords, uint32_t d_expected,
     const uint32_t* sh = w + ORC_GLOBAL_HEADER_WORDS + ORC_SEG_HEADER_WORDS * r;
     h->y[r] = sh[0]; h->P[r] = sh[1]; h->m[r] = u2f(sh[2]); h->M[r] = u2f(sh[3]);
     if (!code_len_ok(h->y[r])) return ORC_ERR_STREAM;
+    if (h->quant == 1 && (h->y[r] < 2 || !(h->m[r] >= 0.0f) || sh[3] != 0)) return ORC_ERR_STREAM; /* {norm, 0} */
     if (!isfinite(h->m[r]) || !isfinite(h->M[r]) || !isfinite(h->M[r] - h->m[r])) return ORC_ERR_STREAM;
     k += h->P[r];
     h->payload_word[r] = pos;
@@ -657,7 +781,8 @@ int orc_decode_aggregate(uint32_t n, const uint32_t* const* streams, const uint6
         /* a group's records come in strictly ascending position */
         if (pid >= d || (e > 0 && pid <= prev_pid)) { free(acc); return ORC_ERR_STREAM; }
         prev_pid = pid;
-        acc[pid] += w * (double)orc_dequantise(cid, h.m[r], h.M[r], h.y[r]);
+        float xt = h.quant == 1 ? orc_dequantise_qsgd(cid, h.m[r], h.y[r]) : orc_dequantise(cid, h.m[r], h.M[r], h.y[r]);
+        acc[pid] += w * (double)xt;
       }
     }
   }
@@ -695,8 +820,7 @@ double orc_next_scale(const orc_plan* p) {
   double worst = 0.0;
   for (uint32_t r = 0; r < p->R; ++r) {
     if (p->y[r] == 32 || p->P[r] == 0) continue;
-    double levels = (double)(((uint64_t)1 << p->y[r]) - 1u);
-    double Q = (double)p->P[r] / (levels * levels);
+    double Q = p->quant == 1 ? q_qsgd((double)p->P[r], (double)p->y[r]) : q_pq((double)p->P[r], (double)p->y[r]);
     if (Q > worst) worst = Q;
   }
   return worst + 1.0;

@@ -84,6 +84,11 @@ def lib() -> C.CDLL:
         L.orc_unpack.argtypes = [u32p, C.c_uint64, C.c_uint32, u32p, u32p, u32p]
         L.orc_unpack.restype = C.c_int64
         L.orc_fit_alpha.argtypes = [f32p, C.c_uint32, C.POINTER(C.c_double)]
+        L.orc_qsgd_norm.argtypes = [f32p, C.c_uint32, C.POINTER(C.c_float)]
+        L.orc_quantise_qsgd.argtypes = [C.c_float, C.c_float, C.c_uint32, C.c_uint32]
+        L.orc_quantise_qsgd.restype = C.c_uint32
+        L.orc_dequantise_qsgd.argtypes = [C.c_uint32, C.c_float, C.c_uint32]
+        L.orc_dequantise_qsgd.restype = C.c_float
         L.orc_next_scale.argtypes = [C.POINTER(Plan)]
         L.orc_next_scale.restype = C.c_double
         L.orc_empirical_gamma.argtypes = [C.POINTER(SegStats), C.c_uint32]
@@ -147,10 +152,13 @@ def plan_alg1(d: int, budget_bits: int, R: int, alpha: float, B: float = 1.0) ->
     return p
 
 
-def plan_manual(d: int, code_len: Sequence[int], counts: Sequence[int], B: float = 1.0) -> Plan:
+PQ, QSGD = 0, 1
+
+
+def plan_manual(d: int, code_len: Sequence[int], counts: Sequence[int], B: float = 1.0, quant: int = PQ) -> Plan:
     """A plan with explicit group sizes (validated by the oracle)."""
     p = Plan()
-    p.d, p.R, p.s, p.B, p.quant = d, len(code_len), s_bits(d), B, 0
+    p.d, p.R, p.s, p.B, p.quant = d, len(code_len), s_bits(d), B, quant
     for r, (y, P) in enumerate(zip(code_len, counts)):
         p.y[r], p.P[r] = y, P
     p.total_bits = lib().orc_plan_total_bits(C.byref(p))
@@ -240,6 +248,21 @@ def unpack(stream: np.ndarray, d: int) -> Tuple[np.ndarray, np.ndarray, np.ndarr
     if k < 0:
         raise OracleError(int(k), "unpack")
     return pid[:k], cid[:k], seg[:k]
+
+
+def qsgd_norm(x: np.ndarray) -> float:
+    """The l2-norm QSGD's header carries: smallest fp32 n with n*n >= sum of x_i^2 (exactly)."""
+    out = C.c_float()
+    _check(lib().orc_qsgd_norm(_f32(x), x.size, C.byref(out)), "qsgd_norm")
+    return float(out.value)
+
+
+def quantise_qsgd(x: float, norm: float, y: int, u: int) -> int:
+    return int(lib().orc_quantise_qsgd(x, norm, y, u))
+
+
+def dequantise_qsgd(cid: int, norm: float, y: int) -> float:
+    return float(lib().orc_dequantise_qsgd(cid, norm, y))
 
 
 def next_scale(plan: Plan) -> float:

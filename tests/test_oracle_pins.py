@@ -589,3 +589,123 @@ def test_next_round_scale_factor():
         q = orc.plan_alg1(500_000, 400_000, R, -0.7)
         Bn = orc.next_scale(q)
         assert all(Bn > (P / (2 ** y - 1) ** 2 + 1) / 2 for P, y in zip(q.counts(), q.code_len()) if y != 32)
+
+
+# --------------------------------------------------------------------------- QSGD, the second quantiser of Sec. IV-D
+def _f32_below(v):
+    return float(np.nextafter(np.float32(v), np.float32(-np.inf)))
+
+
+def test_qsgd_norm_is_the_smallest_fp32_whose_square_reaches_the_exact_sum():
+    """The header's l2-norm must not depend on the order of a floating-point sum: it is defined
+    on the exact sum of squares (rational arithmetic here)."""
+    from fractions import Fraction
+    rng = np.random.default_rng(19)
+    cases = [rng.standard_normal(1000).astype(np.float32),
+             (rng.standard_normal(500) * 10.0 ** rng.uniform(-44, 18, 500)).astype(np.float32),   # denormals to 1e18
+             np.array([3.0, 4.0], dtype=np.float32),
+             np.array([-7.25e-12], dtype=np.float32),
+             np.array([1e-45, 1e-45, 1e-45], dtype=np.float32),
+             np.full(4096, 0.1, dtype=np.float32),
+             np.zeros(17, dtype=np.float32),
+             np.array([3.0e38], dtype=np.float32)]
+    for x in cases:
+        n = orc.qsgd_norm(x)
+        S = sum(Fraction(float(v)) ** 2 for v in x)
+        assert Fraction(n) ** 2 >= S
+        if n > 0.0:
+            assert Fraction(_f32_below(n)) ** 2 < S
+        assert n >= float(np.abs(x).max())                      # no entry exceeds the norm
+        assert n == orc.qsgd_norm(x[::-1].copy())
+        assert n == pytest.approx(math.sqrt(math.fsum(float(v) ** 2 for v in x)), rel=2e-7, abs=1e-45)
+    assert orc.qsgd_norm(np.array([3.0, 4.0], dtype=np.float32)) == 5.0
+    assert orc.qsgd_norm(np.array([-7.25e-12], dtype=np.float32)) == float(np.float32(7.25e-12))
+    with pytest.raises(orc.OracleError):                        # the norm itself overflows fp32
+        orc.qsgd_norm(np.array([3.0e38, 3.0e38], dtype=np.float32))
+
+
+def test_qsgd_quantiser_invariants_and_textbook_rule():
+    """QSGD's rule (Alistarh et al.): |x|/norm is rounded to a neighbouring level l/s or (l+1)/s,
+    up with probability equal to the fractional position; the sign travels beside the level."""
+    rng = np.random.default_rng(29)
+    for y in (2, 3, 5, 8, 12, 16):
+        s = (1 << (y - 1)) - 1
+        x = (rng.standard_normal(400) * 10.0 ** rng.uniform(-3, 0, 400)).astype(np.float32)
+        norm = orc.qsgd_norm(x)
+        u = rng.integers(0, 1 << 24, x.size)
+        cid = np.array([orc.quantise_qsgd(float(v), norm, y, int(uu)) for v, uu in zip(x, u)])
+        level, sign = cid & s, cid >> (y - 1)
+        assert np.all(cid < (1 << y)) and np.all(level <= s)
+        assert np.array_equal(sign == 1, np.signbit(x))
+        t = np.abs(x.astype(np.float64)) / norm * s
+        ref = np.minimum(np.floor(t) + (u / 2.0**24 < t - np.floor(t)), s)
+        assert np.abs(level - ref).max() <= 1 and (level != ref).mean() < 0.01      # fp32 vs fp64 at a boundary
+        xt = np.array([orc.dequantise_qsgd(int(c), norm, y) for c in cid], dtype=np.float64)
+        assert np.all(np.abs(xt - x) <= norm / s * (1 + 1e-5))
+        assert np.all(np.signbit(xt) == np.signbit(x))
+        lo = np.array([orc.quantise_qsgd(float(v), norm, y, (1 << 24) - 1) for v in x]) & s
+        hi = np.array([orc.quantise_qsgd(float(v), norm, y, 0) for v in x]) & s
+        assert np.all((hi - lo >= 0) & (hi - lo <= 1)) and np.all((level == lo) | (level == hi))
+    one = np.array([-0.75], dtype=np.float32)                    # a single entry sits on the top level exactly
+    assert orc.quantise_qsgd(-0.75, orc.qsgd_norm(one), 4, 123) == 7 | 8
+    assert orc.dequantise_qsgd(7 | 8, 0.75, 4) == -0.75
+    assert orc.quantise_qsgd(0.0, 0.0, 4, 5) == 0 and orc.dequantise_qsgd(3, 0.0, 4) == 0.0   # all-zero group
+    v = np.float32(-1.2345e-7)
+    assert orc.quantise_qsgd(float(v), 1.0, 32, 5) == int(v.view(np.uint32))
+    assert orc.dequantise_qsgd(int(v.view(np.uint32)), 1.0, 32) == float(v)
+
+
+def test_qsgd_stream_is_unbiased_within_the_published_variance_bound():
+    """Through the whole encoder and decoder: E[x~] = x, and E||x~ - x||^2 <= min(P/s^2, sqrt(P)/s) ||x||^2
+    (Lemma 3.1 of the QSGD paper; the Q(P_r) of the appendix case study)."""
+    d, y, n_seeds = 60, 4, 4000
+    U = syn.update_vector(1, 11, d=d)
+    p = orc.plan_manual(d, [y], [d], quant=orc.QSGD)
+    s = (1 << (y - 1)) - 1
+    x = U.astype(np.float64)
+    norm = orc.qsgd_norm(U)
+    t = np.abs(x) / norm * s
+    frac = t - np.floor(t)
+    dec = np.empty((n_seeds, d))
+    for seed in range(n_seeds):
+        dec[seed] = orc.decode_aggregate([orc.encode(U, p, seed, 0).words], d)
+    sd = norm / s * np.sqrt(frac * (1 - frac) / n_seeds)
+    assert np.all(np.abs(dec.mean(axis=0) - x) <= 5 * sd + 1e-9)
+    mse = ((dec - x) ** 2).sum(axis=1).mean()
+    closed = ((norm / s) ** 2 * frac * (1 - frac)).sum()
+    assert abs(mse - closed) <= 0.05 * closed
+    assert mse <= min(d / s**2, math.sqrt(d) / s) * (x**2).sum()
+
+
+def test_qsgd_stream_layout_and_plan_rules():
+    """Header {y, P, norm, 0} per group, quantiser id in the version word, sign above the level;
+    a 1-bit code cannot hold a sign and a level."""
+    d = 5000
+    U = syn.update_vector(3, 4, d=d)
+    p = orc.plan_manual(d, [32, 9, 2], [30, 400, 1500], quant=orc.QSGD)
+    pq = orc.plan_manual(d, [32, 9, 2], [30, 400, 1500])
+    enc = orc.encode(U, p, 5, 1, debug=True)
+    assert enc.words[1] >> 16 == 1 and p.total_bits == pq.total_bits
+    assert np.array_equal(orc.segments(U, p), orc.segments(U, pq))          # the grouping does not depend on the quantiser
+    pid, cid, seg = orc.unpack(enc.words, d)
+    out = orc.decode_aggregate([enc.words], d)
+    for r, y in enumerate([32, 9, 2]):
+        sel = seg == r + 1
+        hdr = enc.words[8 + 4 * r: 12 + 4 * r]
+        norm = float(hdr[2:3].view(np.float32)[0])
+        assert int(hdr[0]) == y and int(hdr[1]) == int(sel.sum()) and int(hdr[3]) == 0
+        assert norm == orc.qsgd_norm(U[pid[sel]])
+        want = np.array([orc.dequantise_qsgd(int(c), norm, y) for c in cid[sel]], dtype=np.float32)
+        assert np.array_equal(out[pid[sel]], want)          # as values: the sum starts from +0, so -0 comes back as +0
+        if y != 32:
+            assert np.array_equal((cid[sel] >> (y - 1)) == 1, np.signbit(U[pid[sel]]))
+    assert np.array_equal(out[pid[seg == 1]], U[pid[seg == 1]])             # raw group
+    with pytest.raises(orc.OracleError):
+        orc.plan_manual(d, [4, 1], [10, 10], quant=orc.QSGD)
+    bad = enc.words.copy()
+    bad[8 + 4 + 3] = 1                                                      # second header word of QSGD must be 0
+    with pytest.raises(orc.OracleError):
+        orc.decode_aggregate([bad], d)
+    # the error model of the appendix: min(P/s^2, sqrt(P)/s) with s = 2^(y-1) - 1
+    q = orc.plan_manual(100_000, [6, 3], [400, 10_000], quant=orc.QSGD)
+    assert orc.next_scale(q) == pytest.approx(1.0 + min(10_000 / 9.0, 100.0 / 3.0), rel=1e-15)
