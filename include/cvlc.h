@@ -58,8 +58,21 @@ typedef struct cvlc_plan_t {
   uint32_t count[CVLC_MAX_CODED];    /* P_r, may be 0                                 */
   uint64_t total_bits;               /* exact stream size, headers and padding included */
   float B;                           /* scale factor of Lemma 1, > 0 (1 = no scaling) */
-  uint32_t quant;                    /* 0 = PQ (uniform centroids on [min,max])       */
+  uint32_t quant;                    /* CVLC_QUANT_PQ or CVLC_QUANT_QSGD (set by the   */
+                                     /* caller; the planner's modes leave PQ)          */
 } cvlc_plan_t;
+
+/* The two quantisers of Sec. IV-D.
+ *   PQ    2^y centroids spread uniformly over the group's [min, max]; the group
+ *         header carries {min, max}.
+ *   QSGD  the magnitude relative to the group's l2-norm is rounded to one of the
+ *         levels 0, 1/s, ..., 1 with s = 2^(y-1) - 1; the code holds the sign in
+ *         its top bit and the level below; the group header carries {norm, 0};
+ *         needs y >= 2.  The norm is the smallest fp32 value whose square reaches
+ *         the exact sum of the group's squares, so the stream does not depend on
+ *         the order anything is added in. */
+#define CVLC_QUANT_PQ 0u
+#define CVLC_QUANT_QSGD 1u
 
 /* Per-group statistics returned by the encoder: entries 0..R-1 are the coded
  * groups, entry R the sparsified tail (min = max = 0 there; its sumsq is the
@@ -135,6 +148,7 @@ size_t cvlc_decode_workspace_bytes(uint32_t d, uint32_t n_clients);
  *   flags            CVLC_ENCODE_ERROR_STATS: also measure every coded group's
  *                    error energy (errsq; needs d_stats_out, else CVLC_ERR_ARG);
  *                    the stream does not depend on it
+ * All plans of a batch must name the same quantiser.
  * The stream is bit-identical for identical (update, plan, seed, client id).
  * Calls that share a workspace must not overlap in time. */
 #define CVLC_ENCODE_ERROR_STATS 1u
@@ -155,10 +169,13 @@ int cvlc_encode(const cvlc_plan_t* plan, const float* d_update, uint64_t seed, u
  *   stream_bytes[i] host; bytes readable at d_streams[i]
  *   weights         host or NULL; NULL => w_i = 1/(n * B_i), B_i from the header
  *   flags bit 0     0 = overwrite d_out, 1 = add to the values already there
+ *   flags bit 1     the quantiser the streams must name: 0 = PQ, 1 = QSGD (a
+ *                   federation uses one; a stream that names the other is malformed)
  * Products and sums are carried in fp64 and rounded to fp32 once.  A malformed
  * stream sets CVLC_DEV_STREAM; its offending records are skipped and nothing is
  * written out of bounds. */
 #define CVLC_DECODE_ACCUMULATE 1u
+#define CVLC_DECODE_QSGD 2u
 int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t* stream_bytes,
                           const float* weights, float* d_out, uint32_t d, uint32_t flags,
                           void* d_workspace, size_t ws_bytes, void* hip_stream);

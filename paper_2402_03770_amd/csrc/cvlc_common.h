@@ -35,6 +35,7 @@ constexpr uint32_t kTieCap = 2048;         // boundary-class members kept per hi
 constexpr uint32_t kSampleBlocks = 16;     // workgroups per client in the sample pass
 constexpr uint32_t kMaxGroups = 3;         // ceil(31 / kSlotGroup)
 constexpr uint32_t kStatsStride = CVLC_STATS_STRIDE;
+constexpr uint32_t kNormLimbs = 20;        // 32-bit limbs of an exact sum of up to 2^31 squares of fp32 values
 
 // Per-client inputs of one encode call, written to the workspace by small
 // upload kernels (kernel arguments are the only host->device path that needs

@@ -112,7 +112,7 @@ __device__ __forceinline__ uint64_t wave_incl_scan_u64(uint64_t v) {
 }
 
 __global__ __launch_bounds__(64) void parse_headers_kernel(ParseChunk chunk, ListDesc* descs, uint32_t d, uint32_t n,
-                                                           uint32_t* __restrict__ stream_bad) {
+                                                           uint32_t* __restrict__ stream_bad, uint32_t quant) {
   const uint32_t client = chunk.first + blockIdx.x, t = threadIdx.x;
   const StreamArg sa = chunk.args[blockIdx.x];
   GlobalConstWordPtr w = (GlobalConstWordPtr)sa.words;
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(64) void parse_headers_kernel(ParseChunk chunk, Lis
   }
   const uint32_t R = g[3], s = g[4];
   const float B = __uint_as_float(g[5]);
-  ok = ok && g[0] == kMagic && g[1] == kVersion && g[2] == d && R <= CVLC_MAX_CODED && s == position_bits(d) &&
+  ok = ok && g[0] == kMagic && g[1] == (kVersion | (quant << 16)) && g[2] == d && R <= CVLC_MAX_CODED && s == position_bits(d) &&
        B > 0.0f && fabsf(B) <= 3.4028234664e38f;
   const uint64_t first_payload = kGlobalHeaderWords + (uint64_t)kSegHeaderWords * R;
   ok = ok && sa.n_words >= first_payload;
@@ -139,8 +139,10 @@ __global__ __launch_bounds__(64) void parse_headers_kernel(ParseChunk chunk, Lis
     m = __uint_as_float(h[2]);
     M = __uint_as_float(h[3]);
   }
-  const bool header_ok = !mine || (code_len_supported(y) && fabsf(m) <= 3.4028234664e38f &&
-                                   fabsf(M) <= 3.4028234664e38f && fabsf(M - m) <= 3.4028234664e38f);
+  bool header_ok = !mine || (code_len_supported(y) && fabsf(m) <= 3.4028234664e38f &&
+                             fabsf(M) <= 3.4028234664e38f && fabsf(M - m) <= 3.4028234664e38f);
+  if (quant == CVLC_QUANT_QSGD && mine)  // {norm, 0}; a sign bit and at least one level bit
+    header_ok = header_ok && y >= 2 && m >= 0.0f && __float_as_uint(M) == 0u;
   ok = ok && __ballot(header_ok) == ~0ull;
   // where every group's records start, and what the stream must add up to (sizes of groups with a bad header
   // do not matter: the stream is rejected)
@@ -156,7 +158,14 @@ __global__ __launch_bounds__(64) void parse_headers_kernel(ParseChunk chunk, Lis
     ld.payload = nullptr; ld.weight = 0.0; ld.P = 0; ld.W = 0; ld.s = 0; ld.y = 0; ld.m = 0.0f; ld.step = 0.0f;
     if (ok && t < R) {
       float step = 0.0f, inv = 0.0f;
-      if (y != 32) centroid_spacing(m, M, y, &step, &inv);
+      if (y != 32) {
+        if (quant == CVLC_QUANT_QSGD) {  // levels 0 .. 2^(y-1) - 1 on [0, norm]
+          centroid_spacing(0.0f, m, y - 1u, &step, &inv);
+          m = 0.0f;
+        } else {
+          centroid_spacing(m, M, y, &step, &inv);
+        }
+      }
       ld.payload = sa.words + (first_payload + incl - words);
       ld.weight = sa.has_weight ? sa.weight : 1.0 / ((double)n * (double)B);
       ld.P = P;
@@ -403,6 +412,8 @@ struct DecodeShared {
 
 constexpr uint32_t kDecBlock = 512;  // threads of a decode workgroup
 
+// SIGNED: the streams' codes hold a sign bit above the level (QSGD).
+template <bool SIGNED>
 __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const CompactDesc* __restrict__ cdesc,
                                                               const DecodeCtl* __restrict__ ctl,
                                                               const uint32_t* __restrict__ table, float* out,
@@ -516,7 +527,15 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
           const uint32_t pid = (uint32_t)(rec & ((1ull << s) - 1ull));
           const uint32_t cid = (uint32_t)(rec >> s);
           if (pid < lo || pid - lo >= kDecTile || pid >= d) { bad = true; continue; }
-          const float xhat = y == 32 ? __uint_as_float(cid) : __fmaf_rn((float)cid, __uint_as_float(d1.w), __uint_as_float(d1.z));
+          float xhat;
+          if (y == 32) {
+            xhat = __uint_as_float(cid);
+          } else if (SIGNED) {
+            const float mag = __fmaf_rn((float)(cid & ((1u << (y - 1u)) - 1u)), __uint_as_float(d1.w), __uint_as_float(d1.z));
+            xhat = __uint_as_float(__float_as_uint(mag) ^ ((cid >> (y - 1u)) << 31));
+          } else {
+            xhat = __fmaf_rn((float)cid, __uint_as_float(d1.w), __uint_as_float(d1.z));
+          }
           atomicAdd(&S.acc[pid - lo], weight * (double)xhat);
         }
       }
@@ -557,6 +576,8 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
     if (stream_bytes[i] < 4u * kGlobalHeaderWords) return CVLC_ERR_STREAM;
   }
   if (ws_bytes < cvlc_decode_workspace_bytes(d, n)) return CVLC_ERR_CAPACITY;
+  if (flags & ~(CVLC_DECODE_ACCUMULATE | CVLC_DECODE_QSGD)) return CVLC_ERR_ARG;
+  const uint32_t quant = (flags & CVLC_DECODE_QSGD) ? CVLC_QUANT_QSGD : CVLC_QUANT_PQ;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const DecodeLayout L = decode_layout(d, n < 1 ? 1 : n);
   char* base = static_cast<char*>(d_workspace);
@@ -584,7 +605,8 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
         sa.has_weight = weights ? 1u : 0u;
         sa.pad = 0;
       }
-      hipLaunchKernelGGL(parse_headers_kernel, dim3(chunk.count), dim3(64), 0, stream, chunk, descs, d, n, stream_bad);
+      hipLaunchKernelGGL(parse_headers_kernel, dim3(chunk.count), dim3(64), 0, stream, chunk, descs, d, n, stream_bad,
+                         quant);
     }
     // also for n = 0: writes the (empty) list counts and the status word
     hipLaunchKernelGGL(compact_lists_kernel, dim3(1), dim3(1024), 0, stream, descs, n_lists, cdesc, item_start, ctl,
@@ -600,7 +622,8 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
   {
     StageScope scope(CVLC_STAGE_DEC_TILES, stream);
     const uint32_t g = L.n_tiles < 768u ? L.n_tiles : 768u;  // three workgroups per CU
-    hipLaunchKernelGGL(decode_tiles_kernel, dim3(g), dim3(kDecBlock), 0, stream, cdesc, ctl, table, d_out, d, L.n_tiles,
+    auto kernel = quant == CVLC_QUANT_QSGD ? decode_tiles_kernel<true> : decode_tiles_kernel<false>;
+    hipLaunchKernelGGL(kernel, dim3(g), dim3(kDecBlock), 0, stream, cdesc, ctl, table, d_out, d, L.n_tiles,
                        flags & CVLC_DECODE_ACCUMULATE, status);
   }
   return hip_check(hipGetLastError());

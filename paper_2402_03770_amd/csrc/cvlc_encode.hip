@@ -57,7 +57,7 @@ struct GroupInfo {
 
 struct EncodeLayout {
   size_t status, ctl, params, region_cnt, region_sumsq, cand_idx, cand_val, dense_idx, dense_val, nz_off, nz_run, span_first, span_cnt, group_info,
-      tie_list, sel_part, l3_hist, total;
+      tie_list, sel_part, l3_hist, norm_limbs, total;
   size_t zero_bytes;        // [status, params) is cleared at the start of a call
   uint32_t n_regions, max_spans;
   uint32_t sel_blocks;      // workgroups per client in a level-2/3 selection pass
@@ -88,6 +88,7 @@ EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   L.status = off; off = align256(off + 256);
   L.ctl = off; off = align256(off + (size_t)n * sizeof(ClientCtl));
   L.l3_hist = off; off = align256(off + (size_t)n * kSlotGroup * kDigitBins * sizeof(uint32_t));
+  L.norm_limbs = off; off = align256(off + (size_t)n * 32 * kNormLimbs * sizeof(uint64_t));
   L.zero_bytes = off;
   L.params = off; off = align256(off + (size_t)n * sizeof(ClientParams));
   L.region_cnt = off; off = align256(off + (size_t)n * L.n_regions * sizeof(uint32_t));
@@ -125,6 +126,7 @@ struct Workspace {  // device pointers into the caller's workspace
   uint2* tie_list;
   uint32_t* sel_part;
   uint32_t* l3_hist;   // level-3 digit counts per (client, slot), zero between uses
+  unsigned long long* norm_limbs;  // QSGD: per (client, group) the exact sum of squares in 32-bit limbs
   uint32_t d, n_regions, max_spans, filter_blocks, sel_blocks;
 };
 
@@ -1110,15 +1112,40 @@ __device__ __forceinline__ void classify_span(const Thresholds& thr, uint32_t R,
 }
 
 // ------------------------------------------------------------------ 6. group counts and statistics
+// QSGD's header carries the group's l2-norm, and the stream must not depend on
+// the order squares are added in: the sum of squares is kept exactly, as a
+// fixed-point number in units of 2^-298 (the square of the smallest denormal)
+// spread over 32-bit limbs, each limb summed in a 64-bit counter of its own.
+// x = m * 2^(q - 149) with m < 2^24, so x^2 = m^2 << 2q: three limbs from 2q / 32.
+struct SquareLimbs {
+  uint32_t word;     // first limb
+  uint32_t part[3];  // the pieces of m^2 << (2q mod 32), each below 2^32
+};
+__device__ __forceinline__ SquareLimbs square_limbs(uint32_t value_bits) {
+  const uint32_t b = value_bits & 0x7FFFFFFFu, e = b >> 23, frac = b & 0x7FFFFFu;
+  const uint64_t m = e ? (frac | 0x800000u) : frac;
+  const uint32_t off = 2u * (e ? e - 1u : 0u), sh = off & 31u;
+  const uint64_t sq = m * m, low = sq << sh;  // the top bits that leave `low` are part[2]
+  SquareLimbs r;
+  r.word = off >> 5;
+  r.part[0] = (uint32_t)low;
+  r.part[1] = (uint32_t)(low >> 32);
+  r.part[2] = sh ? (uint32_t)(sq >> (64u - sh)) : 0u;
+  return r;
+}
+
 // Every wavefront takes spans of 512 candidates (gw, gw + wavefronts, ...) and
 // writes, per span, the number of members of every group (for the records'
 // places in the stream).  Min, max and sum of squares of the groups go to LDS
 // columns private to a lane id, so that the LDS atomics of one instruction never
 // collide; they are reduced once at the end.  Wavefronts do not wait for each
 // other before that.
+// QSGD: also the exact sum of squares of every group (see above).
+template <bool QSGD>
 __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* __restrict__ params,
                                                            ClientCtl* __restrict__ ctls, Workspace ws) {
   __shared__ Thresholds thr;
+  __shared__ unsigned long long s_limb[QSGD ? 32 : 1][kNormLimbs];
   __shared__ uint32_t s_max[33][kWave], s_negmin[33][kWave];
   __shared__ double s_sq[33][kWave];
   __shared__ uint32_t s_cnt[kEmitWaves][32];
@@ -1136,6 +1163,8 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
     (&s_negmin[0][0])[i] = 0;
     (&s_sq[0][0])[i] = 0.0;
   }
+  if (QSGD)
+    for (uint32_t i = tid; i < 32 * kNormLimbs; i += kEmitBlock) (&s_limb[0][0])[i] = 0;
   __syncthreads();
   for (uint32_t span = blockIdx.x * kEmitWaves + wave; span < n_spans; span += gridDim.x * kEmitWaves) {
     uint32_t v[kPerLane], grp[kPerLane];
@@ -1159,10 +1188,23 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
         atomicMax(&s_max[g][lane], o);
         atomicMax(&s_negmin[g][lane], ~o);
         atomicAdd(&s_sq[g][lane], (double)x * (double)x);
+        if (QSGD && g < R) {
+          const SquareLimbs sl = square_limbs(v[j]);  // word + 2 <= 17
+          atomicAdd(&s_limb[g][sl.word], (unsigned long long)sl.part[0]);
+          if (sl.part[1]) atomicAdd(&s_limb[g][sl.word + 1], (unsigned long long)sl.part[1]);
+          if (sl.part[2]) atomicAdd(&s_limb[g][sl.word + 2], (unsigned long long)sl.part[2]);
+        }
       }
     }
   }
   __syncthreads();
+  if (QSGD) {  // a workgroup sees fewer than 2^31 candidates, so no counter has wrapped
+    unsigned long long* dst = ws.norm_limbs + (size_t)client * 32 * kNormLimbs;
+    for (uint32_t i = tid; i < R * kNormLimbs; i += kEmitBlock) {
+      const unsigned long long t = (&s_limb[0][0])[i];
+      if (t) atomicAdd(&dst[i], t);
+    }
+  }
   // group g's columns are reduced by wavefront g mod 8; finite values never code to 0, so 0 = no member here
   for (uint32_t g = wave; g <= R; g += kEmitWaves) {
     const uint32_t mx = wave_max_u32(s_max[g][lane]);
@@ -1188,8 +1230,9 @@ typedef uint32_t __attribute__((address_space(1))) * GlobalWordPtr;
 // stored whole.  Then the headers and the statistics block.
 __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* __restrict__ params,
                                                             ClientCtl* __restrict__ ctls, Workspace ws,
-                                                            cvlc_seg_stats_t* __restrict__ stats_out) {
+                                                            cvlc_seg_stats_t* __restrict__ stats_out, uint32_t quant) {
   __shared__ double s_tail[kWideWaves];
+  __shared__ uint32_t s_sum[32][kNormLimbs];  // QSGD: a group's sum of squares, limbs below 2^32
   __shared__ uint32_t s_payload[32];
   __shared__ uint32_t s_tot[kWideWaves][32];
   const uint32_t client = blockIdx.x, tid = threadIdx.x;
@@ -1294,11 +1337,43 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
       atomicOr(ws.status, CVLC_DEV_INTERNAL);
     }
     if (!(fabsf(M - m) <= 3.4028234664e38f)) atomicOr(ws.status, CVLC_DEV_NONFINITE);
+    float norm = 0.0f;
+    if (quant == CVLC_QUANT_QSGD) {
+      // carry the 64-bit counters into 32-bit limbs, then look for the smallest fp32 value whose
+      // square reaches the sum: squares grow with the bit pattern, so a binary search over it
+      const unsigned long long* src = ws.norm_limbs + ((size_t)client * 32 + r) * kNormLimbs;
+      unsigned long long carry = 0;
+      for (uint32_t i = 0; i < kNormLimbs; ++i) {
+        const unsigned long long t = src[i] + carry;
+        s_sum[r][i] = (uint32_t)t;
+        carry = t >> 32;
+      }
+      auto reaches = [&](uint32_t key) {  // key^2 >= sum, compared limb by limb from the top
+        const SquareLimbs sl = square_limbs(key);
+        for (int i = (int)kNormLimbs - 1; i >= 0; --i) {
+          const uint32_t j = (uint32_t)i - sl.word;  // wraps to a large value below sl.word
+          const uint32_t mine = j < 3u ? sl.part[j] : 0u;
+          const uint32_t theirs = s_sum[r][i];
+          if (mine != theirs) return mine > theirs;
+        }
+        return true;
+      };
+      uint32_t lo = 0, hi = 0x7F7FFFFFu;
+      if (!reaches(hi)) {
+        atomicOr(ws.status, CVLC_DEV_NONFINITE);  // the norm overflows fp32
+        lo = hi;
+      }
+      while (lo < hi) {
+        const uint32_t mid = lo + (hi - lo) / 2u;
+        if (reaches(mid)) hi = mid; else lo = mid + 1u;
+      }
+      norm = __uint_as_float(lo);
+    }
     GlobalWordPtr hdr = stream + kGlobalHeaderWords + kSegHeaderWords * r;
     hdr[0] = p.y[r];
     hdr[1] = P;
-    hdr[2] = __float_as_uint(m);
-    hdr[3] = __float_as_uint(M);
+    hdr[2] = quant == CVLC_QUANT_QSGD ? __float_as_uint(norm) : __float_as_uint(m);
+    hdr[3] = quant == CVLC_QUANT_QSGD ? 0u : __float_as_uint(M);
     if (stats_out) {
       cvlc_seg_stats_t* st = stats_out + (size_t)client * kStatsStride + r;
       st->min = m; st->max = M; st->sumsq = ctl->seg_sumsq[r]; st->count = P; st->reserved = 0;
@@ -1306,7 +1381,12 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
     }
     GroupInfo* gi = ws.group_info + client;
     float step, inv;
-    centroid_spacing(m, M, p.y[r] == 32 ? 1u : p.y[r], &step, &inv);
+    if (quant == CVLC_QUANT_QSGD) {  // levels 0 .. s on [0, norm]: the same spacing rule with s = 2^(y-1) - 1 steps
+      centroid_spacing(0.0f, norm, p.y[r] == 32 ? 1u : p.y[r] - 1u, &step, &inv);
+      m = 0.0f;
+    } else {
+      centroid_spacing(m, M, p.y[r] == 32 ? 1u : p.y[r], &step, &inv);
+    }
     gi->payload[r] = s_payload[r];
     gi->P[r] = P;
     gi->W[r] = sbits + p.y[r];
@@ -1317,7 +1397,7 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
   }
   if (tid == 32) {
     stream[0] = kMagic;
-    stream[1] = kVersion;  // quantiser id 0 (PQ) in the upper half
+    stream[1] = kVersion | (quant << 16);
     stream[2] = ws.d;
     stream[3] = R;
     stream[4] = sbits;
@@ -1394,7 +1474,8 @@ struct alignas(16) EmitGroup {  // per (chunk, group)
 // ERR: every record also adds (xtilde / B - x)^2 to its group's error energy in
 // the statistics block (Lemma 1's left side for this draw), xtilde being the
 // centroid value the decoder will compute from the header.
-template <bool ERR>
+// QSGD: the code is the level of |x| on [0, norm] with the sign bit above it.
+template <bool ERR, bool QSGD>
 __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams* __restrict__ params,
                                                           ClientCtl* __restrict__ ctls, Workspace ws, uint64_t seed,
                                                           cvlc_seg_stats_t* __restrict__ stats_out) {
@@ -1508,11 +1589,22 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
           cid = v[j];
         } else {
           const uint32_t u24 = philox_word0(pid[j], client_id, k0, k1) >> 8;
-          cid = quantise(__uint_as_float(v[j]), eg.m, eg.inv, y, u24);
+          if (QSGD)
+            cid = quantise(fabsf(__uint_as_float(v[j])), 0.0f, eg.inv, y - 1u, u24) | ((v[j] >> 31) << (y - 1u));
+          else
+            cid = quantise(__uint_as_float(v[j]), eg.m, eg.inv, y, u24);
         }
         if (ERR) {
           const float x = __uint_as_float(v[j]);
-          const float xt = y == 32 ? x : __fmaf_rn((float)cid, eg.step, eg.m);
+          float xt = x;
+          if (y != 32) {
+            if (QSGD) {
+              const float mag = __fmaf_rn((float)(cid & ((1u << (y - 1u)) - 1u)), eg.step, 0.0f);
+              xt = (cid >> (y - 1u)) ? -mag : mag;
+            } else {
+              xt = __fmaf_rn((float)cid, eg.step, eg.m);
+            }
+          }
           const double err = (double)xt * inv_B - (double)x;
           atomicAdd(&s_err[wave][g], err * err);
         }
@@ -1620,6 +1712,9 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   int rc = validate_batch(n, plans, d_updates, client_ids, d_streams_out, capacities, d_workspace, ws_bytes);
   if (rc) return rc;
   if (flags & ~CVLC_ENCODE_ERROR_STATS) return CVLC_ERR_ARG;
+  const uint32_t quant = plans[0].quant;
+  for (uint32_t i = 1; i < n; ++i)
+    if (plans[i].quant != quant) return CVLC_ERR_ARG;
   if ((flags & CVLC_ENCODE_ERROR_STATS) && !d_stats_out) return CVLC_ERR_ARG;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const uint32_t d = plans[0].d;
@@ -1643,6 +1738,7 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   ws.tie_list = reinterpret_cast<uint2*>(base + L.tie_list);
   ws.sel_part = reinterpret_cast<uint32_t*>(base + L.sel_part);
   ws.l3_hist = reinterpret_cast<uint32_t*>(base + L.l3_hist);
+  ws.norm_limbs = reinterpret_cast<unsigned long long*>(base + L.norm_limbs);
   ws.d = d;
   ws.n_regions = L.n_regions;
   ws.max_spans = L.max_spans;
@@ -1761,11 +1857,14 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   if (g_count > (L.max_spans + kEmitWaves - 1) / kEmitWaves) g_count = (L.max_spans + kEmitWaves - 1) / kEmitWaves;
   {
     StageScope scope(CVLC_STAGE_ENC_CLASSIFY, stream);
-    hipLaunchKernelGGL(count_kernel, dim3(g_count, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws);
+    if (quant == CVLC_QUANT_QSGD)
+      hipLaunchKernelGGL(count_kernel<true>, dim3(g_count, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws);
+    else
+      hipLaunchKernelGGL(count_kernel<false>, dim3(g_count, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws);
   }
   {
     StageScope scope(CVLC_STAGE_ENC_LAYOUT, stream);
-    hipLaunchKernelGGL(layout_kernel, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, d_stats_out);
+    hipLaunchKernelGGL(layout_kernel, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, d_stats_out, quant);
   }
   {
     // emit: workgroups walk the chunks; about what the device holds at once (three per CU)
@@ -1773,12 +1872,10 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
     uint32_t g_emit = (768u + n - 1) / n;
     const uint32_t max_chunks = (L.max_spans + kChunkSpans - 1) / kChunkSpans;
     if (g_emit > max_chunks) g_emit = max_chunks;
-    if (flags & CVLC_ENCODE_ERROR_STATS)
-      hipLaunchKernelGGL(emit_kernel<true>, dim3(g_emit, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws, seed,
-                         d_stats_out);
-    else
-      hipLaunchKernelGGL(emit_kernel<false>, dim3(g_emit, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws, seed,
-                         d_stats_out);
+    const bool err = flags & CVLC_ENCODE_ERROR_STATS, qsgd = quant == CVLC_QUANT_QSGD;
+    auto kernel = err ? (qsgd ? emit_kernel<true, true> : emit_kernel<true, false>)
+                      : (qsgd ? emit_kernel<false, true> : emit_kernel<false, false>);
+    hipLaunchKernelGGL(kernel, dim3(g_emit, n), dim3(kEmitBlock), 0, stream, ws.params, ws.ctl, ws, seed, d_stats_out);
   }
   return hip_check(hipGetLastError());
 }

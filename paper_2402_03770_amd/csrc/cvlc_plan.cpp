@@ -40,18 +40,31 @@ double pq_error(double P, double y) {
   return P / (levels * levels);
 }
 
+// QSGD: Q(P, y) = min(P / s^2, sqrt(P) / s) (Appendix, case study), s = 2^(y-1) - 1 the
+// levels above zero that y bits hold beside the sign.
+double qsgd_error(double P, double y) {
+  if (!(y > 1.0)) return std::numeric_limits<double>::infinity();
+  const double levels = std::exp2(y - 1.0) - 1.0;
+  const double a = P / (levels * levels), b = std::sqrt(P) / levels;
+  return a < b ? a : b;
+}
+
 struct ErrorModel {  // the bracket (Q/B^2 + 1/B_c^2) of Eq. (5)/(6), 1/B + 1/B_c = 1
   double inv_b2, inv_bc2;
-  explicit ErrorModel(double B) : inv_b2(1.0 / (B * B)) {
+  uint32_t quant;
+  explicit ErrorModel(double B, uint32_t quant_ = CVLC_QUANT_PQ) : inv_b2(1.0 / (B * B)), quant(quant_) {
     const double inv_bc = 1.0 - 1.0 / B;
     inv_bc2 = inv_bc * inv_bc;
   }
-  double weight(double P, double y) const { return pq_error(P, y) * inv_b2 + inv_bc2; }
+  double weight(double P, double y) const {
+    return (quant == CVLC_QUANT_QSGD ? qsgd_error(P, y) : pq_error(P, y)) * inv_b2 + inv_bc2;
+  }
 };
 
-double gamma_integer(uint32_t d, uint32_t R, const uint32_t* P, const uint32_t* y, double alpha, double B) {
+double gamma_integer(uint32_t d, uint32_t R, const uint32_t* P, const uint32_t* y, double alpha, double B,
+                     uint32_t quant = CVLC_QUANT_PQ) {
   const PowerLaw law((double)d, alpha);
-  const ErrorModel err(B);
+  const ErrorModel err(B, quant);
   double k = 0.0;
   for (uint32_t r = 0; r < R; ++r) k += (double)P[r];
   double g = law.share((double)d, k + 1.0);
@@ -250,11 +263,12 @@ int cvlc_plan_validate(const cvlc_plan_t* p) {
   if (p->d < 1 || p->d > 0x7FFFFFFFu) return CVLC_ERR_PLAN;
   if (p->n_coded > CVLC_MAX_CODED) return CVLC_ERR_PLAN;
   if (p->s != cvlc::position_bits(p->d)) return CVLC_ERR_PLAN;
-  if (p->quant != 0) return CVLC_ERR_PLAN;
+  if (p->quant > CVLC_QUANT_QSGD) return CVLC_ERR_PLAN;
   if (!(p->B > 0.0f) || !std::isfinite(p->B)) return CVLC_ERR_PLAN;
   uint64_t k = 0;
   for (uint32_t r = 0; r < p->n_coded; ++r) {
     if (!cvlc::code_len_supported(p->code_len[r])) return CVLC_ERR_PLAN;
+    if (p->quant == CVLC_QUANT_QSGD && p->code_len[r] < 2) return CVLC_ERR_PLAN;  // a sign bit and a level bit
     if (r > 0 && p->code_len[r] > p->code_len[r - 1]) return CVLC_ERR_PLAN;
     k += p->count[r];
   }
@@ -265,7 +279,7 @@ int cvlc_plan_validate(const cvlc_plan_t* p) {
 
 double cvlc_plan_gamma(const cvlc_plan_t* p, double alpha) {
   if (!p || p->n_coded > CVLC_MAX_CODED) return std::numeric_limits<double>::quiet_NaN();
-  return gamma_integer(p->d, p->n_coded, p->count, p->code_len, alpha, (double)p->B);
+  return gamma_integer(p->d, p->n_coded, p->count, p->code_len, alpha, (double)p->B, p->quant);
 }
 
 double cvlc_plan_next_scale(const cvlc_plan_t* plan) {
@@ -275,8 +289,8 @@ double cvlc_plan_next_scale(const cvlc_plan_t* plan) {
     for (uint32_t r = 0; r < R; ++r) {
       const uint32_t y = plan->code_len[r];
       if (y == 0 || y >= 32 || plan->count[r] == 0) continue;  // raw values carry no quantisation error
-      const double top = (double)((1ull << y) - 1ull);
-      const double Q = (double)plan->count[r] / (top * top);
+      const double Q = plan->quant == CVLC_QUANT_QSGD ? qsgd_error((double)plan->count[r], (double)y)
+                                                      : pq_error((double)plan->count[r], (double)y);
       if (Q > worst) worst = Q;
     }
   }

@@ -14,6 +14,8 @@ MAX_CODED = 31
 STATS_STRIDE = 32
 DEV_NONFINITE, DEV_STREAM, DEV_INTERNAL = 1, 2, 4
 DECODE_ACCUMULATE = 1
+DECODE_QSGD = 2
+QUANT_PQ, QUANT_QSGD = 0, 1
 ENCODE_ERROR_STATS = 1
 FIT_RANKS_MAX = 32
 
@@ -138,10 +140,11 @@ def plan(d: int, budget_bits: int = 0, n_coded: Optional[int] = None, code_len: 
     return out
 
 
-def plan_manual(d: int, code_len: Sequence[int], counts: Sequence[int], B: float = 1.0) -> Plan:
+def plan_manual(d: int, code_len: Sequence[int], counts: Sequence[int], B: float = 1.0,
+                quant: int = QUANT_PQ) -> Plan:
     """A caller-built plan, checked by cvlc_plan_validate."""
     p = Plan()
-    p.d, p.n_coded, p.s, p.B, p.quant = d, len(code_len), position_bits(d), B, 0
+    p.d, p.n_coded, p.s, p.B, p.quant = d, len(code_len), position_bits(d), B, quant
     for r, (y, P) in enumerate(zip(code_len, counts)):
         p.code_len[r], p.count[r] = y, P
     p.total_bits = lib().cvlc_plan_total_bits(C.byref(p))
@@ -225,7 +228,7 @@ def encode(p: Plan, update: torch.Tensor, seed: int, client_id: int, stream_out:
 
 def decode_aggregate(streams: Sequence[torch.Tensor], out: torch.Tensor, workspace: torch.Tensor,
                      weights: Optional[Sequence[float]] = None, accumulate: bool = False,
-                     stream_bytes: Optional[Sequence[int]] = None) -> None:
+                     stream_bytes: Optional[Sequence[int]] = None, quant: int = QUANT_PQ) -> None:
     """cvlc_decode_aggregate on the current stream; `out` is a float32 device tensor of d entries."""
     n = len(streams)
     vp = C.c_void_p
@@ -235,7 +238,8 @@ def decode_aggregate(streams: Sequence[torch.Tensor], out: torch.Tensor, workspa
     sizes = (C.c_size_t * max(n, 1))(*stream_bytes)
     w = (C.c_float * max(n, 1))(*weights) if weights is not None else None
     _check(lib().cvlc_decode_aggregate(n, ptrs, sizes, w, out.data_ptr(), out.numel(),
-                                       DECODE_ACCUMULATE if accumulate else 0, workspace.data_ptr(),
+                                       (DECODE_ACCUMULATE if accumulate else 0) | (DECODE_QSGD if quant == QUANT_QSGD else 0),
+                                       workspace.data_ptr(),
                                        workspace.numel(), _stream_handle()), "cvlc_decode_aggregate")
 
 

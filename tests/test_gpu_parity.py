@@ -24,7 +24,7 @@ DEV = "cuda:0"
 
 def to_lib_plan(po: orc.Plan) -> cv.Plan:
     """The same plan in the library's struct (plans are inputs to both sides)."""
-    return cv.plan_manual(po.d, po.code_len(), po.counts(), B=float(po.B))
+    return cv.plan_manual(po.d, po.code_len(), po.counts(), B=float(po.B), quant=int(po.quant))
 
 
 def gpu_encode(host_updates, oracle_plans, seed, client_ids, want_stats=True, error_stats=False):
@@ -76,10 +76,10 @@ def check_encode(host_updates, oracle_plans, seed, client_ids):
     return refs, streams
 
 
-def gpu_decode(streams_dev, d, weights=None, accumulate_into=None):
+def gpu_decode(streams_dev, d, weights=None, accumulate_into=None, quant=cv.QUANT_PQ):
     out = torch.full((d,), float("nan"), dtype=torch.float32, device=DEV) if accumulate_into is None else accumulate_into
     ws = cv.new_workspace(cv.decode_workspace_bytes(d, len(streams_dev)), DEV)
-    cv.decode_aggregate(streams_dev, out, ws, weights=weights, accumulate=accumulate_into is not None)
+    cv.decode_aggregate(streams_dev, out, ws, weights=weights, accumulate=accumulate_into is not None, quant=quant)
     return out.cpu().numpy(), cv.device_status(ws)
 
 
@@ -358,6 +358,81 @@ def test_error_statistics_and_the_scale_factor_carried_across_rounds():
         assert nxt == [orc.next_scale(p) for p in plans]
         B = float(np.float32(max(nxt)))   # one factor for the round, as the paper's constant B
     assert B > 1.0
+
+
+# --------------------------------------------------------------------------- QSGD, the second quantiser
+def check_qsgd(host, plans, seed, ids, weights=None):
+    """Streams bit for bit (header norms included), statistics, error energy, aggregate."""
+    d = host[0].size
+    words, stats, status, streams = gpu_encode(host, plans, seed, ids, error_stats=True)
+    assert status == 0
+    refs = []
+    for c, (u, p) in enumerate(zip(host, plans)):
+        ref = orc.encode(u, p, seed, ids[c])
+        assert_stream_equal(words[c], ref.words, f"client {c}")
+        assert_stats_close(stats[c], ref.stats, p.R, error_stats=True)
+        refs.append(ref.words)
+    got, status = gpu_decode(streams, d, weights=weights, quant=cv.QUANT_QSGD)
+    assert status == 0
+    ref = orc.decode_aggregate(refs, d, weights=weights)
+    n = len(host)
+    tol = np.zeros(d)
+    for i, s in enumerate(refs):
+        w = abs(float(np.float32(weights[i]))) if weights is not None else 1.0 / (n * float(s[5:6].view(np.float32)[0]))
+        tol += np.abs(orc.decode_aggregate([s], d, weights=[1.0]).astype(np.float64)) * w
+    assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= 1e-5 * tol)
+    if n == 1 and weights is None:
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    return streams
+
+
+def test_qsgd_on_the_workload_distributions():
+    d = 200_003
+    host = [syn.update_vector(3, c, d=d) for c in range(4)]
+    plans = [orc.plan_manual(d, [32, 12, 7, 4, 2], [300, 2000, 5000, 9000, 14000], quant=orc.QSGD),
+             orc.plan_manual(d, [16, 8, 5, 3, 2], [1000, 3000, 7000, 11000, 20001], B=1.5, quant=orc.QSGD),
+             orc.plan_manual(d, [2], [50_000], quant=orc.QSGD),
+             orc.plan_manual(d, [9, 9, 9], [1, 0, 4097], quant=orc.QSGD)]
+    check_qsgd(host, plans, 31, [9, 8, 7, 6])
+    check_qsgd(host[:1], plans[:1], 32, [0])
+    check_qsgd(host[:2], plans[:2], 33, [1, 2], weights=[0.25, -2.0])
+    check_qsgd([syn.update_vector(1, 0)], [orc.plan_manual(65_536, [8, 4, 2], [6553, 9831, 16384], quant=orc.QSGD)], 34, [3])
+
+
+@pytest.mark.parametrize("kind", ["all_equal_mixed_sign", "few_levels", "zeros_and_denormals", "all_zero"])
+def test_qsgd_on_colliding_magnitudes_and_extreme_exponents(kind):
+    """Ties, signed zeros, denormals (squares down at 2^-298) and, in one vector, magnitudes from
+    1e-38 to 1e18: every limb of the exact sum of squares is exercised."""
+    d = 30_011
+    U = syn.tie_heavy_vector(kind, d, seed=5)
+    plans = [orc.plan_manual(d, [10, 4, 2], [2000, 6000, 12_000], quant=orc.QSGD)]
+    check_qsgd([U], plans, 41, [2])
+    rng = np.random.default_rng(43)
+    wide = (rng.standard_normal(d) * 10.0 ** rng.uniform(-38, 18, d)).astype(np.float32)
+    check_qsgd([wide, -wide[::-1].copy()], plans * 2, 42, [0, 1])
+
+
+def test_qsgd_norm_overflow_and_mismatched_quantiser_are_reported():
+    d = 10_000
+    U = np.full(d, 3.0e38, dtype=np.float32)                       # every square is finite in the limbs, the norm is not
+    p = orc.plan_manual(d, [8], [100], quant=orc.QSGD)
+    _, _, status, _ = gpu_encode([U], [p], 1, [0], want_stats=False)
+    assert status & cv.DEV_NONFINITE
+    with pytest.raises(orc.OracleError):
+        orc.encode(U, p, 1, 0)
+    V = syn.update_vector(1, 0, d=d)
+    _, _, status, streams = gpu_encode([V], [p], 1, [0], want_stats=False)
+    assert status == 0
+    _, status = gpu_decode(streams, d)                             # the server expects PQ streams
+    assert status & cv.DEV_STREAM
+    pq = orc.plan_manual(d, [8], [100])
+    _, _, _, streams = gpu_encode([V], [pq], 1, [0], want_stats=False)
+    out, status = gpu_decode(streams, d, quant=cv.QUANT_QSGD)      # and the other way round
+    assert status & cv.DEV_STREAM and not out.any()
+    with pytest.raises(cv.CvlcError):                              # one quantiser per batch
+        gpu_encode([V, V], [p, pq], 1, [0, 1], want_stats=False)
+    with pytest.raises(cv.CvlcError):
+        cv.plan_manual(d, [4, 1], [10, 10], quant=cv.QUANT_QSGD)
 
 
 # --------------------------------------------------------------------------- power-law exponent (Algorithm 1, first step)
