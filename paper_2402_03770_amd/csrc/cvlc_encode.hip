@@ -1134,6 +1134,8 @@ __device__ __forceinline__ SquareLimbs square_limbs(uint32_t value_bits) {
   return r;
 }
 
+constexpr uint32_t kLimbBanks = 2;  // copies of a workgroup's limb counters, to thin out colliding LDS atomics
+
 // Every wavefront takes spans of 512 candidates (gw, gw + wavefronts, ...) and
 // writes, per span, the number of members of every group (for the records'
 // places in the stream).  Min, max and sum of squares of the groups go to LDS
@@ -1145,7 +1147,7 @@ template <bool QSGD>
 __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* __restrict__ params,
                                                            ClientCtl* __restrict__ ctls, Workspace ws) {
   __shared__ Thresholds thr;
-  __shared__ unsigned long long s_limb[QSGD ? 32 : 1][kNormLimbs];
+  __shared__ unsigned long long s_limb[QSGD ? kLimbBanks : 1][QSGD ? 32 : 1][kNormLimbs];  // bank = lane mod kLimbBanks
   __shared__ uint32_t s_max[33][kWave], s_negmin[33][kWave];
   __shared__ double s_sq[33][kWave];
   __shared__ uint32_t s_cnt[kEmitWaves][32];
@@ -1164,7 +1166,7 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
     (&s_sq[0][0])[i] = 0.0;
   }
   if (QSGD)
-    for (uint32_t i = tid; i < 32 * kNormLimbs; i += kEmitBlock) (&s_limb[0][0])[i] = 0;
+    for (uint32_t i = tid; i < kLimbBanks * 32 * kNormLimbs; i += kEmitBlock) (&s_limb[0][0][0])[i] = 0;
   __syncthreads();
   for (uint32_t span = blockIdx.x * kEmitWaves + wave; span < n_spans; span += gridDim.x * kEmitWaves) {
     uint32_t v[kPerLane], grp[kPerLane];
@@ -1190,9 +1192,10 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
         atomicAdd(&s_sq[g][lane], (double)x * (double)x);
         if (QSGD && g < R) {
           const SquareLimbs sl = square_limbs(v[j]);  // word + 2 <= 17
-          atomicAdd(&s_limb[g][sl.word], (unsigned long long)sl.part[0]);
-          if (sl.part[1]) atomicAdd(&s_limb[g][sl.word + 1], (unsigned long long)sl.part[1]);
-          if (sl.part[2]) atomicAdd(&s_limb[g][sl.word + 2], (unsigned long long)sl.part[2]);
+          unsigned long long* mine = s_limb[lane % kLimbBanks][g] + sl.word;
+          atomicAdd(mine, (unsigned long long)sl.part[0]);
+          if (sl.part[1]) atomicAdd(mine + 1, (unsigned long long)sl.part[1]);
+          if (sl.part[2]) atomicAdd(mine + 2, (unsigned long long)sl.part[2]);
         }
       }
     }
@@ -1201,7 +1204,8 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
   if (QSGD) {  // a workgroup sees fewer than 2^31 candidates, so no counter has wrapped
     unsigned long long* dst = ws.norm_limbs + (size_t)client * 32 * kNormLimbs;
     for (uint32_t i = tid; i < R * kNormLimbs; i += kEmitBlock) {
-      const unsigned long long t = (&s_limb[0][0])[i];
+      unsigned long long t = 0;
+      for (uint32_t b = 0; b < kLimbBanks; ++b) t += (&s_limb[b][0][0])[i];
       if (t) atomicAdd(&dst[i], t);
     }
   }
@@ -1343,14 +1347,17 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
       // square reaches the sum: squares grow with the bit pattern, so a binary search over it
       const unsigned long long* src = ws.norm_limbs + ((size_t)client * 32 + r) * kNormLimbs;
       unsigned long long carry = 0;
+      int top = -1;  // highest limb that is not zero
       for (uint32_t i = 0; i < kNormLimbs; ++i) {
         const unsigned long long t = src[i] + carry;
         s_sum[r][i] = (uint32_t)t;
+        if ((uint32_t)t) top = (int)i;
         carry = t >> 32;
       }
       auto reaches = [&](uint32_t key) {  // key^2 >= sum, compared limb by limb from the top
         const SquareLimbs sl = square_limbs(key);
-        for (int i = (int)kNormLimbs - 1; i >= 0; --i) {
+        const int from = max(top, (int)sl.word + 2);
+        for (int i = from; i >= 0; --i) {
           const uint32_t j = (uint32_t)i - sl.word;  // wraps to a large value below sl.word
           const uint32_t mine = j < 3u ? sl.part[j] : 0u;
           const uint32_t theirs = s_sum[r][i];
@@ -1362,6 +1369,21 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
       if (!reaches(hi)) {
         atomicOr(ws.status, CVLC_DEV_NONFINITE);  // the norm overflows fp32
         lo = hi;
+      } else if (top >= 0) {
+        // a floating-point estimate from the three top limbs brackets the answer within a few
+        // patterns; the exact comparison decides, and the full range stays as the fallback
+        double head = (double)s_sum[r][top];
+        if (top >= 1) head = head * 4294967296.0 + (double)s_sum[r][top - 1];
+        if (top >= 2) head = head * 4294967296.0 + (double)s_sum[r][top - 2];
+        const float guess = (float)sqrt(ldexp(head, 32 * (top - (top >= 2 ? 2 : top)) - 298));
+        const uint32_t g = min(__float_as_uint(guess), 0x7F7FFFFFu);
+        const uint32_t glo = g > 2u ? g - 2u : 0u, ghi = g < 0x7F7FFFFDu ? g + 2u : 0x7F7FFFFFu;
+        if (reaches(ghi) && (glo == 0u || !reaches(glo - 1u))) {
+          lo = glo;
+          hi = ghi;
+        }
+      } else {
+        hi = 0;  // an all-zero group
       }
       while (lo < hi) {
         const uint32_t mid = lo + (hi - lo) / 2u;

@@ -545,6 +545,28 @@ def test_full_size_32_clients(cfg):
     assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= tol)
 
 
+def test_full_size_qsgd_8_clients():
+    """cfg 3's vectors at full length with the second quantiser: 8 clients, 1 bit/coordinate spread
+    over eight code lengths; streams (norms included) word for word, aggregate element by element."""
+    w = syn.WORKLOADS[3]
+    n, d = 8, w.d
+    host = _parallel(lambda c: syn.update_vector(3, c), range(n), workers=8)
+    pq = orc.plan_budget(d, w.budget_bits(0), [12, 10, 8, 6, 5, 4, 3, 2])
+    plan = orc.plan_manual(d, pq.code_len(), pq.counts(), quant=orc.QSGD)
+    words, stats, status, dev_streams = gpu_encode(host, [plan] * n, w.quant_seed, list(range(n)), error_stats=True)
+    assert status == 0
+    refs = _parallel(lambda c: orc.encode(host[c], plan, w.quant_seed, c), range(n))
+    for c in range(n):
+        assert_stream_equal(words[c], refs[c].words, f"client {c}")
+        assert_stats_close(stats[c], refs[c].stats, plan.R, error_stats=True)
+    got, status = gpu_decode(dev_streams, d, quant=cv.QUANT_QSGD)
+    assert status == 0
+    ref_streams = [r.words for r in refs]
+    ref = orc.decode_aggregate(ref_streams, d)
+    tol = 1e-5 * abs_terms(ref_streams, d)
+    assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= tol)
+
+
 def test_fit_alpha_full_size_32_clients():
     """The benchmark's launch configuration of the exponent fit: 32 clients, d = 11.2M."""
     w = syn.WORKLOADS[3]
