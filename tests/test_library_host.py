@@ -140,5 +140,17 @@ def test_next_scale_and_stats_gamma_match_the_oracle():
         gs = [cv.SegStats(0.0, 0.0, float(rng.uniform(0, 5)), 1, 0, float(rng.uniform(0, 1))) for _ in range(R + 1)]
         os_ = [orc.SegStats(g.min, g.max, g.sumsq, g.count, 0, g.errsq) for g in gs]
         assert cv.stats_gamma(gs, R) == orc.empirical_gamma(os_, R)
+    for _ in range(20):                                           # the second quantiser's error model
+        d = int(rng.integers(1000, 2_000_000))
+        R = int(rng.integers(1, 7))
+        y = sorted(rng.choice([2, 3, 4, 6, 8, 12, 16, 32], size=R).tolist(), reverse=True)
+        P = [int(v) for v in rng.integers(0, d // (R + 1), size=R)]
+        pg = cv.plan_manual(d, y, P, B=2.0, quant=cv.QUANT_QSGD)
+        po = orc.plan_manual(d, y, P, B=2.0, quant=orc.QSGD)
+        assert pg.total_bits == po.total_bits
+        assert cv.plan_next_scale(pg) == orc.next_scale(po)
+        assert cv.plan_gamma(pg, -0.6) == pytest.approx(orc.gamma(po, -0.6), rel=1e-12)
+    with pytest.raises(cv.CvlcError):
+        cv.plan_manual(1000, [1], [10], quant=cv.QUANT_QSGD)
     assert cv.stats_gamma([cv.SegStats()] * 2, 1) == 0.0
     assert C.sizeof(cv.SegStats) == C.sizeof(orc.SegStats) == 32
