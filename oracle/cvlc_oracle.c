@@ -812,6 +812,133 @@ int64_t orc_unpack(const uint32_t* stream, uint64_t nwords, uint32_t d, uint32_t
   return k;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Packets (Sec. IV-C, Eq. (3); Sec. IV-D).  A stream is cut into packets of  */
+/* at most mtu bytes, every packet carrying records of one group only and a   */
+/* header from which the parameter server can decode it on its own: s, y_r    */
+/* and the centroid distribution, as the paper lists, plus what ties it back  */
+/* to its place (group, first record) and the stream's global fields.         */
+/*   word 0 "CVLP"; 1 version | quant << 16; 2 d; 3 client; 4 bits(B);        */
+/*   5 r | R << 8 | y_r << 16 | s << 24; 6 P_r; 7 e0 (first record's number    */
+/*   inside its group); 8, 9 the group's two centroid words;                  */
+/*   then c = min(cap_r, P_r - e0) records of W_r bits from bit 0, zero padded */
+/*   to a word; cap_r = floor((8 mtu - H) / W_r) with H = 320, the largest P   */
+/*   that satisfies Eq. (3).  Packets are numbered group by group; an empty    */
+/*   group still sends one packet (c = 0) so that its header survives.         */
+/* ------------------------------------------------------------------------- */
+#define ORC_PKT_MAGIC 0x504C5643u
+#define ORC_PKT_HEADER_WORDS 10u
+
+static int pkt_mtu_ok(uint32_t mtu) { return mtu % 4u == 0 && mtu >= 64u && mtu <= 65532u; }
+
+static uint32_t pkt_cap(uint32_t mtu, uint32_t W) { return (8u * mtu - 32u * ORC_PKT_HEADER_WORDS) / W; }
+
+static uint32_t pkt_count_of_group(uint32_t P, uint32_t cap) { return P == 0 ? 1u : (P + cap - 1u) / cap; }
+
+int64_t orc_packet_count(const orc_plan* p, uint32_t mtu) {
+  if (!p || !pkt_mtu_ok(mtu)) return ORC_ERR_ARG;
+  int64_t n = 0;
+  for (uint32_t r = 0; r < p->R; ++r) {
+    uint32_t cap = pkt_cap(mtu, p->s + p->y[r]);
+    if (cap < 1) return ORC_ERR_ARG;
+    n += pkt_count_of_group(p->P[r], cap);
+  }
+  return n;
+}
+
+/* Cuts a stream into packets laid out at a stride of mtu bytes in packets_out
+ * (zero filled behind each packet's end); sizes_out[p] receives packet p's
+ * length in bytes.  Returns the number of packets or a negative error. */
+int64_t orc_packetize(const uint32_t* stream, uint64_t nwords, uint32_t d, uint32_t mtu,
+                      uint32_t* packets_out, uint64_t cap_packets, uint32_t* sizes_out) {
+  if (!stream || !packets_out || !pkt_mtu_ok(mtu)) return ORC_ERR_ARG;
+  orc_header h;
+  int rc = parse_header(stream, nwords, d, &h);
+  if (rc) return rc;
+  uint32_t stride = mtu / 4u;
+  uint64_t n = 0;
+  for (uint32_t r = 0; r < h.R; ++r) {
+    uint32_t W = h.s + h.y[r], cap = pkt_cap(mtu, W);
+    if (cap < 1) return ORC_ERR_ARG;
+    uint32_t npk = pkt_count_of_group(h.P[r], cap);
+    const uint32_t* hdr = stream + ORC_GLOBAL_HEADER_WORDS + ORC_SEG_HEADER_WORDS * r;
+    for (uint32_t j = 0; j < npk; ++j, ++n) {
+      if (n >= cap_packets) return ORC_ERR_CAPACITY;
+      uint32_t* pk = packets_out + n * stride;
+      memset(pk, 0, (size_t)mtu);
+      uint32_t e0 = j * cap, c = h.P[r] - e0 < cap ? h.P[r] - e0 : cap;
+      pk[0] = ORC_PKT_MAGIC; pk[1] = stream[1]; pk[2] = h.d; pk[3] = h.client; pk[4] = f2u(h.B);
+      pk[5] = r | (h.R << 8) | (h.y[r] << 16) | (h.s << 24);
+      pk[6] = h.P[r]; pk[7] = e0; pk[8] = hdr[2]; pk[9] = hdr[3];
+      for (uint32_t e = 0; e < c; ++e)
+        put_bits(pk + ORC_PKT_HEADER_WORDS, (uint64_t)e * W,
+                 get_bits(stream + h.payload_word[r], (uint64_t)(e0 + e) * W, W), W);
+      if (sizes_out) sizes_out[n] = 4u * (ORC_PKT_HEADER_WORDS + (uint32_t)seg_payload_words(c, W));
+    }
+  }
+  return (int64_t)n;
+}
+
+/* Puts a stream back together from all its packets, given in any order at a
+ * stride of mtu bytes.  Every packet must agree with the others on the global
+ * fields and on its group's fields, and every (group, packet number) must be
+ * there exactly once.  Returns the stream's length in words or a negative error. */
+int64_t orc_depacketize(const uint32_t* packets, uint32_t n_packets, uint32_t mtu, uint32_t d,
+                        uint32_t* words_out, uint64_t cap_words) {
+  if (!packets || !words_out || !pkt_mtu_ok(mtu) || n_packets < 1) return ORC_ERR_ARG;
+  uint32_t stride = mtu / 4u;
+  const uint32_t* first = packets;
+  uint32_t R = (first[5] >> 8) & 0xFFu, s = first[5] >> 24;
+  if (first[0] != ORC_PKT_MAGIC || R > ORC_MAX_R || first[2] != d || s != orc_s_bits(d)) return ORC_ERR_STREAM;
+  uint32_t y[ORC_MAX_R], P[ORC_MAX_R], c0[ORC_MAX_R], c1[ORC_MAX_R], have[ORC_MAX_R];
+  memset(have, 0, sizeof(have));
+  for (uint32_t i = 0; i < n_packets; ++i) { /* the first packet of every group describes it */
+    const uint32_t* pk = packets + (uint64_t)i * stride;
+    uint32_t r = pk[5] & 0xFFu;
+    if (pk[0] != ORC_PKT_MAGIC || r >= R) return ORC_ERR_STREAM;
+    if (pk[7] == 0) {
+      if (have[r]) return ORC_ERR_STREAM;
+      have[r] = 1; y[r] = (pk[5] >> 16) & 0xFFu; P[r] = pk[6]; c0[r] = pk[8]; c1[r] = pk[9];
+    }
+  }
+  uint64_t base[ORC_MAX_R + 1], payload[ORC_MAX_R + 1];
+  base[0] = 0; payload[0] = ORC_GLOBAL_HEADER_WORDS + (uint64_t)ORC_SEG_HEADER_WORDS * R;
+  for (uint32_t r = 0; r < R; ++r) {
+    if (!have[r] || !code_len_ok(y[r])) return ORC_ERR_STREAM;
+    uint32_t cap = pkt_cap(mtu, s + y[r]);
+    if (cap < 1) return ORC_ERR_STREAM;
+    base[r + 1] = base[r] + pkt_count_of_group(P[r], cap);
+    payload[r + 1] = payload[r] + seg_payload_words(P[r], s + y[r]);
+  }
+  if (base[R] != n_packets) return ORC_ERR_STREAM;
+  if (payload[R] > cap_words || payload[R] > 0xFFFFFFFFull) return ORC_ERR_CAPACITY;
+  memset(words_out, 0, (size_t)payload[R] * 4u);
+  words_out[0] = ORC_MAGIC; words_out[1] = first[1]; words_out[2] = d; words_out[3] = R; words_out[4] = s;
+  words_out[5] = first[4]; words_out[6] = first[3]; words_out[7] = (uint32_t)payload[R];
+  uint8_t* seen = (uint8_t*)calloc(n_packets, 1);
+  if (!seen) return ORC_ERR_ARG;
+  for (uint32_t i = 0; i < n_packets; ++i) {
+    const uint32_t* pk = packets + (uint64_t)i * stride;
+    uint32_t r = pk[5] & 0xFFu, W = s + y[r], cap = pkt_cap(mtu, W), e0 = pk[7];
+    int ok = pk[1] == first[1] && pk[2] == d && pk[3] == first[3] && pk[4] == first[4] &&
+             pk[5] == (r | (R << 8) | (y[r] << 16) | (s << 24)) && pk[6] == P[r] && pk[8] == c0[r] && pk[9] == c1[r] &&
+             e0 % cap == 0 && (e0 < P[r] || (e0 == 0 && P[r] == 0));
+    if (ok) {
+      uint64_t slot = base[r] + e0 / cap;
+      ok = !seen[slot];
+      seen[slot] = 1;
+    }
+    if (!ok) { free(seen); return ORC_ERR_STREAM; }
+    uint32_t c = P[r] - e0 < cap ? P[r] - e0 : cap;
+    for (uint32_t e = 0; e < c; ++e)
+      put_bits(words_out + payload[r], (uint64_t)(e0 + e) * W, get_bits(pk + ORC_PKT_HEADER_WORDS, (uint64_t)e * W, W), W);
+    uint32_t* hdr = words_out + ORC_GLOBAL_HEADER_WORDS + ORC_SEG_HEADER_WORDS * r;
+    hdr[0] = y[r]; hdr[1] = P[r]; hdr[2] = c0[r]; hdr[3] = c1[r];
+  }
+  free(seen); /* n_packets slots, each taken once: none is missing */
+  return (int64_t)payload[R];
+}
+
 /* Scale factor for the next round (footnote to Proposition 1): max over the
  * coded groups of Q(P_r, y_r), plus 1, with PQ's quantisation error
  * Q(P, y) = P / (2^y - 1)^2 (appendix case study); a raw 32-bit group has no

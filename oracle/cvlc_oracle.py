@@ -84,6 +84,12 @@ def lib() -> C.CDLL:
         L.orc_unpack.argtypes = [u32p, C.c_uint64, C.c_uint32, u32p, u32p, u32p]
         L.orc_unpack.restype = C.c_int64
         L.orc_fit_alpha.argtypes = [f32p, C.c_uint32, C.POINTER(C.c_double)]
+        L.orc_packet_count.argtypes = [C.POINTER(Plan), C.c_uint32]
+        L.orc_packet_count.restype = C.c_int64
+        L.orc_packetize.argtypes = [u32p, C.c_uint64, C.c_uint32, C.c_uint32, u32p, C.c_uint64, u32p]
+        L.orc_packetize.restype = C.c_int64
+        L.orc_depacketize.argtypes = [u32p, C.c_uint32, C.c_uint32, C.c_uint32, u32p, C.c_uint64]
+        L.orc_depacketize.restype = C.c_int64
         L.orc_qsgd_norm.argtypes = [f32p, C.c_uint32, C.POINTER(C.c_float)]
         L.orc_quantise_qsgd.argtypes = [C.c_float, C.c_float, C.c_uint32, C.c_uint32]
         L.orc_quantise_qsgd.restype = C.c_uint32
@@ -248,6 +254,34 @@ def unpack(stream: np.ndarray, d: int) -> Tuple[np.ndarray, np.ndarray, np.ndarr
     if k < 0:
         raise OracleError(int(k), "unpack")
     return pid[:k], cid[:k], seg[:k]
+
+
+def packet_count(plan: Plan, mtu: int = 1500) -> int:
+    n = int(lib().orc_packet_count(C.byref(plan), mtu))
+    if n < 0:
+        raise OracleError(n, "packet_count")
+    return n
+
+
+def packetize(stream: np.ndarray, d: int, mtu: int = 1500) -> Tuple[np.ndarray, np.ndarray]:
+    """(packets as an (n, mtu/4) uint32 array, zero behind each packet's end; their lengths in bytes)."""
+    cap = stream.size // 1 + 64   # never more packets than words
+    buf = np.zeros((cap, mtu // 4), dtype=np.uint32)
+    sizes = np.zeros(cap, dtype=np.uint32)
+    n = int(lib().orc_packetize(_u32(stream), stream.size, d, mtu, _u32(buf), cap, _u32(sizes)))
+    if n < 0:
+        raise OracleError(n, "packetize")
+    return buf[:n].copy(), sizes[:n].copy()
+
+
+def depacketize(packets: np.ndarray, d: int, mtu: int = 1500, cap_words: Optional[int] = None) -> np.ndarray:
+    packets = np.ascontiguousarray(packets, dtype=np.uint32)
+    cap = int(cap_words) if cap_words is not None else packets.size + 64
+    out = np.zeros(cap, dtype=np.uint32)
+    n = int(lib().orc_depacketize(_u32(packets), packets.shape[0], mtu, d, _u32(out), cap))
+    if n < 0:
+        raise OracleError(n, "depacketize")
+    return out[:n].copy()
 
 
 def qsgd_norm(x: np.ndarray) -> float:

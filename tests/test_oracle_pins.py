@@ -709,3 +709,67 @@ def test_qsgd_stream_layout_and_plan_rules():
     # the error model of the appendix: min(P/s^2, sqrt(P)/s) with s = 2^(y-1) - 1
     q = orc.plan_manual(100_000, [6, 3], [400, 10_000], quant=orc.QSGD)
     assert orc.next_scale(q) == pytest.approx(1.0 + min(10_000 / 9.0, 100.0 / 3.0), rel=1e-15)
+
+
+# --------------------------------------------------------------------------- packets (Eq. (3), Sec. IV-D)
+def test_packets_obey_the_size_constraint_and_carry_their_own_header():
+    """Eq. (3): P (s + y_r) + H <= b for every packet, with the largest P that fits; one code length
+    per packet; the fields the paper lists (s, y_r, centroid distribution) are in every packet, read
+    here straight from the bits."""
+    d = 40_000
+    U = syn.update_vector(3, 6, d=d)
+    for quant, ys in ((orc.PQ, [32, 9, 4, 1]), (orc.QSGD, [32, 9, 4, 2])):
+        p = orc.plan_manual(d, ys, [300, 2500, 0, 9000], B=1.5, quant=quant)
+        enc = orc.encode(U, p, 11, 7)
+        for mtu in (1500, 256, 9000):
+            pk, sizes = orc.packetize(enc.words, d, mtu)
+            assert pk.shape[0] == orc.packet_count(p, mtu)
+            b, H, s = 8 * mtu, 320, p.s
+            pid, cid, seg = orc.unpack(enc.words, d)
+            at = 0
+            for r, (y, P) in enumerate(zip(ys, p.counts())):
+                W = s + y
+                cap = (b - H) // W
+                assert cap * W + H <= b < (cap + 1) * W + H                   # maximal under Eq. (3)
+                npk = max(1, -(-P // cap))
+                rec_pid, rec_cid = pid[seg == r + 1], cid[seg == r + 1]
+                for j in range(npk):
+                    w = pk[at]
+                    c = min(cap, P - j * cap)
+                    assert int(sizes[at]) == 4 * (10 + -(-c * W // 32)) <= mtu
+                    assert w[0] == 0x504C5643 and w[1] == enc.words[1] and w[2] == d and w[3] == 7
+                    assert w[4] == enc.words[5]                                # B
+                    assert w[5] == r | (4 << 8) | (y << 16) | (s << 24) and w[6] == P and w[7] == j * cap
+                    assert w[8] == enc.words[8 + 4 * r + 2] and w[9] == enc.words[8 + 4 * r + 3]
+                    bits = _bits_of(w[10:])
+                    for e in (0, c // 2, c - 1) if c else ():
+                        assert _field(bits, e * W, s) == int(rec_pid[j * cap + e])
+                        assert _field(bits, e * W + s, y) == int(rec_cid[j * cap + e])
+                    assert not bits[c * W:].any()                              # padding and the slot's tail are zero
+                    at += 1
+            assert at == pk.shape[0]
+
+
+def test_packets_reassemble_in_any_order_and_reject_loss_and_tampering():
+    d = 25_000
+    U = syn.update_vector(1, 3, d=d)
+    p = orc.plan_manual(d, [12, 6, 3], [700, 0, 5000])
+    enc = orc.encode(U, p, 5, 2)
+    pk, _ = orc.packetize(enc.words, d, 1500)
+    assert np.array_equal(orc.depacketize(pk, d), enc.words)
+    rng = np.random.default_rng(3)
+    assert np.array_equal(orc.depacketize(pk[rng.permutation(pk.shape[0])], d), enc.words)
+    with pytest.raises(orc.OracleError):
+        orc.depacketize(pk[:-1], d)                                            # a packet is missing
+    with pytest.raises(orc.OracleError):
+        orc.depacketize(np.concatenate([pk, pk[3:4]]), d)                      # one arrives twice
+    for word, value in ((0, 1), (2, d - 1), (5, int(pk[4][5]) ^ (1 << 16)), (6, int(pk[4][6]) + 1), (7, 1), (8, 0)):
+        bad = pk.copy()
+        bad[4][word] = value
+        with pytest.raises(orc.OracleError):
+            orc.depacketize(bad, d)
+    # a stream that is nothing but headers still travels: one packet per (empty) group
+    empty = orc.encode(U, orc.plan_manual(d, [8, 2], [0, 0]), 5, 2)
+    pk, sizes = orc.packetize(empty.words, d, 1500)
+    assert pk.shape[0] == 2 and sizes.tolist() == [40, 40]
+    assert np.array_equal(orc.depacketize(pk, d), empty.words)
