@@ -207,6 +207,45 @@ size_t cvlc_fit_workspace_bytes(uint32_t n_clients);
 int cvlc_fit_alpha(uint32_t n, const float* const* d_updates, uint32_t d, double* d_alpha_out,
                    uint32_t* d_keys_out, void* d_workspace, size_t ws_bytes, void* hip_stream);
 
+/* Packets (Sec. IV-C Eq. (3), Sec. IV-D).  A stream is cut into packets of at
+ * most mtu_bytes (a multiple of 4 in 64..65532; 1500 in the paper), each with
+ * records of one group only and a header of CVLC_PACKET_HEADER_WORDS words that
+ * lets the parameter server place and decode it on its own:
+ *   0 "CVLP"  1 version | quantiser << 16  2 d  3 client  4 bits(B)
+ *   5 r | R << 8 | y_r << 16 | s << 24     6 P_r
+ *   7 e0 = number of the packet's first record inside its group
+ *   8, 9 the group's centroid words ({min, max} or {norm, 0})
+ * followed by min(cap_r, P_r - e0) records of s + y_r bits from bit 0, zero
+ * padded to a word; cap_r = floor((8 mtu - 320) / (s + y_r)), the largest count
+ * Eq. (3) allows with H = 320 bits.  Packets are numbered group by group (an
+ * empty group sends one packet without records) and sit at a stride of
+ * mtu_bytes in memory, zero filled behind each packet's end. */
+#define CVLC_PACKET_HEADER_WORDS 10u
+
+/* CPU.  Number of packets of a stream made with this plan (0: invalid plan or
+ * mtu), and the length in bytes of packet `index` (0: out of range). */
+uint32_t cvlc_packet_count(const cvlc_plan_t* plan, uint32_t mtu_bytes);
+uint32_t cvlc_packet_size(const cvlc_plan_t* plan, uint32_t mtu_bytes, uint32_t index);
+
+/* GPU, sender.  Cuts the stream that cvlc_encode wrote for `plan` into packets.
+ *   d_stream       device, the encoded stream (4-byte aligned)
+ *   d_packets_out  device, 4-byte aligned, capacity >= cvlc_packet_count * mtu_bytes */
+int cvlc_packetize(const cvlc_plan_t* plan, const void* d_stream, uint32_t mtu_bytes, void* d_packets_out,
+                   size_t capacity, void* hip_stream);
+
+/* GPU, receiver.  Puts a stream back together from all n_packets packets of one
+ * client, given in any order at a stride of mtu_bytes.  Every packet must agree
+ * with the others on the global fields and on its group's fields, and every
+ * place must be taken exactly once; otherwise CVLC_DEV_STREAM is set in the
+ * workspace's status word and d_stream_out does not hold a stream (its first
+ * word is cleared).  The result is what cvlc_decode_aggregate takes.
+ *   d_stream_out  device, 4-byte aligned, `capacity` bytes (a stream that needs
+ *                 more is refused the same way)
+ *   d_workspace   device, 256-byte aligned, >= cvlc_depacketize_workspace_bytes(n_packets) */
+size_t cvlc_depacketize_workspace_bytes(uint32_t n_packets);
+int cvlc_depacketize(const void* d_packets, uint32_t n_packets, uint32_t mtu_bytes, uint32_t d,
+                     void* d_stream_out, size_t capacity, void* d_workspace, size_t ws_bytes, void* hip_stream);
+
 /* Waits for hip_stream and copies the workspace's device status word to
  * *status_out (0 = clean, else CVLC_DEV_* bits). */
 int cvlc_device_status(const void* d_workspace, void* hip_stream, uint32_t* status_out);

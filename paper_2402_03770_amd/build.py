@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcvlc.so")
-SOURCES = ["cvlc_plan.cpp", "cvlc_encode.hip", "cvlc_decode.hip", "cvlc_rank.hip"]
+SOURCES = ["cvlc_plan.cpp", "cvlc_encode.hip", "cvlc_decode.hip", "cvlc_rank.hip", "cvlc_packet.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off", "-fno-fast-math", "-munsafe-fp-atomics",

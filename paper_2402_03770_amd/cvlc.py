@@ -96,6 +96,14 @@ def lib() -> C.CDLL:
         L.cvlc_decode_aggregate.argtypes = [C.c_uint32, C.POINTER(vp), szp, C.POINTER(C.c_float), vp, C.c_uint32,
                                             C.c_uint32, vp, C.c_size_t, vp]
         L.cvlc_device_status.argtypes = [vp, vp, u32p]
+        L.cvlc_packet_count.argtypes = [C.POINTER(Plan), C.c_uint32]
+        L.cvlc_packet_count.restype = C.c_uint32
+        L.cvlc_packet_size.argtypes = [C.POINTER(Plan), C.c_uint32, C.c_uint32]
+        L.cvlc_packet_size.restype = C.c_uint32
+        L.cvlc_packetize.argtypes = [C.POINTER(Plan), vp, C.c_uint32, vp, C.c_size_t, vp]
+        L.cvlc_depacketize_workspace_bytes.argtypes = [C.c_uint32]
+        L.cvlc_depacketize_workspace_bytes.restype = C.c_size_t
+        L.cvlc_depacketize.argtypes = [vp, C.c_uint32, C.c_uint32, C.c_uint32, vp, C.c_size_t, vp, C.c_size_t, vp]
         L.cvlc_fit_ranks.argtypes = [C.c_uint32, u32p]
         L.cvlc_fit_ranks.restype = C.c_uint32
         L.cvlc_fit_workspace_bytes.argtypes = [C.c_uint32]
@@ -179,6 +187,18 @@ def decode_workspace_bytes(d: int, n_clients: int) -> int:
     return int(lib().cvlc_decode_workspace_bytes(d, n_clients))
 
 
+def packet_count(p: Plan, mtu: int = 1500) -> int:
+    return int(lib().cvlc_packet_count(C.byref(p), mtu))
+
+
+def packet_size(p: Plan, index: int, mtu: int = 1500) -> int:
+    return int(lib().cvlc_packet_size(C.byref(p), mtu, index))
+
+
+def depacketize_workspace_bytes(n_packets: int) -> int:
+    return int(lib().cvlc_depacketize_workspace_bytes(n_packets))
+
+
 def fit_ranks(d: int) -> List[int]:
     """cvlc_fit_ranks: the ranks at which cvlc_fit_alpha reads the magnitudes."""
     out = (C.c_uint32 * FIT_RANKS_MAX)()
@@ -241,6 +261,20 @@ def decode_aggregate(streams: Sequence[torch.Tensor], out: torch.Tensor, workspa
                                        (DECODE_ACCUMULATE if accumulate else 0) | (DECODE_QSGD if quant == QUANT_QSGD else 0),
                                        workspace.data_ptr(),
                                        workspace.numel(), _stream_handle()), "cvlc_decode_aggregate")
+
+
+def packetize(p: Plan, stream: torch.Tensor, packets_out: torch.Tensor, mtu: int = 1500) -> None:
+    """cvlc_packetize on the current stream; `packets_out` holds packet_count(p, mtu) * mtu bytes."""
+    _check(lib().cvlc_packetize(C.byref(p), stream.data_ptr(), mtu, packets_out.data_ptr(),
+                                packets_out.numel() * packets_out.element_size(), _stream_handle()), "cvlc_packetize")
+
+
+def depacketize(packets: torch.Tensor, n_packets: int, d: int, stream_out: torch.Tensor, workspace: torch.Tensor,
+                mtu: int = 1500) -> None:
+    """cvlc_depacketize on the current stream."""
+    _check(lib().cvlc_depacketize(packets.data_ptr(), n_packets, mtu, d, stream_out.data_ptr(),
+                                  stream_out.numel() * stream_out.element_size(), workspace.data_ptr(),
+                                  workspace.numel(), _stream_handle()), "cvlc_depacketize")
 
 
 def fit_alpha(updates: Sequence[torch.Tensor], alpha_out: torch.Tensor, workspace: torch.Tensor,

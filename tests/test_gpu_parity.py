@@ -435,6 +435,108 @@ def test_qsgd_norm_overflow_and_mismatched_quantiser_are_reported():
         cv.plan_manual(d, [4, 1], [10, 10], quant=cv.QUANT_QSGD)
 
 
+# --------------------------------------------------------------------------- packets
+def gpu_packetize(plan_lib, stream_dev, mtu):
+    n = cv.packet_count(plan_lib, mtu)
+    buf = torch.full((max(n, 1) * mtu // 4,), -1, dtype=torch.int32, device=DEV)   # every word of every slot is written
+    cv.packetize(plan_lib, stream_dev, buf, mtu)
+    torch.cuda.synchronize()
+    return buf, n
+
+
+def gpu_depacketize(packets_dev, n, d, mtu, cap_words):
+    out = torch.full((cap_words,), -1, dtype=torch.int32, device=DEV)
+    ws = cv.new_workspace(cv.depacketize_workspace_bytes(n), DEV)
+    ws.fill_(0x5A)
+    cv.depacketize(packets_dev, n, d, out, ws, mtu)
+    return out, cv.device_status(ws)
+
+
+@pytest.mark.parametrize("mtu", [1500, 64, 9000])
+def test_packets_match_the_oracle_and_reassemble(mtu):
+    """Sender: the packets of a GPU-encoded stream are the oracle's, byte for byte.  Receiver: from
+    the packets in shuffled order the stream comes back bit for bit and decodes as before."""
+    d = 120_011
+    host = [syn.update_vector(3, 0, d=d), syn.tie_heavy_vector("few_levels", d, seed=1)]
+    plans = [orc.plan_manual(d, [32, 11, 5, 2, 1], [200, 3000, 0, 9000, 17_001], B=2.0),
+             orc.plan_manual(d, [7, 3], [1, 40_000], quant=orc.QSGD)]
+    for U, po in zip(host, plans):
+        words, _, status, streams = gpu_encode([U], [po], 17, [12], want_stats=False)
+        assert status == 0
+        ref_pk, ref_sizes = orc.packetize(words[0], d, mtu)
+        pl = to_lib_plan(po)
+        buf, n = gpu_packetize(pl, streams[0], mtu)
+        assert n == ref_pk.shape[0]
+        got = buf.cpu().numpy().view(np.uint32).reshape(n, mtu // 4)
+        assert np.array_equal(got, ref_pk)
+        assert [cv.packet_size(pl, i, mtu) for i in range(n)] == ref_sizes.tolist()
+        g = torch.Generator(device="cpu")
+        g.manual_seed(5)
+        shuffled = buf.view(n, mtu // 4)[torch.randperm(n, generator=g).to(DEV)].contiguous()
+        out, status = gpu_depacketize(shuffled, n, d, mtu, words[0].size + 7)
+        assert status == 0
+        back = out.cpu().numpy().view(np.uint32)
+        assert np.array_equal(back[: words[0].size], words[0])
+        assert np.array_equal(back[: words[0].size], orc.depacketize(ref_pk, d, mtu))
+        assert np.all(back[words[0].size:] == 0xFFFFFFFF)                      # nothing written behind the stream
+        dec, status = gpu_decode([out], d, quant=int(po.quant))
+        assert status == 0
+        assert np.array_equal(dec.view(np.uint32), orc.decode_aggregate([words[0]], d).view(np.uint32))
+
+
+def test_reassembly_refuses_loss_duplicates_tampering_and_short_buffers():
+    d, mtu = 50_000, 1500
+    U = syn.update_vector(1, 1, d=d)
+    po = orc.plan_manual(d, [12, 6, 3], [700, 0, 9000])
+    words, _, _, streams = gpu_encode([U], [po], 3, [1], want_stats=False)
+    buf, n = gpu_packetize(to_lib_plan(po), streams[0], mtu)
+    pk = buf.view(n, mtu // 4)
+    cap = words[0].size
+    out, status = gpu_depacketize(pk.contiguous(), n, d, mtu, cap)
+    assert status == 0 and np.array_equal(out.cpu().numpy().view(np.uint32), words[0])
+
+    def refused(packets, count, cap_words=cap):
+        out, status = gpu_depacketize(packets.contiguous(), count, d, mtu, cap_words)
+        got = out.cpu().numpy().view(np.uint32)
+        with pytest.raises(orc.OracleError):
+            orc.depacketize(packets.cpu().numpy().view(np.uint32)[:count], d, mtu, cap_words=cap_words)
+        return bool(status & cv.DEV_STREAM) and got[0] == 0
+
+    assert refused(pk[:-1], n - 1)                                             # a packet is missing
+    assert refused(torch.cat([pk, pk[3:4]]), n + 1)                            # one arrives twice
+    assert refused(torch.cat([pk[:5], pk[4:5], pk[6:]]), n)                    # one replaced by a copy of another
+    for word, value in ((0, 1), (2, d - 1), (4, 0), (6, int(pk[4, 6]) + 1), (7, 1), (8, 0)):
+        bad = pk.clone()
+        bad[4, word] = value
+        assert refused(bad, n), word
+    bad = pk.clone()
+    bad[4, 5] = int(pk[4, 5]) ^ (1 << 16)                                      # another code length
+    assert refused(bad, n)
+    assert refused(pk, n, cap_words=cap - 1)                                   # the stream does not fit
+    # the tail of a packet's payload is not trusted: junk behind the records does not reach the stream
+    junk = pk.clone()
+    last = n - 1                                                               # last packet of the last group
+    size = cv.packet_size(to_lib_plan(po), last, mtu) // 4
+    junk[last, size:] = -1
+    out, status = gpu_depacketize(junk.contiguous(), n, d, mtu, cap)
+    assert status == 0 and np.array_equal(out.cpu().numpy().view(np.uint32), words[0])
+
+
+def test_packets_at_the_benchmark_size():
+    """One client of cfg 3 at d = 11.2 M: 1.4 MB stream, 15 groups, about 950 packets of 1500 bytes."""
+    w = syn.WORKLOADS[3]
+    d = w.d
+    U = syn.update_vector(3, 5)
+    po = orc.plan_for(w, client=0, alpha=-0.5)
+    words, _, status, streams = gpu_encode([U], [po], w.quant_seed, [5], want_stats=False)
+    assert status == 0
+    ref_pk, _ = orc.packetize(words[0], d, 1500)
+    buf, n = gpu_packetize(to_lib_plan(po), streams[0], 1500)
+    assert np.array_equal(buf.cpu().numpy().view(np.uint32).reshape(n, 375), ref_pk)
+    out, status = gpu_depacketize(buf.view(n, 375).flip(0).contiguous(), n, d, 1500, words[0].size)
+    assert status == 0 and np.array_equal(out.cpu().numpy().view(np.uint32), words[0])
+
+
 # --------------------------------------------------------------------------- power-law exponent (Algorithm 1, first step)
 def gpu_fit_alpha(host_updates):
     n = len(host_updates)

@@ -154,3 +154,36 @@ def test_next_scale_and_stats_gamma_match_the_oracle():
         cv.plan_manual(1000, [1], [10], quant=cv.QUANT_QSGD)
     assert cv.stats_gamma([cv.SegStats()] * 2, 1) == 0.0
     assert C.sizeof(cv.SegStats) == C.sizeof(orc.SegStats) == 32
+
+
+def test_packet_geometry_matches_the_oracle_and_argument_errors():
+    rng = np.random.default_rng(31)
+    for _ in range(30):
+        d = int(rng.integers(1000, 3_000_000))
+        R = int(rng.integers(1, 8))
+        y = sorted(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 32], size=R).tolist(), reverse=True)
+        P = [int(v) for v in rng.integers(0, d // (R + 1), size=R)]
+        P[int(rng.integers(0, R))] = 0
+        pg, po = cv.plan_manual(d, y, P), orc.plan_manual(d, y, P)
+        for mtu in (1500, 64, 9000):
+            n = cv.packet_count(pg, mtu)
+            assert n == orc.packet_count(po, mtu)
+            sizes = [cv.packet_size(pg, i, mtu) for i in range(n)]
+            assert all(40 <= sz <= mtu and sz % 4 == 0 for sz in sizes)
+            assert cv.packet_size(pg, n, mtu) == 0
+            # what the packets carry beyond their headers and the padding of their last words is the plan's records
+            assert sum(sz - 40 for sz in sizes) * 8 >= sum(c * (pg.s + yy) for c, yy in zip(P, y))
+        assert cv.packet_count(pg, 1502) == 0 and cv.packet_count(pg, 60) == 0
+    lib = cv.lib()
+    vp = C.c_void_p
+    p = cv.plan_manual(1000, [8], [100])
+    n = cv.packet_count(p, 1500)
+    assert lib.cvlc_packetize(C.byref(p), None, 1500, vp(0x2000), n * 1500, None) == -1
+    assert lib.cvlc_packetize(C.byref(p), vp(0x1000), 1500, vp(0x2000), n * 1500 - 1, None) == -4
+    assert lib.cvlc_packetize(C.byref(p), vp(0x1000), 1501, vp(0x2000), n * 1501, None) == -1
+    ws = cv.depacketize_workspace_bytes(n)
+    assert ws > 0
+    assert lib.cvlc_depacketize(vp(0x1000), 0, 1500, 1000, vp(0x2000), 4096, vp(0x10000), ws, None) == -1
+    assert lib.cvlc_depacketize(vp(0x1000), n, 1500, 1000, vp(0x2000), 4096, vp(0x10000), ws - 1, None) == -4
+    assert lib.cvlc_depacketize(vp(0x1000), n, 1500, 1000, vp(0x2000), 16, vp(0x10000), ws, None) == -4
+    assert lib.cvlc_depacketize(vp(0x1000), n, 1500, 1000, vp(0x2000), 4096, vp(0x10010), ws, None) == -1
