@@ -6,12 +6,14 @@
 // list is sorted.  Each workgroup owns a tile of output coordinates, pulls the
 // slice of every list that falls into its tile, accumulates in LDS in fp64 and
 // writes the tile once; nothing is scattered into global memory.
-//   parse_headers  validate headers, build one descriptor per list
+//   parse_headers  validate headers (which must name the quantiser the caller
+//                  expects), build one descriptor per list
 //   compact_lists  the non-empty lists, numbered consecutively, with the
 //                  tile_table work items they need
 //   tile_table     one streaming pass over all records: for every list, the
 //                  first record of every output tile (and the order/range checks)
-//   decode_tiles   fused decode + accumulate + single write of each tile
+//   decode_tiles   fused decode + accumulate + single write of each tile (a second
+//                  instance splits QSGD's sign bit from the level)
 #include <hip/hip_runtime.h>
 
 #include <cmath>

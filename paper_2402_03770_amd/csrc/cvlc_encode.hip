@@ -32,10 +32,12 @@
 //                 boundary cuts a class of equal magnitudes, the position of
 //                 its last member inside the boundary
 //   count         per span: group of every candidate, per-group count,
-//                 min/max/sum of squares
-//   layout        prefix of the per-span counts, headers, statistics
+//                 min/max/sum of squares; for the QSGD quantiser also every
+//                 group's exact sum of squares in integer limbs
+//   layout        prefix of the per-span counts, headers (QSGD: the group norms
+//                 from the exact sums), statistics
 //   emit          per chunk of 8 spans: stochastic rounding (Philox4x32-10)
-//                 and bit packing
+//                 and bit packing; on request the error energy of every group
 #include <hip/hip_runtime.h>
 
 #include <cmath>
