@@ -326,6 +326,50 @@ def test_non_finite_update_sets_status():
             orc.encode(U, p, 1, 0)
 
 
+# --------------------------------------------------------------------------- the caller's stream
+def test_every_call_runs_on_the_callers_stream():
+    """All work is enqueued on the stream handed in: on a side stream, behind a long-running
+    kernel that produces the input, results are right without any device-wide synchronisation."""
+    d, n = 150_001, 2
+    host = [syn.update_vector(2, c, d=d) for c in range(n)]
+    po = orc.plan_alg1(d, d, 5, -0.6)
+    pl = to_lib_plan(po)
+    side = torch.cuda.Stream()
+    staged = [torch.from_numpy(u).to(DEV) for u in host]
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        filler = torch.empty(1 << 28, dtype=torch.float32, device=DEV)
+        for _ in range(4):
+            filler.normal_()                                       # keeps the side stream busy for a while
+        updates = [u * 1.0 for u in staged]                        # the inputs exist only once the side stream gets here
+        streams = [cv.new_stream_buffer(pl, DEV) for _ in range(n)]
+        ws = cv.new_workspace(cv.encode_workspace_bytes(d, n), DEV)
+        cv.encode_batch([pl] * n, updates, 8, [0, 1], streams, ws)
+        out = torch.empty(d, dtype=torch.float32, device=DEV)
+        dws = cv.new_workspace(cv.decode_workspace_bytes(d, n), DEV)
+        cv.decode_aggregate(streams, out, dws)
+        alpha = torch.empty(n, dtype=torch.float64, device=DEV)
+        fws = cv.new_workspace(cv.fit_workspace_bytes(n), DEV)
+        cv.fit_alpha(updates, alpha, fws)
+        npk = cv.packet_count(pl, 1500)
+        pk = torch.empty(npk * 375, dtype=torch.int32, device=DEV)
+        cv.packetize(pl, streams[1], pk)
+        back = torch.empty_like(streams[1])
+        pws = cv.new_workspace(cv.depacketize_workspace_bytes(npk), DEV)
+        cv.depacketize(pk, npk, d, back, pws)
+        assert cv.device_status(ws) == 0 and cv.device_status(dws) == 0 and cv.device_status(pws) == 0
+        assert cv.device_status(fws) == 0                          # each waits for the side stream only
+        refs = [orc.encode(u, po, 8, c).words for c, u in enumerate(host)]
+        for c in range(n):
+            assert_stream_equal(streams[c].cpu().numpy().view(np.uint32)[: refs[c].size], refs[c], f"client {c}")
+        assert np.array_equal(back.cpu().numpy().view(np.uint32)[: refs[1].size], refs[1])
+        ref = orc.decode_aggregate(refs, d)
+        assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * abs_terms(refs, d))
+        assert alpha.cpu().numpy().tolist() == pytest.approx([orc.fit_alpha(u) for u in host], rel=1e-11)
+    torch.cuda.synchronize()
+    del filler
+
+
 # --------------------------------------------------------------------------- error energy, scale factor across rounds
 def test_error_statistics_and_the_scale_factor_carried_across_rounds():
     """Round t uses B from round t-1's plan (footnote to Proposition 1); the encoder reports the
