@@ -370,6 +370,52 @@ def test_every_call_runs_on_the_callers_stream():
     del filler
 
 
+def test_calls_can_be_captured_in_a_graph_and_replayed():
+    """The calls only launch kernels on the caller's stream (clears included), so a step can be
+    recorded once and replayed: three replays on fresh inputs, with eager work and
+    synchronisation in between, each checked against the oracle."""
+    d, n = 90_001, 3
+    po = orc.plan_manual(d, [10, 5, 2], [900, 4000, 9000])
+    pl = to_lib_plan(po)
+    updates = [torch.zeros(d, dtype=torch.float32, device=DEV) for _ in range(n)]
+    streams = [cv.new_stream_buffer(pl, DEV) for _ in range(n)]
+    ws = cv.new_workspace(cv.encode_workspace_bytes(d, n), DEV)
+    dws = cv.new_workspace(cv.decode_workspace_bytes(d, n), DEV)
+    fws = cv.new_workspace(cv.fit_workspace_bytes(n), DEV)
+    out = torch.empty(d, dtype=torch.float32, device=DEV)
+    alpha = torch.empty(n, dtype=torch.float64, device=DEV)
+
+    def step():
+        cv.encode_batch([pl] * n, updates, 21, [0, 1, 2], streams, ws)
+        cv.decode_aggregate(streams, out, dws)
+        cv.fit_alpha(updates, alpha, fws)
+
+    for c in range(n):
+        updates[c].copy_(torch.from_numpy(syn.update_vector(1, c, d=d)))
+    step()                                                         # first use outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        host = [syn.update_vector(2 + rep % 2, 10 * rep + c, d=d) for c in range(n)]
+        for c in range(n):
+            updates[c].copy_(torch.from_numpy(host[c]))
+        out.fill_(float("nan"))
+        for s_ in streams:
+            s_.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert cv.device_status(ws) == 0 and cv.device_status(dws) == 0 and cv.device_status(fws) == 0
+        refs = [orc.encode(u, po, 21, c).words for c, u in enumerate(host)]
+        for c in range(n):
+            assert_stream_equal(streams[c].cpu().numpy().view(np.uint32)[: refs[c].size], refs[c], f"replay {rep} client {c}")
+        ref = orc.decode_aggregate(refs, d)
+        assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * abs_terms(refs, d)), rep
+        assert alpha.cpu().numpy().tolist() == pytest.approx([orc.fit_alpha(u) for u in host], rel=1e-11)
+
+
 # --------------------------------------------------------------------------- error energy, scale factor across rounds
 def test_error_statistics_and_the_scale_factor_carried_across_rounds():
     """Round t uses B from round t-1's plan (footnote to Proposition 1); the encoder reports the
