@@ -747,6 +747,19 @@ __device__ __forceinline__ void span_slots(const CandView& cv, uint32_t span, co
   for (uint32_t j = 0; j < kPerLane; ++j) slot[j] += begin + j * kWave + lane;  // meaningless for i >= n, never used there
 }
 
+// A workgroup's partial level-2 histogram is stored in 16-bit counters when no workgroup can
+// see more than 65535 candidates (the gather: whole spans dealt round the wavefronts; the
+// later passes: an equal share each): half the bytes written and read back.
+__device__ __forceinline__ bool narrow_partials(uint32_t n_cand, uint32_t blocks) { return n_cand <= 32768u * blocks; }
+
+__device__ __forceinline__ void store_partials(const uint32_t* hist, uint32_t used, uint32_t* part, bool narrow) {
+  if (narrow) {
+    for (uint32_t i = threadIdx.x; i < used / 2u; i += kWideBlock) part[i] = hist[2u * i] | (hist[2u * i + 1u] << 16);
+  } else {
+    for (uint32_t i = threadIdx.x; i < used; i += kWideBlock) part[i] = hist[i];
+  }
+}
+
 // Fills the workgroup's slot tables for one group of boundaries.
 template <int LEVEL>
 __device__ __forceinline__ void select_setup(SelectShared& S, const ClientCtl* ctl, uint32_t r0, uint32_t nb) {
@@ -801,13 +814,11 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
     span_slots(cv, span, span_window(cv, span), slot);
 #pragma unroll
     for (uint32_t j = 0; j < kPerLane; ++j) {
-      const uint32_t i = span * kSpan + j * kWave + lane;
-      v[j] = 0;
-      x[j] = 0;
-      if (i < cv.n) {
-        v[j] = cv.val[slot[j]];
-        x[j] = (slot[j] & ~(kRegion - 1u)) + cv.idx[slot[j]];  // a slot starts where its region starts
-      }
+      // rows past the last candidate read some valid place instead of branching, so that the
+      // sixteen loads of a span go out together
+      const uint32_t sl = min(slot[j], ws.d - 1u);
+      v[j] = cv.val[sl];
+      x[j] = (sl & ~(kRegion - 1u)) + cv.idx[sl];  // a slot starts where its region starts
     }
 #pragma unroll
     for (uint32_t j = 0; j < kPerLane; ++j) {
@@ -823,8 +834,7 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
   __syncthreads();
   if (nb == 0) return;
   uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * kSlotGroup * kDigitBins;
-  const uint32_t used = S.slots.n * kDigitBins;
-  for (uint32_t i = tid; i < used; i += kWideBlock) part[i] = S.hist[i];
+  store_partials(S.hist, S.slots.n * kDigitBins, part, narrow_partials(cv.n, gridDim.x));
 }
 
 // Every other selection pass reads the dense list.
@@ -876,7 +886,7 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
     }
   } else {
     uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * kSlotGroup * kDigitBins;
-    for (uint32_t i = tid; i < used; i += kWideBlock) part[i] = S.hist[i];
+    store_partials(S.hist, used, part, narrow_partials(n, gridDim.x));
   }
 }
 
@@ -897,6 +907,7 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   const uint32_t r0 = group * kSlotGroup;
+  const uint32_t n_cand = ctl->n_cand;  // asked for together with R
   if (p.R <= r0) return;
   const uint32_t nb = min(p.R - r0, kSlotGroup);
   const uint32_t n_parts = ws.sel_blocks;
@@ -919,8 +930,15 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
     h = *mine;
     *mine = 0;
   } else {
+    if (narrow_partials(n_cand, n_parts)) {
+      const uint16_t* narrow = reinterpret_cast<const uint16_t*>(parts);
 #pragma unroll 8
-    for (uint32_t b = 0; b < n_parts; ++b) h += parts[((size_t)b * kSlotGroup + slot) * kDigitBins + digit];
+      for (uint32_t b = 0; b < n_parts; ++b)
+        h += narrow[((size_t)b * kSlotGroup * kDigitBins) * 2u + (size_t)slot * kDigitBins + digit];
+    } else {
+#pragma unroll 8
+      for (uint32_t b = 0; b < n_parts; ++b) h += parts[((size_t)b * kSlotGroup + slot) * kDigitBins + digit];
+    }
   }
   if (tid < kSlotGroup) {
     s_need[tid] = 0;
