@@ -326,6 +326,57 @@ def test_non_finite_update_sets_status():
             orc.encode(U, p, 1, 0)
 
 
+# --------------------------------------------------------------------------- seeded random sweep
+def test_random_plans_sizes_and_quantisers():
+    """150 seeded combinations of length, group count, code lengths (raw, empty and 1-bit groups
+    included), group sizes from a handful to everything, scale factor, quantiser, client ids and
+    vector family: streams, statistics and error energy, aggregate, packets and their reassembly,
+    the exponent fit."""
+    rng = np.random.default_rng(20240203)
+    for case in range(150):
+        d = int(rng.choice([1, 2, 7, 63, 64, 65, 511, 4097, 8192, 8193, 20_000, 70_001, 131_072]))
+        quant = int(rng.integers(0, 2))
+        R = int(rng.integers(1, 9))
+        pool = [2, 3, 4, 6, 8, 11, 16, 32] if quant else [1, 2, 3, 4, 6, 8, 11, 16, 32]
+        ys = sorted(rng.choice(pool, size=R).tolist(), reverse=True)
+        k = int(rng.integers(0, d + 1)) if rng.random() < 0.3 else int(rng.integers(0, max(1, d // 8) + 1))
+        cuts = np.sort(rng.integers(0, k + 1, size=R - 1)) if R > 1 else np.array([], dtype=np.int64)
+        counts = np.diff(np.concatenate([[0], cuts, [k]])).astype(int).tolist()
+        B = float(rng.choice([1.0, 1.0, 2.5, 40.0]))
+        po = orc.plan_manual(d, ys, counts, B=B, quant=quant)
+        n = int(rng.integers(1, 4))
+        kind = rng.choice(["cfg1", "cfg3", "few_levels", "zeros_and_denormals"])
+        host = []
+        for c in range(n):
+            if kind.startswith("cfg"):
+                host.append(syn.update_vector(int(kind[3]), 100 * case + c, d=d))
+            else:
+                host.append(syn.tie_heavy_vector(str(kind), d, seed=100 * case + c))
+        ids = [int(v) for v in rng.integers(0, 2**32, size=n)]
+        seed = int(rng.integers(0, 2**63))
+        what = f"case {case}: d={d} quant={quant} y={ys} P={counts} B={B} {kind} n={n}"
+        words, stats, status, streams = gpu_encode(host, [po] * n, seed, ids, error_stats=True)
+        assert status == 0, what
+        refs = []
+        for c in range(n):
+            ref = orc.encode(host[c], po, seed, ids[c])
+            assert_stream_equal(words[c], ref.words, what + f" client {c}")
+            assert_stats_close(stats[c], ref.stats, po.R, error_stats=True)
+            refs.append(ref.words)
+        got, status = gpu_decode(streams, d, quant=quant)
+        assert status == 0, what
+        ref = orc.decode_aggregate(refs, d)
+        assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= 1e-5 * abs_terms(refs, d)), what
+        mtu = int(rng.choice([64, 1500]))
+        pl = to_lib_plan(po)
+        buf, npk = gpu_packetize(pl, streams[0], mtu)
+        ref_pk, _ = orc.packetize(refs[0], d, mtu)
+        assert np.array_equal(buf.cpu().numpy().view(np.uint32)[: npk * mtu // 4].reshape(npk, mtu // 4), ref_pk), what
+        out, status = gpu_depacketize(buf.view(-1, mtu // 4)[:npk].flip(0).contiguous(), npk, d, mtu, refs[0].size)
+        assert status == 0 and np.array_equal(out.cpu().numpy().view(np.uint32), refs[0]), what
+        check_fit(host)
+
+
 # --------------------------------------------------------------------------- the caller's stream
 def test_every_call_runs_on_the_callers_stream():
     """All work is enqueued on the stream handed in: on a side stream, behind a long-running
