@@ -106,6 +106,14 @@ uint32_t cvlc_position_bits(uint32_t d);
 int cvlc_plan(uint32_t d, uint64_t budget_bits, uint32_t n_coded, const uint32_t* code_len,
               const double* fractions, double alpha, float B, cvlc_plan_t* out);
 
+/* CPU.  Algorithm 1 for either quantiser: as cvlc_plan with both arrays NULL,
+ * but the groups are priced with the named quantiser's error model Q(P_r)
+ * (appendix case study: PQ P/(2^y-1)^2, QSGD min(P/s^2, sqrt(P)/s)), code
+ * lengths stay at or above the quantiser's shortest code (1 bit, QSGD 2) and
+ * the plan's `quant` is set. */
+int cvlc_plan_algorithm1(uint32_t d, uint64_t budget_bits, uint32_t n_coded, double alpha, float B,
+                         uint32_t quant, cvlc_plan_t* out);
+
 /* CPU.  Checks a caller-built plan (sizes, monotone code lengths, total_bits). */
 int cvlc_plan_validate(const cvlc_plan_t* plan);
 

@@ -291,54 +291,58 @@ double orc_gamma(const orc_plan* p, double alpha) {
 }
 
 /* f(X, P_{r-1}, P_r) of Eq. (6) as a function of P_r, with Z_{r-2} and X fixed. */
+static double q_of(uint32_t quant, double P, double y) { return quant == 1 ? q_qsgd(P, y) : q_pq(P, y); }
+
 static double f_eq6(double Pr, double X, double Zr2, double d, double u, uint32_t s, double beta,
-                    double B) {
+                    double B, uint32_t quant) {
   double invB2 = 1.0 / (B * B);
   double invBc = 1.0 - 1.0 / B;
   double Pr1 = X - Pr;
   double Zr1 = Zr2 + Pr1, Zr = Zr2 + X;
-  double a = (q_pq(Pr, u / Pr - (double)s) * invB2 + invBc * invBc) * energy_share(Zr, Zr1, d, beta);
-  double b = (q_pq(Pr1, u / Pr1 - (double)s) * invB2 + invBc * invBc) * energy_share(Zr1, Zr2, d, beta);
+  double a = (q_of(quant, Pr, u / Pr - (double)s) * invB2 + invBc * invBc) * energy_share(Zr, Zr1, d, beta);
+  double b = (q_of(quant, Pr1, u / Pr1 - (double)s) * invB2 + invBc * invBc) * energy_share(Zr1, Zr2, d, beta);
   return a + b;
 }
 
 /* The atomic operation: minimise f over P_r.  f is strongly convex (Lemma 3)
  * and its minimiser lies in (X/2, X) (end of the proof of Lemma 3), so a
  * golden-section search on that interval finds it; the interval is cut so that
- * both groups keep at least one update and at least one bit. */
+ * both groups keep at least one update and the shortest code the quantiser
+ * takes (1 bit for PQ; QSGD needs a sign bit and a level bit). */
 static double atomic_operation(double X, double Zr2, double d, double u, uint32_t s, double beta,
-                               double B) {
-  double Pmax = u / ((double)s + 1.0);
+                               double B, uint32_t quant) {
+  double Pmax = u / ((double)s + (quant == 1 ? 2.0 : 1.0));
   double lo = 0.5 * X, hi = X - 1.0;
   if (hi > Pmax) hi = Pmax;
   if (lo < X - Pmax) lo = X - Pmax;
   if (!(hi > lo)) return 0.5 * X > Pmax ? Pmax : 0.5 * X;
   const double invphi = 0.6180339887498949;
   double x1 = hi - invphi * (hi - lo), x2 = lo + invphi * (hi - lo);
-  double f1 = f_eq6(x1, X, Zr2, d, u, s, beta, B), f2 = f_eq6(x2, X, Zr2, d, u, s, beta, B);
+  double f1 = f_eq6(x1, X, Zr2, d, u, s, beta, B, quant), f2 = f_eq6(x2, X, Zr2, d, u, s, beta, B, quant);
   for (int it = 0; it < 80; ++it) {
     if (f1 <= f2) {
       hi = x2; x2 = x1; f2 = f1;
       x1 = hi - invphi * (hi - lo);
-      f1 = f_eq6(x1, X, Zr2, d, u, s, beta, B);
+      f1 = f_eq6(x1, X, Zr2, d, u, s, beta, B, quant);
     } else {
       lo = x1; x1 = x2; f1 = f2;
       x2 = lo + invphi * (hi - lo);
-      f2 = f_eq6(x2, X, Zr2, d, u, s, beta, B);
+      f2 = f_eq6(x2, X, Zr2, d, u, s, beta, B, quant);
     }
   }
   return 0.5 * (lo + hi);
 }
 
 /* Integer code lengths and group sizes from real-valued P_r: y_r = floor(u/P_r)
- * - s clamped to [1,16] and kept non-increasing, then the group is refilled to
- * P_r = floor(u/(s+y_r)) (Eq. (3) with equality as far as integers allow). */
+ * - s clamped to [1,16] ([2,16] for QSGD) and kept non-increasing, then the group is
+ * refilled to P_r = floor(u/(s+y_r)) (Eq. (3) with equality as far as integers allow). */
 static void integerise(uint32_t d, uint32_t R, const double* P, double u, uint32_t s, uint32_t* y,
-                       uint32_t* Pint) {
+                       uint32_t* Pint, uint32_t quant) {
   uint64_t left = d;
   for (uint32_t r = 0; r < R; ++r) {
     double yr = floor(u / P[r]) - (double)s;
-    if (yr < 1.0) yr = 1.0;
+    double ymin = quant == 1 ? 2.0 : 1.0;
+    if (yr < ymin) yr = ymin;
     if (yr > 16.0) yr = 16.0;
     uint32_t yi = (uint32_t)yr;
     if (r > 0 && yi > y[r - 1]) yi = y[r - 1];
@@ -351,20 +355,21 @@ static void integerise(uint32_t d, uint32_t R, const double* P, double u, uint32
 }
 
 /* Planner mode C: Algorithm 1.  For every k on a 128-point equidistant grid of
- * [k_min, k_max] = [R, R(b-H)/(s+1)]: start from P_r = k/R, sweep the atomic
+ * [k_min, k_max] = [R, R(b-H)/(s+y_min)], y_min the quantiser's shortest code: start from P_r = k/R, sweep the atomic
  * operation over r = 2..R until no P_r moves by 0.5, make the result integer
  * and evaluate Eq. (5); keep the k with the smallest gamma. */
-int orc_plan_alg1(uint32_t d, uint64_t budget_bits, uint32_t R, double alpha, float B,
-                  orc_plan* out) {
-  if (!out || R < 1 || R > ORC_MAX_R || d < 1) return ORC_ERR_ARG;
+int orc_plan_alg1_quant(uint32_t d, uint64_t budget_bits, uint32_t R, double alpha, float B,
+                        uint32_t quant, orc_plan* out) {
+  if (!out || R < 1 || R > ORC_MAX_R || d < 1 || quant > 1) return ORC_ERR_ARG;
   if (!isfinite(alpha)) return ORC_ERR_ARG;
   plan_begin(out, d, R, B);
+  out->quant = quant;
   int64_t b = share_bits(budget_bits, R);
   if (b < (int64_t)ORC_SEG_HEADER_BITS) return ORC_ERR_BUDGET;
   uint32_t s = out->s;
   double u = (double)(b - ORC_SEG_HEADER_BITS);
   double kmin = (double)R;
-  double kmax = (double)R * u / ((double)s + 1.0);
+  double kmax = (double)R * u / ((double)s + (quant == 1 ? 2.0 : 1.0));
   if (kmax > (double)d) kmax = (double)d;
   if (kmax < kmin) return ORC_ERR_BUDGET;
   double beta = 2.0 * alpha + 1.0;
@@ -377,7 +382,7 @@ int orc_plan_alg1(uint32_t d, uint64_t budget_bits, uint32_t R, double alpha, fl
       double moved = 0.0, Zr2 = 0.0;
       for (uint32_t r = 1; r < R; ++r) {
         double X = P[r - 1] + P[r];
-        double Pr = atomic_operation(X, Zr2, (double)d, u, s, beta, (double)B);
+        double Pr = atomic_operation(X, Zr2, (double)d, u, s, beta, (double)B, quant);
         double delta = fabs(Pr - P[r]);
         if (delta > moved) moved = delta;
         P[r] = Pr;
@@ -388,9 +393,9 @@ int orc_plan_alg1(uint32_t d, uint64_t budget_bits, uint32_t R, double alpha, fl
     }
     uint32_t y[ORC_MAX_R], Pi[ORC_MAX_R];
     double Pd[ORC_MAX_R];
-    integerise(d, R, P, u, s, y, Pi);
+    integerise(d, R, P, u, s, y, Pi, quant);
     for (uint32_t r = 0; r < R; ++r) Pd[r] = (double)Pi[r];
-    double gam = gamma_eq5(d, R, Pd, y, u, s, beta, (double)B, 0);
+    double gam = gamma_eq5(d, R, Pd, y, u, s, beta, (double)B, quant);
     if (gam < best) {
       best = gam;
       for (uint32_t r = 0; r < R; ++r) { out->y[r] = y[r]; out->P[r] = Pi[r]; }
@@ -400,6 +405,11 @@ int orc_plan_alg1(uint32_t d, uint64_t budget_bits, uint32_t R, double alpha, fl
   out->total_bits = orc_plan_total_bits(out);
   if (out->total_bits > budget_bits) return ORC_ERR_BUDGET;
   return orc_plan_validate(out);
+}
+
+int orc_plan_alg1(uint32_t d, uint64_t budget_bits, uint32_t R, double alpha, float B,
+                  orc_plan* out) {
+  return orc_plan_alg1_quant(d, budget_bits, R, alpha, B, 0, out);
 }
 
 /* ------------------------------------------------------------------------- */

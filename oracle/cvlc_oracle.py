@@ -70,6 +70,8 @@ def lib() -> C.CDLL:
         L.orc_plan_fractions.argtypes = [C.c_uint32, C.c_uint32, u32p, C.POINTER(C.c_double), C.c_float, C.POINTER(Plan)]
         L.orc_plan_budget.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, u32p, C.c_float, C.POINTER(Plan)]
         L.orc_plan_alg1.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, C.c_double, C.c_float, C.POINTER(Plan)]
+        L.orc_plan_alg1_quant.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, C.c_double, C.c_float, C.c_uint32,
+                                          C.POINTER(Plan)]
         L.orc_gamma.argtypes = [C.POINTER(Plan), C.c_double]
         L.orc_gamma.restype = C.c_double
         L.orc_rank.argtypes = [f32p, C.c_uint32, u32p]
@@ -152,9 +154,9 @@ def plan_budget(d: int, budget_bits: int, code_len: Sequence[int], B: float = 1.
     return p
 
 
-def plan_alg1(d: int, budget_bits: int, R: int, alpha: float, B: float = 1.0) -> Plan:
+def plan_alg1(d: int, budget_bits: int, R: int, alpha: float, B: float = 1.0, quant: int = 0) -> Plan:
     p = Plan()
-    _check(lib().orc_plan_alg1(d, budget_bits, R, alpha, B, C.byref(p)), "plan_alg1")
+    _check(lib().orc_plan_alg1_quant(d, budget_bits, R, alpha, B, quant, C.byref(p)), "plan_alg1")
     return p
 
 

@@ -134,8 +134,9 @@ int plan_from_budget(uint32_t d, uint64_t budget, uint32_t R, const uint32_t* y,
 // One instance of problem P2 for a fixed budget share: Algorithm 1.
 class Algorithm1 {
  public:
-  Algorithm1(uint32_t d, uint32_t R, uint32_t s, double usable_bits, double alpha, double B)
-      : d_(d), R_(R), s_(s), u_(usable_bits), law_((double)d, alpha), err_(B), alpha_(alpha), B_(B) {}
+  Algorithm1(uint32_t d, uint32_t R, uint32_t s, double usable_bits, double alpha, double B, uint32_t quant)
+      : d_(d), R_(R), s_(s), u_(usable_bits), law_((double)d, alpha), err_(B, quant), alpha_(alpha), B_(B),
+        quant_(quant), y_min_(quant == CVLC_QUANT_QSGD ? 2.0 : 1.0) {}
 
   // f(X, P_{r-1}, P_r) of Eq. (6) as a function of P_r.
   double pair_cost(double Pr, double X, double z_r2) const {
@@ -147,9 +148,10 @@ class Algorithm1 {
   }
 
   // Atomic operation: golden-section search for the minimiser of the strongly
-  // convex pair cost (Lemma 3) on (X/2, X), kept inside "one update, one bit".
+  // convex pair cost (Lemma 3) on (X/2, X), kept inside "one update, the quantiser's
+  // shortest code" (1 bit for PQ; QSGD needs a sign bit and a level bit).
   double atomic_operation(double X, double z_r2) const {
-    const double p_max = u_ / ((double)s_ + 1.0);
+    const double p_max = u_ / ((double)s_ + y_min_);
     double lo = 0.5 * X, hi = X - 1.0;
     if (hi > p_max) hi = p_max;
     if (lo < X - p_max) lo = X - p_max;
@@ -192,7 +194,7 @@ class Algorithm1 {
     uint64_t room = d_;
     for (uint32_t r = 0; r < R_; ++r) {
       double yr = std::floor(u_ / Pc[r]) - (double)s_;
-      if (yr < 1.0) yr = 1.0;
+      if (yr < y_min_) yr = y_min_;
       if (yr > 16.0) yr = 16.0;
       uint32_t yi = (uint32_t)yr;
       if (r > 0 && yi > y[r - 1]) yi = y[r - 1];
@@ -202,7 +204,7 @@ class Algorithm1 {
       P[r] = (uint32_t)Pi;
       room -= Pi;
     }
-    return gamma_integer(d_, R_, P, y, alpha_, B_);
+    return gamma_integer(d_, R_, P, y, alpha_, B_, quant_);
   }
 
  private:
@@ -211,19 +213,23 @@ class Algorithm1 {
   PowerLaw law_;
   ErrorModel err_;
   double alpha_, B_;
+  uint32_t quant_;
+  double y_min_;
 };
 
-int plan_algorithm1(uint32_t d, uint64_t budget, uint32_t R, double alpha, float B, cvlc_plan_t* out) {
-  if (R < 1 || !std::isfinite(alpha)) return CVLC_ERR_ARG;
+int plan_algorithm1(uint32_t d, uint64_t budget, uint32_t R, double alpha, float B, uint32_t quant,
+                    cvlc_plan_t* out) {
+  if (R < 1 || !std::isfinite(alpha) || quant > CVLC_QUANT_QSGD) return CVLC_ERR_ARG;
   plan_init(out, d, R, B);
+  out->quant = quant;
   const int64_t b = group_share_bits(budget, R);
   if (b < (int64_t)kSegHeaderBits) return CVLC_ERR_BUDGET;
   const double u = (double)(b - kSegHeaderBits);
   const double k_min = (double)R;
-  double k_max = (double)R * u / ((double)out->s + 1.0);
+  double k_max = (double)R * u / ((double)out->s + (quant == CVLC_QUANT_QSGD ? 2.0 : 1.0));
   if (k_max > (double)d) k_max = (double)d;
   if (k_max < k_min) return CVLC_ERR_BUDGET;
-  const Algorithm1 alg(d, R, out->s, u, alpha, (double)B);
+  const Algorithm1 alg(d, R, out->s, u, alpha, (double)B, quant);
   double best = std::numeric_limits<double>::infinity();
   constexpr int kGrid = 128;  // equidistant search over k
   for (int g = 0; g < kGrid; ++g) {
@@ -318,7 +324,14 @@ int cvlc_plan(uint32_t d, uint64_t budget_bits, uint32_t n_coded, const uint32_t
     return plan_from_fractions(d, n_coded, code_len, fractions, B, out);
   }
   if (code_len) return plan_from_budget(d, budget_bits, n_coded, code_len, B, out);
-  return plan_algorithm1(d, budget_bits, n_coded, alpha, B, out);
+  return plan_algorithm1(d, budget_bits, n_coded, alpha, B, CVLC_QUANT_PQ, out);
+}
+
+int cvlc_plan_algorithm1(uint32_t d, uint64_t budget_bits, uint32_t n_coded, double alpha, float B, uint32_t quant,
+                         cvlc_plan_t* out) {
+  if (!out || d < 1 || d > 0x7FFFFFFFu || n_coded > CVLC_MAX_CODED) return CVLC_ERR_ARG;
+  if (!(B > 0.0f) || !std::isfinite(B)) return CVLC_ERR_ARG;
+  return plan_algorithm1(d, budget_bits, n_coded, alpha, B, quant, out);
 }
 
 const char* cvlc_status_string(int status) {

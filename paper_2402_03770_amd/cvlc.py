@@ -74,6 +74,8 @@ def lib() -> C.CDLL:
         L.cvlc_position_bits.restype = C.c_uint32
         L.cvlc_plan.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, u32p, C.POINTER(C.c_double), C.c_double,
                                 C.c_float, C.POINTER(Plan)]
+        L.cvlc_plan_algorithm1.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, C.c_double, C.c_float, C.c_uint32,
+                                           C.POINTER(Plan)]
         L.cvlc_plan_validate.argtypes = [C.POINTER(Plan)]
         L.cvlc_plan_total_bits.argtypes = [C.POINTER(Plan)]
         L.cvlc_plan_total_bits.restype = C.c_uint64
@@ -145,6 +147,14 @@ def plan(d: int, budget_bits: int = 0, n_coded: Optional[int] = None, code_len: 
     fr = (C.c_double * max(n_coded, 1))(*fractions) if fractions is not None else None
     out = Plan()
     _check(lib().cvlc_plan(d, budget_bits, n_coded, cl, fr, alpha, B, C.byref(out)), "cvlc_plan")
+    return out
+
+
+def plan_algorithm1(d: int, budget_bits: int, n_coded: int, alpha: float = -0.5, B: float = 1.0,
+                    quant: int = QUANT_PQ) -> Plan:
+    """cvlc_plan_algorithm1: Algorithm 1 priced with the named quantiser's error model."""
+    out = Plan()
+    _check(lib().cvlc_plan_algorithm1(d, budget_bits, n_coded, alpha, B, quant, C.byref(out)), "cvlc_plan_algorithm1")
     return out
 
 

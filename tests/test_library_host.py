@@ -56,6 +56,10 @@ def test_planner_matches_oracle_on_random_inputs():
         y = sorted(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 32], size=R).tolist(), reverse=True)
         assert _same(cv.plan(d, budget, code_len=y, B=B), orc.plan_budget(d, budget, y, B))
         assert _same(cv.plan(d, budget, n_coded=R, alpha=alpha, B=B), orc.plan_alg1(d, budget, R, alpha, B))
+        for quant in (cv.QUANT_PQ, cv.QUANT_QSGD):
+            pg, po = cv.plan_algorithm1(d, budget, R, alpha, B, quant), orc.plan_alg1(d, budget, R, alpha, B, quant)
+            assert _same(pg, po) and pg.quant == po.quant == quant
+            assert quant == cv.QUANT_PQ or min(pg.code_lens()) >= 2
         frac = rng.dirichlet(np.ones(R + 1))[:R].tolist()
         assert _same(cv.plan(d, code_len=y, fractions=frac, B=B), orc.plan_fractions(d, y, frac, B))
 

@@ -421,8 +421,8 @@ def test_malformed_input_is_rejected():
 
 
 # --------------------------------------------------------------------------- planner (Proposition 2, Algorithm 1)
-def _gamma_eq5(d, counts, code_len, alpha, B=1.0):
-    """Eq. (5) typed from the paper, in Python floats."""
+def _gamma_eq5(d, counts, code_len, alpha, B=1.0, qsgd=False):
+    """Eq. (5) typed from the paper, in Python floats; Q from the appendix case study."""
     beta = 2 * alpha + 1
     pw = lambda z: max(z, 1.0) ** beta
     k = sum(counts)
@@ -430,7 +430,8 @@ def _gamma_eq5(d, counts, code_len, alpha, B=1.0):
     Z = 0
     for P, y in zip(counts, code_len):
         if P:
-            Q = P / (2.0**y - 1) ** 2
+            levels = 2.0 ** (y - 1) - 1 if qsgd else 2.0**y - 1
+            Q = min(P / levels**2, math.sqrt(P) / levels) if qsgd else P / levels**2
             g += (Q / B**2 + (1 - 1 / B) ** 2) * (pw(Z + P) - pw(Z)) / (pw(d) - 1)
         Z += P
     return g
@@ -466,6 +467,28 @@ def test_algorithm1_plan_is_feasible_monotone_and_near_the_integer_optimum(alpha
         got = _gamma_eq5(d, P, y, alpha)
         assert got <= best * 1.05 + 1e-12
         if R == 1:                                                   # the P_y Top_k family of Sec. V: picks its best y
+            assert math.isclose(got, best, rel_tol=1e-9)
+
+
+@pytest.mark.parametrize("alpha", [-0.8, -0.4])
+def test_algorithm1_with_the_qsgd_error_model(alpha):
+    """The same sweep priced with QSGD's Q(P_r) = min(P/s^2, sqrt(P)/s): feasible, monotone, Eq. (3)
+    tight, no code shorter than sign + one level bit, and near the best integer assignment."""
+    d, budget = 200_000, 150_000
+    s = orc.s_bits(d)
+    for R in (1, 2, 3):
+        p = orc.plan_alg1(d, budget, R, alpha, quant=orc.QSGD)
+        assert p.quant == orc.QSGD and p.total_bits <= budget
+        y, P = p.code_len(), p.counts()
+        assert min(y) >= 2 and all(a >= b for a, b in zip(y[:-1], y[1:]))
+        u = 32 * ((budget - 256) // (32 * R)) - 128
+        assert all(Pr == u // (s + yr) for Pr, yr in zip(P, y))
+        assert math.isclose(orc.gamma(p, alpha), _gamma_eq5(d, P, y, alpha, qsgd=True), rel_tol=1e-10)
+        best = min(_gamma_eq5(d, [u // (s + yr) for yr in ys], ys, alpha, qsgd=True)
+                   for ys in itertools.combinations_with_replacement(range(16, 1, -1), R))
+        got = _gamma_eq5(d, P, y, alpha, qsgd=True)
+        assert got <= best * 1.05 + 1e-12
+        if R == 1:
             assert math.isclose(got, best, rel_tol=1e-9)
 
 
