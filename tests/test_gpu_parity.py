@@ -894,7 +894,26 @@ def test_properties_at_sizes_beyond_the_oracle(d, ys, counts):
         else:
             assert err <= (M - m) / (2 ** ys[r] - 1) * (1 + 1e-5)
     assert int((out != 0).sum()) <= k
-    del U, kept, mag, xhat, pid_dev
+    del kept, mag, xhat, pid_dev
     ref = orc.decode_aggregate([words], d)
     got = out.cpu().numpy()
     assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), "single-client decode is bit exact"
+    del out, dws, ref, got
+
+    # the exponent fit at the same length: its order statistics against a library sort on the device
+    alpha = torch.empty(1, dtype=torch.float64, device=DEV)
+    keys = torch.empty(cv.FIT_RANKS_MAX, dtype=torch.int32, device=DEV)
+    fws = cv.new_workspace(cv.fit_workspace_bytes(1), DEV)
+    cv.fit_alpha([U], alpha, fws, keys)
+    assert cv.device_status(fws) == 0
+    ranks = cv.fit_ranks(d)
+    desc = torch.sort(U.abs_(), descending=True).values            # U is not needed any more
+    want = desc[torch.tensor([l - 1 for l in ranks], device=DEV)].view(torch.int32).cpu().numpy()
+    del desc
+    got_keys = keys.cpu().numpy()
+    assert np.array_equal(got_keys[: len(ranks)], want) and not got_keys[len(ranks):].any()
+    mags = want.view(np.float32).astype(np.float64)
+    use = mags > 0.0                                               # a zero magnitude has no logarithm
+    x, y, m = np.log(np.array(ranks, dtype=np.float64)[use]), np.log(mags[use]), int(use.sum())
+    slope = (m * (x * y).sum() - x.sum() * y.sum()) / (m * (x * x).sum() - x.sum() ** 2)
+    assert float(alpha[0]) == pytest.approx(slope, rel=1e-9)
