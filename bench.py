@@ -57,7 +57,13 @@ def recorded_traffic():
         return None
 
 
-def make_plans(cv, w, n, d):
+def make_plans(cv, w, n, d, quant=0):
+    if quant:   # the second quantiser: Algorithm 1 priced with its error model (planned workloads only)
+        if w.mode != "alg1":
+            raise SystemExit("--quant qsgd needs a workload planned by Algorithm 1 (cfg 2, 3 or 5)")
+        cache = {}
+        return [cache.setdefault(w.budget_bits(c), cv.plan_algorithm1(d, w.budget_bits(c), w.n_coded, PLANNER_ALPHA, 1.0, quant))
+                for c in range(n)]
     if w.mode == "fractions":
         return [cv.plan(d, code_len=w.code_len, fractions=w.fractions)] * n
     if w.mode == "budget":
@@ -119,6 +125,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--cfg", type=int, default=3, help="workload number (cvlc_synth.WORKLOADS)")
     ap.add_argument("--clients", type=int, default=0, help="override the number of clients")
+    ap.add_argument("--quant", choices=["pq", "qsgd"], default="pq", help="quantiser (the benchmark's is pq)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true", help="also print a per-stage event breakdown to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -146,7 +153,8 @@ def main() -> int:
     with ThreadPoolExecutor(max_workers=8) as ex:
         host = list(ex.map(lambda c: syn.update_vector(args.cfg, c), range(n)))
     updates = [torch.from_numpy(u).to(dev) for u in host]
-    plans = make_plans(cv, w, n, d)
+    quant = cv.QUANT_QSGD if args.quant == "qsgd" else cv.QUANT_PQ
+    plans = make_plans(cv, w, n, d, quant)
     streams = [cv.new_stream_buffer(p, dev) for p in plans]
     enc_ws = cv.new_workspace(cv.encode_workspace_bytes(d, n), dev)
     dec_ws = cv.new_workspace(cv.decode_workspace_bytes(d, n), dev)
@@ -167,7 +175,7 @@ def main() -> int:
         cv.encode_batch(plans, updates, w.quant_seed, ids, streams, enc_ws, stats)
 
     def decode():
-        cv.decode_aggregate(streams, out, dec_ws)
+        cv.decode_aggregate(streams, out, dec_ws, quant=quant)
 
     def timed(fn, steps):
         torch.cuda.synchronize()
@@ -235,7 +243,9 @@ def main() -> int:
     result["fit_alpha"] = {"ms": t_fit * 1e3, "g_coords_s": n * d / t_fit / 1e9, "algorithmic_gb": 4.0 * n * d / 1e9,
                            "hbm_frac": 4.0 * n * d / t_fit / 1e9 / HBM_PEAK_GBS, "passes_over_input": 3,
                            "in_step": False}
-    if not args.no_cpu_baseline:
+    if quant:
+        result["config"]["quantiser"] = "qsgd"
+    if not args.no_cpu_baseline and not quant:   # the baseline is defined for the benchmark's quantiser
         result["cpu_baseline"] = cpu_baseline(host, w, d)
     print(json.dumps(result))
     return 0
