@@ -7,6 +7,7 @@ the aggregate to 1e-5 * sum_i |w_i xhat_ij| per element (fp summation order is
 free), single-client decode bit for bit.
 """
 import ctypes as C
+import os
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -332,11 +333,11 @@ def test_random_plans_sizes_and_quantisers():
     included), group sizes from a handful to everything, scale factor, quantiser, client ids and
     vector family: streams, statistics and error energy, aggregate, packets and their reassembly,
     the exponent fit."""
-    rng = np.random.default_rng(20240203)
+    rng = np.random.default_rng(int(os.environ.get("CVLC_SWEEP_SEED", "20240203")))   # another seed: another 150 cases
     for case in range(150):
         d = int(rng.choice([1, 2, 7, 63, 64, 65, 511, 4097, 8192, 8193, 20_000, 70_001, 131_072]))
         quant = int(rng.integers(0, 2))
-        R = int(rng.integers(1, 9))
+        R = int(rng.integers(1, 9)) if rng.random() < 0.7 else int(rng.integers(9, 32))   # beyond 15: several selection rounds
         pool = [2, 3, 4, 6, 8, 11, 16, 32] if quant else [1, 2, 3, 4, 6, 8, 11, 16, 32]
         ys = sorted(rng.choice(pool, size=R).tolist(), reverse=True)
         k = int(rng.integers(0, d + 1)) if rng.random() < 0.3 else int(rng.integers(0, max(1, d // 8) + 1))
@@ -367,6 +368,14 @@ def test_random_plans_sizes_and_quantisers():
         assert status == 0, what
         ref = orc.decode_aggregate(refs, d)
         assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= 1e-5 * abs_terms(refs, d)), what
+        # caller's weights (either sign), added to what the output holds
+        wts = [float(np.float32(v)) for v in rng.uniform(-2.0, 2.0, size=n)]
+        start = rng.standard_normal(d).astype(np.float32)
+        acc, status = gpu_decode(streams, d, weights=wts, accumulate_into=torch.from_numpy(start.copy()).to(DEV), quant=quant)
+        assert status == 0, what
+        ref = orc.decode_aggregate(refs, d, weights=wts, out=start.copy())
+        tol = 1e-5 * (abs_terms(refs, d, weights=wts) + np.abs(start.astype(np.float64)))
+        assert np.all(np.abs(acc.astype(np.float64) - ref.astype(np.float64)) <= tol), what
         mtu = int(rng.choice([64, 1500]))
         pl = to_lib_plan(po)
         buf, npk = gpu_packetize(pl, streams[0], mtu)
