@@ -37,9 +37,13 @@
  *   bit layout ........... numpy unpackbits field extraction; closed-form sizes
  *   decode/aggregate ..... dense numpy sum of single-client decodes
  *   planner (mode A, B) .. closed forms and the worked sizes of the configs
- *   planner (Algorithm 1)  brute force over integer code lengths for R <= 3;
- *                          optimality for larger R: parity unpinned (the paper
- *                          prints no worked plan)
+ *   planner (Algorithm 1)  exhaustion over all integer code-length vectors for
+ *                          R <= 6; the sweep's fixed point against a general
+ *                          constrained minimiser of Eq. (5) (Theorem 1) at
+ *                          R = 4, 7, 15, 31; one-bit moves and the one-length
+ *                          plans of Sec. V at the workloads' R = 7, 15, 31
+ *   memory / arithmetic .. the whole file under ASan + UBSan
+ * Parity unpinned: the learning results of Sec. V (they need the datasets).
  */
 #include <math.h>
 #include <stdint.h>
@@ -270,7 +274,9 @@ static double gamma_eq5(uint32_t d, uint32_t R, const double* P, const uint32_t*
   double invBc = 1.0 - 1.0 / B; /* 1/B + 1/B_c = 1 */
   double k = 0.0;
   for (uint32_t r = 0; r < R; ++r) k += P[r];
-  double g = energy_share((double)d, k + 1.0, (double)d, beta);
+  /* first term: the energy of the sparsified ranks k+1..d; there are none when k = d (the printed
+   * closed form would then give minus the share of a rank d+1 that does not exist) */
+  double g = k >= (double)d ? 0.0 : energy_share((double)d, k + 1.0, (double)d, beta);
   double Zprev = 0.0;
   for (uint32_t r = 0; r < R; ++r) {
     double Z = Zprev + P[r];
@@ -354,10 +360,46 @@ static void integerise(uint32_t d, uint32_t R, const double* P, double u, uint32
   }
 }
 
+/* Step 2 of the solution of P2 (the inner loop of Algorithm 1) for one k:
+ * start from P_r = k/R and sweep the atomic operation over r = 2..R until no
+ * P_r moves by 0.5 (at most 200 sweeps).  P holds the real-valued group sizes
+ * on return; their sum is k throughout. */
+static void alg1_sweep(double k, uint32_t d, uint32_t R, double u, uint32_t s, double beta, double B,
+                       uint32_t quant, double* P) {
+  for (uint32_t r = 0; r < R; ++r) P[r] = k / (double)R;
+  for (int sweep = 0; sweep < 200; ++sweep) {
+    double moved = 0.0, Zr2 = 0.0;
+    for (uint32_t r = 1; r < R; ++r) {
+      double X = P[r - 1] + P[r];
+      double Pr = atomic_operation(X, Zr2, (double)d, u, s, beta, B, quant);
+      double delta = fabs(Pr - P[r]);
+      if (delta > moved) moved = delta;
+      P[r] = Pr;
+      P[r - 1] = X - Pr;
+      Zr2 += P[r - 1];
+    }
+    if (moved < 0.5) break;
+  }
+}
+
+/* The sweep alone, for the tests: real-valued P_1..P_R for a given k under the
+ * budget's bit share, and gamma of Eq. (5) at that point with y_r = u/P_r - s. */
+int orc_alg1_sweep(uint32_t d, uint64_t budget_bits, uint32_t R, double alpha, float B, uint32_t quant,
+                   double k, double* P_out, double* gamma_out) {
+  if (!P_out || R < 1 || R > ORC_MAX_R || d < 1 || quant > 1 || !isfinite(alpha)) return ORC_ERR_ARG;
+  int64_t b = share_bits(budget_bits, R);
+  if (b < (int64_t)ORC_SEG_HEADER_BITS) return ORC_ERR_BUDGET;
+  uint32_t s = orc_s_bits(d);
+  double u = (double)(b - ORC_SEG_HEADER_BITS);
+  double beta = 2.0 * alpha + 1.0;
+  alg1_sweep(k, d, R, u, s, beta, (double)B, quant, P_out);
+  if (gamma_out) *gamma_out = gamma_eq5(d, R, P_out, NULL, u, s, beta, (double)B, quant);
+  return ORC_OK;
+}
+
 /* Planner mode C: Algorithm 1.  For every k on a 128-point equidistant grid of
- * [k_min, k_max] = [R, R(b-H)/(s+y_min)], y_min the quantiser's shortest code: start from P_r = k/R, sweep the atomic
- * operation over r = 2..R until no P_r moves by 0.5, make the result integer
- * and evaluate Eq. (5); keep the k with the smallest gamma. */
+ * [k_min, k_max] = [R, R(b-H)/(s+y_min)], y_min the quantiser's shortest code: run the sweep,
+ * make the result integer and evaluate Eq. (5); keep the k with the smallest gamma. */
 int orc_plan_alg1_quant(uint32_t d, uint64_t budget_bits, uint32_t R, double alpha, float B,
                         uint32_t quant, orc_plan* out) {
   if (!out || R < 1 || R > ORC_MAX_R || d < 1 || quant > 1) return ORC_ERR_ARG;
@@ -377,20 +419,7 @@ int orc_plan_alg1_quant(uint32_t d, uint64_t budget_bits, uint32_t R, double alp
   for (int g = 0; g < 128; ++g) {
     double k = kmin + (kmax - kmin) * (double)g / 127.0;
     double P[ORC_MAX_R];
-    for (uint32_t r = 0; r < R; ++r) P[r] = k / (double)R;
-    for (int sweep = 0; sweep < 200; ++sweep) {
-      double moved = 0.0, Zr2 = 0.0;
-      for (uint32_t r = 1; r < R; ++r) {
-        double X = P[r - 1] + P[r];
-        double Pr = atomic_operation(X, Zr2, (double)d, u, s, beta, (double)B, quant);
-        double delta = fabs(Pr - P[r]);
-        if (delta > moved) moved = delta;
-        P[r] = Pr;
-        P[r - 1] = X - Pr;
-        Zr2 += P[r - 1];
-      }
-      if (moved < 0.5) break;
-    }
+    alg1_sweep(k, d, R, u, s, beta, (double)B, quant, P);
     uint32_t y[ORC_MAX_R], Pi[ORC_MAX_R];
     double Pd[ORC_MAX_R];
     integerise(d, R, P, u, s, y, Pi, quant);

@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
         L.orc_plan_alg1.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, C.c_double, C.c_float, C.POINTER(Plan)]
         L.orc_plan_alg1_quant.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, C.c_double, C.c_float, C.c_uint32,
                                           C.POINTER(Plan)]
+        L.orc_alg1_sweep.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, C.c_double, C.c_float, C.c_uint32, C.c_double,
+                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.orc_gamma.argtypes = [C.POINTER(Plan), C.c_double]
         L.orc_gamma.restype = C.c_double
         L.orc_rank.argtypes = [f32p, C.c_uint32, u32p]
@@ -161,6 +163,15 @@ def plan_alg1(d: int, budget_bits: int, R: int, alpha: float, B: float = 1.0, qu
 
 
 PQ, QSGD = 0, 1
+
+
+def alg1_sweep(d: int, budget_bits: int, R: int, alpha: float, k: float, B: float = 1.0,
+               quant: int = 0) -> Tuple[List[float], float]:
+    """Real-valued P_1..P_R the sweep of atomic operations settles on for this k, and gamma there."""
+    P = (C.c_double * R)()
+    g = C.c_double()
+    _check(lib().orc_alg1_sweep(d, budget_bits, R, alpha, B, quant, k, P, C.byref(g)), "alg1_sweep")
+    return [float(v) for v in P], float(g.value)
 
 
 def plan_manual(d: int, code_len: Sequence[int], counts: Sequence[int], B: float = 1.0, quant: int = PQ) -> Plan:

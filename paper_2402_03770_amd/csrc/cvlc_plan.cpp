@@ -67,7 +67,8 @@ double gamma_integer(uint32_t d, uint32_t R, const uint32_t* P, const uint32_t* 
   const ErrorModel err(B, quant);
   double k = 0.0;
   for (uint32_t r = 0; r < R; ++r) k += (double)P[r];
-  double g = law.share((double)d, k + 1.0);
+  // ranks k+1..d are sparsified away; with k = d there are none
+  double g = k >= (double)d ? 0.0 : law.share((double)d, k + 1.0);
   double z_prev = 0.0;
   for (uint32_t r = 0; r < R; ++r) {
     const double z = z_prev + (double)P[r];
