@@ -797,6 +797,77 @@ def test_full_size_32_clients(cfg):
     assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= tol)
 
 
+def _progress(msg):
+    """A line in gpurun_out/ (when that folder exists), so that a long test is seen to be alive."""
+    folder = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(folder):
+        with open(os.path.join(folder, "test_progress.log"), "a") as f:
+            f.write(msg + "\n")
+
+
+def _stored_cfg5_plans():
+    """The 100 plans of configuration 5 as the oracle's Algorithm 1 made them from the oracle's exponent fit
+    (tests/golden/cfg5_plans.txt, written by tests/golden/make_cfg5_plans.py: minutes of CPU time).  Each is
+    rebuilt through the oracle's validation and must fit the client's budget."""
+    w = syn.WORKLOADS[5]
+    plans = []
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "cfg5_plans.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            head, ys, Ps = line.split("|")
+            client, _alpha, budget, total = head.split()
+            assert int(client) == len(plans) and int(budget) == w.budget_bits(int(client))
+            p = orc.plan_manual(w.d, [int(v) for v in ys.split()], [int(v) for v in Ps.split()])
+            assert p.total_bits == int(total) <= int(budget)
+            plans.append(p)
+    assert len(plans) == w.n_clients
+    return plans
+
+
+def test_full_size_100_clients_31_groups_streamed_aggregate():
+    """Configuration 5 at full size: 100 clients, d = 25.6M, Laplace or Gaussian per client, a budget of its
+    own per client (0.25 .. 2 bit/coordinate), 31 coded groups planned by Algorithm 1 from each vector's
+    fitted exponent; one batched encode, every stream compared word for word with the oracle's; then the
+    100 streams are aggregated in four calls of 25 in accumulate mode with the caller's weights 1/100 and
+    compared element by element with the oracle doing the same.  n * d passes 2^31 (workspace offsets),
+    the plans differ (several parameter uploads), the selection takes three rounds of 15 boundaries and a
+    decode call sees 775 record lists."""
+    w = syn.WORKLOADS[5]
+    n, d = w.n_clients, w.d
+    _progress("cfg5: vectors")
+    host = _parallel(lambda c: syn.update_vector(5, c), range(n), workers=16)
+    plans = _stored_cfg5_plans()
+    assert len({tuple(p.counts()) for p in plans}) > 50 and all(p.R == 31 for p in plans)
+    _progress("cfg5: gpu encode")
+    words, stats, status, dev_streams = gpu_encode(host, plans, w.quant_seed, list(range(n)))
+    assert status == 0
+    _progress("cfg5: oracle encode")
+    refs = _parallel(lambda c: orc.encode(host[c], plans[c], w.quant_seed, c), range(n), workers=16)
+    for c in range(n):
+        assert_stream_equal(words[c], refs[c].words, f"cfg 5 client {c}")
+        assert_stats_close(stats[c], refs[c].stats, plans[c].R)
+    del host, words
+    _progress("cfg5: decode")
+    ref_streams = [r.words for r in refs]
+    wts = [float(np.float32(1.0 / n))] * n
+    acc = torch.zeros(d, dtype=torch.float32, device=DEV)
+    ref = np.zeros(d, dtype=np.float32)
+    for b in range(0, n, 25):
+        got, status = gpu_decode(dev_streams[b:b + 25], d, weights=wts[b:b + 25], accumulate_into=acc)
+        assert status == 0
+        ref = orc.decode_aggregate(ref_streams[b:b + 25], d, weights=wts[b:b + 25], out=ref)
+        _progress(f"cfg5: batch {b}")
+    # sum_i |w_i xhat_ij|: the oracle's aggregate of the same streams with the signs of the values removed,
+    # i.e. of |xhat|; computed from single-client decodes, a few at a time
+    tot = np.zeros(d)
+    for part in _parallel(lambda c: np.abs(orc.decode_aggregate([ref_streams[c]], d, weights=[1.0]).astype(np.float64)),
+                          range(n), workers=8):
+        tot += part * wts[0]
+    assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= 1e-5 * tot)
+    assert int(np.count_nonzero(ref)) > d // 2
+
+
 def test_full_size_qsgd_8_clients():
     """cfg 3's vectors at full length with the second quantiser: 8 clients, 1 bit/coordinate spread
     over eight code lengths; streams (norms included) word for word, aggregate element by element."""
