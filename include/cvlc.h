@@ -188,6 +188,24 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
                           const float* weights, float* d_out, uint32_t d, uint32_t flags,
                           void* d_workspace, size_t ws_bytes, void* hip_stream);
 
+/* GPU.  cvlc_decode_aggregate for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the same kernels, working in an array of CVLC_DECODE_STATIC_BYTES
+ * that the library holds in every device's memory from the moment it is loaded
+ * until the process ends, instead of a caller's workspace.  The call allocates
+ * nothing.  Arguments as for cvlc_decode_aggregate, except
+ *   d_status_out  device or NULL: receives the call's status word (CVLC_DEV_*
+ *                 bits) when the stream reaches that point
+ * Returns CVLC_ERR_CAPACITY when cvlc_decode_workspace_bytes(d, n) exceeds
+ * CVLC_DECODE_STATIC_BYTES (16 MiB: 32 clients of an 11.2 M-dimensional model
+ * fit), before anything is launched.  All calls on one device share that
+ * device's array: calls that overlap in time on one device race (also on
+ * different streams); calls on different devices do not touch each other. */
+#define CVLC_DECODE_STATIC_BYTES (16u << 20)
+int cvlc_decode_aggregate_static(uint32_t n, const void* const* d_streams, const size_t* stream_bytes,
+                                 const float* weights, float* d_out, uint32_t d, uint32_t flags,
+                                 uint32_t* d_status_out, void* hip_stream);
+
 /* Ranks at which Definition 1's power law is fitted: 1, 2, 4, ... (powers of two
  * below d) and d itself, ascending.  Writes them to ranks_out (CVLC_FIT_RANKS_MAX
  * entries, may be NULL) and returns how many there are (0 for d = 0). */

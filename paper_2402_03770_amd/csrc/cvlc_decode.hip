@@ -18,6 +18,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "cvlc_common.h"
 
@@ -555,6 +556,33 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
   if (bad) atomicOr(status, CVLC_DEV_STREAM);
 }
 
+// ------------------------------------------------------------------ scratch for callers that cannot allocate
+// cvlc_decode_aggregate_static works in this array instead of a caller's
+// workspace.  Every device the library runs on holds its own copy at its own
+// address; host code never uses the array's name as an address, only what
+// hipGetSymbolAddress returned for the current device.
+static __device__ __align__(256) unsigned char scratch[CVLC_DECODE_STATIC_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Address of `scratch` on the current device, looked up once per device.
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CVLC_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return CVLC_ERR_DEVICE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CVLC_OK;
+}
+
+__global__ void copy_status_kernel(const uint32_t* __restrict__ status, uint32_t* __restrict__ dst) { *dst = *status; }
+
 }  // namespace
 }  // namespace cvlc
 
@@ -629,6 +657,29 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
                        flags & CVLC_DECODE_ACCUMULATE, status);
   }
   return hip_check(hipGetLastError());
+}
+
+int cvlc_decode_aggregate_static(uint32_t n, const void* const* d_streams, const size_t* stream_bytes,
+                                 const float* weights, float* d_out, uint32_t d, uint32_t flags,
+                                 uint32_t* d_status_out, void* hip_stream) {
+  using namespace cvlc;
+  if (d < 1 || d > 0x7FFFFFFFu || n > 65535u) return CVLC_ERR_ARG;
+  if (d_status_out && reinterpret_cast<uintptr_t>(d_status_out) % 4u) return CVLC_ERR_ARG;
+  if (cvlc_decode_workspace_bytes(d, n) > (size_t)CVLC_DECODE_STATIC_BYTES) return CVLC_ERR_CAPACITY;
+  void* ptr = nullptr;
+  int rc = static_scratch(&ptr);
+  if (rc) return rc;
+  // everything the kernels read from the array they have written earlier in the same call, so what the
+  // call before left there does not matter
+  rc = cvlc_decode_aggregate(n, d_streams, stream_bytes, weights, d_out, d, flags, ptr, CVLC_DECODE_STATIC_BYTES,
+                             hip_stream);
+  if (rc) return rc;
+  if (d_status_out) {
+    hipLaunchKernelGGL(copy_status_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const uint32_t*>(ptr), d_status_out);
+    rc = hip_check(hipGetLastError());
+  }
+  return rc;
 }
 
 }  // extern "C"

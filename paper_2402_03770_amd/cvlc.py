@@ -97,6 +97,8 @@ def lib() -> C.CDLL:
         L.cvlc_stats_gamma.restype = C.c_double
         L.cvlc_decode_aggregate.argtypes = [C.c_uint32, C.POINTER(vp), szp, C.POINTER(C.c_float), vp, C.c_uint32,
                                             C.c_uint32, vp, C.c_size_t, vp]
+        L.cvlc_decode_aggregate_static.argtypes = [C.c_uint32, C.POINTER(vp), szp, C.POINTER(C.c_float), vp, C.c_uint32,
+                                                   C.c_uint32, vp, vp]
         L.cvlc_device_status.argtypes = [vp, vp, u32p]
         L.cvlc_packet_count.argtypes = [C.POINTER(Plan), C.c_uint32]
         L.cvlc_packet_count.restype = C.c_uint32
@@ -271,6 +273,28 @@ def decode_aggregate(streams: Sequence[torch.Tensor], out: torch.Tensor, workspa
                                        (DECODE_ACCUMULATE if accumulate else 0) | (DECODE_QSGD if quant == QUANT_QSGD else 0),
                                        workspace.data_ptr(),
                                        workspace.numel(), _stream_handle()), "cvlc_decode_aggregate")
+
+
+DECODE_STATIC_BYTES = 16 << 20
+
+
+def decode_aggregate_static(streams: Sequence[torch.Tensor], out: torch.Tensor,
+                            status_out: Optional[torch.Tensor] = None, weights: Optional[Sequence[float]] = None,
+                            accumulate: bool = False, stream_bytes: Optional[Sequence[int]] = None,
+                            quant: int = QUANT_PQ) -> None:
+    """cvlc_decode_aggregate_static on the current stream: no workspace, no allocation; `status_out` is an
+    optional int32 device tensor of one entry that receives the status word."""
+    n = len(streams)
+    vp = C.c_void_p
+    ptrs = (vp * max(n, 1))(*[s.data_ptr() for s in streams])
+    if stream_bytes is None:
+        stream_bytes = [s.numel() * s.element_size() for s in streams]
+    sizes = (C.c_size_t * max(n, 1))(*stream_bytes)
+    w = (C.c_float * max(n, 1))(*weights) if weights is not None else None
+    _check(lib().cvlc_decode_aggregate_static(n, ptrs, sizes, w, out.data_ptr(), out.numel(),
+                                              (DECODE_ACCUMULATE if accumulate else 0) | (DECODE_QSGD if quant == QUANT_QSGD else 0),
+                                              status_out.data_ptr() if status_out is not None else None,
+                                              _stream_handle()), "cvlc_decode_aggregate_static")
 
 
 def packetize(p: Plan, stream: torch.Tensor, packets_out: torch.Tensor, mtu: int = 1500) -> None:
