@@ -114,10 +114,10 @@ __device__ __forceinline__ uint64_t wave_incl_scan_u64(uint64_t v) {
   return v;
 }
 
-__global__ __launch_bounds__(64) void parse_headers_kernel(ParseChunk chunk, ListDesc* descs, uint32_t d, uint32_t n,
-                                                           uint32_t* __restrict__ stream_bad, uint32_t quant) {
-  const uint32_t client = chunk.first + blockIdx.x, t = threadIdx.x;
-  const StreamArg sa = chunk.args[blockIdx.x];
+// Whole wavefront: the headers of one stream.
+__device__ __forceinline__ void parse_stream(const StreamArg& sa, uint32_t client, ListDesc* descs, uint32_t d, uint32_t n,
+                                             uint32_t* __restrict__ stream_bad, uint32_t quant) {
+  const uint32_t t = lane_id();
   GlobalConstWordPtr w = (GlobalConstWordPtr)sa.words;
   ListDesc* out = descs + (size_t)client * kListsPerClient;
   bool ok = sa.n_words >= kGlobalHeaderWords;  // everything about `ok` is uniform over the wavefront
@@ -182,15 +182,17 @@ __global__ __launch_bounds__(64) void parse_headers_kernel(ParseChunk chunk, Lis
   }
 }
 
+__global__ __launch_bounds__(64) void parse_headers_kernel(ParseChunk chunk, ListDesc* descs, uint32_t d, uint32_t n,
+                                                           uint32_t* __restrict__ stream_bad, uint32_t quant) {
+  parse_stream(chunk.args[blockIdx.x], chunk.first + blockIdx.x, descs, d, n, stream_bad, quant);
+}
+
 // ------------------------------------------------------------------ 1b. the non-empty lists
-// One workgroup.  Lists with records are numbered in (client, group) order;
-// item_start is the exclusive prefix of their tile_table work items.
-__global__ __launch_bounds__(1024) void compact_lists_kernel(const ListDesc* __restrict__ descs, uint32_t n_lists,
-                                                             CompactDesc* __restrict__ cdesc,
-                                                             uint32_t* __restrict__ item_start, DecodeCtl* ctl,
-                                                             const uint32_t* __restrict__ stream_bad, uint32_t n,
-                                                             uint32_t* status) {
-  __shared__ uint32_t scan_tmp[16];
+// One workgroup of 1024 threads.  Lists with records are numbered in (client,
+// group) order; item_start is the exclusive prefix of their tile_table work items.
+__device__ __forceinline__ void compact_lists(const ListDesc* descs, uint32_t n_lists, CompactDesc* __restrict__ cdesc,
+                                              uint32_t* __restrict__ item_start, DecodeCtl* ctl,
+                                              const uint32_t* stream_bad, uint32_t n, uint32_t* status, uint32_t* scan_tmp) {
   const uint32_t tid = threadIdx.x;
   // the call's status word starts here: set if any stream failed its header checks
   uint32_t any_bad = 0;
@@ -223,6 +225,29 @@ __global__ __launch_bounds__(1024) void compact_lists_kernel(const ListDesc* __r
     ctl->n_active = lists_before;
     ctl->n_items = items_before;
   }
+}
+
+__global__ __launch_bounds__(1024) void compact_lists_kernel(const ListDesc* __restrict__ descs, uint32_t n_lists,
+                                                             CompactDesc* __restrict__ cdesc,
+                                                             uint32_t* __restrict__ item_start, DecodeCtl* ctl,
+                                                             const uint32_t* __restrict__ stream_bad, uint32_t n,
+                                                             uint32_t* status) {
+  __shared__ uint32_t scan_tmp[16];
+  compact_lists(descs, n_lists, cdesc, item_start, ctl, stream_bad, n, status, scan_tmp);
+}
+
+// Both steps in one launch, for calls whose streams fit one set of kernel arguments: the sixteen wavefronts
+// share out the streams, then the workgroup numbers the lists it has just described.
+__global__ __launch_bounds__(1024) void setup_kernel(ParseChunk chunk, ListDesc* descs, uint32_t d, uint32_t quant,
+                                                     CompactDesc* __restrict__ cdesc, uint32_t* __restrict__ item_start,
+                                                     DecodeCtl* ctl, uint32_t* stream_bad, uint32_t* status) {
+  __shared__ uint32_t scan_tmp[16];
+  const uint32_t n = chunk.count;
+  for (uint32_t i = threadIdx.x / kWave; i < n; i += 1024u / kWave)  // uniform per wavefront
+    parse_stream(chunk.args[i], i, descs, d, n, stream_bad, quant);
+  __threadfence_block();
+  __syncthreads();  // the descriptors and flags written above are read below by other wavefronts of this workgroup
+  compact_lists(descs, n * kListsPerClient, cdesc, item_start, ctl, stream_bad, n, status, scan_tmp);
 }
 
 // ------------------------------------------------------------------ 2. tile table
@@ -403,17 +428,59 @@ __global__ __launch_bounds__(kBlock, 6) void tile_table_kernel(const CompactDesc
 // Workgroups walk the output tiles (b, b + workgroups, ...), so that at any time
 // neighbouring tiles are in flight and the stream lines they share are fetched
 // from HBM once.  The records of a tile, over all lists, are numbered
-// 0..total-1 list by list (an exclusive scan of the slice lengths); thread
-// q mod 256 decodes record q, so the work is even however the records are
-// spread over the lists.  List descriptors sit in LDS.
+// 0..total-1 list by list (an exclusive scan of the slice lengths); every
+// wavefront takes a contiguous share of them, 64 at a time ("turn"), so the work
+// is even however the records are spread over the lists and neighbouring lanes
+// read neighbouring records.  Which list a lane's record belongs to: the
+// non-empty slices that start inside the turn set a bit at their first record's
+// place in a 64-bit mask, and a lane counts the bits at or below its own place;
+// only the wavefront's first record needs a search.  List descriptors sit in LDS.
+constexpr uint32_t kDecBlock = 512;  // threads of a decode workgroup
+constexpr uint32_t kDecWaves = kDecBlock / kWave;
+constexpr uint32_t kFirstBits = 22;  // a tile's records over one batch of lists are numbered below 2^22 ...
+constexpr uint32_t kFirstMask = (1u << kFirstBits) - 1u;
+static_assert((uint64_t)kListBatch * kDecTile < (1ull << kFirstBits) && kListBatch <= (1u << (32 - kFirstBits)),
+              "... and the list of a slice fits above that number in one word");
+static_assert(kListBatch == kDecBlock, "one list per thread and batch");
+
 struct DecodeShared {
   double acc[kDecTile];
-  uint4 desc[kListBatch][2];      // CompactDesc, as loaded
-  uint32_t begin[kListBatch];     // first record of the list's slice
-  uint32_t first[kListBatch + 1]; // number of the slice's first record in the tile
+  uint4 desc[kListBatch][2];       // CompactDesc, as loaded
+  // per non-empty slice of the batch, in list order
+  uint32_t begin[kListBatch];      // first record of the slice inside its list
+  uint32_t first[kListBatch + 1];  // number of the slice's first record in the tile | list << kFirstBits; then the total
+  unsigned long long turn_mask[kDecWaves];  // per wavefront: starts of slices inside its current turn
+  uint32_t scan_a[kDecWaves], scan_b[kDecWaves];
 };
 
-constexpr uint32_t kDecBlock = 512;  // threads of a decode workgroup
+// Exclusive prefix sums of two values per thread over the workgroup, in thread order.
+__device__ __forceinline__ void block_excl_scan2(uint32_t va, uint32_t vb, uint32_t* sa, uint32_t* sb, uint32_t* before_a,
+                                                 uint32_t* before_b, uint32_t* total_a, uint32_t* total_b) {
+  const uint32_t ia = wave_incl_scan_u32(va), ib = wave_incl_scan_u32(vb);
+  const uint32_t wave = threadIdx.x / kWave;
+  __syncthreads();
+  if (lane_id() == kWave - 1) {
+    sa[wave] = ia;
+    sb[wave] = ib;
+  }
+  __syncthreads();
+  uint32_t ba = 0, bb = 0, ta = 0, tb = 0;
+#pragma unroll
+  for (uint32_t w = 0; w < kDecWaves; ++w) {
+    const uint32_t xa = sa[w], xb = sb[w];
+    if (w < wave) { ba += xa; bb += xb; }
+    ta += xa;
+    tb += xb;
+  }
+  *before_a = ba + ia - va;
+  *before_b = bb + ib - vb;
+  *total_a = ta;
+  *total_b = tb;
+}
+
+// LDS accesses of one wavefront complete in order; this keeps the compiler from
+// moving them across the point where lanes read what other lanes wrote.
+__device__ __forceinline__ void wave_lds_fence() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
 
 // SIGNED: the streams' codes hold a sign bit above the level (QSGD).
 template <bool SIGNED>
@@ -423,8 +490,8 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
                                                               uint32_t d, uint32_t n_tiles, uint32_t accumulate,
                                                               uint32_t* status) {
   __shared__ DecodeShared S;
-  __shared__ uint32_t scan_tmp[kDecBlock / kWave];
-  const uint32_t tid = threadIdx.x;
+  const uint32_t tid = threadIdx.x, lane = lane_id();
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const uint32_t n_active = ctl->n_active;
   const bool one_batch = n_active <= kListBatch;
   bool bad = false;
@@ -444,102 +511,105 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
         load_descs(l0, nl);
         __syncthreads();
       }
-      // slice of every list of the batch: [begin, end) from two neighbouring table entries
-      constexpr uint32_t per = kListBatch / kDecBlock;
-      uint32_t len[per], mine = 0;
-#pragma unroll
-      for (uint32_t u = 0; u < per; ++u) {
-        const uint32_t li = tid * per + u;  // consecutive lists per thread: the scan below is in list order
-        len[u] = 0;
-        if (li < nl) {
-          const uint32_t P = S.desc[li][1].x;
-          const uint32_t* row = table + (size_t)(l0 + li) * (n_tiles + 1) + tile;
-          uint32_t begin = row[0], end = row[1];
-          if (begin > P) begin = P;  // table entries of a malformed list may hold anything
-          if (end > P) end = P;
-          if (end > begin) len[u] = end - begin;
-          S.begin[li] = begin;
+      // this thread's list: its slice [begin, end) from two neighbouring table entries
+      uint32_t len = 0, begin = 0;
+      if (tid < nl) {
+        const uint32_t P = S.desc[tid][1].x;
+        const uint32_t* row = table + (size_t)(l0 + tid) * (n_tiles + 1) + tile;
+        uint32_t end = row[1];
+        begin = row[0];
+        if (begin > P) begin = P;  // table entries of a malformed list may hold anything
+        if (end > P) end = P;
+        if (end > begin) len = end - begin;
+        if (len > kDecTile) {  // positions ascend strictly: a tile holds at most one record per coordinate
+          bad = true;
+          len = 0;
         }
-        mine += len[u];
       }
-      uint32_t total;
-      uint32_t before = block_excl_scan<kDecBlock / kWave>(mine, scan_tmp, &total);
-#pragma unroll
-      for (uint32_t u = 0; u < per; ++u) {
-        const uint32_t li = tid * per + u;
-        if (li < nl) S.first[li] = before;
-        before += len[u];
+      uint32_t before, j, total, n_live;
+      // (its barriers also separate the writes below from the reads of the batch before)
+      block_excl_scan2(len, len ? 1u : 0u, S.scan_a, S.scan_b, &before, &j, &total, &n_live);
+      if (len) {
+        S.first[j] = before | (tid << kFirstBits);
+        S.begin[j] = begin;
       }
-      if (tid == 0) S.first[nl] = total;
+      if (tid == 0) S.first[n_live] = total;
       __syncthreads();
-      // Six records per thread at a time: searches and descriptors from LDS, then all
-      // record loads together, so that their latencies overlap.  Nothing in the first
-      // half branches (a thread past the end works on the last record again, a record
-      // near the end of its payload reads the last word twice), so that no load has
-      // to be waited for before the next one is issued.
-      constexpr uint32_t kUnroll = 6;
-      uint32_t steps = 0;  // binary search steps that settle any list index below nl
-      while ((1u << steps) < nl) ++steps;
-      for (uint32_t q0 = tid; q0 < total; q0 += kDecBlock * kUnroll) {
-        uint32_t at_of[kUnroll], w0_of[kUnroll], w1_of[kUnroll], w2_of[kUnroll];  // at: list << 8 | flags | shift
-        // the six searches advance together, one LDS round trip per step for all of them
-        uint32_t lo_of[kUnroll], hi_of[kUnroll];
-#pragma unroll
-        for (uint32_t u = 0; u < kUnroll; ++u) {
-          lo_of[u] = 0;   // last list with first <= q (lists with no record in the tile are skipped over)
-          hi_of[u] = nl;
-        }
-        for (uint32_t it = 0; it < steps; ++it) {
-#pragma unroll
-          for (uint32_t u = 0; u < kUnroll; ++u) {
-            const uint32_t q = min(q0 + u * kDecBlock, total - 1u);
-            const uint32_t mid = (lo_of[u] + hi_of[u]) >> 1;
-            const bool take = S.first[mid] <= q;  // mid == lo once hi - lo <= 1: nothing moves any more
-            lo_of[u] = take ? mid : lo_of[u];
-            hi_of[u] = take ? hi_of[u] : mid;
+      // the wavefront's share of the records, a multiple of 64
+      const uint32_t share = ((total + kDecBlock - 1) / kDecBlock) * kWave;
+      const uint32_t q_begin = min(wave * share, total), q_end = min(q_begin + share, total);
+      if (q_begin < q_end) {  // uniform per wavefront
+        uint32_t cur = 0;     // last slice whose first record is at or before the turn's first record (uniform)
+        {
+          uint32_t hi = n_live;
+          while (hi - cur > 1) {
+            const uint32_t mid = (cur + hi) >> 1;
+            if ((S.first[mid] & kFirstMask) <= q_begin) cur = mid; else hi = mid;
           }
+          cur = __builtin_amdgcn_readfirstlane(cur);
         }
+        // Six turns at a time: list lookups and descriptors from LDS, then all record loads together, so
+        // that their latencies overlap.  Nothing in the first half branches on data (a lane past the end
+        // works on the last record again, the words after a record's first are clamped to the record's
+        // last), so that no load has to be waited for before the next one is issued.
+        constexpr uint32_t kTurns = 6;
+        for (uint32_t q0 = q_begin; q0 < q_end; q0 += kWave * kTurns) {
+          const uint32_t n_turns = __builtin_amdgcn_readfirstlane((q_end - q0 + kWave - 1u) / kWave);
+          uint32_t w0[kTurns], w1[kTurns], w2[kTurns], at[kTurns];  // at: list | bit inside the first word << 9
 #pragma unroll
-        for (uint32_t u = 0; u < kUnroll; ++u) {
-          const uint32_t q = min(q0 + u * kDecBlock, total - 1u);
-          const uint32_t a = lo_of[u];
-          const uint4 d0 = S.desc[a][0], d1 = S.desc[a][1];
-          GlobalConstWordPtr pay = (GlobalConstWordPtr)(((uint64_t)d0.y << 32) | d0.x);
-          const uint32_t P = d1.x, W = d1.y & 0xFFu;
-          const uint32_t last_word = (uint32_t)payload_words(P, W) - 1u;  // P >= 1; sizes were checked against 2^32 words
-          const uint32_t e = S.begin[a] + (q - S.first[a]);
-          const uint64_t bit = (uint64_t)e * W;
-          const uint32_t w = (uint32_t)(bit >> 5);
-          at_of[u] = (a << 8) | (uint32_t)(bit & 31u);
-          w0_of[u] = pay[w];
-          w1_of[u] = pay[min(w + 1u, last_word)];
-          w2_of[u] = pay[min(w + 2u, last_word)];
-          if (w + 1u > last_word) at_of[u] |= 0x80u;  // the second word does not exist: reads as 0
-        }
-#pragma unroll
-        for (uint32_t u = 0; u < kUnroll; ++u) {
-          if (q0 + u * kDecBlock >= total) continue;
-          const uint4 d0 = S.desc[at_of[u] >> 8][0], d1 = S.desc[at_of[u] >> 8][1];
-          const uint32_t W = d1.y & 0xFFu, s = (d1.y >> 8) & 0xFFu, y = (d1.y >> 16) & 0xFFu;
-          const double weight = __hiloint2double((int)d0.w, (int)d0.z);
-          const uint32_t sh = at_of[u] & 31u;
-          const uint32_t w1 = (at_of[u] & 0x80u) ? 0u : w1_of[u];
-          uint64_t rec = (((uint64_t)w1 << 32) | w0_of[u]) >> sh;
-          if (sh + W > 64u) rec |= (uint64_t)w2_of[u] << (64u - sh);  // the record's last bit lies in the third word
-          rec &= (1ull << W) - 1ull;
-          const uint32_t pid = (uint32_t)(rec & ((1ull << s) - 1ull));
-          const uint32_t cid = (uint32_t)(rec >> s);
-          if (pid < lo || pid - lo >= kDecTile || pid >= d) { bad = true; continue; }
-          float xhat;
-          if (y == 32) {
-            xhat = __uint_as_float(cid);
-          } else if (SIGNED) {
-            const float mag = __fmaf_rn((float)(cid & ((1u << (y - 1u)) - 1u)), __uint_as_float(d1.w), __uint_as_float(d1.z));
-            xhat = __uint_as_float(__float_as_uint(mag) ^ ((cid >> (y - 1u)) << 31));
-          } else {
-            xhat = __fmaf_rn((float)cid, __uint_as_float(d1.w), __uint_as_float(d1.z));
+          for (uint32_t u = 0; u < kTurns; ++u) {
+            w0[u] = w1[u] = w2[u] = at[u] = 0;
+            if (u >= n_turns) continue;          // uniform
+            const uint32_t qt = q0 + u * kWave;  // the turn's first record (uniform)
+            const uint32_t place = min(lane, q_end - 1u - qt);
+            // slices after `cur` that start inside the turn: first[] ascends strictly, first[n_live] = total
+            const uint32_t f = (S.first[min(cur + 1u + lane, n_live)] & kFirstMask) - qt;  // >= 0
+            if (lane == 0) S.turn_mask[wave] = 0ull;
+            wave_lds_fence();
+            if (f < kWave) atomicOr(&S.turn_mask[wave], 1ull << f);
+            wave_lds_fence();
+            const unsigned long long starts = S.turn_mask[wave];
+            const uint32_t a = cur + (uint32_t)__popcll(starts & ((2ull << place) - 1ull));
+            cur += (uint32_t)__popc((uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)starts)) +
+                   (uint32_t)__popc((uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(starts >> 32)));
+            const uint32_t x = S.first[a], li = x >> kFirstBits;
+            const uint32_t e = S.begin[a] + (qt + place - (x & kFirstMask));
+            const uint4 d0 = S.desc[li][0], d1 = S.desc[li][1];
+            GlobalConstWordPtr pay = (GlobalConstWordPtr)(((uint64_t)d0.y << 32) | d0.x);
+            const uint32_t W = d1.y & 0xFFu;
+            const uint64_t bit = (uint64_t)e * W;
+            const uint32_t w = (uint32_t)(bit >> 5), sh = (uint32_t)bit & 31u;  // payloads have fewer than 2^32 words
+            const uint32_t w_end = w + ((sh + W - 1u) >> 5);                   // the word that holds the record's last bit
+            at[u] = li | (sh << 9);
+            w0[u] = pay[w];
+            w1[u] = pay[min(w + 1u, w_end)];
+            w2[u] = pay[min(w + 2u, w_end)];
           }
-          atomicAdd(&S.acc[pid - lo], weight * (double)xhat);
+#pragma unroll
+          for (uint32_t u = 0; u < kTurns; ++u) {
+            if (u >= n_turns) continue;  // uniform
+            if (q0 + u * kWave + lane >= q_end) continue;
+            const uint32_t li = at[u] & 511u, sh = at[u] >> 9;
+            const uint4 d0 = S.desc[li][0], d1 = S.desc[li][1];
+            const uint32_t s = (d1.y >> 8) & 0xFFu, y = (d1.y >> 16) & 0xFFu;
+            const double weight = __hiloint2double((int)d0.w, (int)d0.z);
+            const uint32_t lo32 = __builtin_amdgcn_alignbit(w1[u], w0[u], sh);  // bits [sh, sh + 32) of the three words
+            const uint32_t hi32 = __builtin_amdgcn_alignbit(w2[u], w1[u], sh);  // bits [sh + 32, sh + 64)
+            const uint32_t pid = lo32 & (s >= 32 ? 0xFFFFFFFFu : (1u << s) - 1u);
+            const uint32_t code_mask = y >= 32 ? 0xFFFFFFFFu : (1u << y) - 1u;
+            const uint32_t cid = __builtin_amdgcn_alignbit(hi32, lo32, s & 31u) & code_mask;  // s <= 31
+            if (pid - lo >= kDecTile || pid >= d) { bad = true; continue; }  // a position below the tile wraps to a large value
+            float xhat;
+            if (y == 32) {
+              xhat = __uint_as_float(cid);
+            } else if (SIGNED) {
+              const float mag = __fmaf_rn((float)(cid & ((1u << (y - 1u)) - 1u)), __uint_as_float(d1.w), __uint_as_float(d1.z));
+              xhat = __uint_as_float(__float_as_uint(mag) ^ ((cid >> (y - 1u)) << 31));
+            } else {
+              xhat = __fmaf_rn((float)cid, __uint_as_float(d1.w), __uint_as_float(d1.z));
+            }
+            atomicAdd(&S.acc[pid - lo], weight * (double)xhat);
+          }
         }
       }
     }
@@ -624,6 +694,7 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
   {
     ParseChunk chunk;
     chunk.pad[0] = chunk.pad[1] = 0;
+    const bool fused = n > 0 && n <= kParseStreams;  // one launch parses and numbers
     for (uint32_t first = 0; first < n; first += kParseStreams) {
       chunk.first = first;
       chunk.count = (n - first < kParseStreams) ? n - first : kParseStreams;
@@ -635,12 +706,17 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
         sa.has_weight = weights ? 1u : 0u;
         sa.pad = 0;
       }
-      hipLaunchKernelGGL(parse_headers_kernel, dim3(chunk.count), dim3(64), 0, stream, chunk, descs, d, n, stream_bad,
-                         quant);
+      if (fused)
+        hipLaunchKernelGGL(setup_kernel, dim3(1), dim3(1024), 0, stream, chunk, descs, d, quant, cdesc, item_start, ctl,
+                           stream_bad, status);
+      else
+        hipLaunchKernelGGL(parse_headers_kernel, dim3(chunk.count), dim3(64), 0, stream, chunk, descs, d, n, stream_bad,
+                           quant);
     }
     // also for n = 0: writes the (empty) list counts and the status word
-    hipLaunchKernelGGL(compact_lists_kernel, dim3(1), dim3(1024), 0, stream, descs, n_lists, cdesc, item_start, ctl,
-                       stream_bad, n, status);
+    if (!fused)
+      hipLaunchKernelGGL(compact_lists_kernel, dim3(1), dim3(1024), 0, stream, descs, n_lists, cdesc, item_start, ctl,
+                         stream_bad, n, status);
   }
   profile_mark(CVLC_STAGE_DEC_SETUP, false, stream);
   if (n > 0) {
