@@ -437,6 +437,7 @@ __global__ __launch_bounds__(kBlock, 6) void tile_table_kernel(const CompactDesc
 // only the wavefront's first record needs a search.  List descriptors sit in LDS.
 constexpr uint32_t kDecBlock = 512;  // threads of a decode workgroup
 constexpr uint32_t kDecWaves = kDecBlock / kWave;
+constexpr uint32_t kDecTurns = 6;    // turns of 64 records a wavefront works on together
 constexpr uint32_t kFirstBits = 22;  // a tile's records over one batch of lists are numbered below 2^22 ...
 constexpr uint32_t kFirstMask = (1u << kFirstBits) - 1u;
 static_assert((uint64_t)kListBatch * kDecTile < (1ull << kFirstBits) && kListBatch <= (1u << (32 - kFirstBits)),
@@ -449,7 +450,7 @@ struct DecodeShared {
   // per non-empty slice of the batch, in list order
   uint32_t begin[kListBatch];      // first record of the slice inside its list
   uint32_t first[kListBatch + 1];  // number of the slice's first record in the tile | list << kFirstBits; then the total
-  unsigned long long turn_mask[kDecWaves];  // per wavefront: starts of slices inside its current turn
+  unsigned long long turn_mask[kDecWaves][kDecTurns];  // per wavefront: starts of slices inside each of its current turns
   uint32_t scan_a[kDecWaves], scan_b[kDecWaves];
 };
 
@@ -500,8 +501,21 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
     for (uint32_t i = tid; i < nl * 2u; i += kDecBlock) (&S.desc[0][0])[i] = src[i];
   };
   if (one_batch) load_descs(0, n_active);
+  // the two table entries of this thread's list (first batch) for the next tile, asked for a tile ahead
+  auto request_rows = [&](uint32_t tile) {
+    uint2 r = make_uint2(0u, 0u);
+    if (tile < n_tiles && tid < min(n_active, kListBatch)) {
+      const uint32_t* row = table + (size_t)tid * (n_tiles + 1) + tile;
+      r.x = row[0];
+      r.y = row[1];
+    }
+    return r;
+  };
+  uint2 next_rows = request_rows(blockIdx.x);
   for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const uint32_t lo = tile * kDecTile;
+    const uint2 rows = next_rows;
+    next_rows = request_rows(tile + gridDim.x);
     __syncthreads();  // the tile before is written out; the descriptors are in place
     for (uint32_t i = tid; i < kDecTile; i += kDecBlock) S.acc[i] = 0.0;
     for (uint32_t l0 = 0; l0 < n_active; l0 += kListBatch) {
@@ -515,9 +529,15 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
       uint32_t len = 0, begin = 0;
       if (tid < nl) {
         const uint32_t P = S.desc[tid][1].x;
-        const uint32_t* row = table + (size_t)(l0 + tid) * (n_tiles + 1) + tile;
-        uint32_t end = row[1];
-        begin = row[0];
+        uint32_t end;
+        if (l0 == 0) {
+          begin = rows.x;
+          end = rows.y;
+        } else {
+          const uint32_t* row = table + (size_t)(l0 + tid) * (n_tiles + 1) + tile;
+          begin = row[0];
+          end = row[1];
+        }
         if (begin > P) begin = P;  // table entries of a malformed list may hold anything
         if (end > P) end = P;
         if (end > begin) len = end - begin;
@@ -539,7 +559,7 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
       const uint32_t share = ((total + kDecBlock - 1) / kDecBlock) * kWave;
       const uint32_t q_begin = min(wave * share, total), q_end = min(q_begin + share, total);
       if (q_begin < q_end) {  // uniform per wavefront
-        uint32_t cur = 0;     // last slice whose first record is at or before the turn's first record (uniform)
+        uint32_t cur = 0;     // last slice whose first record is at or before the first record of the turns at hand (uniform)
         {
           uint32_t hi = n_live;
           while (hi - cur > 1) {
@@ -548,35 +568,57 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
           }
           cur = __builtin_amdgcn_readfirstlane(cur);
         }
-        // Six turns at a time: list lookups and descriptors from LDS, then all record loads together, so
-        // that their latencies overlap.  Nothing in the first half branches on data (a lane past the end
-        // works on the last record again, the words after a record's first are clamped to the record's
-        // last), so that no load has to be waited for before the next one is issued.
-        constexpr uint32_t kTurns = 6;
-        for (uint32_t q0 = q_begin; q0 < q_end; q0 += kWave * kTurns) {
-          const uint32_t n_turns = __builtin_amdgcn_readfirstlane((q_end - q0 + kWave - 1u) / kWave);
-          uint32_t w0[kTurns], w1[kTurns], w2[kTurns], at[kTurns];  // at: list | bit inside the first word << 9
+        // kDecTurns turns at a time.  First the start masks of all of them; then, turn by turn but without one
+        // turn waiting for another, list and record number from LDS; then all record loads together, so that their
+        // latencies overlap.  Nothing in this half branches on data (a lane past the end works on the last record
+        // again, the words after a record's first are clamped to the record's last), so that no load has to be
+        // waited for before the next one is issued.
+        unsigned long long* masks = S.turn_mask[wave];
+        for (uint32_t q0 = q_begin; q0 < q_end; q0 += kWave * kDecTurns) {
+          const uint32_t n_turns = __builtin_amdgcn_readfirstlane(min((q_end - q0 + kWave - 1u) / kWave, kDecTurns));
+          // slices after `cur` that start inside the turns: first[] ascends strictly, first[n_live] = total.
+          // 64 slices are looked at per round; more start inside the turns only when most hold a few records.
+          if (lane < kDecTurns) masks[lane] = 0ull;
+          wave_lds_fence();
+          for (uint32_t seen = 0;; seen += kWave) {  // uniform
+            const uint32_t idx = cur + 1u + seen + lane;
+            const uint32_t f = (S.first[min(idx, n_live)] & kFirstMask) - q0;  // >= 0
+            if (idx <= n_live && f < kWave * kDecTurns) atomicOr(&masks[f >> 6], 1ull << (f & 63u));
+            // done when the last one looked at lies past the turns at hand, or nothing is left to look at
+            if (cur + seen + kWave >= n_live || __builtin_amdgcn_readlane(f, kWave - 1) >= kWave * n_turns) break;
+          }
+          wave_lds_fence();
+          uint32_t base_of[kDecTurns], w0[kDecTurns], w1[kDecTurns], w2[kDecTurns], at[kDecTurns];  // at: list | bit inside the first word << 9
+          unsigned long long starts[kDecTurns];
 #pragma unroll
-          for (uint32_t u = 0; u < kTurns; ++u) {
-            w0[u] = w1[u] = w2[u] = at[u] = 0;
+          for (uint32_t u = 0; u < kDecTurns; ++u) starts[u] = masks[u];
+#pragma unroll
+          for (uint32_t u = 0; u < kDecTurns; ++u) {
+            base_of[u] = cur;
+            if (u < n_turns)  // uniform; the sentinel's bit lies in the last turn at hand or past it
+              cur += (uint32_t)__popc((uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)starts[u])) +
+                     (uint32_t)__popc((uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(starts[u] >> 32)));
+          }
+          uint32_t x_of[kDecTurns], e_of[kDecTurns];
+#pragma unroll
+          for (uint32_t u = 0; u < kDecTurns; ++u) {
+            x_of[u] = e_of[u] = 0;
             if (u >= n_turns) continue;          // uniform
             const uint32_t qt = q0 + u * kWave;  // the turn's first record (uniform)
             const uint32_t place = min(lane, q_end - 1u - qt);
-            // slices after `cur` that start inside the turn: first[] ascends strictly, first[n_live] = total
-            const uint32_t f = (S.first[min(cur + 1u + lane, n_live)] & kFirstMask) - qt;  // >= 0
-            if (lane == 0) S.turn_mask[wave] = 0ull;
-            wave_lds_fence();
-            if (f < kWave) atomicOr(&S.turn_mask[wave], 1ull << f);
-            wave_lds_fence();
-            const unsigned long long starts = S.turn_mask[wave];
-            const uint32_t a = cur + (uint32_t)__popcll(starts & ((2ull << place) - 1ull));
-            cur += (uint32_t)__popc((uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)starts)) +
-                   (uint32_t)__popc((uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(starts >> 32)));
-            const uint32_t x = S.first[a], li = x >> kFirstBits;
-            const uint32_t e = S.begin[a] + (qt + place - (x & kFirstMask));
-            const uint4 d0 = S.desc[li][0], d1 = S.desc[li][1];
-            GlobalConstWordPtr pay = (GlobalConstWordPtr)(((uint64_t)d0.y << 32) | d0.x);
-            const uint32_t W = d1.y & 0xFFu;
+            const uint32_t a = base_of[u] + (uint32_t)__popcll(starts[u] & ((2ull << place) - 1ull));
+            x_of[u] = S.first[a];
+            e_of[u] = S.begin[a] + (qt + place);
+          }
+#pragma unroll
+          for (uint32_t u = 0; u < kDecTurns; ++u) {
+            w0[u] = w1[u] = w2[u] = at[u] = 0;
+            if (u >= n_turns) continue;  // uniform
+            const uint32_t li = x_of[u] >> kFirstBits;
+            const uint32_t e = e_of[u] - (x_of[u] & kFirstMask);
+            const uint2 ptr = *reinterpret_cast<const uint2*>(&S.desc[li][0]);  // payload
+            const uint32_t W = S.desc[li][1].y & 0xFFu;
+            GlobalConstWordPtr pay = (GlobalConstWordPtr)(((uint64_t)ptr.y << 32) | ptr.x);
             const uint64_t bit = (uint64_t)e * W;
             const uint32_t w = (uint32_t)(bit >> 5), sh = (uint32_t)bit & 31u;  // payloads have fewer than 2^32 words
             const uint32_t w_end = w + ((sh + W - 1u) >> 5);                   // the word that holds the record's last bit
@@ -586,7 +628,7 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
             w2[u] = pay[min(w + 2u, w_end)];
           }
 #pragma unroll
-          for (uint32_t u = 0; u < kTurns; ++u) {
+          for (uint32_t u = 0; u < kDecTurns; ++u) {
             if (u >= n_turns) continue;  // uniform
             if (q0 + u * kWave + lane >= q_end) continue;
             const uint32_t li = at[u] & 511u, sh = at[u] >> 9;
@@ -614,12 +656,34 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
       }
     }
     __syncthreads();
-    for (uint32_t i = tid; i < kDecTile; i += kDecBlock) {
-      const uint32_t j = lo + i;
-      if (j < d) {
-        double v = S.acc[i];
-        if (accumulate) v += (double)out[j];
-        out[j] = (float)v;
+    // eight consecutive coordinates per thread: four 16-byte LDS reads, then the stores
+    static_assert(kDecTile == kDecBlock * 8u, "eight coordinates per thread");
+    {
+      const uint32_t j0 = lo + tid * 8u;
+      double v[8];
+#pragma unroll
+      for (uint32_t c = 0; c < 8u; c += 2u) {
+        const double2 t = *reinterpret_cast<const double2*>(&S.acc[tid * 8u + c]);
+        v[c] = t.x;
+        v[c + 1] = t.y;
+      }
+      if (j0 + 8u <= d && (reinterpret_cast<uintptr_t>(out + j0) & 15u) == 0) {
+        float4* dst = reinterpret_cast<float4*>(out + j0);
+        if (accumulate) {
+          const float4 o0 = dst[0], o1 = dst[1];
+          v[0] += (double)o0.x; v[1] += (double)o0.y; v[2] += (double)o0.z; v[3] += (double)o0.w;
+          v[4] += (double)o1.x; v[5] += (double)o1.y; v[6] += (double)o1.z; v[7] += (double)o1.w;
+        }
+        dst[0] = make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
+        dst[1] = make_float4((float)v[4], (float)v[5], (float)v[6], (float)v[7]);
+      } else {
+        for (uint32_t c = 0; c < 8u; ++c) {
+          if (j0 + c < d) {
+            double x = v[c];
+            if (accumulate) x += (double)out[j0 + c];
+            out[j0 + c] = (float)x;
+          }
+        }
       }
     }
   }
