@@ -559,14 +559,18 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
       const uint32_t share = ((total + kDecBlock - 1) / kDecBlock) * kWave;
       const uint32_t q_begin = min(wave * share, total), q_end = min(q_begin + share, total);
       if (q_begin < q_end) {  // uniform per wavefront
-        uint32_t cur = 0;     // last slice whose first record is at or before the first record of the turns at hand (uniform)
+        // last slice whose first record is at or before the first record of the turns at hand (uniform): the
+        // lanes look at all slices of the batch at once (first[] ascends; slice 0 starts at record 0)
+        uint32_t cur = 0;
         {
-          uint32_t hi = n_live;
-          while (hi - cur > 1) {
-            const uint32_t mid = (cur + hi) >> 1;
-            if ((S.first[mid] & kFirstMask) <= q_begin) cur = mid; else hi = mid;
+          uint32_t at_or_before = 0;
+#pragma unroll
+          for (uint32_t k = 0; k < kListBatch / kWave; ++k) {
+            const uint32_t i = k * kWave + lane;
+            const bool hit = i < n_live && (S.first[min(i, n_live)] & kFirstMask) <= q_begin;
+            at_or_before += (uint32_t)__popcll(__ballot(hit));
           }
-          cur = __builtin_amdgcn_readfirstlane(cur);
+          cur = __builtin_amdgcn_readfirstlane(at_or_before) - 1u;
         }
         // kDecTurns turns at a time.  First the start masks of all of them; then, turn by turn but without one
         // turn waiting for another, list and record number from LDS; then all record loads together, so that their
@@ -656,33 +660,28 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
       }
     }
     __syncthreads();
-    // eight consecutive coordinates per thread: four 16-byte LDS reads, then the stores
-    static_assert(kDecTile == kDecBlock * 8u, "eight coordinates per thread");
+    // four pairs of coordinates per thread, neighbouring lanes neighbouring pairs (LDS reads without bank
+    // conflicts, 512-byte stores per wavefront): all reads first, then the stores
+    static_assert(kDecTile == kDecBlock * 8u, "four pairs of coordinates per thread");
     {
-      const uint32_t j0 = lo + tid * 8u;
-      double v[8];
+      double2 v[4];
 #pragma unroll
-      for (uint32_t c = 0; c < 8u; c += 2u) {
-        const double2 t = *reinterpret_cast<const double2*>(&S.acc[tid * 8u + c]);
-        v[c] = t.x;
-        v[c + 1] = t.y;
-      }
-      if (j0 + 8u <= d && (reinterpret_cast<uintptr_t>(out + j0) & 15u) == 0) {
-        float4* dst = reinterpret_cast<float4*>(out + j0);
-        if (accumulate) {
-          const float4 o0 = dst[0], o1 = dst[1];
-          v[0] += (double)o0.x; v[1] += (double)o0.y; v[2] += (double)o0.z; v[3] += (double)o0.w;
-          v[4] += (double)o1.x; v[5] += (double)o1.y; v[6] += (double)o1.z; v[7] += (double)o1.w;
-        }
-        dst[0] = make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
-        dst[1] = make_float4((float)v[4], (float)v[5], (float)v[6], (float)v[7]);
-      } else {
-        for (uint32_t c = 0; c < 8u; ++c) {
-          if (j0 + c < d) {
-            double x = v[c];
-            if (accumulate) x += (double)out[j0 + c];
-            out[j0 + c] = (float)x;
+      for (uint32_t c = 0; c < 4u; ++c) v[c] = *reinterpret_cast<const double2*>(&S.acc[c * (2u * kDecBlock) + tid * 2u]);
+      const bool aligned = (reinterpret_cast<uintptr_t>(out + lo) & 7u) == 0;  // uniform
+#pragma unroll
+      for (uint32_t c = 0; c < 4u; ++c) {
+        const uint32_t j0 = lo + c * (2u * kDecBlock) + tid * 2u;
+        if (aligned && j0 + 2u <= d) {
+          float2* dst = reinterpret_cast<float2*>(out + j0);
+          if (accumulate) {
+            const float2 o = *dst;
+            v[c].x += (double)o.x;
+            v[c].y += (double)o.y;
           }
+          *dst = make_float2((float)v[c].x, (float)v[c].y);
+        } else {
+          if (j0 < d) out[j0] = (float)(accumulate ? v[c].x + (double)out[j0] : v[c].x);
+          if (j0 + 1u < d) out[j0 + 1u] = (float)(accumulate ? v[c].y + (double)out[j0 + 1u] : v[c].y);
         }
       }
     }
