@@ -25,12 +25,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E peak
 PLANNER_ALPHA = -0.5      # power-law exponent handed to Algorithm 1 for the planned workloads
 DOMINANT_KERNEL = "filter_kernel<0>"   # the one full pass over the update vectors
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "filter_kernel_cfg3_hbm_traffic.txt")
-KERNEL_SOURCES = ["cvlc_common.h", "cvlc_encode.hip"]
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hot_path_cfg3_hbm_traffic.txt")
+KERNEL_SOURCES = ["cvlc_common.h", "cvlc_encode.hip", "cvlc_decode.hip"]
+CALL_TARGET_FRAC = 0.60   # the bar each call is held to: 60 % of the HBM peak on its algorithmic bytes
 
 
 def kernel_source_digest():
-    """sha256 over the sources the dominant kernel is built from."""
+    """sha256 over the sources the hot path's kernels are built from."""
     import hashlib
 
     h = hashlib.sha256()
@@ -41,8 +42,11 @@ def kernel_source_digest():
 
 
 def recorded_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed counter summary, or
-    None when there is none or the kernel's sources have changed since it was taken."""
+    """HBM bytes per launch (dominant kernel) and per call (encode, decode-aggregate) from the committed
+    counter summary: {"filter": .., "encode": .., "decode_aggregate": ..}, every entry None when there is no
+    summary or the kernels' sources have changed since the counters were taken."""
+    keys = {"filter": "filter_traffic_bytes_per_launch", "encode": "encode_traffic_bytes_per_call",
+            "decode_aggregate": "decode_aggregate_traffic_bytes_per_call"}
     try:
         fields = {}
         with open(TRAFFIC_FILE) as f:
@@ -51,10 +55,10 @@ def recorded_traffic():
                     k, v = line.split(":", 1)
                     fields[k.strip()] = v.strip()
         if fields.get("source_sha256") != kernel_source_digest():
-            return None
-        return float(fields["traffic_bytes_per_launch"])
+            return {k: None for k in keys}
+        return {k: float(fields[name]) for k, name in keys.items()}
     except (OSError, KeyError, ValueError):
-        return None
+        return {k: None for k in keys}
 
 
 def make_plans(cv, w, n, d, quant=0):
@@ -78,8 +82,10 @@ def make_plans(cv, w, n, d, quant=0):
     return plans
 
 
-def cpu_baseline(host_updates, w, d, seconds_cap=25.0):
-    """The oracle, single thread, on as many clients as fit the time cap (at least one)."""
+def cpu_baseline(host_updates, w, d, gpu_streams, gpu_aggregate_of, seconds_cap=25.0):
+    """The oracle, single thread, on as many clients as fit the time cap (at least one).  Before anything is
+    reported, the streams it has just produced are compared word for word with the ones the timed GPU run left
+    behind, and its aggregate of them with the GPU's aggregate of the same clients."""
     from oracle import cvlc_oracle as orc
 
     streams, t_enc, done = [], 0.0, 0
@@ -92,12 +98,23 @@ def cpu_baseline(host_updates, w, d, seconds_cap=25.0):
         if t_enc > seconds_cap * 0.8:
             break
     t0 = time.perf_counter()
-    orc.decode_aggregate(streams, d)
+    ref = orc.decode_aggregate(streams, d)
     t_dec = time.perf_counter() - t0
+    # parity of the run that was timed
+    for c in range(done):
+        got = gpu_streams[c].cpu().numpy().view(np.uint32)[: streams[c].size]
+        if not np.array_equal(got, streams[c]):
+            raise SystemExit(f"bench.py: the GPU stream of client {c} differs from the oracle's")
+    got = gpu_aggregate_of(done).astype(np.float64)
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        terms = sum(ex.map(lambda sw: np.abs(orc.decode_aggregate([sw], d, weights=[1.0]).astype(np.float64)), streams))
+    if not np.all(np.abs(got - ref.astype(np.float64)) <= 1e-5 * terms / done):
+        raise SystemExit("bench.py: the GPU aggregate differs from the oracle's beyond 1e-5 of the summed magnitudes")
     total = t_enc + t_dec
     result = {
         "value": done * d / total / 1e9, "unit": "G-coords/s", "cores": 1, "kind": "oracle",
         "sample": f"{done} of {len(host_updates)} clients, d={d}: encode {t_enc:.2f}s + decode-aggregate {t_dec:.2f}s, single thread",
+        "parity": f"streams of these {done} clients word for word equal to the timed GPU run's; aggregate of them within 1e-5 of the summed magnitudes",
     }
     # the same oracle with whole clients spread over the host's cores (one client per thread, one round)
     avail = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
@@ -222,6 +239,15 @@ def main() -> int:
     dec_bytes = stream_bytes + 4.0 * d                # streams read + dense vector written
     filter_bytes = 4.0 * n * d                        # what the filter launch must read
     achieved = filter_bytes / (filter_ms * 1e-3) / 1e9
+    traffic = recorded_traffic()
+
+    def call(t, alg_bytes, key):
+        """One call of the boundary against the HBM roofline on its algorithmic bytes."""
+        gbs = alg_bytes / t / 1e9
+        return {"ms": t * 1e3, "g_coords_s": n * d / t / 1e9, "algorithmic_gb": alg_bytes / 1e9, "achieved_gb_s": gbs,
+                "hbm_frac": gbs / HBM_PEAK_GBS, "target_frac": CALL_TARGET_FRAC, "meets_target": gbs / HBM_PEAK_GBS >= CALL_TARGET_FRAC,
+                "traffic": traffic[key]}
+
     result = {
         "metric": "encode + decode-aggregate G-coords/s and % of HBM peak, 1 MI355X",
         "value": n * d / t_step / 1e9,
@@ -232,12 +258,12 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"cfg{args.cfg} {w.name}: {n} clients, d={d}, {w.n_coded} coded groups + 0-bit tail, "
                                f"{stream_bytes * 8 / (n * d):.3f} bit/coord", "clients": n, "d": d},
-        "encode": {"ms": t_enc * 1e3, "g_coords_s": n * d / t_enc / 1e9, "algorithmic_gb": enc_bytes / 1e9,
-                   "hbm_frac": enc_bytes / t_enc / 1e9 / HBM_PEAK_GBS},
-        "decode_aggregate": {"ms": t_dec * 1e3, "g_coords_s": n * d / t_dec / 1e9, "algorithmic_gb": dec_bytes / 1e9,
-                             "hbm_frac": dec_bytes / t_dec / 1e9 / HBM_PEAK_GBS},
+        # the two calls of the boundary, each as a whole (what the 60 % bar is stated on)
+        "encode": call(t_enc, enc_bytes, "encode"),
+        "decode_aggregate": call(t_dec, dec_bytes, "decode_aggregate"),
+        # the dominant kernel alone
         "roofline": {"bound": "hbm", "kernel": DOMINANT_KERNEL, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": recorded_traffic(),
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic["filter"],
                      "launch_ms": filter_ms},
     }
     result["fit_alpha"] = {"ms": t_fit * 1e3, "g_coords_s": n * d / t_fit / 1e9, "algorithmic_gb": 4.0 * n * d / 1e9,
@@ -246,7 +272,13 @@ def main() -> int:
     if quant:
         result["config"]["quantiser"] = "qsgd"
     if not args.no_cpu_baseline and not quant:   # the baseline is defined for the benchmark's quantiser
-        result["cpu_baseline"] = cpu_baseline(host, w, d)
+        def gpu_aggregate_of(count):
+            sub = torch.empty(d, dtype=torch.float32, device=dev)
+            cv.decode_aggregate(streams[:count], sub, dec_ws)
+            assert cv.device_status(dec_ws) == 0
+            return sub.cpu().numpy()
+
+        result["cpu_baseline"] = cpu_baseline(host, w, d, streams, gpu_aggregate_of)
     print(json.dumps(result))
     return 0
 

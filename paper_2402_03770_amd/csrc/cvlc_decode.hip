@@ -122,9 +122,15 @@ __device__ __forceinline__ void parse_stream(const StreamArg& sa, uint32_t clien
   ListDesc* out = descs + (size_t)client * kListsPerClient;
   bool ok = sa.n_words >= kGlobalHeaderWords;  // everything about `ok` is uniform over the wavefront
   uint32_t g[kGlobalHeaderWords] = {0, 0, 0, 0, 0, 0, 0, 0};
+  // The group headers are asked for together with the global header, before the number of groups is known
+  // (lane r: where group r's header would be, clamped to the stream), so that one memory round trip serves both.
+  uint32_t hw[kSegHeaderWords] = {0, 0, 0, 0};
   if (ok) {
 #pragma unroll
     for (uint32_t i = 0; i < kGlobalHeaderWords; ++i) g[i] = w[i];
+#pragma unroll
+    for (uint32_t i = 0; i < kSegHeaderWords; ++i)
+      hw[i] = w[min((uint64_t)(kGlobalHeaderWords + kSegHeaderWords * min(t, CVLC_MAX_CODED - 1u) + i), sa.n_words - 1u)];
   }
   const uint32_t R = g[3], s = g[4];
   const float B = __uint_as_float(g[5]);
@@ -135,12 +141,11 @@ __device__ __forceinline__ void parse_stream(const StreamArg& sa, uint32_t clien
   const bool mine = ok && t < R;
   uint32_t y = 0, P = 0;
   float m = 0.0f, M = 0.0f;
-  if (mine) {
-    GlobalConstWordPtr h = w + kGlobalHeaderWords + kSegHeaderWords * t;
-    y = h[0];
-    P = h[1];
-    m = __uint_as_float(h[2]);
-    M = __uint_as_float(h[3]);
+  if (mine) {  // t < R <= 31 and the stream holds all R headers: the words read above are group t's
+    y = hw[0];
+    P = hw[1];
+    m = __uint_as_float(hw[2]);
+    M = __uint_as_float(hw[3]);
   }
   bool header_ok = !mine || (code_len_supported(y) && fabsf(m) <= 3.4028234664e38f &&
                              fabsf(M) <= 3.4028234664e38f && fabsf(M - m) <= 3.4028234664e38f);
