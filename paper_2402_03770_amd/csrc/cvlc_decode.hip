@@ -26,8 +26,7 @@ namespace cvlc {
 namespace {
 
 constexpr uint32_t kListsPerClient = 32;   // descriptor slots per client (CVLC_MAX_CODED used)
-constexpr uint32_t kTabChunk = 2048;       // records per tile_table work item
-constexpr uint32_t kTabWords = kTabChunk / 32u * 63u + 8u;  // words such a chunk can span, plus the record before it, plus one
+constexpr uint32_t kTabChunk = 512;        // records per tile_table work item (one wavefront, eight a lane)
 constexpr uint32_t kListBatch = 512;       // lists a decode workgroup handles per sweep
 
 struct CompactDesc {  // one non-empty (client, group) record list, 32 bytes
@@ -259,35 +258,18 @@ __global__ __launch_bounds__(1024) void setup_kernel(ParseChunk chunk, ListDesc*
 // table[list][t] = index of the first record of `list` whose position lies in
 // output tile t or later; entry n_tiles holds the list length.  (List-major: a
 // list's entries are written in ascending t by neighbouring threads.)  A work
-// item is a run of kTabChunk records of one list: its stream words are brought
-// into LDS with coalesced loads, then thread e compares the tiles of records e-1
-// and e and fills the entries in between.
+// item is a run of kTabChunk records of one list and belongs to one wavefront:
+// lane l reads the position fields of records l, l + 64, ... of the run straight
+// from the stream (neighbouring lanes, neighbouring words), all of them in flight
+// together, and compares each with the one before it.  Wavefronts never wait for
+// each other.  The pass also checks that positions ascend and stay below d.
+constexpr uint32_t kTabTurns = kTabChunk / kWave;  // records of an item a lane looks at
 
-// What a work item needs from its list, and where its records sit.
-struct TabItem {
-  GlobalConstWordPtr src;  // first word brought into LDS
-  uint32_t list, P, W, s;
-  uint32_t e0, cnt;        // records e0 .. e0+cnt-1
-  uint32_t e_lo;           // e0 - 1 (the record before, whose tile the first comparison needs), or 0
-  uint32_t nw;             // words that hold records e_lo .. e0+cnt-1
-  uint32_t bit_base;       // bit of record e_lo inside the first word
-};
-
-constexpr uint32_t kTabRegs = (kTabWords + kBlock - 1) / kBlock;  // stream words a thread carries for the next item
-
-// Position field of the record whose first bit is `bit` of an LDS word array: its s <= 31 low bits lie in
-// at most two words, whatever the record's width.  The word after must exist in the array (not in the data).
-__device__ __forceinline__ uint32_t lds_pid(const uint32_t* words, uint32_t bit, uint32_t pid_mask) {
-  const uint32_t w = bit >> 5;
-  return __builtin_amdgcn_alignbit(words[w + 1], words[w], bit & 31u) & pid_mask;
-}
-
-__global__ __launch_bounds__(kBlock, 6) void tile_table_kernel(const CompactDesc* __restrict__ cdesc,
-                                                            const uint32_t* __restrict__ item_start,
-                                                            const DecodeCtl* __restrict__ ctl, uint32_t* table,
-                                                            uint32_t d, uint32_t n_tiles, uint32_t* status) {
+__global__ __launch_bounds__(kBlock, 8) void tile_table_kernel(const CompactDesc* __restrict__ cdesc,
+                                                         const uint32_t* __restrict__ item_start,
+                                                         const DecodeCtl* __restrict__ ctl, uint32_t* table,
+                                                         uint32_t d, uint32_t n_tiles, uint32_t* status) {
   constexpr uint32_t kStartCache = 2048;
-  __shared__ uint32_t s_words[kTabWords];
   __shared__ uint32_t s_start[kStartCache];
   const uint32_t tid = threadIdx.x, lane = lane_id();
   const uint32_t n_active = ctl->n_active, n_items = ctl->n_items;
@@ -295,136 +277,100 @@ __global__ __launch_bounds__(kBlock, 6) void tile_table_kernel(const CompactDesc
   if (cached)
     for (uint32_t i = tid; i < n_active; i += kBlock) s_start[i] = item_start[i];
   __syncthreads();
-  // The items of a workgroup (b, b + workgroups, ...) go through a pipeline two deep: while item i is
-  // worked on from LDS, the stream words of item i+1 are on their way into registers and the list
-  // descriptor of item i+2 is on its way as well, so that no step waits for a whole memory round trip.
-  struct Located {
-    uint4 d0, d1;  // the list's CompactDesc as loaded
-    uint32_t list, first_item;
-  };
-  auto locate = [&](uint32_t q) {
-    Located L;
-    L.d0 = make_uint4(0u, 0u, 0u, 0u);
-    L.d1 = L.d0;
-    L.list = 0;
-    L.first_item = 0;
-    if (q < n_items) {
-      uint32_t a = 0, b = n_active;  // the list that owns item q: last list with item_start <= q (uniform)
-      while (b - a > 1) {
-        const uint32_t mid = (a + b) >> 1;
-        const uint32_t v = cached ? s_start[mid] : item_start[mid];
-        if (v <= q) a = mid; else b = mid;
-      }
-      L.list = a;
-      L.first_item = cached ? s_start[a] : item_start[a];
-      const uint4* src = reinterpret_cast<const uint4*>(cdesc + a);
-      L.d0 = src[0];
-      L.d1 = src[1];
-    }
-    return L;
-  };
-  auto geometry = [&](const Located& L, uint32_t q) {
-    TabItem it;
-    it.list = L.list;
-    it.P = L.d1.x;
-    it.W = L.d1.y & 0xFFu;
-    it.s = (L.d1.y >> 8) & 0xFFu;
-    it.e0 = (q - L.first_item) * kTabChunk;
-    it.cnt = min(it.P - it.e0, kTabChunk);
-    it.e_lo = it.e0 ? it.e0 - 1 : 0;
-    const uint64_t bit_lo = (uint64_t)it.e_lo * it.W, bit_hi = (uint64_t)(it.e0 + it.cnt) * it.W;
-    const uint64_t w_lo = bit_lo >> 5;
-    it.nw = (uint32_t)(((bit_hi + 31u) >> 5) - w_lo);
-    it.bit_base = (uint32_t)(bit_lo - (w_lo << 5));
-    it.src = (GlobalConstWordPtr)(((uint64_t)L.d0.y << 32) | L.d0.x) + w_lo;
-    return it;
-  };
-  uint32_t regs[kTabRegs];
-  auto request_words = [&](const TabItem& it) {  // no branches: a thread past the end reads the last word again
-#pragma unroll
-    for (uint32_t k = 0; k < kTabRegs; ++k) regs[k] = it.src[min(tid + k * kBlock, it.nw - 1u)];
-  };
-
+  const uint32_t n_waves = gridDim.x * kWavesPerBlock;
   bool bad = false;
-  uint32_t q = blockIdx.x;
-  const uint32_t stride = gridDim.x;
-  if (q >= n_items) return;
-  TabItem cur = geometry(locate(q), q);
-  Located next_loc = locate(q + stride);
-  request_words(cur);
-  for (; q < n_items; q += stride) {
-    __syncthreads();  // the item before is done with s_words
-#pragma unroll
-    for (uint32_t k = 0; k < kTabRegs; ++k)
-      if (tid + k * kBlock < cur.nw) s_words[tid + k * kBlock] = regs[k];
-    __syncthreads();
-    TabItem nxt = cur;
-    const bool more = q + stride < n_items;
-    if (more) {  // uniform
-      nxt = geometry(next_loc, q + stride);
-      request_words(nxt);
-      next_loc = locate(q + 2 * stride);
+  for (uint32_t q = blockIdx.x * kWavesPerBlock + tid / kWave; q < n_items; q += n_waves) {  // uniform per wavefront
+    uint32_t a = 0, b = n_active;  // the list that owns item q: last list with item_start <= q
+    while (b - a > 1) {
+      const uint32_t mid = (a + b) >> 1;
+      const uint32_t v = cached ? s_start[mid] : item_start[mid];
+      if (v <= q) a = mid; else b = mid;
     }
-    const TabItem& ld = cur;
-    const uint32_t W = ld.W, s = ld.s, e0 = ld.e0, cnt = ld.cnt, e_lo = ld.e_lo, bit_base = ld.bit_base;
+    a = __builtin_amdgcn_readfirstlane(a);
+    const uint32_t first_item = __builtin_amdgcn_readfirstlane(cached ? s_start[a] : item_start[a]);
+    // the list's descriptor is the same for all lanes: keeping it in scalar registers keeps the address
+    // arithmetic of the loads below off the vector unit
+    const uint4* dsrc = reinterpret_cast<const uint4*>(cdesc + a);
+    const uint4 d0 = dsrc[0], d1 = dsrc[1];
+    GlobalConstWordPtr pay = (GlobalConstWordPtr)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane(d0.y) << 32) |
+                                                  (uint32_t)__builtin_amdgcn_readfirstlane(d0.x));
+    const uint32_t P = __builtin_amdgcn_readfirstlane(d1.x), wsy = __builtin_amdgcn_readfirstlane(d1.y);
+    const uint32_t W = wsy & 0xFFu, s = (wsy >> 8) & 0xFFu;
     const uint32_t pid_mask = s >= 32 ? 0xFFFFFFFFu : (1u << s) - 1u;
-    uint32_t* row = table + (size_t)ld.list * (n_tiles + 1);
-    // a wavefront takes a contiguous quarter of the item's records, 64 at a time: the record before lane 0's
-    // is then the one lane 63 held a turn earlier, except at the start of the quarter
-    const uint32_t per_wave = ((cnt + kWavesPerBlock * kWave - 1) / (kWavesPerBlock * kWave)) * kWave;
-    const uint32_t j_begin = (tid / kWave) * per_wave;
-    const uint32_t j_end = min(j_begin + per_wave, cnt);
-    uint32_t carry = 0;
-    if (j_begin < j_end && e0 + j_begin > 0)
-      carry = lds_pid(s_words, bit_base + (e0 + j_begin - 1 - e_lo) * W, pid_mask);  // uniform
-    for (uint32_t j0 = j_begin; j0 < j_end; j0 += kWave) {  // uniform per wavefront: the shuffles need all lanes
-      const uint32_t j = j0 + lane;
-      const bool live = j < j_end;
+    const uint32_t e0 = (q - first_item) * kTabChunk, cnt = min(P - e0, kTabChunk);
+    uint32_t* row = table + (size_t)a * (n_tiles + 1);
+    // The window of the item starts at the record before the run (the run's first record for the first
+    // item of a list); records are addressed by their number in the window, bits by their offset from the
+    // window's first word: both stay far below 2^24.
+    const uint32_t lead = e0 ? 1u : 0u;
+    const uint64_t bit0 = (uint64_t)(e0 - lead) * W;
+    GlobalConstWordPtr src = pay + (bit0 >> 5);
+    const uint32_t sh0 = (uint32_t)bit0 & 31u;
+    const uint64_t words_left = ((((uint64_t)P * W + 31u) >> 5) - 1u) - (bit0 >> 5);  // the list's last word, from src
+    const uint32_t rel_last = words_left < (1u << 24) ? (uint32_t)words_left : 1u << 24;
+    // position field of record r of the window: its s <= 31 low bits lie in at most two words
+    auto request = [&](uint32_t r, uint32_t& w0, uint32_t& w1) {
+      const uint32_t bit = sh0 + __umul24(r, W), w = bit >> 5;
+      w0 = src[w];
+      w1 = src[min(w + 1u, rel_last)];
+      return bit & 31u;
+    };
+    uint32_t lo[kTabTurns], hi[kTabTurns], sh[kTabTurns], c_lo, c_hi, c_sh;
+    c_sh = request(0u, c_lo, c_hi);  // the record before the run (uniform)
+#pragma unroll
+    for (uint32_t i = 0; i < kTabTurns; ++i)  // no branch: a lane past the end reads the last record again
+      sh[i] = request(lead + min(i * kWave + lane, cnt - 1u), lo[i], hi[i]);
+    uint32_t carry = __builtin_amdgcn_alignbit(c_hi, c_lo, c_sh) & pid_mask;
+#pragma unroll
+    for (uint32_t i = 0; i < kTabTurns; ++i) {
+      if (i * kWave >= cnt) break;  // uniform
+      const uint32_t j = i * kWave + lane;
+      const bool live = j < cnt;
       const uint32_t e = e0 + j;
-      // no branch here: a lane past the end reads the last record again
-      const uint32_t pid = lds_pid(s_words, bit_base + (min(e, e0 + cnt - 1u) - e_lo) * W, pid_mask);
-      uint32_t prev = __shfl_up(pid, 1, 64);  // the record before mine sits in the lane below
-      if (lane == 0) prev = carry;
-      carry = __shfl(pid, kWave - 1, 64);
+      const uint32_t pid = __builtin_amdgcn_alignbit(hi[i], lo[i], sh[i]) & pid_mask;
+      // the record before mine sits in the lane below; lane 0 takes the last one of the turn before
+      const uint32_t prev = (uint32_t)__builtin_amdgcn_update_dpp((int)carry, (int)pid, 0x138 /* wave_shr:1 */, 0xF, 0xF, false);
+      carry = __builtin_amdgcn_readlane(pid, kWave - 1);
+      // a position past the end (an error, reported below) counts as lying behind the last tile
+      const uint32_t t_cur = min(pid / kDecTile, n_tiles), t_prev = min(prev / kDecTile, n_tiles);
+      const bool first = e == 0, last = e == P - 1;
+      bad |= live && ((!first && prev >= pid) || pid >= d);  // positions must ascend strictly and stay below d
       // entries (tile of record e-1, tile of record e] point at e; past the last record they hold P
-      uint32_t t_first = 1, t_cur = 0, tail_first = 1, tail_last = 0;
-      if (live) {
-        t_first = 0;
-        if (e > 0) {
-          bad |= prev >= pid;  // positions must ascend strictly
-          t_first = (prev < d ? prev / kDecTile : n_tiles) + 1;
-        }
-        bad |= pid >= d;
-        t_cur = pid < d ? pid / kDecTile : n_tiles;
-        if (e == ld.P - 1) {
-          tail_first = t_cur + 1;
-          tail_last = n_tiles;
-        }
+      const bool starts = live && (first || last || t_cur != t_prev);
+      if (!__ballot(starts)) continue;
+      const uint32_t t_first = first ? 0u : t_prev + 1u;
+      const bool single = starts && !last && t_first == t_cur;  // nearly always: the next tile, one entry
+      if (single) row[t_cur] = e;
+      if (!__ballot(starts && !single)) continue;
+      const bool run = starts && !single && t_cur >= t_first;
+      uint32_t tail_first = 1, tail_last = 0;
+      if (starts && last) {
+        tail_first = t_cur + 1;
+        tail_last = n_tiles;
       }
       // short runs of entries are written by the lane that found them, long ones (the stretch before a
       // list's first record, after its last, or across a region it skips) by the whole wavefront
       constexpr uint32_t kLong = 16;
-      const bool long_run = t_cur >= t_first && t_cur - t_first >= kLong;
+      const bool long_run = run && t_cur - t_first >= kLong;
       const bool long_tail = tail_last >= tail_first;
-      if (t_cur >= t_first && !long_run)
+      if (run && !long_run)
         for (uint32_t t = t_first; t <= t_cur; ++t) row[t] = e;
       uint64_t todo = __ballot(long_run);
       while (todo) {
-        const uint32_t src = (uint32_t)__builtin_ctzll(todo);
-        const uint32_t a0 = __builtin_amdgcn_readlane(t_first, src), a1 = __builtin_amdgcn_readlane(t_cur, src);
-        const uint32_t val = __builtin_amdgcn_readlane(e, src);
+        const uint32_t from = (uint32_t)__builtin_ctzll(todo);
+        const uint32_t a0 = __builtin_amdgcn_readlane(t_first, from), a1 = __builtin_amdgcn_readlane(t_cur, from);
+        const uint32_t val = __builtin_amdgcn_readlane(e, from);
         for (uint32_t t = a0 + lane; t <= a1; t += kWave) row[t] = val;
         todo &= todo - 1;
       }
       todo = __ballot(long_tail);
       while (todo) {
-        const uint32_t src = (uint32_t)__builtin_ctzll(todo);
-        const uint32_t a0 = __builtin_amdgcn_readlane(tail_first, src), a1 = __builtin_amdgcn_readlane(tail_last, src);
-        for (uint32_t t = a0 + lane; t <= a1; t += kWave) row[t] = ld.P;
+        const uint32_t from = (uint32_t)__builtin_ctzll(todo);
+        const uint32_t a0 = __builtin_amdgcn_readlane(tail_first, from), a1 = __builtin_amdgcn_readlane(tail_last, from);
+        for (uint32_t t = a0 + lane; t <= a1; t += kWave) row[t] = P;
         todo &= todo - 1;
       }
     }
-    cur = nxt;
   }
   if (bad) atomicOr(status, CVLC_DEV_STREAM);
 }
@@ -739,10 +685,13 @@ int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t
   if (n > 65535u) return CVLC_ERR_ARG;  // streams index the grid's y dimension
   if (n > 0 && (!d_streams || !stream_bytes)) return CVLC_ERR_ARG;
   if (reinterpret_cast<uintptr_t>(d_workspace) % 256u || reinterpret_cast<uintptr_t>(d_out) % 4u) return CVLC_ERR_ARG;
+  uint64_t items_bound = 0;  // tile_table work items are counted in 32 bits: a record takes two bits at least
   for (uint32_t i = 0; i < n; ++i) {
     if (!d_streams[i] || reinterpret_cast<uintptr_t>(d_streams[i]) % 4u) return CVLC_ERR_ARG;
     if (stream_bytes[i] < 4u * kGlobalHeaderWords) return CVLC_ERR_STREAM;
+    items_bound += (uint64_t)stream_bytes[i] * 4u / kTabChunk + kListsPerClient;
   }
+  if (items_bound > 0xFFFFFFFFull) return CVLC_ERR_ARG;
   if (ws_bytes < cvlc_decode_workspace_bytes(d, n)) return CVLC_ERR_CAPACITY;
   if (flags & ~(CVLC_DECODE_ACCUMULATE | CVLC_DECODE_QSGD)) return CVLC_ERR_ARG;
   const uint32_t quant = (flags & CVLC_DECODE_QSGD) ? CVLC_QUANT_QSGD : CVLC_QUANT_PQ;
