@@ -42,6 +42,7 @@ typedef enum cvlc_status {
 #define CVLC_DEV_NONFINITE 1u /* update holds NaN/Inf, or a group's max-min overflows  */
 #define CVLC_DEV_STREAM 2u    /* malformed stream: header, code length, PID >= d, order */
 #define CVLC_DEV_INTERNAL 4u  /* an internal consistency check failed                   */
+#define CVLC_DEV_WORKSPACE 8u /* encode: a vector needs more candidate room than given  */
 
 #define CVLC_MAX_CODED 31u    /* at most 31 coded groups plus the implicit 0-bit tail   */
 #define CVLC_STATS_STRIDE 32u /* stats entries per client: groups 1..R, then the tail   */
@@ -139,9 +140,31 @@ double cvlc_stats_gamma(const cvlc_seg_stats_t* stats, uint32_t n_coded);
 size_t cvlc_stream_capacity(const cvlc_plan_t* plan);
 
 /* Scratch bytes cvlc_encode_batch needs for n_clients vectors of length d, and
- * cvlc_decode_aggregate needs for n_clients streams of a d-dimensional model. */
+ * cvlc_decode_aggregate needs for n_clients streams of a d-dimensional model.
+ * The encoder's figure is the worst case, enough for any vector and plan. */
 size_t cvlc_encode_workspace_bytes(uint32_t d, uint32_t n_clients);
 size_t cvlc_decode_workspace_bytes(uint32_t d, uint32_t n_clients);
+
+/* Encoder scratch sized to what is kept (Sec. IV-B keeps k of d updates).  The
+ * encoder first drops every coordinate below a sampled magnitude threshold; the
+ * survivors ("candidates", somewhat more than k) are what all later steps work
+ * on.  cvlc_encode_workspace_bytes_for gives the bytes for at most
+ * max_candidates of them per client (1 .. d; d = the worst case above): about
+ * 6 bytes per coordinate for the threshold pass plus 8.25 per candidate,
+ * against 14.25 per coordinate.  cvlc_encode_batch reads the room off
+ * ws_bytes, which must hold at least the largest k of the batch
+ * (CVLC_ERR_CAPACITY otherwise).  A vector with more candidates than there is
+ * room for (many equal magnitudes, or the rare sample that places the
+ * threshold below the k-th magnitude, after which every coordinate is a
+ * candidate) sets CVLC_DEV_WORKSPACE in the status word and gets no stream:
+ * the first word of its buffer is cleared, its statistics entries are not
+ * written, the other clients of the batch are encoded as usual.  Encode it
+ * again with more room.
+ * cvlc_plan_candidates_hint: CPU; a max_candidates that holds for vectors
+ * without heavy ties, from the plan's k and the sampling margins (d for plans
+ * that keep too much to sample; 0 for an invalid plan). */
+size_t cvlc_encode_workspace_bytes_for(uint32_t d, uint32_t n_clients, uint32_t max_candidates);
+uint32_t cvlc_plan_candidates_hint(const cvlc_plan_t* plan);
 
 /* GPU.  Compresses n clients' update vectors (Sec. IV-B sparsification and
  * quantisation, Algorithm 1's final loop, packet format of Sec. IV-D).
@@ -151,7 +174,8 @@ size_t cvlc_decode_workspace_bytes(uint32_t d, uint32_t n_clients);
  *   client_ids[i]    host; written to the header and mixed into the generator
  *   d_streams_out[i] host array of device pointers, 4-byte aligned, each at
  *                    least capacities[i] >= cvlc_stream_capacity(&plans[i]) bytes
- *   d_workspace      device, 256-byte aligned, ws_bytes >= cvlc_encode_workspace_bytes(d, n)
+ *   d_workspace      device, 256-byte aligned, ws_bytes >= cvlc_encode_workspace_bytes(d, n),
+ *                    or less as cvlc_encode_workspace_bytes_for describes
  *   d_stats_out      device or NULL: n * CVLC_STATS_STRIDE cvlc_seg_stats_t
  *   flags            CVLC_ENCODE_ERROR_STATS: also measure every coded group's
  *                    error energy (errsq; needs d_stats_out, else CVLC_ERR_ARG);

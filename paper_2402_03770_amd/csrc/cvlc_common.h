@@ -60,6 +60,8 @@ struct ClientCtl {
   uint32_t n_cand;           // candidates kept by the filter pass that counts
   uint32_t refilter;         // 1: the sampled threshold kept fewer than k, the keep-all pass must run
   uint32_t n_nz;             // regions that kept at least one coordinate
+  uint32_t dead;             // 1: more candidates than the workspace has room for; nothing further is done for the client
+  uint32_t reserved;
   double tail_sumsq;         // energy of the coordinates the filter dropped
   double seg_sumsq[32];      // energy of every coded group; entry R: candidates below the last boundary (atomic)
   uint32_t tie_cnt[kMaxGroups][16];  // kept-aside class members per (boundary group, histogram slot)

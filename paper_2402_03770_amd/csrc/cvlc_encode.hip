@@ -62,6 +62,7 @@ struct EncodeLayout {
       tie_list, sel_part, l3_hist, norm_limbs, total;
   size_t zero_bytes;        // [status, params) is cleared at the start of a call
   uint32_t n_regions, max_spans;
+  uint32_t dense_cap;       // candidates the dense list of a client has room for
   uint32_t sel_blocks;      // workgroups per client in a level-2/3 selection pass
 };
 
@@ -78,10 +79,13 @@ uint32_t filter_blocks_per_client(uint32_t n_regions, uint32_t n, uint32_t resid
   return (waves + kWavesPerBlock - 1) / kWavesPerBlock;
 }
 
-EncodeLayout encode_layout(uint32_t d, uint32_t n) {
+// `cap`: candidates (coordinates at or above the sampled threshold) a client may have; the filter's own
+// output is laid out by region and stays d long, everything behind it is as long as the candidates.
+EncodeLayout encode_layout(uint32_t d, uint32_t n, uint32_t cap) {
   EncodeLayout L;
   L.n_regions = (uint32_t)(((uint64_t)d + kRegion - 1) / kRegion);
-  L.max_spans = (uint32_t)(((uint64_t)d + kSpan - 1) / kSpan);
+  L.dense_cap = cap < d ? cap : d;
+  L.max_spans = (uint32_t)(((uint64_t)L.dense_cap + kSpan - 1) / kSpan);
   {
     uint32_t b = (512u + n - 1) / n;
     L.sel_blocks = b < 2 ? 2u : (b > 32 ? 32u : b);
@@ -97,8 +101,8 @@ EncodeLayout encode_layout(uint32_t d, uint32_t n) {
   L.region_sumsq = off; off = align256(off + (size_t)n * L.n_regions * sizeof(double));
   L.cand_idx = off; off = align256(off + (size_t)n * d * sizeof(uint16_t));
   L.cand_val = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
-  L.dense_idx = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
-  L.dense_val = off; off = align256(off + (size_t)n * d * sizeof(uint32_t));
+  L.dense_idx = off; off = align256(off + (size_t)n * L.dense_cap * sizeof(uint32_t));
+  L.dense_val = off; off = align256(off + (size_t)n * L.dense_cap * sizeof(uint32_t));
   L.nz_off = off; off = align256(off + (size_t)n * (L.n_regions + 1) * sizeof(uint32_t));
   L.nz_run = off; off = align256(off + (size_t)n * (L.n_regions + 1) * sizeof(uint32_t));
   L.span_first = off; off = align256(off + (size_t)n * (L.max_spans + 1) * sizeof(uint32_t));
@@ -129,7 +133,7 @@ struct Workspace {  // device pointers into the caller's workspace
   uint32_t* sel_part;
   uint32_t* l3_hist;   // level-3 digit counts per (client, slot), zero between uses
   unsigned long long* norm_limbs;  // QSGD: per (client, group) the exact sum of squares in 32-bit limbs
-  uint32_t d, n_regions, max_spans, filter_blocks, sel_blocks;
+  uint32_t d, n_regions, max_spans, dense_cap, filter_blocks, sel_blocks;
 };
 
 // ------------------------------------------------------------------ parameter upload
@@ -508,12 +512,24 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
         const uint32_t begin = run + excl, end = begin + v;
         nz_off[q] = begin;
         nz_run[q] = j;
-        // spans whose first candidate lies in this run
-        for (uint32_t sp = (begin + kSpan - 1) / kSpan; (uint64_t)sp * kSpan < end; ++sp) span_first[sp] = q;
+        // spans whose first candidate lies in this run (those the workspace has room for; more: see below)
+        for (uint32_t sp = (begin + kSpan - 1) / kSpan; (uint64_t)sp * kSpan < end && sp <= ws.max_spans; ++sp)
+          span_first[sp] = q;
       }
     }
     run += tot;
     n_nz += tot_nz;
+  }
+  if (run > ws.dense_cap) {  // the caller's workspace is too short for this vector: no stream, and say so
+    if (tid == 0) {
+      nz_off[0] = 0;
+      ctl->n_cand = 0;
+      ctl->n_nz = 0;
+      ctl->dead = 1u;
+      p.stream[0] = 0u;  // not a stream header
+      atomicOr(ws.status, CVLC_DEV_WORKSPACE);
+    }
+    return;
   }
   if (tid == 0) {
     nz_off[n_nz] = run;
@@ -803,11 +819,12 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
   const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
+  if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
   const uint32_t nb = min(p.R, kSlotGroup);
   select_setup<2>(S, ctl, 0, nb);
   const CandView cv = cand_view(ws, ctl, client);
-  uint32_t* __restrict__ dst_idx = ws.dense_idx + (size_t)client * ws.d;
-  uint32_t* __restrict__ dst_val = ws.dense_val + (size_t)client * ws.d;
+  uint32_t* __restrict__ dst_idx = ws.dense_idx + (size_t)client * ws.dense_cap;
+  uint32_t* __restrict__ dst_val = ws.dense_val + (size_t)client * ws.dense_cap;
   const uint32_t n_spans = (cv.n + kSpan - 1) / kSpan;
   for (uint32_t span = blockIdx.x * kWideWaves + wave; span < n_spans; span += gridDim.x * kWideWaves) {
     uint32_t slot[kPerLane], v[kPerLane], x[kPerLane];
@@ -846,10 +863,11 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
   const uint32_t client = blockIdx.y, tid = threadIdx.x, wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
+  if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
   const uint32_t r0 = group * kSlotGroup;
   if (p.R <= r0) return;  // this client has no boundary in the group
   const uint32_t nb = min(p.R - r0, kSlotGroup);
-  const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
+  const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.dense_cap;
   uint2* ties = ws.tie_list + (size_t)client * kSlotGroup * kTieCap;
   uint32_t* tie_cnt = ctl->tie_cnt[group];
   select_setup<LEVEL>(S, ctl, r0, nb);
@@ -906,6 +924,7 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   const uint32_t slot = blockIdx.x, client = blockIdx.y, tid = threadIdx.x;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
+  if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
   const uint32_t r0 = group * kSlotGroup;
   const uint32_t n_cand = ctl->n_cand;  // asked for together with R
   if (p.R <= r0) return;
@@ -977,7 +996,7 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
     __syncthreads();
     // a class of equal keys straddles the boundary: find its quota-th member in position order
     const uint2* list = ws.tie_list + ((size_t)client * kSlotGroup + slot) * kTieCap;
-    const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
+    const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.dense_cap;
     const uint32_t n = ctl->n_cand;
     for (uint32_t b = 0; b < nb; ++b) {
       if (!s_need[b]) continue;  // uniform
@@ -1174,9 +1193,10 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
   const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
+  if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
   const uint32_t R = p.R, n = ctl->n_cand;
   const uint32_t n_spans = (n + kSpan - 1) / kSpan;
-  const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
+  const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.dense_cap;
   uint32_t* __restrict__ span_cnt = ws.span_cnt + (size_t)client * (ws.max_spans + 1) * 32;
   load_thresholds(thr, ctl, R);
   if (tid < kEmitWaves * 32) (&s_cnt[0][0])[tid] = 0;
@@ -1262,6 +1282,7 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
   const uint32_t client = blockIdx.x, tid = threadIdx.x;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
+  if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
   const uint32_t R = p.R, sbits = position_bits(ws.d);
   const uint32_t n_spans = (ctl->n_cand + kSpan - 1) / kSpan;
   const uint32_t lane = lane_id(), wave = tid / kWave;
@@ -1533,11 +1554,12 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
   const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
+  if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
   const uint32_t n = ctl->n_cand;
   const uint32_t n_spans = (n + kSpan - 1) / kSpan;
   const uint32_t R = p.R, sbits = position_bits(ws.d);
-  const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.d;
-  const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.d;
+  const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.dense_cap;
+  const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.dense_cap;
   const uint32_t* __restrict__ prefix = ws.span_cnt + (size_t)client * (ws.max_spans + 1) * 32;
   GlobalWordPtr stream = (GlobalWordPtr)p.stream;
   const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32), client_id = p.client_id;
@@ -1688,6 +1710,18 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
 }
 
 // ------------------------------------------------------------------ host side
+// Candidates per client a workspace of ws_bytes has room for: the largest cap <= d whose layout fits (the
+// layout grows with cap), 0 if not even one does.
+uint32_t candidate_room(uint32_t d, uint32_t n, size_t ws_bytes) {
+  if (encode_layout(d, n, 1u).total > ws_bytes) return 0u;
+  uint32_t lo = 1u, hi = d;  // lo fits
+  while (lo < hi) {
+    const uint32_t mid = lo + (hi - lo + 1u) / 2u;
+    if (encode_layout(d, n, mid).total <= ws_bytes) lo = mid; else hi = mid - 1u;
+  }
+  return lo;
+}
+
 int validate_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* d_updates,
                    const uint32_t* client_ids, void* const* d_streams, const size_t* capacities,
                    void* d_workspace, size_t ws_bytes) {
@@ -1704,7 +1738,13 @@ int validate_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* d_u
     if (capacities[i] < cvlc_stream_capacity(&plans[i])) return CVLC_ERR_CAPACITY;
     if (plans[i].total_bits / 32u > 0xFFFFFFFFull) return CVLC_ERR_PLAN;
   }
-  if (ws_bytes < cvlc_encode_workspace_bytes(d, n)) return CVLC_ERR_CAPACITY;
+  uint32_t k_max = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    uint64_t k = 0;
+    for (uint32_t r = 0; r < plans[i].n_coded; ++r) k += plans[i].count[r];
+    if (k > k_max) k_max = (uint32_t)k;  // a valid plan keeps at most d
+  }
+  if (candidate_room(d, n, ws_bytes) < (k_max < 1 ? 1u : k_max)) return CVLC_ERR_CAPACITY;
   return CVLC_OK;
 }
 
@@ -1743,7 +1783,29 @@ extern "C" {
 
 size_t cvlc_encode_workspace_bytes(uint32_t d, uint32_t n_clients) {
   if (d < 1 || n_clients < 1) return 0;
-  return cvlc::encode_layout(d, n_clients).total;
+  return cvlc::encode_layout(d, n_clients, d).total;
+}
+
+size_t cvlc_encode_workspace_bytes_for(uint32_t d, uint32_t n_clients, uint32_t max_candidates) {
+  if (d < 1 || n_clients < 1) return 0;
+  return cvlc::encode_layout(d, n_clients, max_candidates < 1 ? 1u : max_candidates).total;
+}
+
+uint32_t cvlc_plan_candidates_hint(const cvlc_plan_t* plan) {
+  using namespace cvlc;
+  if (!plan || cvlc_plan_validate(plan) != CVLC_OK) return 0;
+  const uint32_t d = plan->d;
+  uint64_t k = 0;
+  for (uint32_t r = 0; r < plan->n_coded; ++r) k += plan->count[r];
+  const uint32_t n_src = d / 16u;
+  const uint32_t n_sampled = (n_src < kSampleChunksMax ? n_src : kSampleChunksMax) * 16u;
+  const uint32_t rank = sample_rank(d, (uint32_t)k, n_sampled);
+  if (rank == 0) return d;  // no threshold is sampled for this plan: every coordinate is a candidate
+  // The share of the vector at or above the sample's rank-th largest key is rank / n_sampled give or take
+  // sqrt(rank) / n_sampled; the threshold is that key rounded down to 13 bits, worth a few percent more.
+  const double share = ((double)rank + 6.0 * std::sqrt((double)rank) + 16.0) / (double)n_sampled;
+  const double want = std::ceil(1.25 * share * (double)d) + 4096.0;
+  return want >= (double)d ? d : (uint32_t)want;
 }
 
 int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* d_updates, uint64_t seed,
@@ -1760,7 +1822,7 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   if ((flags & CVLC_ENCODE_ERROR_STATS) && !d_stats_out) return CVLC_ERR_ARG;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const uint32_t d = plans[0].d;
-  const EncodeLayout L = encode_layout(d, n);
+  const EncodeLayout L = encode_layout(d, n, candidate_room(d, n, ws_bytes));
   char* base = static_cast<char*>(d_workspace);
   Workspace ws;
   ws.status = reinterpret_cast<uint32_t*>(base + L.status);
@@ -1784,6 +1846,7 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   ws.d = d;
   ws.n_regions = L.n_regions;
   ws.max_spans = L.max_spans;
+  ws.dense_cap = L.dense_cap;
   ws.filter_blocks = filter_blocks_per_client(L.n_regions, n, filter_resident_blocks());
   ws.sel_blocks = L.sel_blocks;
 

@@ -12,7 +12,7 @@ import torch
 
 MAX_CODED = 31
 STATS_STRIDE = 32
-DEV_NONFINITE, DEV_STREAM, DEV_INTERNAL = 1, 2, 4
+DEV_NONFINITE, DEV_STREAM, DEV_INTERNAL, DEV_WORKSPACE = 1, 2, 4, 8
 DECODE_ACCUMULATE = 1
 DECODE_QSGD = 2
 QUANT_PQ, QUANT_QSGD = 0, 1
@@ -85,6 +85,10 @@ def lib() -> C.CDLL:
         L.cvlc_stream_capacity.restype = C.c_size_t
         L.cvlc_encode_workspace_bytes.argtypes = [C.c_uint32, C.c_uint32]
         L.cvlc_encode_workspace_bytes.restype = C.c_size_t
+        L.cvlc_encode_workspace_bytes_for.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32]
+        L.cvlc_encode_workspace_bytes_for.restype = C.c_size_t
+        L.cvlc_plan_candidates_hint.argtypes = [C.POINTER(Plan)]
+        L.cvlc_plan_candidates_hint.restype = C.c_uint32
         L.cvlc_decode_workspace_bytes.argtypes = [C.c_uint32, C.c_uint32]
         L.cvlc_decode_workspace_bytes.restype = C.c_size_t
         L.cvlc_encode_batch.argtypes = [C.c_uint32, C.POINTER(Plan), C.POINTER(vp), C.c_uint64, u32p, C.POINTER(vp),
@@ -193,6 +197,14 @@ def stream_capacity(p: Plan) -> int:
 
 def encode_workspace_bytes(d: int, n_clients: int) -> int:
     return int(lib().cvlc_encode_workspace_bytes(d, n_clients))
+
+
+def encode_workspace_bytes_for(d: int, n_clients: int, max_candidates: int) -> int:
+    return int(lib().cvlc_encode_workspace_bytes_for(d, n_clients, max_candidates))
+
+
+def plan_candidates_hint(p: Plan) -> int:
+    return int(lib().cvlc_plan_candidates_hint(C.byref(p)))
 
 
 def decode_workspace_bytes(d: int, n_clients: int) -> int:

@@ -245,6 +245,54 @@ def test_sample_that_misjudges_the_threshold():
     check_decode(refs, d)
 
 
+def test_workspace_sized_to_the_candidates():
+    """A workspace with room for cvlc_plan_candidates_hint candidates (a fraction of the worst case)
+    gives the very streams the worst-case workspace gives; a vector whose magnitudes are all equal has
+    d candidates, so in that workspace it is refused (status bit, cleared first word) while the other
+    clients of the batch are encoded as usual."""
+    cfg, d, n = 3, 1_500_000, 3
+    w = syn.WORKLOADS[cfg]
+    host = [syn.update_vector(cfg, c, d=d) for c in range(n)]
+    oplans = [orc.plan_for(w, client=c, alpha=orc.fit_alpha(host[c]), d=d) for c in range(n)]
+    plans = [to_lib_plan(p) for p in oplans]
+    cap = max(cv.plan_candidates_hint(p) for p in plans)
+    k_max = max(sum(p.counts()) for p in oplans)
+    assert k_max <= cap < d // 4
+    small = cv.encode_workspace_bytes_for(d, n, cap)
+    assert small < 0.6 * cv.encode_workspace_bytes(d, n)
+
+    def run(updates_host, ws_bytes):
+        updates = [torch.from_numpy(u).to(DEV) for u in updates_host]
+        streams = [cv.new_stream_buffer(p, DEV) for p in plans]
+        for s in streams:
+            s.fill_(-1)
+        ws = cv.new_workspace(ws_bytes, DEV)
+        cv.encode_batch(plans, updates, w.quant_seed, list(range(n)), streams, ws)
+        status = cv.device_status(ws)
+        return [s.cpu().numpy().view(np.uint32)[: p.stream_bytes // 4] for s, p in zip(streams, plans)], status
+
+    words, status = run(host, small)
+    assert status == 0
+    for c in range(n):
+        assert_stream_equal(words[c], orc.encode(host[c], oplans[c], w.quant_seed, c).words, f"client {c}")
+
+    flat = host[1].copy()
+    flat[:] = np.where(np.arange(d) % 3 == 0, -0.25, 0.25).astype(np.float32)
+    words, status = run([host[0], flat, host[2]], small)
+    assert status == cv.DEV_WORKSPACE
+    assert words[1][0] == 0
+    for c in (0, 2):
+        assert_stream_equal(words[c], orc.encode(host[c], oplans[c], w.quant_seed, c).words, f"client {c}")
+    # the same batch in the worst-case workspace: every client encoded
+    words, status = run([host[0], flat, host[2]], cv.encode_workspace_bytes(d, n))
+    assert status == 0
+    assert_stream_equal(words[1], orc.encode(flat, oplans[1], w.quant_seed, 1).words, "flat client")
+
+    # less room than the largest k of the batch can never work: refused before anything is launched
+    with pytest.raises(cv.CvlcError):
+        run(host, cv.encode_workspace_bytes_for(d, n, k_max // 2))
+
+
 def test_values_rounded_to_few_mantissa_bits():
     """Updates that were computed in a very short format: thousands of coordinates share each
     magnitude, so every boundary cuts through a large class of equal keys."""

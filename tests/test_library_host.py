@@ -93,7 +93,7 @@ def test_argument_errors_are_returned_before_any_launch():
     assert call(upd + 4, out, 4096, ws, good_ws) == -1          # update not 16-byte aligned
     assert call(upd, out + 2, 4096, ws, good_ws) == -1          # stream not 4-byte aligned
     assert call(upd, out, p.stream_bytes - 1, ws, good_ws) == -4
-    assert call(upd, out, 4096, ws, good_ws - 1) == -4
+    assert call(upd, out, 4096, ws, cv.encode_workspace_bytes_for(1000, 1, 100) - 1) == -4   # no room for the plan's k = 100
     assert call(upd, out, 4096, ws + 8, good_ws) == -1          # workspace not 256-byte aligned
     bad = cv.Plan.from_buffer_copy(p)
     bad.total_bits += 32
@@ -108,6 +108,30 @@ def test_argument_errors_are_returned_before_any_launch():
     assert lib.cvlc_decode_aggregate(1, streams, sizes, None, None, 1000, 0, vp(ws), dws, None) == -1
     assert lib.cvlc_decode_aggregate(1, streams, sizes, None, vp(0x3000), 1000, 0, vp(ws), dws - 1, None) == -4
     assert cv.status_string(-4) == "buffer too small"
+
+
+def test_encode_workspace_sized_to_the_candidates():
+    """The workspace grows with the candidate room asked for, reaches the worst case at d, and the hint for a
+    plan lies between its k and d (d itself for a plan that keeps too much to sample)."""
+    d, n = 11_200_000, 32
+    worst = cv.encode_workspace_bytes(d, n)
+    assert cv.encode_workspace_bytes_for(d, n, d) == worst
+    assert cv.encode_workspace_bytes_for(d, n, 0xFFFFFFFF) == worst
+    sizes = [cv.encode_workspace_bytes_for(d, n, c) for c in (1, 1000, 300_000, 3_000_000, d)]
+    assert sizes == sorted(sizes) and len(set(sizes)) == len(sizes)
+    w = syn.WORKLOADS[3]
+    p = orc.plan_for(w, client=0, alpha=-0.7)
+    lib_plan = cv.plan_manual(p.d, p.code_len(), p.counts(), B=float(p.B))
+    k = sum(p.counts())
+    hint = cv.plan_candidates_hint(lib_plan)
+    assert k < hint < 2 * k
+    assert cv.encode_workspace_bytes_for(d, n, hint) < 0.5 * worst
+    keep_most = cv.plan_manual(1000, [8], [900])
+    assert cv.plan_candidates_hint(keep_most) == 1000
+    bad = cv.Plan.from_buffer_copy(keep_most)
+    bad.total_bits += 32
+    assert cv.plan_candidates_hint(bad) == 0
+    assert cv.encode_workspace_bytes_for(0, 1, 5) == 0 and cv.encode_workspace_bytes_for(5, 0, 5) == 0
 
 
 def test_fit_ranks_and_argument_errors():
