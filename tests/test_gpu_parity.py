@@ -316,8 +316,10 @@ def test_repeatable_and_without_statistics():
     out1, st1 = gpu_decode(streams, d)
     out2, st2 = gpu_decode(streams, d)
     assert st1 == 0 and st2 == 0
-    # the order of the fp64 additions may differ between runs; the rounded sums may differ in the last place at most
-    assert np.allclose(out1, out2, rtol=2e-7, atol=0.0)
+    # the order of the fp64 additions may differ between runs: the rounded sum of a coordinate that three or
+    # more lists meet in may then differ by one unit in the last place (about once in 2^29 such coordinates)
+    gap = np.abs(out1.view(np.int32).astype(np.int64) - out2.view(np.int32).astype(np.int64))
+    assert gap.max() <= 1 and np.count_nonzero(gap) <= 2
 
 
 # --------------------------------------------------------------------------- decode / aggregate specifics
