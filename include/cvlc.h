@@ -203,9 +203,13 @@ int cvlc_encode(const cvlc_plan_t* plan, const float* d_update, uint64_t seed, u
  *   flags bit 0     0 = overwrite d_out, 1 = add to the values already there
  *   flags bit 1     the quantiser the streams must name: 0 = PQ, 1 = QSGD (a
  *                   federation uses one; a stream that names the other is malformed)
- * Products and sums are carried in fp64 and rounded to fp32 once.  A malformed
- * stream sets CVLC_DEV_STREAM; its offending records are skipped and nothing is
- * written out of bounds. */
+ * Products and sums are carried in fp64 and rounded to fp32 once; the order of
+ * the fp64 additions is not fixed, so a coordinate that three or more records
+ * meet in may differ by one unit in the last place between two runs.  A
+ * malformed stream sets CVLC_DEV_STREAM; its offending records are skipped and
+ * nothing is written out of bounds.  Positions must ascend strictly inside a
+ * group; a position that two groups of one stream both name (no encoder writes
+ * that) is not an error: both records are added. */
 #define CVLC_DECODE_ACCUMULATE 1u
 #define CVLC_DECODE_QSGD 2u
 int cvlc_decode_aggregate(uint32_t n, const void* const* d_streams, const size_t* stream_bytes,
