@@ -219,7 +219,7 @@ def main() -> int:
     t_dec = timed(decode, args.steps)
 
     # outside the step: Algorithm 1's exponent fit, which a planner runs once per round before encoding
-    fit_ws = cv.new_workspace(cv.fit_workspace_bytes(n), dev)
+    fit_ws = cv.new_workspace(cv.fit_workspace_bytes_for(n, d), dev)   # with room for the keys the second pass sets aside
     alpha = torch.empty(n, dtype=torch.float64, device=dev)
 
     def fit():
@@ -271,7 +271,7 @@ def main() -> int:
                      "launch_ms": filter_ms},
     }
     result["fit_alpha"] = {"ms": t_fit * 1e3, "g_coords_s": n * d / t_fit / 1e9, "algorithmic_gb": 4.0 * n * d / 1e9,
-                           "hbm_frac": 4.0 * n * d / t_fit / 1e9 / HBM_PEAK_GBS, "passes_over_input": 3,
+                           "hbm_frac": 4.0 * n * d / t_fit / 1e9 / HBM_PEAK_GBS, "passes_over_input": 2,
                            "in_step": False}
     if quant:
         result["config"]["quantiser"] = "qsgd"

@@ -240,21 +240,30 @@ int cvlc_decode_aggregate_static(uint32_t n, const void* const* d_streams, const
 #define CVLC_FIT_RANKS_MAX 32u
 uint32_t cvlc_fit_ranks(uint32_t d, uint32_t* ranks_out);
 
-/* Scratch bytes cvlc_fit_alpha needs for n_clients vectors (independent of d). */
+/* Scratch bytes for cvlc_fit_alpha.  cvlc_fit_workspace_bytes(n): the least it
+ * runs in, independent of d (about 100 KB per client); it then reads the vectors
+ * three times.  cvlc_fit_workspace_bytes_for(n, d): with room for the keys the
+ * second pass sets aside (4 bytes per coordinate in the worst case, every
+ * wavefront owning room for all it reads); given that much, cvlc_fit_alpha reads
+ * the vectors twice.  Same results either way.  0 for n = 0 or d outside
+ * 1 .. 2^31-1. */
 size_t cvlc_fit_workspace_bytes(uint32_t n_clients);
+size_t cvlc_fit_workspace_bytes_for(uint32_t n_clients, uint32_t d);
 
 /* GPU.  First step of Algorithm 1: the decay exponent alpha_i of Definition 1
  * for each of n update vectors, |U{l}| ~ phi * l^alpha with U{l} the l-th
  * largest magnitude.  alpha is the ordinary-least-squares slope of ln|U{l}| on
  * ln l over the ranks of cvlc_fit_ranks(d), ranks whose magnitude is zero left
  * out; fewer than two usable ranks give alpha = -1.  The magnitudes are exact
- * order statistics of the whole vector (three counting passes over it).
+ * order statistics of the whole vector (two or three passes over it, by the
+ * size of the workspace).
  *   d_updates[i]  host array of device pointers, each d fp32, 16-byte aligned
  *   d_alpha_out   device, n doubles
  *   d_keys_out    device or NULL: n * CVLC_FIT_RANKS_MAX words; word j of client
  *                 i = fp32 bit pattern (sign cleared) of the magnitude at the
  *                 j-th fitted rank, 0 beyond the last rank
- *   d_workspace   device, 256-byte aligned, ws_bytes >= cvlc_fit_workspace_bytes(n)
+ *   d_workspace   device, 256-byte aligned, ws_bytes >= cvlc_fit_workspace_bytes(n);
+ *                 from cvlc_fit_workspace_bytes_for(n, d) on, the faster path runs
  * A NaN or Inf in a vector sets CVLC_DEV_NONFINITE in the workspace's status
  * word (cvlc_device_status); that vector's outputs are then meaningless.
  * Calls that share a workspace must not overlap in time. */

@@ -21,6 +21,14 @@
 //   walk<2>     22-bit prefixes, ranks inside, classes again
 //   pass<3>     keys that match a 22-bit prefix: counts of the last 9 bits
 //   walk<3>     the keys themselves; the fit (fp64, one thread per client)
+//
+// Only a few percent of a vector's keys lie in a level-1 bin that holds one of
+// the ranks.  Given a workspace with room for them (cvlc_fit_workspace_bytes_for)
+// the second pass writes those keys out, every wavefront to a stretch of its
+// own, and the third pass never happens:
+//   collect     all keys: those whose level-1 bin belongs to a class go to the
+//               wavefront's list (rows of 64 through LDS)
+//   pass<2>, walk<2>, pass<3>, walk<3>   as above, the passes reading the lists
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -63,19 +71,37 @@ struct RankCtl {
 };
 
 struct RankLayout {
-  size_t status, ptrs, ctl, total;
+  size_t status, ptrs, ctl, list_cnt, lists, total;
   size_t zero_bytes;  // [status, ptrs) and the ctl array are cleared at the start of a call
+  uint32_t blocks;    // workgroups per client in a streaming pass
+  uint32_t wave_cap;  // keys a wavefront's list has room for (0: no lists, three passes)
 };
 
 size_t align256(size_t v) { return (v + 255u) & ~(size_t)255u; }
 
-RankLayout rank_layout(uint32_t n) {
+uint32_t pass_blocks_per_client(uint32_t d, uint32_t n);
+
+// d = 0: the layout without lists.  With lists, every wavefront of the collecting pass owns room for all
+// the keys it reads (whole tiles, plus the last d % 4 coordinates), so nothing has to be counted first.
+RankLayout rank_layout(uint32_t n, uint32_t d) {
   RankLayout L;
   size_t off = 0;
   L.status = off; off = align256(off + 256);
   L.ctl = off; off = align256(off + (size_t)n * sizeof(RankCtl));
   L.zero_bytes = off;
   L.ptrs = off; off = align256(off + (size_t)n * sizeof(const float*));
+  L.list_cnt = L.lists = off;
+  L.blocks = 0;
+  L.wave_cap = 0;
+  if (d) {
+    L.blocks = pass_blocks_per_client(d, n);
+    const uint32_t tiles = (d / 4u + kRankBlock * kDeep - 1) / (kRankBlock * kDeep);
+    const uint32_t tiles_per_block = (tiles + L.blocks - 1) / L.blocks;
+    L.wave_cap = tiles_per_block * (kDeep * kWave * 4u) + kWave;
+    const size_t n_lists = (size_t)n * L.blocks * kRankWaves;
+    L.list_cnt = off; off = align256(off + n_lists * sizeof(uint32_t));
+    L.lists = off; off = align256(off + n_lists * L.wave_cap * sizeof(uint32_t));
+  }
   L.total = off;
   return L;
 }
@@ -148,9 +174,36 @@ __global__ __launch_bounds__(kRankBlock) void rank_hist1_kernel(const float* con
 // LEVEL 2: prefix = level-1 bin, digit = bits 17..9.  LEVEL 3: prefix = top 22
 // bits, digit = bits 8..0.  first_cls maps a level-1 bin to the first class whose
 // prefix starts with it; classes are sorted, so the others follow it.
-template <int LEVEL>
+//
+// LISTS: the keys come from the lists the collecting pass wrote (`lists`, `list_cnt`, `wave_cap`; a
+// wavefront takes every (16 x workgroups)-th list of the client) instead of from the vectors.
+struct KeyLists {
+  const uint32_t* lists;
+  const uint32_t* list_cnt;
+  uint32_t per_client, wave_cap;
+};
+
+template <class Visit>
+__device__ __forceinline__ void list_keys(const KeyLists& kl, Visit visit) {
+  const uint32_t lane = lane_id();
+  const uint32_t* __restrict__ cnts = kl.list_cnt + (size_t)blockIdx.y * kl.per_client;
+  for (uint32_t l = blockIdx.x * kRankWaves + wave_id(); l < kl.per_client; l += gridDim.x * kRankWaves) {
+    const uint32_t cnt = cnts[l];
+    const uint32_t* __restrict__ keys = kl.lists + ((size_t)blockIdx.y * kl.per_client + l) * kl.wave_cap;
+    for (uint32_t i0 = 0; i0 < cnt; i0 += kWave * 8u) {
+      uint32_t k[8];
+#pragma unroll
+      for (uint32_t u = 0; u < 8; ++u) k[u] = keys[min(i0 + u * kWave + lane, cnt - 1u)];  // clamped: all in flight
+#pragma unroll
+      for (uint32_t u = 0; u < 8; ++u)
+        if (i0 + u * kWave + lane < cnt) visit(k[u]);
+    }
+  }
+}
+
+template <int LEVEL, bool LISTS>
 __global__ __launch_bounds__(kRankBlock) void rank_pass_kernel(const float* const* __restrict__ updates,
-                                                               RankCtl* __restrict__ ctls, uint32_t d) {
+                                                               RankCtl* __restrict__ ctls, uint32_t d, KeyLists kl) {
   __shared__ uint32_t hist[kRanksMax * kSubBins];
   __shared__ alignas(16) uint8_t first_cls[kTopBins];
   __shared__ uint32_t cls_prefix[kRanksMax + 1];
@@ -168,7 +221,7 @@ __global__ __launch_bounds__(kRankBlock) void rank_pass_kernel(const float* cons
     if (bin != before) first_cls[bin] = (uint8_t)c;
   }
   __syncthreads();
-  stream_keys(updates[blockIdx.y], d, [&](uint32_t key) {
+  auto visit = [&](uint32_t key) {
     const uint32_t bin = key >> kTopShift;
     uint32_t c = first_cls[bin];
     if (c == kNoClass) return;
@@ -183,7 +236,8 @@ __global__ __launch_bounds__(kRankBlock) void rank_pass_kernel(const float* cons
           break;
         }
     }
-  });
+  };
+  if (LISTS) list_keys(kl, visit); else stream_keys(updates[blockIdx.y], d, visit);
   __syncthreads();
   for (uint32_t i = threadIdx.x; i < n_cls * kSubBins; i += kRankBlock) {
     const uint32_t h = hist[i];
@@ -245,6 +299,28 @@ __global__ __launch_bounds__(kRankBlock) void rank_walk1_kernel(RankCtl* __restr
   if (threadIdx.x < kWave) write_classes(ctl, s_prefix, s_rem, ranks.n);
 }
 
+// Ordinary least squares of ln(magnitude) on ln(rank) over the keys (in LDS) of the ranks: the logarithms
+// side by side, the sums by one thread with the ranks in ascending order.  Whole workgroup.
+__device__ __forceinline__ void fit_exponent(const uint32_t* s_keys, const RankSet& ranks, double* alpha_out) {
+  __shared__ double s_x[kRanksMax], s_y[kRanksMax];
+  if (threadIdx.x < ranks.n) {
+    const double mag = (double)__uint_as_float(s_keys[threadIdx.x]);
+    s_x[threadIdx.x] = log((double)ranks.rank[threadIdx.x]);
+    s_y[threadIdx.x] = mag > 0.0 ? log(mag) : 0.0;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double sx = 0.0, sy = 0.0, sxx = 0.0, sxy = 0.0;
+    uint32_t m = 0;
+    for (uint32_t j = 0; j < ranks.n; ++j) {
+      if (s_keys[j] == 0u) continue;  // a zero magnitude has no logarithm
+      const double x = s_x[j], y = s_y[j];
+      sx += x; sy += y; sxx += x * x; sxy += x * y; ++m;
+    }
+    *alpha_out = m < 2 ? -1.0 : ((double)m * sxy - sx * sy) / ((double)m * sxx - sx * sx);
+  }
+}
+
 // One wavefront per class: lane l holds the 8 digits ending at 511 - 8 l.
 template <int LEVEL>
 __global__ __launch_bounds__(kRankBlock) void rank_walk_kernel(RankCtl* __restrict__ ctls, RankSet ranks,
@@ -300,25 +376,84 @@ __global__ __launch_bounds__(kRankBlock) void rank_walk_kernel(RankCtl* __restri
   // level 3: s_prefix holds the keys
   if (keys_out && threadIdx.x < kRanksMax)
     keys_out[(size_t)blockIdx.x * kRanksMax + threadIdx.x] = threadIdx.x < ranks.n ? s_prefix[threadIdx.x] : 0u;
-  // ordinary least squares of ln(magnitude) on ln(rank): the logarithms side by side,
-  // the sums by one thread with the ranks in ascending order
-  __shared__ double s_x[kRanksMax], s_y[kRanksMax];
-  if (threadIdx.x < ranks.n) {
-    const double mag = (double)__uint_as_float(s_prefix[threadIdx.x]);
-    s_x[threadIdx.x] = log((double)ranks.rank[threadIdx.x]);
-    s_y[threadIdx.x] = mag > 0.0 ? log(mag) : 0.0;
-  }
+  fit_exponent(s_prefix, ranks, alpha_out + blockIdx.x);
+}
+
+// ------------------------------------------------------------------ two passes: collect, select
+// The keys of the class bins, as the collecting pass leaves them: list (client, workgroup, wavefront) holds
+// list_cnt[...] keys in no particular order.
+constexpr uint32_t kCollectStage = 512;  // keys a wavefront stages in LDS; rows of 64 leave once 256 are there
+
+__global__ __launch_bounds__(kRankBlock) void rank_collect_kernel(const float* const* __restrict__ updates,
+                                                                  RankCtl* __restrict__ ctls, uint32_t d,
+                                                                  uint32_t* __restrict__ lists,
+                                                                  uint32_t* __restrict__ list_cnt, uint32_t wave_cap) {
+  __shared__ alignas(16) uint8_t first_cls[kTopBins];
+  __shared__ uint32_t stage[kRankWaves][kCollectStage];
+  RankCtl* ctl = ctls + blockIdx.y;
+  const uint32_t n_cls = ctl->n_cls;
+  for (uint32_t i = threadIdx.x; i < kTopBins / 4u; i += kRankBlock)
+    reinterpret_cast<uint32_t*>(first_cls)[i] = 0xFFFFFFFFu;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    double sx = 0.0, sy = 0.0, sxx = 0.0, sxy = 0.0;
-    uint32_t m = 0;
-    for (uint32_t j = 0; j < ranks.n; ++j) {
-      if (s_prefix[j] == 0u) continue;  // a zero magnitude has no logarithm
-      const double x = s_x[j], y = s_y[j];
-      sx += x; sy += y; sxx += x * x; sxy += x * y; ++m;
+  if (threadIdx.x < n_cls) first_cls[ctl->cls_prefix[threadIdx.x]] = (uint8_t)threadIdx.x;  // level-1 classes: one per bin
+  __syncthreads();
+  const uint32_t lane = lane_id(), wave = wave_id();
+  const size_t list = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * kRankWaves + wave;
+  uint32_t* __restrict__ out = lists + list * wave_cap;
+  uint32_t* mine = stage[wave];
+  uint32_t fill = 0, run = 0;  // staged keys, keys already written (uniform over the wavefront)
+  // whole wavefront; LDS accesses of a wavefront complete in order, the fences keep the compiler from moving them
+  auto take = [&](uint32_t key, bool valid) {
+    const bool hit = valid && first_cls[key >> kTopShift] != kNoClass;
+    const uint64_t m = __ballot(hit);
+    if (m == 0) return;
+    if (hit) mine[fill + lanes_below(m)] = key;
+    fill += (uint32_t)__popcll(m);
+  };
+  auto flush = [&](bool all) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    uint32_t g = 0;
+    for (; g + kWave <= fill; g += kWave) out[run + g + lane] = mine[g + lane];
+    const uint32_t left = fill - g;
+    if (left) {
+      const uint32_t k = lane < left ? mine[g + lane] : 0u;
+      if (all) {
+        if (lane < left) out[run + g + lane] = k;
+        g += left;
+      } else if (g) {  // the partial row moves to the front
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (lane < left) mine[lane] = k;
+      }
     }
-    alpha_out[blockIdx.x] = m < 2 ? -1.0 : ((double)m * sxy - sx * sy) / ((double)m * sxx - sx * sx);
+    run += g;
+    fill -= g;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  };
+  const float* update = updates[blockIdx.y];
+  const uint32_t n_quads = d / 4u;
+  GlobalFloat4Ptr src = (GlobalFloat4Ptr)update;
+  constexpr uint32_t kTileQuads = kRankBlock * kDeep;
+  for (uint32_t q0 = blockIdx.x * kTileQuads; q0 < n_quads; q0 += gridDim.x * kTileQuads) {
+    Float4V v[kDeep];
+#pragma unroll
+    for (uint32_t u = 0; u < kDeep; ++u) {
+      const uint32_t q = q0 + u * kRankBlock + threadIdx.x;
+      v[u] = __builtin_nontemporal_load(src + min(q, n_quads - 1u));
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < kDeep; ++u) {
+      const uint32_t q = q0 + u * kRankBlock + threadIdx.x;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) take(__float_as_uint(v[u][c]) & 0x7FFFFFFFu, q < n_quads);
+      if (fill >= kCollectStage - 4u * kWave) flush(false);  // room for the next four keys of every lane
+    }
   }
+  if (blockIdx.x == 0 && wave == 0) {  // the last d % 4 coordinates
+    const bool valid = lane < d - n_quads * 4u;
+    take(valid ? __float_as_uint(update[n_quads * 4u + lane]) & 0x7FFFFFFFu : 0u, valid);
+  }
+  flush(true);
+  if (lane == 0) list_cnt[list] = run;
 }
 
 // Workgroups per client in a streaming pass: enough to fill the device twice
@@ -354,7 +489,12 @@ uint32_t cvlc_fit_ranks(uint32_t d, uint32_t* ranks_out) {
   return n + 1;
 }
 
-size_t cvlc_fit_workspace_bytes(uint32_t n_clients) { return cvlc::rank_layout(n_clients).total; }
+size_t cvlc_fit_workspace_bytes(uint32_t n_clients) { return cvlc::rank_layout(n_clients, 0).total; }
+
+size_t cvlc_fit_workspace_bytes_for(uint32_t n_clients, uint32_t d) {
+  if (n_clients == 0 || d == 0 || d > 0x7FFFFFFFu) return 0;
+  return cvlc::rank_layout(n_clients, d).total;
+}
 
 int cvlc_fit_alpha(uint32_t n, const float* const* d_updates, uint32_t d, double* d_alpha_out, uint32_t* d_keys_out,
                    void* d_workspace, size_t ws_bytes, void* hip_stream) {
@@ -364,7 +504,8 @@ int cvlc_fit_alpha(uint32_t n, const float* const* d_updates, uint32_t d, double
   if (reinterpret_cast<uintptr_t>(d_workspace) % 256u) return CVLC_ERR_ARG;
   for (uint32_t i = 0; i < n; ++i)
     if (!d_updates[i] || reinterpret_cast<uintptr_t>(d_updates[i]) % 16u) return CVLC_ERR_ARG;
-  const RankLayout L = rank_layout(n);
+  RankLayout L = rank_layout(n, d);  // with room for the collected keys: two passes
+  if (ws_bytes < L.total) L = rank_layout(n, 0);
   if (ws_bytes < L.total) return CVLC_ERR_CAPACITY;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   char* base = static_cast<char*>(d_workspace);
@@ -392,10 +533,29 @@ int cvlc_fit_alpha(uint32_t n, const float* const* d_updates, uint32_t d, double
   const dim3 pass_grid(pass_blocks_per_client(d, n), n);
   hipLaunchKernelGGL(rank_hist1_kernel, pass_grid, dim3(kRankBlock), 0, stream, ptrs, ctls, d, status);
   hipLaunchKernelGGL(rank_walk1_kernel, dim3(n), dim3(kRankBlock), 0, stream, ctls, ranks);
-  hipLaunchKernelGGL(rank_pass_kernel<2>, pass_grid, dim3(kRankBlock), 0, stream, ptrs, ctls, d);
+  KeyLists kl = {nullptr, nullptr, 0u, 0u};
+  if (L.wave_cap) {  // two passes: the keys of the class bins are set aside, levels 2 and 3 count among those
+    uint32_t* lists = reinterpret_cast<uint32_t*>(base + L.lists);
+    uint32_t* list_cnt = reinterpret_cast<uint32_t*>(base + L.list_cnt);
+    kl.lists = lists;
+    kl.list_cnt = list_cnt;
+    kl.per_client = L.blocks * kRankWaves;
+    kl.wave_cap = L.wave_cap;
+    hipLaunchKernelGGL(rank_collect_kernel, pass_grid, dim3(kRankBlock), 0, stream, ptrs, ctls, d, lists, list_cnt,
+                       L.wave_cap);
+    // a few workgroups per client: their cost is clearing and adding up the counters, not reading the keys
+    const dim3 list_grid(L.blocks < 16u ? L.blocks : 16u, n), list_grid2(L.blocks < 8u ? L.blocks : 8u, n);
+    hipLaunchKernelGGL((rank_pass_kernel<2, true>), list_grid2, dim3(kRankBlock), 0, stream, ptrs, ctls, d, kl);
+    hipLaunchKernelGGL(rank_walk_kernel<2>, dim3(n), dim3(kRankBlock), 0, stream, ctls, ranks, (uint32_t*)nullptr,
+                       (double*)nullptr);
+    hipLaunchKernelGGL((rank_pass_kernel<3, true>), list_grid, dim3(kRankBlock), 0, stream, ptrs, ctls, d, kl);
+    hipLaunchKernelGGL(rank_walk_kernel<3>, dim3(n), dim3(kRankBlock), 0, stream, ctls, ranks, d_keys_out, d_alpha_out);
+    return hip_check(hipGetLastError());
+  }
+  hipLaunchKernelGGL((rank_pass_kernel<2, false>), pass_grid, dim3(kRankBlock), 0, stream, ptrs, ctls, d, kl);
   hipLaunchKernelGGL(rank_walk_kernel<2>, dim3(n), dim3(kRankBlock), 0, stream, ctls, ranks, (uint32_t*)nullptr,
                      (double*)nullptr);
-  hipLaunchKernelGGL(rank_pass_kernel<3>, pass_grid, dim3(kRankBlock), 0, stream, ptrs, ctls, d);
+  hipLaunchKernelGGL((rank_pass_kernel<3, false>), pass_grid, dim3(kRankBlock), 0, stream, ptrs, ctls, d, kl);
   hipLaunchKernelGGL(rank_walk_kernel<3>, dim3(n), dim3(kRankBlock), 0, stream, ctls, ranks, d_keys_out, d_alpha_out);
   return hip_check(hipGetLastError());
 }

@@ -116,6 +116,8 @@ def lib() -> C.CDLL:
         L.cvlc_fit_ranks.restype = C.c_uint32
         L.cvlc_fit_workspace_bytes.argtypes = [C.c_uint32]
         L.cvlc_fit_workspace_bytes.restype = C.c_size_t
+        L.cvlc_fit_workspace_bytes_for.argtypes = [C.c_uint32, C.c_uint32]
+        L.cvlc_fit_workspace_bytes_for.restype = C.c_size_t
         L.cvlc_fit_alpha.argtypes = [C.c_uint32, C.POINTER(vp), C.c_uint32, vp, vp, vp, C.c_size_t, vp]
         L.cvlc_profile_start.argtypes = [C.c_uint32]
         L.cvlc_profile_stop.argtypes = [C.POINTER(C.c_float), u32p]
@@ -232,6 +234,10 @@ def fit_ranks(d: int) -> List[int]:
 
 def fit_workspace_bytes(n_clients: int) -> int:
     return int(lib().cvlc_fit_workspace_bytes(n_clients))
+
+
+def fit_workspace_bytes_for(n_clients: int, d: int) -> int:
+    return int(lib().cvlc_fit_workspace_bytes_for(n_clients, d))
 
 
 # ----------------------------------------------------------------------------- device side

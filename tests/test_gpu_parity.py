@@ -738,12 +738,17 @@ def test_packets_at_the_benchmark_size():
 
 
 # --------------------------------------------------------------------------- power-law exponent (Algorithm 1, first step)
-def gpu_fit_alpha(host_updates):
+def gpu_fit_alpha(host_updates, two_passes=True):
+    """two_passes: in the workspace that has room for the keys set aside by the second pass; else in the
+    least workspace (three passes)."""
     n = len(host_updates)
+    d = host_updates[0].size
     updates = [torch.from_numpy(u).to(DEV) for u in host_updates]
     alpha = torch.full((n,), float("nan"), dtype=torch.float64, device=DEV)
     keys = torch.full((n * cv.FIT_RANKS_MAX,), -1, dtype=torch.int32, device=DEV)
-    ws = cv.new_workspace(cv.fit_workspace_bytes(n), DEV)
+    small, large = cv.fit_workspace_bytes(n), cv.fit_workspace_bytes_for(n, d)
+    assert large > small
+    ws = cv.new_workspace(large if two_passes else large - 256, DEV)
     ws.fill_(0xA5)  # the call must clear what it counts in
     cv.fit_alpha(updates, alpha, ws, keys)
     status = cv.device_status(ws)
@@ -753,14 +758,16 @@ def gpu_fit_alpha(host_updates):
 def check_fit(host_updates):
     """Magnitudes at the fitted ranks bit for bit; the slope to 1e-11 (fp64 on both
     sides, but two implementations of log)."""
-    alpha, keys, status = gpu_fit_alpha(host_updates)
-    assert status == 0
-    for c, u in enumerate(host_updates):
-        ranks, ref_keys = orc.fit_points(u)
-        assert ranks.tolist() == cv.fit_ranks(u.size)
-        assert keys[c, : ranks.size].tolist() == ref_keys.tolist(), f"client {c}"
-        assert not keys[c, ranks.size:].any()
-        assert alpha[c] == pytest.approx(orc.fit_alpha(u), rel=1e-11, abs=1e-11), f"client {c}"
+    refs = [(orc.fit_points(u), orc.fit_alpha(u)) for u in host_updates]
+    for two_passes in (True, False):
+        alpha, keys, status = gpu_fit_alpha(host_updates, two_passes)
+        assert status == 0
+        for c, u in enumerate(host_updates):
+            (ranks, ref_keys), ref_alpha = refs[c]
+            assert ranks.tolist() == cv.fit_ranks(u.size)
+            assert keys[c, : ranks.size].tolist() == ref_keys.tolist(), f"client {c}, two passes: {two_passes}"
+            assert not keys[c, ranks.size:].any()
+            assert alpha[c] == pytest.approx(ref_alpha, rel=1e-11, abs=1e-11), f"client {c}"
     return alpha
 
 
