@@ -272,7 +272,10 @@ def main() -> int:
     }
     result["fit_alpha"] = {"ms": t_fit * 1e3, "g_coords_s": n * d / t_fit / 1e9, "algorithmic_gb": 4.0 * n * d / 1e9,
                            "hbm_frac": 4.0 * n * d / t_fit / 1e9 / HBM_PEAK_GBS, "passes_over_input": 2,
-                           "in_step": False}
+                           "in_step": False,
+                           # a round whose planner refits the exponent first: the fit, then the step
+                           "step_plus_fit_ms": (t_step + t_fit) * 1e3,
+                           "step_plus_fit_g_coords_s": n * d / (t_step + t_fit) / 1e9}
     if quant:
         result["config"]["quantiser"] = "qsgd"
     if not args.no_cpu_baseline and not quant:   # the baseline is defined for the benchmark's quantiser

@@ -29,11 +29,11 @@ constexpr uint32_t kSampleBins = 8192;     // sample histogram on key >> 18 (8 e
 constexpr uint32_t kSampleShift = 18;
 constexpr uint32_t kL1Bins = 2048;         // level-1 digit: key >> 20 (8 exponent + 3 mantissa bits)
 constexpr uint32_t kDigitBins = 1024;      // level-2 and level-3 digits: 10 bits each
-constexpr uint32_t kSlotGroup = 15;        // boundaries refined per level-2/3 launch (60 KB of LDS)
+constexpr uint32_t kSlotGroup = 15;        // boundaries refined per level-2/3 launch (60 KB of LDS) for plans of up to 15 groups
+constexpr uint32_t kSlotGroupWide = 31;    // ... for plans of more groups: all boundaries at once (124 KB of LDS)
 constexpr uint32_t kSampleChunksMax = 16384;  // 64-byte pieces in the sample (256 Ki coordinates)
 constexpr uint32_t kTieCap = 2048;         // boundary-class members kept per histogram slot for tie resolution
 constexpr uint32_t kSampleBlocks = 16;     // workgroups per client in the sample pass
-constexpr uint32_t kMaxGroups = 3;         // ceil(31 / kSlotGroup)
 constexpr uint32_t kStatsStride = CVLC_STATS_STRIDE;
 constexpr uint32_t kNormLimbs = 20;        // 32-bit limbs of an exact sum of up to 2^31 squares of fp32 values
 
@@ -64,7 +64,7 @@ struct ClientCtl {
   uint32_t reserved;
   double tail_sumsq;         // energy of the coordinates the filter dropped
   double seg_sumsq[32];      // energy of every coded group; entry R: candidates below the last boundary (atomic)
-  uint32_t tie_cnt[kMaxGroups][16];  // kept-aside class members per (boundary group, histogram slot)
+  uint32_t tie_cnt[32];      // kept-aside class members per histogram slot
   uint32_t sel_prefix[2][32];  // key prefix of boundary r after level 1 (11 bits) and level 2 (21 bits); 0xFFFFFFFF: Z_r = 0
   uint32_t sel_rem[2][32];     // rank of the boundary element inside that prefix class, 1-based from the top
   uint32_t tau[32];          // Z_r-th largest key (0xFFFFFFFF: Z_r = 0)

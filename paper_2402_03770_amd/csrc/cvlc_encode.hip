@@ -93,7 +93,7 @@ EncodeLayout encode_layout(uint32_t d, uint32_t n, uint32_t cap) {
   size_t off = 0;
   L.status = off; off = align256(off + 256);
   L.ctl = off; off = align256(off + (size_t)n * sizeof(ClientCtl));
-  L.l3_hist = off; off = align256(off + (size_t)n * kSlotGroup * kDigitBins * sizeof(uint32_t));
+  L.l3_hist = off; off = align256(off + (size_t)n * kSlotGroupWide * kDigitBins * sizeof(uint32_t));
   L.norm_limbs = off; off = align256(off + (size_t)n * 32 * kNormLimbs * sizeof(uint64_t));
   L.zero_bytes = off;
   L.params = off; off = align256(off + (size_t)n * sizeof(ClientParams));
@@ -108,8 +108,8 @@ EncodeLayout encode_layout(uint32_t d, uint32_t n, uint32_t cap) {
   L.span_first = off; off = align256(off + (size_t)n * (L.max_spans + 1) * sizeof(uint32_t));
   L.span_cnt = off; off = align256(off + (size_t)n * (L.max_spans + 1) * 32 * sizeof(uint32_t));
   L.group_info = off; off = align256(off + (size_t)n * sizeof(GroupInfo));
-  L.tie_list = off; off = align256(off + (size_t)n * kSlotGroup * kTieCap * sizeof(uint2));
-  L.sel_part = off; off = align256(off + (size_t)n * L.sel_blocks * kSlotGroup * kDigitBins * sizeof(uint32_t));
+  L.tie_list = off; off = align256(off + (size_t)n * kSlotGroupWide * kTieCap * sizeof(uint2));
+  L.sel_part = off; off = align256(off + (size_t)n * L.sel_blocks * kSlotGroupWide * kDigitBins * sizeof(uint32_t));
   L.total = off;
   return L;
 }
@@ -585,21 +585,23 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
 // can find the position of the last member inside it (ties rank by position).
 constexpr uint32_t kNoSlot = 0xFFFFFFFFu;
 
+template <uint32_t SG>
 struct SlotTable {
-  uint32_t prefix[kSlotGroup];  // slot -> key prefix (11 bits at level 2, 21 bits at level 3)
-  uint32_t leader[kSlotGroup];  // boundary inside the group -> its slot, kNoSlot for Z_r = 0
+  uint32_t prefix[SG];  // slot -> key prefix (11 bits at level 2, 21 bits at level 3)
+  uint32_t leader[SG];  // boundary inside the group -> its slot, kNoSlot for Z_r = 0
   uint32_t n;
 };
 
-// Lane of the first of the lanes 0..kSlotGroup-1 that are `valid` and hold the
+// Lane of the first of the lanes 0..SG-1 that are `valid` and hold the
 // caller's value (the caller's own lane if none is earlier).  Whole wavefront;
-// the result means something for valid lanes below kSlotGroup only.
+// the result means something for valid lanes below SG only.
+template <uint32_t SG>
 __device__ __forceinline__ uint32_t first_equal_lane(uint32_t value, bool valid) {
   const uint64_t vmask = __ballot(valid);
   const uint32_t lane = lane_id();
   uint32_t first = lane;
 #pragma unroll
-  for (int j = (int)kSlotGroup - 1; j >= 0; --j) {
+  for (int j = (int)SG - 1; j >= 0; --j) {
     const uint32_t vj = __builtin_amdgcn_readlane(value, j);
     if (((vmask >> j) & 1u) && (uint32_t)j < lane && vj == value) first = (uint32_t)j;
   }
@@ -609,42 +611,47 @@ __device__ __forceinline__ uint32_t first_equal_lane(uint32_t value, bool valid)
 // Slots in order of first appearance among the group's boundaries.  Run by one
 // whole wavefront whose lane b < nb holds boundary b's prefix.  Returns the
 // caller's slot (kNoSlot: Z_r = 0 or no boundary) and whether it opens it.
-__device__ __forceinline__ uint32_t build_slots(SlotTable& st, uint32_t pre, uint32_t nb, bool* opens) {
+template <uint32_t SG>
+__device__ __forceinline__ uint32_t build_slots(SlotTable<SG>& st, uint32_t pre, uint32_t nb, bool* opens) {
   const uint32_t lane = lane_id();
   const bool valid = lane < nb && pre != 0xFFFFFFFFu;
-  const uint32_t first = first_equal_lane(pre, valid);
+  const uint32_t first = first_equal_lane<SG>(pre, valid);
   const bool leader = valid && first == lane;
   const uint64_t leaders = __ballot(leader);
   const uint32_t slot = valid ? (uint32_t)__popcll(leaders & ((1ull << first) - 1ull)) : kNoSlot;
   if (leader) st.prefix[slot] = pre;
-  if (lane < kSlotGroup) st.leader[lane] = slot;
+  if (lane < SG) st.leader[lane] = slot;
   if (lane == 0) st.n = (uint32_t)__popcll(leaders);
   *opens = leader;
   return slot;
 }
 
+template <uint32_t SG>
 struct SelectShared {
-  uint32_t hist[kSlotGroup * kDigitBins];
-  SlotTable slots;
-  uint32_t bin_slot[kL1Bins / 8];                // top 11 key bits -> 1 + (level 2: slot, level 3: bin id), 4 bits each
-  uint32_t digit_map[kSlotGroup][kDigitBins / 32];  // level 3: second digits present per bin id
-  uint32_t tie_full[kSlotGroup];                 // this workgroup has seen the slot's kept-aside list overflow
+  uint32_t hist[SG * kDigitBins];
+  SlotTable<SG> slots;
+  // top 11 key bits -> 1 + (level 2: slot, level 3: bin id); 4 bits each for up to 15 slots, 8 bits beyond
+  static constexpr uint32_t kTagBits = SG <= 15 ? 4u : 8u, kTagsPerWord = 32u / kTagBits;
+  uint32_t bin_slot[kL1Bins / kTagsPerWord];
+  uint32_t digit_map[SG][kDigitBins / 32];  // level 3: second digits present per bin id
+  uint32_t tie_full[SG];                 // this workgroup has seen the slot's kept-aside list overflow
 
   __device__ __forceinline__ uint32_t bin_tag(uint32_t top11) const {
-    return (bin_slot[top11 >> 3] >> ((top11 & 7u) * 4u)) & 15u;
+    return (bin_slot[top11 / kTagsPerWord] >> ((top11 % kTagsPerWord) * kTagBits)) & ((1u << kTagBits) - 1u);
   }
-  __device__ __forceinline__ void set_bin_tag(uint32_t top11, uint32_t tag) {  // once per top11, tag <= 15
-    atomicOr(&bin_slot[top11 >> 3], tag << ((top11 & 7u) * 4u));
+  __device__ __forceinline__ void set_bin_tag(uint32_t top11, uint32_t tag) {  // once per top11, tag <= SG
+    atomicOr(&bin_slot[top11 / kTagsPerWord], tag << ((top11 % kTagsPerWord) * kTagBits));
   }
 };
-static_assert(kSlotGroup <= 15, "bin tags are 4 bits wide");
-static_assert(sizeof(SelectShared) <= 65536, "SelectShared must fit the 64 KB static LDS limit");
+// Up to 15 boundaries a launch: two workgroups to a CU.  All 31 at once: one workgroup, a single round.
+static_assert(sizeof(SelectShared<kSlotGroup>) <= 65536 && sizeof(SelectShared<kSlotGroupWide>) <= 160 * 1024 - 2048,
+              "SelectShared must fit the CU's LDS");
 
 // Counts one candidate per lane (`live` lanes only); dense_i is its number in the
 // position-ordered candidate list (which ranks equal keys just as positions do).
 // Must be reached by all lanes of the wavefront.
-template <int LEVEL>
-__device__ __forceinline__ void select_count(SelectShared& S, uint32_t key, uint32_t dense_i,
+template <int LEVEL, uint32_t SG>
+__device__ __forceinline__ void select_count(SelectShared<SG>& S, uint32_t key, uint32_t dense_i,
                                              bool live, uint32_t* tie_cnt, uint2* __restrict__ ties) {
   uint32_t q = kNoSlot;
   if (live) {
@@ -777,25 +784,25 @@ __device__ __forceinline__ void store_partials(const uint32_t* hist, uint32_t us
 }
 
 // Fills the workgroup's slot tables for one group of boundaries.
-template <int LEVEL>
-__device__ __forceinline__ void select_setup(SelectShared& S, const ClientCtl* ctl, uint32_t r0, uint32_t nb) {
+template <int LEVEL, uint32_t SG>
+__device__ __forceinline__ void select_setup(SelectShared<SG>& S, const ClientCtl* ctl, uint32_t r0, uint32_t nb) {
   const uint32_t tid = threadIdx.x;
-  for (uint32_t i = tid; i < kSlotGroup * kDigitBins; i += kWideBlock) S.hist[i] = 0;
-  for (uint32_t i = tid; i < kL1Bins / 8; i += kWideBlock) S.bin_slot[i] = 0;
-  for (uint32_t i = tid; i < kSlotGroup * (kDigitBins / 32); i += kWideBlock) (&S.digit_map[0][0])[i] = 0;
-  if (tid < kSlotGroup) S.tie_full[tid] = 0;
+  for (uint32_t i = tid; i < SG * kDigitBins; i += kWideBlock) S.hist[i] = 0;
+  for (uint32_t i = tid; i < kL1Bins / SelectShared<SG>::kTagsPerWord; i += kWideBlock) S.bin_slot[i] = 0;
+  for (uint32_t i = tid; i < SG * (kDigitBins / 32); i += kWideBlock) (&S.digit_map[0][0])[i] = 0;
+  if (tid < SG) S.tie_full[tid] = 0;
   uint32_t pre = 0xFFFFFFFFu;
   if (tid < nb) pre = ctl->sel_prefix[LEVEL - 2][r0 + tid];
   __syncthreads();
   if (tid < kWave) {  // the first wavefront, lane b = boundary b
     bool opens;
-    const uint32_t slot = build_slots(S.slots, pre, nb, &opens);
+    const uint32_t slot = build_slots<SG>(S.slots, pre, nb, &opens);
     if (LEVEL == 2) {
       if (opens) S.set_bin_tag(pre, slot + 1);
     } else {
       // the slots' top 11 bits are numbered in order of first appearance as well
       const uint32_t top11 = pre >> 10, second = pre & (kDigitBins - 1);
-      const uint32_t first = first_equal_lane(top11, opens);
+      const uint32_t first = first_equal_lane<SG>(top11, opens);
       const uint64_t bin_openers = __ballot(opens && first == tid);
       if (opens) {
         const uint32_t bin = (uint32_t)__popcll(bin_openers & ((1ull << first) - 1ull));
@@ -813,15 +820,16 @@ __device__ __forceinline__ void select_setup(SelectShared& S, const ClientCtl* c
 // dense position-ordered candidate list and counts the level-2 digits on the
 // way.  Every span is the same amount of work wherever its candidates lie.
 // The wavefronts do not wait for each other until the histogram is stored.
+template <uint32_t SG>
 __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParams* __restrict__ params,
                                                                ClientCtl* __restrict__ ctls, Workspace ws) {
-  __shared__ SelectShared S;
+  __shared__ SelectShared<SG> S;
   const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
-  const uint32_t nb = min(p.R, kSlotGroup);
-  select_setup<2>(S, ctl, 0, nb);
+  const uint32_t nb = min(p.R, SG);
+  select_setup<2, SG>(S, ctl, 0, nb);
   const CandView cv = cand_view(ws, ctl, client);
   uint32_t* __restrict__ dst_idx = ws.dense_idx + (size_t)client * ws.dense_cap;
   uint32_t* __restrict__ dst_val = ws.dense_val + (size_t)client * ws.dense_cap;
@@ -845,32 +853,32 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
         dst_val[i] = v[j];
         dst_idx[i] = x[j];
       }
-      if (nb) select_count<2>(S, v[j] & 0x7FFFFFFFu, 0u, i < cv.n, nullptr, nullptr);
+      if (nb) select_count<2, SG>(S, v[j] & 0x7FFFFFFFu, 0u, i < cv.n, nullptr, nullptr);
     }
   }
   __syncthreads();
   if (nb == 0) return;
-  uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * kSlotGroup * kDigitBins;
+  uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * SG * kDigitBins;
   store_partials(S.hist, S.slots.n * kDigitBins, part, narrow_partials(cv.n, gridDim.x));
 }
 
 // Every other selection pass reads the dense list.
-template <int LEVEL>
+template <int LEVEL, uint32_t SG>
 __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientParams* __restrict__ params,
                                                                  ClientCtl* __restrict__ ctls, Workspace ws,
                                                                  uint32_t group) {
-  __shared__ SelectShared S;
+  __shared__ SelectShared<SG> S;
   const uint32_t client = blockIdx.y, tid = threadIdx.x, wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
-  const uint32_t r0 = group * kSlotGroup;
+  const uint32_t r0 = group * SG;
   if (p.R <= r0) return;  // this client has no boundary in the group
-  const uint32_t nb = min(p.R - r0, kSlotGroup);
+  const uint32_t nb = min(p.R - r0, SG);
   const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.dense_cap;
-  uint2* ties = ws.tie_list + (size_t)client * kSlotGroup * kTieCap;
-  uint32_t* tie_cnt = ctl->tie_cnt[group];
-  select_setup<LEVEL>(S, ctl, r0, nb);
+  uint2* ties = ws.tie_list + (size_t)client * SG * kTieCap;
+  uint32_t* tie_cnt = ctl->tie_cnt + group * SG;
+  select_setup<LEVEL, SG>(S, ctl, r0, nb);
 
   const uint32_t n = ctl->n_cand;
   const uint32_t span = (uint32_t)(((uint64_t)n + gridDim.x - 1) / gridDim.x);
@@ -889,7 +897,7 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
     for (uint32_t u = 0; u < 8; ++u) {
       const uint32_t i = base + u * kWideBlock + tid;
       if (base + u * kWideBlock + wave * kWave >= end) break;  // uniform per wavefront
-      select_count<LEVEL>(S, v[u] & 0x7FFFFFFFu, i, i < end, tie_cnt, ties);
+      select_count<LEVEL, SG>(S, v[u] & 0x7FFFFFFFu, i, i < end, tie_cnt, ties);
     }
   }
   __syncthreads();
@@ -897,13 +905,13 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
   if (LEVEL == 3) {
     // a handful of candidates per slot share a boundary's 21-bit prefix (more only among heavy ties):
     // the few non-empty counters are added straight to the client's table
-    uint32_t* table = ws.l3_hist + (size_t)client * kSlotGroup * kDigitBins;
+    uint32_t* table = ws.l3_hist + (size_t)client * SG * kDigitBins;
     for (uint32_t i = tid; i < used; i += kWideBlock) {
       const uint32_t h = S.hist[i];
       if (h) atomicAdd(&table[i], h);
     }
   } else {
-    uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * kSlotGroup * kDigitBins;
+    uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * SG * kDigitBins;
     store_partials(S.hist, used, part, narrow_partials(n, gridDim.x));
   }
 }
@@ -912,12 +920,12 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
 // partial histograms are added up, a suffix sum from the largest digit gives
 // "keys with digit >= t", and every boundary that shares the slot reads off its
 // digit and the rank left inside it.
-template <int LEVEL>
+template <int LEVEL, uint32_t SG>
 __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientParams* __restrict__ params,
                                                                  ClientCtl* __restrict__ ctls, Workspace ws,
                                                                  uint32_t group) {
-  __shared__ SlotTable slots;
-  __shared__ uint32_t s_digit[kSlotGroup], s_quota[kSlotGroup], s_need[kSlotGroup], s_rem[kSlotGroup];
+  __shared__ SlotTable<SG> slots;
+  __shared__ uint32_t s_digit[SG], s_quota[SG], s_need[SG], s_rem[SG];
   __shared__ uint32_t s_found;
   __shared__ uint32_t scan_tmp[kWideWaves];
   __shared__ uint2 s_list[LEVEL == 3 ? kTieCap : 1];
@@ -925,12 +933,12 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
-  const uint32_t r0 = group * kSlotGroup;
+  const uint32_t r0 = group * SG;
   const uint32_t n_cand = ctl->n_cand;  // asked for together with R
   if (p.R <= r0) return;
-  const uint32_t nb = min(p.R - r0, kSlotGroup);
+  const uint32_t nb = min(p.R - r0, SG);
   const uint32_t n_parts = ws.sel_blocks;
-  const uint32_t* parts = ws.sel_part + (size_t)client * n_parts * kSlotGroup * kDigitBins;
+  const uint32_t* parts = ws.sel_part + (size_t)client * n_parts * SG * kDigitBins;
   // Everything the walk reads from global memory is requested here, before the
   // first wait.  Thread t takes digit 1023 - t, so that the scan runs from the top
   // digit down; a slot past the last one in use adds up stale partials for nothing.
@@ -941,11 +949,11 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
     // the level's results go to arrays of their own: other workgroups of this launch may still have to read its inputs
     if (LEVEL == 2 && slot == 0 && pre == 0xFFFFFFFFu) ctl->sel_prefix[1][r0 + tid] = pre;
   }
-  const uint32_t kept = LEVEL == 3 ? ctl->tie_cnt[group][slot] : 0u;
+  const uint32_t kept = LEVEL == 3 ? ctl->tie_cnt[group * SG + slot] : 0u;
   const uint32_t digit = kDigitBins - 1 - tid;
   uint32_t h = 0;
   if (LEVEL == 3) {  // one table per client; left cleared for the next group of boundaries or the next call
-    uint32_t* mine = ws.l3_hist + ((size_t)client * kSlotGroup + slot) * kDigitBins + digit;
+    uint32_t* mine = ws.l3_hist + ((size_t)client * SG + slot) * kDigitBins + digit;
     h = *mine;
     *mine = 0;
   } else {
@@ -953,19 +961,19 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
       const uint16_t* narrow = reinterpret_cast<const uint16_t*>(parts);
 #pragma unroll 8
       for (uint32_t b = 0; b < n_parts; ++b)
-        h += narrow[((size_t)b * kSlotGroup * kDigitBins) * 2u + (size_t)slot * kDigitBins + digit];
+        h += narrow[((size_t)b * SG * kDigitBins) * 2u + (size_t)slot * kDigitBins + digit];
     } else {
 #pragma unroll 8
-      for (uint32_t b = 0; b < n_parts; ++b) h += parts[((size_t)b * kSlotGroup + slot) * kDigitBins + digit];
+      for (uint32_t b = 0; b < n_parts; ++b) h += parts[((size_t)b * SG + slot) * kDigitBins + digit];
     }
   }
-  if (tid < kSlotGroup) {
+  if (tid < SG) {
     s_need[tid] = 0;
     s_rem[tid] = rem_in;
   }
   if (tid < kWave) {
     bool opens;
-    build_slots(slots, pre, nb, &opens);
+    build_slots<SG>(slots, pre, nb, &opens);
   }
   __syncthreads();
   if (slot >= slots.n) return;
@@ -995,7 +1003,7 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   if (LEVEL == 3) {
     __syncthreads();
     // a class of equal keys straddles the boundary: find its quota-th member in position order
-    const uint2* list = ws.tie_list + ((size_t)client * kSlotGroup + slot) * kTieCap;
+    const uint2* list = ws.tie_list + ((size_t)client * SG + slot) * kTieCap;
     const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.dense_cap;
     const uint32_t n = ctl->n_cand;
     for (uint32_t b = 0; b < nb; ++b) {
@@ -1946,15 +1954,21 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   {
     StageScope scope(CVLC_STAGE_ENC_SELECT, stream);
     const dim3 grid(L.sel_blocks, n);
-    const uint32_t groups = (max_R + kSlotGroup - 1) / kSlotGroup;
-    // level 2 of the first group of boundaries also builds the dense candidate list (also when nothing is coded)
-    hipLaunchKernelGGL(gather_l2_kernel, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
-    for (uint32_t gr = 0; gr < groups; ++gr) {
-      if (gr > 0)
-        hipLaunchKernelGGL(select_pass_kernel<2>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
-      hipLaunchKernelGGL(select_walk_kernel<2>, dim3(kSlotGroup, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
-      hipLaunchKernelGGL(select_pass_kernel<3>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
-      hipLaunchKernelGGL(select_walk_kernel<3>, dim3(kSlotGroup, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, gr);
+    // The gather also builds the dense candidate list (also when nothing is coded).  Up to 15 boundaries:
+    // 60 KB of LDS counters, two workgroups to a CU.  More: all of them in one round of launches with
+    // 124 KB of counters, one workgroup to a CU, instead of three rounds over the candidates.
+    if (max_R <= kSlotGroup) {
+      constexpr uint32_t SG = kSlotGroup;
+      hipLaunchKernelGGL(gather_l2_kernel<SG>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
+      hipLaunchKernelGGL((select_walk_kernel<2, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
+      hipLaunchKernelGGL((select_pass_kernel<3, SG>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
+      hipLaunchKernelGGL((select_walk_kernel<3, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
+    } else {
+      constexpr uint32_t SG = kSlotGroupWide;
+      hipLaunchKernelGGL(gather_l2_kernel<SG>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
+      hipLaunchKernelGGL((select_walk_kernel<2, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
+      hipLaunchKernelGGL((select_pass_kernel<3, SG>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
+      hipLaunchKernelGGL((select_walk_kernel<3, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
     }
   }
   // count: wavefronts walk the spans; about what the device holds at once (four workgroups per CU)
