@@ -376,9 +376,8 @@ __global__ __launch_bounds__(kBlock, 8) void tile_table_kernel(const CompactDesc
 }
 
 // ------------------------------------------------------------------ 3. fused decode + accumulate
-// Workgroups walk the output tiles (b, b + workgroups, ...), so that at any time
-// neighbouring tiles are in flight and the stream lines they share are fetched
-// from HBM once.  The records of a tile, over all lists, are numbered
+// Persistent workgroups walk the output tiles, neighbouring tiles at the same
+// time on the same XCD (see tile_of below).  The records of a tile, over all lists, are numbered
 // 0..total-1 list by list (an exclusive scan of the slice lengths); every
 // wavefront takes a contiguous share of them, 64 at a time ("turn"), so the work
 // is even however the records are spread over the lists and neighbouring lanes
@@ -389,6 +388,7 @@ __global__ __launch_bounds__(kBlock, 8) void tile_table_kernel(const CompactDesc
 constexpr uint32_t kDecBlock = 512;  // threads of a decode workgroup
 constexpr uint32_t kDecWaves = kDecBlock / kWave;
 constexpr uint32_t kDecTurns = 6;    // turns of 64 records a wavefront works on together
+constexpr uint32_t kChunkTiles = 16; // consecutive tiles decoded side by side on one XCD (more: less refetching, less even load)
 constexpr uint32_t kFirstBits = 22;  // a tile's records over one batch of lists are numbered below 2^22 ...
 constexpr uint32_t kFirstMask = (1u << kFirstBits) - 1u;
 static_assert((uint64_t)kListBatch * kDecTile < (1ull << kFirstBits) && kListBatch <= (1u << (32 - kFirstBits)),
@@ -462,11 +462,23 @@ __global__ __launch_bounds__(kDecBlock, 6) void decode_tiles_kernel(const Compac
     }
     return r;
   };
-  uint2 next_rows = request_rows(blockIdx.x);
-  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+  // Which tiles a workgroup takes.  Workgroup b runs on XCD b mod 8, and every XCD has an L2 of its own: a
+  // tile's slice of a list shares its first and last cache line with the neighbouring tiles', so chunks of
+  // kChunkTiles consecutive tiles are decoded at the same time by as many workgroups of one XCD, and the
+  // chunks go round the XCDs (whole eighths of the vector per XCD would leave the XCD with the dense layers
+  // behind).  Grids that do not divide into such chunks (fewer tiles than the device holds): tile b, b + grid, ...
+  const bool chunked = gridDim.x % (8u * kChunkTiles) == 0;
+  const uint32_t xcd = blockIdx.x & 7u, seat = blockIdx.x >> 3, chunks_at_once = gridDim.x / (8u * kChunkTiles);
+  auto tile_of = [&](uint32_t r) {
+    return chunked ? ((seat / kChunkTiles + chunks_at_once * r) * 8u + xcd) * kChunkTiles + seat % kChunkTiles
+                   : blockIdx.x + r * gridDim.x;
+  };
+  uint32_t round = 0;
+  uint2 next_rows = request_rows(tile_of(0));
+  for (uint32_t tile = tile_of(0); tile < n_tiles; tile = tile_of(++round)) {
     const uint32_t lo = tile * kDecTile;
     const uint2 rows = next_rows;
-    next_rows = request_rows(tile + gridDim.x);
+    next_rows = request_rows(tile_of(round + 1u));
     __syncthreads();  // the tile before is written out; the descriptors are in place
     for (uint32_t i = tid; i < kDecTile; i += kDecBlock) S.acc[i] = 0.0;
     for (uint32_t l0 = 0; l0 < n_active; l0 += kListBatch) {
