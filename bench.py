@@ -241,7 +241,9 @@ def main() -> int:
     dec_bytes = stream_bytes + 4.0 * d                # streams read + dense vector written
     filter_bytes = 4.0 * n * d                        # what the filter launch must read
     achieved = filter_bytes / (filter_ms * 1e-3) / 1e9
-    traffic = recorded_traffic()
+    # the counters were taken on the benchmark workload: no figure for any other
+    on_profiled_workload = args.cfg == 3 and n == w.n_clients and not quant
+    traffic = recorded_traffic() if on_profiled_workload else {"filter": None, "encode": None, "decode_aggregate": None}
 
     def call(t, alg_bytes, key):
         """One call of the boundary against the HBM roofline on its algorithmic bytes."""
