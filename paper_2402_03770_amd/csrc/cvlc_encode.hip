@@ -23,10 +23,9 @@
 //                 time, keeping everything, for a client whose sample misjudged)
 //   gather_l2     copies the runs into one dense, position-ordered candidate
 //                 list, spans of 512 candidates per wavefront, and histograms
-//                 level 2 (the next 10 key bits) of the first 15 boundaries
-//   select_pass   level 3 (and level 2 of further groups of 15 boundaries):
-//                 LDS histograms of the next 10 key bits of the candidates that
-//                 match a boundary's prefix
+//                 level 2 (the next 10 key bits) of the boundaries
+//   select_pass3  level 3: LDS histograms of the last 10 key bits of the
+//                 candidates that match a boundary's 21-bit prefix
 //   select_walk   adds up the histograms, fixes the next digit of every
 //                 boundary; after level 3 the exact boundary keys and, where a
 //                 boundary cuts a class of equal magnitudes, the position of
@@ -574,12 +573,15 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
 }
 
 // ------------------------------------------------------------------ 4. selection, levels 2 and 3
-// LEVEL 2 refines bits 19..10, LEVEL 3 bits 9..0 of the boundary keys of one
-// group of up to kSlotGroup boundaries.  Boundaries that share a prefix share a
-// histogram ("slot").  The pass kernel histograms, in LDS, the next digit of
-// every candidate whose key starts with a slot's prefix and stores one partial
-// histogram per workgroup; the walk kernel (one workgroup per client) adds the
-// partials up and, one wavefront per boundary, walks the digits from the top.
+// LEVEL 2 refines bits 19..10, LEVEL 3 bits 9..0 of the boundary keys.  The
+// kernels come in two sizes SG: room for 15 boundaries (plans of up to 15
+// groups: 60 KB of counters, two workgroups to a CU) or for all 31 (124 KB, one
+// workgroup to a CU).  Boundaries that share a prefix share a histogram
+// ("slot").  The pass (level 2: the gather) histograms, in LDS, the next digit
+// of every candidate whose key starts with a slot's prefix; level 2 stores one
+// partial histogram per workgroup, level 3 adds its few counts to one table per
+// client; the walk kernel (one workgroup per slot and client) adds them up and
+// reads off every boundary's digit.
 // During level 3 the few candidates matching a boundary's 21-bit prefix are
 // also kept aside, so that a boundary cutting through a class of equal keys
 // can find the position of the last member inside it (ties rank by position).
@@ -783,16 +785,16 @@ __device__ __forceinline__ void store_partials(const uint32_t* hist, uint32_t us
   }
 }
 
-// Fills the workgroup's slot tables for one group of boundaries.
+// Fills the workgroup's slot tables for the plan's boundaries.
 template <int LEVEL, uint32_t SG>
-__device__ __forceinline__ void select_setup(SelectShared<SG>& S, const ClientCtl* ctl, uint32_t r0, uint32_t nb) {
+__device__ __forceinline__ void select_setup(SelectShared<SG>& S, const ClientCtl* ctl, uint32_t nb) {
   const uint32_t tid = threadIdx.x;
   for (uint32_t i = tid; i < SG * kDigitBins; i += kWideBlock) S.hist[i] = 0;
   for (uint32_t i = tid; i < kL1Bins / SelectShared<SG>::kTagsPerWord; i += kWideBlock) S.bin_slot[i] = 0;
   for (uint32_t i = tid; i < SG * (kDigitBins / 32); i += kWideBlock) (&S.digit_map[0][0])[i] = 0;
   if (tid < SG) S.tie_full[tid] = 0;
   uint32_t pre = 0xFFFFFFFFu;
-  if (tid < nb) pre = ctl->sel_prefix[LEVEL - 2][r0 + tid];
+  if (tid < nb) pre = ctl->sel_prefix[LEVEL - 2][tid];
   __syncthreads();
   if (tid < kWave) {  // the first wavefront, lane b = boundary b
     bool opens;
@@ -814,7 +816,7 @@ __device__ __forceinline__ void select_setup(SelectShared<SG>& S, const ClientCt
   __syncthreads();
 }
 
-// Level 2 of the first group of boundaries, fused with the gather: every
+// Level 2, fused with the gather: every
 // wavefront takes spans of 512 candidates (gw, gw + wavefronts, ...), collects
 // them from the region runs they lie in, stores them at their place in the
 // dense position-ordered candidate list and counts the level-2 digits on the
@@ -829,7 +831,7 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
   ClientCtl* ctl = ctls + client;
   if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
   const uint32_t nb = min(p.R, SG);
-  select_setup<2, SG>(S, ctl, 0, nb);
+  select_setup<2, SG>(S, ctl, nb);
   const CandView cv = cand_view(ws, ctl, client);
   uint32_t* __restrict__ dst_idx = ws.dense_idx + (size_t)client * ws.dense_cap;
   uint32_t* __restrict__ dst_val = ws.dense_val + (size_t)client * ws.dense_cap;
@@ -862,23 +864,21 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
   store_partials(S.hist, S.slots.n * kDigitBins, part, narrow_partials(cv.n, gridDim.x));
 }
 
-// Every other selection pass reads the dense list.
-template <int LEVEL, uint32_t SG>
-__global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientParams* __restrict__ params,
-                                                                 ClientCtl* __restrict__ ctls, Workspace ws,
-                                                                 uint32_t group) {
+// Level 3 reads the dense list.
+template <uint32_t SG>
+__global__ __launch_bounds__(kWideBlock) void select_pass3_kernel(const ClientParams* __restrict__ params,
+                                                                  ClientCtl* __restrict__ ctls, Workspace ws) {
   __shared__ SelectShared<SG> S;
   const uint32_t client = blockIdx.y, tid = threadIdx.x, wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
-  const uint32_t r0 = group * SG;
-  if (p.R <= r0) return;  // this client has no boundary in the group
-  const uint32_t nb = min(p.R - r0, SG);
+  if (p.R == 0) return;  // nothing is coded
+  const uint32_t nb = min(p.R, SG);
   const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.dense_cap;
   uint2* ties = ws.tie_list + (size_t)client * SG * kTieCap;
-  uint32_t* tie_cnt = ctl->tie_cnt + group * SG;
-  select_setup<LEVEL, SG>(S, ctl, r0, nb);
+  uint32_t* tie_cnt = ctl->tie_cnt;
+  select_setup<3, SG>(S, ctl, nb);
 
   const uint32_t n = ctl->n_cand;
   const uint32_t span = (uint32_t)(((uint64_t)n + gridDim.x - 1) / gridDim.x);
@@ -897,22 +897,17 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
     for (uint32_t u = 0; u < 8; ++u) {
       const uint32_t i = base + u * kWideBlock + tid;
       if (base + u * kWideBlock + wave * kWave >= end) break;  // uniform per wavefront
-      select_count<LEVEL, SG>(S, v[u] & 0x7FFFFFFFu, i, i < end, tie_cnt, ties);
+      select_count<3, SG>(S, v[u] & 0x7FFFFFFFu, i, i < end, tie_cnt, ties);
     }
   }
   __syncthreads();
+  // a handful of candidates per slot share a boundary's 21-bit prefix (more only among heavy ties):
+  // the few non-empty counters are added straight to the client's table
   const uint32_t used = S.slots.n * kDigitBins;
-  if (LEVEL == 3) {
-    // a handful of candidates per slot share a boundary's 21-bit prefix (more only among heavy ties):
-    // the few non-empty counters are added straight to the client's table
-    uint32_t* table = ws.l3_hist + (size_t)client * SG * kDigitBins;
-    for (uint32_t i = tid; i < used; i += kWideBlock) {
-      const uint32_t h = S.hist[i];
-      if (h) atomicAdd(&table[i], h);
-    }
-  } else {
-    uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * SG * kDigitBins;
-    store_partials(S.hist, used, part, narrow_partials(n, gridDim.x));
+  uint32_t* table = ws.l3_hist + (size_t)client * SG * kDigitBins;
+  for (uint32_t i = tid; i < used; i += kWideBlock) {
+    const uint32_t h = S.hist[i];
+    if (h) atomicAdd(&table[i], h);
   }
 }
 
@@ -922,8 +917,7 @@ __global__ __launch_bounds__(kWideBlock) void select_pass_kernel(const ClientPar
 // digit and the rank left inside it.
 template <int LEVEL, uint32_t SG>
 __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientParams* __restrict__ params,
-                                                                 ClientCtl* __restrict__ ctls, Workspace ws,
-                                                                 uint32_t group) {
+                                                                 ClientCtl* __restrict__ ctls, Workspace ws) {
   __shared__ SlotTable<SG> slots;
   __shared__ uint32_t s_digit[SG], s_quota[SG], s_need[SG], s_rem[SG];
   __shared__ uint32_t s_found;
@@ -933,10 +927,9 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
-  const uint32_t r0 = group * SG;
   const uint32_t n_cand = ctl->n_cand;  // asked for together with R
-  if (p.R <= r0) return;
-  const uint32_t nb = min(p.R - r0, SG);
+  if (p.R == 0) return;
+  const uint32_t nb = min(p.R, SG);
   const uint32_t n_parts = ws.sel_blocks;
   const uint32_t* parts = ws.sel_part + (size_t)client * n_parts * SG * kDigitBins;
   // Everything the walk reads from global memory is requested here, before the
@@ -944,15 +937,15 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   // digit down; a slot past the last one in use adds up stale partials for nothing.
   uint32_t pre = 0xFFFFFFFFu, rem_in = 0;
   if (tid < nb) {
-    pre = ctl->sel_prefix[LEVEL - 2][r0 + tid];
-    rem_in = ctl->sel_rem[LEVEL - 2][r0 + tid];
+    pre = ctl->sel_prefix[LEVEL - 2][tid];
+    rem_in = ctl->sel_rem[LEVEL - 2][tid];
     // the level's results go to arrays of their own: other workgroups of this launch may still have to read its inputs
-    if (LEVEL == 2 && slot == 0 && pre == 0xFFFFFFFFu) ctl->sel_prefix[1][r0 + tid] = pre;
+    if (LEVEL == 2 && slot == 0 && pre == 0xFFFFFFFFu) ctl->sel_prefix[1][tid] = pre;
   }
-  const uint32_t kept = LEVEL == 3 ? ctl->tie_cnt[group * SG + slot] : 0u;
+  const uint32_t kept = LEVEL == 3 ? ctl->tie_cnt[slot] : 0u;
   const uint32_t digit = kDigitBins - 1 - tid;
   uint32_t h = 0;
-  if (LEVEL == 3) {  // one table per client; left cleared for the next group of boundaries or the next call
+  if (LEVEL == 3) {  // one table per client; left cleared for the next call
     uint32_t* mine = ws.l3_hist + ((size_t)client * SG + slot) * kDigitBins + digit;
     h = *mine;
     *mine = 0;
@@ -982,7 +975,7 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
   const uint32_t prefix = slots.prefix[slot];
   for (uint32_t b = 0; b < nb; ++b) {
     if (slots.leader[b] != slot) continue;
-    const uint32_t r = r0 + b;
+    const uint32_t r = b;
     const uint32_t rem = s_rem[b];
     if (rem > total && tid == 0) atomicOr(ws.status, CVLC_DEV_INTERNAL);  // histogram short of the rank
     if (above < rem && rem <= above + h) {  // exactly one thread
@@ -1008,7 +1001,7 @@ __global__ __launch_bounds__(kWideBlock) void select_walk_kernel(const ClientPar
     const uint32_t n = ctl->n_cand;
     for (uint32_t b = 0; b < nb; ++b) {
       if (!s_need[b]) continue;  // uniform
-      const uint32_t r = r0 + b, w_digit = s_digit[b], w_quota = s_quota[b];
+      const uint32_t r = b, w_digit = s_digit[b], w_quota = s_quota[b];
       if (kept <= kTieCap) {
         // position-order rank of every kept-aside member of the class, all threads, list in LDS
         __syncthreads();
@@ -1960,15 +1953,15 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
     if (max_R <= kSlotGroup) {
       constexpr uint32_t SG = kSlotGroup;
       hipLaunchKernelGGL(gather_l2_kernel<SG>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
-      hipLaunchKernelGGL((select_walk_kernel<2, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
-      hipLaunchKernelGGL((select_pass_kernel<3, SG>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
-      hipLaunchKernelGGL((select_walk_kernel<3, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
+      hipLaunchKernelGGL((select_walk_kernel<2, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
+      hipLaunchKernelGGL(select_pass3_kernel<SG>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
+      hipLaunchKernelGGL((select_walk_kernel<3, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
     } else {
       constexpr uint32_t SG = kSlotGroupWide;
       hipLaunchKernelGGL(gather_l2_kernel<SG>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
-      hipLaunchKernelGGL((select_walk_kernel<2, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
-      hipLaunchKernelGGL((select_pass_kernel<3, SG>), grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
-      hipLaunchKernelGGL((select_walk_kernel<3, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws, 0u);
+      hipLaunchKernelGGL((select_walk_kernel<2, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
+      hipLaunchKernelGGL(select_pass3_kernel<SG>, grid, dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
+      hipLaunchKernelGGL((select_walk_kernel<3, SG>), dim3(SG, n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
     }
   }
   // count: wavefronts walk the spans; about what the device holds at once (four workgroups per CU)
