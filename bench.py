@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E peak
 PLANNER_ALPHA = -0.5      # power-law exponent handed to Algorithm 1 for the planned workloads
-DOMINANT_KERNEL = "filter_kernel<0>"   # the one full pass over the update vectors
+DOMINANT_KERNEL = "filter_kernel"   # the one full pass over the update vectors
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hot_path_cfg3_hbm_traffic.txt")
 KERNEL_SOURCES = ["cvlc_common.h", "cvlc_encode.hip", "cvlc_decode.hip"]
 CALL_TARGET_FRAC = 0.60   # the bar each call is held to: 60 % of the HBM peak on its algorithmic bytes

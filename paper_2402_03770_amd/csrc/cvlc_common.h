@@ -58,11 +58,10 @@ static_assert(sizeof(ClientParams) % 8 == 0, "ClientParams must stay 8-byte gran
 struct ClientCtl {
   uint32_t tau_lo;           // candidate threshold key from the sample (0: keep every coordinate)
   uint32_t n_cand;           // candidates kept by the filter pass that counts
-  uint32_t refilter;         // 1: the sampled threshold kept fewer than k, the keep-all pass must run
+  uint32_t keep_all;         // 1: the sampled threshold kept fewer than k: every coordinate is a candidate, read from the vector
   uint32_t n_nz;             // regions that kept at least one coordinate
   uint32_t dead;             // 1: more candidates than the workspace has room for; nothing further is done for the client
   uint32_t reserved;
-  double tail_sumsq;         // energy of the coordinates the filter dropped
   double seg_sumsq[32];      // energy of every coded group; entry R: candidates below the last boundary (atomic)
   uint32_t tie_cnt[32];      // kept-aside class members per histogram slot
   uint32_t sel_prefix[2][32];  // key prefix of boundary r after level 1 (11 bits) and level 2 (21 bits); 0xFFFFFFFF: Z_r = 0
@@ -72,7 +71,7 @@ struct ClientCtl {
   uint32_t seg_max_enc[32];  // max over the group of ordered(x); 0 = empty
   uint32_t seg_negmin_enc[32];  // max over the group of ~ordered(x); 0 = empty
   uint32_t hist_sample[kSampleBins];  // sample histogram, accumulated with device-wide atomics
-  uint32_t hist_l1[2][kL1Bins];       // level-1 digit counts of the candidates, per filter pass, likewise
+  uint32_t hist_l1[kL1Bins];    // level-1 digit counts of the candidates (device-wide atomics from the filter)
 };
 
 // ---- decoder -------------------------------------------------------------------

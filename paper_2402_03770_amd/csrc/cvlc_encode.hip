@@ -19,8 +19,8 @@
 //                 order; it also counts the level-1 digit (top 11 key bits) of
 //                 what it keeps and sums the squares of what it drops
 //   scan_l1       prefix over the region counts, list of the non-empty runs;
-//                 level-1 bins of the boundaries (filter and scan run a second
-//                 time, keeping everything, for a client whose sample misjudged)
+//                 level-1 bins of the boundaries (for a client whose sample
+//                 misjudged, every coordinate becomes a candidate here)
 //   gather_l2     copies the runs into one dense, position-ordered candidate
 //                 list, spans of 512 candidates per wavefront, and histograms
 //                 level 2 (the next 10 key bits) of the boundaries
@@ -41,6 +41,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <type_traits>
 
 #include "cvlc_common.h"
 
@@ -395,9 +396,6 @@ __device__ __forceinline__ void filter_subtile(const SubTile& t, uint32_t sbase,
   }
 }
 
-// PASS 0 filters against the sampled threshold; PASS 1 keeps everything and
-// only runs for clients whose PASS 0 kept fewer than k coordinates.
-template <int PASS>
 __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __restrict__ params,
                                                         ClientCtl* __restrict__ ctls, Workspace ws) {
   __shared__ uint32_t s_hist[kL1Bins];
@@ -405,13 +403,7 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __re
   const uint32_t client = blockIdx.y;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  uint32_t tau_lo;
-  if (PASS == 0) {
-    tau_lo = ctl->tau_lo;
-  } else {
-    if (!ctl->refilter) return;  // the sampled threshold kept enough
-    tau_lo = 0;
-  }
+  const uint32_t tau_lo = ctl->tau_lo;
   const uint32_t d = ws.d, n_regions = ws.n_regions;
   GlobalFloatPtr U = (GlobalFloatPtr)p.update;
   const uint32_t lane = lane_id();
@@ -473,7 +465,7 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __re
   __syncthreads();
   for (uint32_t i = threadIdx.x; i < kL1Bins; i += kBlock) {
     const uint32_t h = s_hist[i];
-    if (h) atomicAdd(&ctl->hist_l1[PASS][i], h);
+    if (h) atomicAdd(&ctl->hist_l1[i], h);
   }
 }
 
@@ -484,7 +476,11 @@ __global__ __launch_bounds__(kBlock) void filter_kernel(const ClientParams* __re
 // candidates, and the run holding every span's first candidate is noted), then reads the level-1
 // histogram the filter's workgroups accumulated and locates, for every boundary
 // Z_r, the bin holding the Z_r-th largest key and the rank left inside it.
-template <int PASS>
+// Should the sampled threshold have kept fewer than k coordinates (the sample
+// misjudged: six standard deviations, or a vector built against the sampling
+// pattern), every coordinate becomes a candidate: the runs are then the regions
+// themselves, read from the vector, and this workgroup counts the level-1
+// digits of the whole vector on its own: slow, and next to never needed.
 __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams* __restrict__ params,
                                                              ClientCtl* __restrict__ ctls, Workspace ws) {
   __shared__ uint32_t hist[kL1Bins];
@@ -493,7 +489,6 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
   const uint32_t client = blockIdx.x, tid = threadIdx.x;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
-  if (PASS == 1 && !ctl->refilter) return;
   const uint32_t n_regions = ws.n_regions;
   const uint32_t* cnt = ws.region_cnt + (size_t)client * n_regions;
   uint32_t* nz_off = ws.nz_off + (size_t)client * (n_regions + 1);
@@ -519,7 +514,8 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
     run += tot;
     n_nz += tot_nz;
   }
-  if (run > ws.dense_cap) {  // the caller's workspace is too short for this vector: no stream, and say so
+  const bool keep_all = run < p.k;  // uniform
+  if (run > ws.dense_cap || (keep_all && ws.d > ws.dense_cap)) {  // the caller's workspace is too short for this vector: no stream, and say so
     if (tid == 0) {
       nz_off[0] = 0;
       ctl->n_cand = 0;
@@ -530,18 +526,50 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
     }
     return;
   }
-  if (tid == 0) {
-    nz_off[n_nz] = run;
-    ctl->n_cand = run;
-    ctl->n_nz = n_nz;
+  if (!keep_all) {
+    if (tid == 0) {
+      nz_off[n_nz] = run;
+      ctl->n_cand = run;
+      ctl->n_nz = n_nz;
+    }
+    hist[2u * tid] = ctl->hist_l1[2u * tid];
+    hist[2u * tid + 1] = ctl->hist_l1[2u * tid + 1];
+  } else {
+    const uint32_t d = ws.d;
+    __syncthreads();  // the runs written above are overwritten
+    double* rsq = ws.region_sumsq + (size_t)client * n_regions;
+    for (uint32_t j = tid; j < n_regions; j += kWideBlock) {
+      nz_off[j] = j * kRegion;
+      nz_run[j] = j;
+      rsq[j] = 0.0;  // nothing is dropped before the selection
+    }
+    for (uint32_t sp = tid; (uint64_t)sp * kSpan < d; sp += kWideBlock) span_first[sp] = sp / (kRegion / kSpan);
+    if (tid == 0) {
+      nz_off[n_regions] = d;
+      ctl->n_cand = d;
+      ctl->n_nz = n_regions;
+      ctl->keep_all = 1u;
+    }
+    hist[2u * tid] = 0;
+    hist[2u * tid + 1] = 0;
+    __syncthreads();
+    const uint32_t* __restrict__ bits = reinterpret_cast<const uint32_t*>(p.update);
+    bool nonfinite = false;
+    for (uint32_t base = 0; base < d; base += kWideBlock * 8u) {
+      uint32_t v[8];
+#pragma unroll
+      for (uint32_t u = 0; u < 8; ++u) v[u] = bits[min(base + u * kWideBlock + tid, d - 1u)];
+#pragma unroll
+      for (uint32_t u = 0; u < 8; ++u) {
+        if (base + u * kWideBlock + tid < d) {
+          const uint32_t key = v[u] & 0x7FFFFFFFu;
+          nonfinite |= key >= 0x7F800000u;
+          atomicAdd(&hist[key >> 20], 1u);
+        }
+      }
+    }
+    if (nonfinite) atomicOr(ws.status, CVLC_DEV_NONFINITE);
   }
-  if (PASS == 0 && run < p.k) {  // the sample misjudged the threshold: everything is redone by pass 1
-    if (tid == 0) ctl->refilter = 1u;
-    return;
-  }
-
-  hist[2u * tid] = ctl->hist_l1[PASS][2u * tid];
-  hist[2u * tid + 1] = ctl->hist_l1[PASS][2u * tid + 1];
   __syncthreads();
   const uint32_t top = kL1Bins - 1 - 2u * tid;
   const uint32_t h0 = hist[top], h1 = hist[top - 1];
@@ -836,28 +864,33 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
   uint32_t* __restrict__ dst_idx = ws.dense_idx + (size_t)client * ws.dense_cap;
   uint32_t* __restrict__ dst_val = ws.dense_val + (size_t)client * ws.dense_cap;
   const uint32_t n_spans = (cv.n + kSpan - 1) / kSpan;
-  for (uint32_t span = blockIdx.x * kWideWaves + wave; span < n_spans; span += gridDim.x * kWideWaves) {
-    uint32_t slot[kPerLane], v[kPerLane], x[kPerLane];
-    span_slots(cv, span, span_window(cv, span), slot);
+  // keep_all: a slot is a region of the vector itself and a candidate's place in it its position
+  auto copy_spans = [&](auto keep_all) {
+    const uint32_t* __restrict__ src_val = keep_all.value ? reinterpret_cast<const uint32_t*>(p.update) : cv.val;
+    for (uint32_t span = blockIdx.x * kWideWaves + wave; span < n_spans; span += gridDim.x * kWideWaves) {
+      uint32_t slot[kPerLane], v[kPerLane], x[kPerLane];
+      span_slots(cv, span, span_window(cv, span), slot);
 #pragma unroll
-    for (uint32_t j = 0; j < kPerLane; ++j) {
-      // rows past the last candidate read some valid place instead of branching, so that the
-      // sixteen loads of a span go out together
-      const uint32_t sl = min(slot[j], ws.d - 1u);
-      v[j] = cv.val[sl];
-      x[j] = (sl & ~(kRegion - 1u)) + cv.idx[sl];  // a slot starts where its region starts
-    }
-#pragma unroll
-    for (uint32_t j = 0; j < kPerLane; ++j) {
-      const uint32_t i = span * kSpan + j * kWave + lane;
-      if (i - lane >= cv.n) break;  // uniform
-      if (i < cv.n) {
-        dst_val[i] = v[j];
-        dst_idx[i] = x[j];
+      for (uint32_t j = 0; j < kPerLane; ++j) {
+        // rows past the last candidate read some valid place instead of branching, so that the
+        // sixteen loads of a span go out together
+        const uint32_t sl = min(slot[j], ws.d - 1u);
+        v[j] = src_val[sl];
+        x[j] = keep_all.value ? sl : (sl & ~(kRegion - 1u)) + cv.idx[sl];  // a slot starts where its region starts
       }
-      if (nb) select_count<2, SG>(S, v[j] & 0x7FFFFFFFu, 0u, i < cv.n, nullptr, nullptr);
+#pragma unroll
+      for (uint32_t j = 0; j < kPerLane; ++j) {
+        const uint32_t i = span * kSpan + j * kWave + lane;
+        if (i - lane >= cv.n) break;  // uniform
+        if (i < cv.n) {
+          dst_val[i] = v[j];
+          dst_idx[i] = x[j];
+        }
+        if (nb) select_count<2, SG>(S, v[j] & 0x7FFFFFFFu, 0u, i < cv.n, nullptr, nullptr);
+      }
     }
-  }
+  };
+  if (ctl->keep_all) copy_spans(std::true_type{}); else copy_spans(std::false_type{});
   __syncthreads();
   if (nb == 0) return;
   uint32_t* part = ws.sel_part + ((size_t)client * gridDim.x + blockIdx.x) * SG * kDigitBins;
@@ -1769,7 +1802,7 @@ uint32_t filter_resident_blocks() {
     int cus = 0, per_cu = 0;
     uint32_t r = kFilterBlocksCap / 2;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, filter_kernel<0>, kBlock, 0) == hipSuccess && cus > 0 &&
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, filter_kernel, kBlock, 0) == hipSuccess && cus > 0 &&
         per_cu > 0)
       r = (uint32_t)cus * (uint32_t)per_cu;
     cached[dev] = r > kFilterBlocksCap ? kFilterBlocksCap : r;
@@ -1934,15 +1967,11 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   }
   {
     StageScope scope(CVLC_STAGE_ENC_FILTER, stream);
-    hipLaunchKernelGGL(filter_kernel<0>, dim3(ws.filter_blocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
+    hipLaunchKernelGGL(filter_kernel, dim3(ws.filter_blocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
   }
   {
     StageScope scope(CVLC_STAGE_ENC_REFILTER, stream);
-    hipLaunchKernelGGL(scan_l1_kernel<0>, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
-    if (any_sampled) {  // only clients whose sampled threshold kept too few do anything here
-      hipLaunchKernelGGL(filter_kernel<1>, dim3(ws.filter_blocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, ws);
-      hipLaunchKernelGGL(scan_l1_kernel<1>, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
-    }
+    hipLaunchKernelGGL(scan_l1_kernel, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl, ws);
   }
   {
     StageScope scope(CVLC_STAGE_ENC_SELECT, stream);

@@ -219,6 +219,19 @@ def test_more_clients_than_the_chip_holds_workgroups_for():
     check_decode(refs, d)
 
 
+def test_more_streams_than_one_header_launch_takes():
+    """130 streams: their pointers travel as kernel arguments, 112 a launch, so the headers are parsed by two
+    launches and the lists numbered by a third (up to 112 streams one launch does both)."""
+    d, n = 30_000, 130
+    refs = []
+    for c in range(n):
+        U = syn.update_vector(2 + c % 2, 2000 + c, d=d)
+        refs.append(orc.encode(U, orc.plan_fractions(d, [8, 4, 1], [0.01, 0.03, 0.05 + 0.001 * (c % 7)]), 9, c).words)
+    check_decode(refs, d)
+    rng = np.random.default_rng(3)
+    check_decode(refs, d, weights=rng.uniform(-1.0, 1.0, n).astype(np.float32).tolist())
+
+
 @pytest.mark.parametrize("cfg,d,n", [(2, 1_200_000, 8), (3, 700_001, 4), (4, 1_000_000, 4), (5, 800_000, 3)])
 def test_workloads_at_oracle_friendly_sizes(cfg, d, n):
     w = syn.WORKLOADS[cfg]
