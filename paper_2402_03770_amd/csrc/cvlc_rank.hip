@@ -390,6 +390,7 @@ __global__ __launch_bounds__(kRankBlock) void rank_collect_kernel(const float* c
                                                                   uint32_t* __restrict__ list_cnt, uint32_t wave_cap) {
   __shared__ alignas(16) uint8_t first_cls[kTopBins];
   __shared__ uint32_t stage[kRankWaves][kCollectStage];
+  __shared__ uint32_t s_fill[kRankWaves];  // keys a wavefront has staged
   RankCtl* ctl = ctls + blockIdx.y;
   const uint32_t n_cls = ctl->n_cls;
   for (uint32_t i = threadIdx.x; i < kTopBins / 4u; i += kRankBlock)
@@ -401,17 +402,28 @@ __global__ __launch_bounds__(kRankBlock) void rank_collect_kernel(const float* c
   const size_t list = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * kRankWaves + wave;
   uint32_t* __restrict__ out = lists + list * wave_cap;
   uint32_t* mine = stage[wave];
-  uint32_t fill = 0, run = 0;  // staged keys, keys already written (uniform over the wavefront)
-  // whole wavefront; LDS accesses of a wavefront complete in order, the fences keep the compiler from moving them
-  auto take = [&](uint32_t key, bool valid) {
-    const bool hit = valid && first_cls[key >> kTopShift] != kNoClass;
-    const uint64_t m = __ballot(hit);
-    if (m == 0) return;
-    if (hit) mine[fill + lanes_below(m)] = key;
-    fill += (uint32_t)__popcll(m);
+  uint32_t fill = 0, run = 0;  // staged keys as of the last look, keys already written (uniform over the wavefront)
+  // LDS accesses of a wavefront complete in order; the fences keep the compiler from moving them.
+  auto lds_fence = [] { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); };
+  if (lane == 0) s_fill[wave] = 0;
+  lds_fence();
+  // Class keys are few (a lane meets one in every sixteenth float4 or so): the lanes that hold some take
+  // their places in the wavefront's stage with an LDS atomic; the order of the keys in a list is free.
+  auto take = [&](const uint32_t* k, uint32_t n_keys, bool valid) {
+    uint32_t hit = 0;
+    for (uint32_t c = 0; c < n_keys; ++c) hit |= (first_cls[k[c] >> kTopShift] != kNoClass ? 1u : 0u) << c;
+    if (valid && hit) {
+      uint32_t pos = atomicAdd(&s_fill[wave], (uint32_t)__popc(hit));
+      for (uint32_t c = 0; c < n_keys; ++c)
+        if ((hit >> c) & 1u) mine[pos++] = k[c];
+    }
+  };
+  auto look = [&] {
+    lds_fence();
+    fill = __builtin_amdgcn_readfirstlane(s_fill[wave]);
   };
   auto flush = [&](bool all) {
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    lds_fence();
     uint32_t g = 0;
     for (; g + kWave <= fill; g += kWave) out[run + g + lane] = mine[g + lane];
     const uint32_t left = fill - g;
@@ -421,13 +433,14 @@ __global__ __launch_bounds__(kRankBlock) void rank_collect_kernel(const float* c
         if (lane < left) out[run + g + lane] = k;
         g += left;
       } else if (g) {  // the partial row moves to the front
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        lds_fence();
         if (lane < left) mine[lane] = k;
       }
     }
     run += g;
     fill -= g;
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    if (lane == 0) s_fill[wave] = fill;
+    lds_fence();
   };
   const float* update = updates[blockIdx.y];
   const uint32_t n_quads = d / 4u;
@@ -443,15 +456,20 @@ __global__ __launch_bounds__(kRankBlock) void rank_collect_kernel(const float* c
 #pragma unroll
     for (uint32_t u = 0; u < kDeep; ++u) {
       const uint32_t q = q0 + u * kRankBlock + threadIdx.x;
+      uint32_t k[4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) take(__float_as_uint(v[u][c]) & 0x7FFFFFFFu, q < n_quads);
+      for (int c = 0; c < 4; ++c) k[c] = __float_as_uint(v[u][c]) & 0x7FFFFFFFu;
+      take(k, 4u, q < n_quads);
+      look();
       if (fill >= kCollectStage - 4u * kWave) flush(false);  // room for the next four keys of every lane
     }
   }
   if (blockIdx.x == 0 && wave == 0) {  // the last d % 4 coordinates
     const bool valid = lane < d - n_quads * 4u;
-    take(valid ? __float_as_uint(update[n_quads * 4u + lane]) & 0x7FFFFFFFu : 0u, valid);
+    const uint32_t k = valid ? __float_as_uint(update[n_quads * 4u + lane]) & 0x7FFFFFFFu : 0u;
+    take(&k, 1u, valid);
   }
+  look();
   flush(true);
   if (lane == 0) list_cnt[list] = run;
 }
