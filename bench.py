@@ -149,7 +149,7 @@ def main() -> int:
                     help="also run one plain device copy of 1 GiB (a known size for scaling HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        print("bench.py measures one GPU: there is no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         return 2
 
     import torch

@@ -868,10 +868,10 @@ def test_full_size_32_clients(cfg):
 
 
 def _progress(msg):
-    """A line in gpurun_out/ (when that folder exists), so that a long test is seen to be alive."""
-    folder = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(folder):
-        with open(os.path.join(folder, "test_progress.log"), "a") as f:
+    """A line in the file CVLC_TEST_PROGRESS names (when set), so that a long test is seen to be alive."""
+    path = os.environ.get("CVLC_TEST_PROGRESS")
+    if path:
+        with open(path, "a") as f:
             f.write(msg + "\n")
 
 
