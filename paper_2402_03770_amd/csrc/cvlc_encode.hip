@@ -1708,7 +1708,7 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
         }
         const uint64_t record = (uint64_t)pid[j] | ((uint64_t)cid << sbits);
         // a chunk's run of a group is at most 4096 records of at most 63 bits: 32 bits hold the offset
-        const uint32_t bit = eg.stage_bit + (e - eg.first) * W;
+        const uint32_t bit = eg.stage_bit + __umul24(e - eg.first, W);  // fewer than 4096 records, at most 63 bits each
         const uint32_t w0 = bit >> 5, sh = bit & 31u;
         const uint64_t lo = record << sh;
         atomicOr(&s_stage[w0], (uint32_t)lo);
