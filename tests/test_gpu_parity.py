@@ -178,6 +178,40 @@ def test_tie_heavy_vectors(kind):
         check_decode(refs, d)
 
 
+@pytest.mark.parametrize("kind", ["all_equal_mixed_sign", "two_valued", "few_levels", "zeros_and_denormals"])
+def test_tie_heavy_vectors_with_more_than_fifteen_groups(kind):
+    """Plans of more than 15 groups select all their boundaries in one round of wider kernels: the same
+    colliding magnitudes through those, with many boundaries inside one class of equal keys."""
+    for d, R in ((65_536, 31), (70_001, 20)):
+        U = syn.tie_heavy_vector(kind, d, seed=d + R)
+        code_len = [max(1, 16 - r // 2) for r in range(R)]
+        counts = [d // (3 * R) + 7 * r for r in range(R)]
+        counts[R // 2] = 0
+        p = orc.plan_manual(d, code_len, counts)
+        refs, _ = check_encode([U], [p], 5, [4])
+        check_decode(refs, d)
+
+
+def test_misjudged_sample_in_a_workspace_sized_to_the_plan():
+    """When the sampled threshold keeps fewer than k coordinates every coordinate becomes a candidate, which a
+    workspace sized to the plan has no room for: that client is refused, not encoded wrongly."""
+    d = 2_000_000
+    rng = np.random.default_rng(5)
+    U = (rng.standard_normal(d) * 1e-4).astype(np.float32)
+    n_src, n_s = d // 16, 16384
+    pieces = (np.arange(n_s, dtype=np.int64) * n_src) // n_s
+    for off in range(16):
+        U[pieces * 16 + off] = (rng.standard_normal(n_s) * 10.0).astype(np.float32)
+    po = orc.plan_manual(d, [8, 4, 2], [50_000, 100_000, 150_000])
+    p = to_lib_plan(po)
+    stream = cv.new_stream_buffer(p, DEV)
+    stream.fill_(-1)
+    ws = cv.new_workspace(cv.encode_workspace_bytes_for(d, 1, cv.plan_candidates_hint(p)), DEV)
+    cv.encode_batch([p], [torch.from_numpy(U).to(DEV)], 21, [3], [stream], ws)
+    assert cv.device_status(ws) == cv.DEV_WORKSPACE
+    assert int(stream[0].item()) == 0
+
+
 def test_boundary_ties_inside_smooth_data():
     """A smooth vector into which runs of equal magnitudes (mixed signs) are planted
     right at the group boundaries."""
