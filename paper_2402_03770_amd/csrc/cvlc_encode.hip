@@ -656,9 +656,23 @@ __device__ __forceinline__ uint32_t build_slots(SlotTable<SG>& st, uint32_t pre,
   return slot;
 }
 
-template <uint32_t SG>
+constexpr uint32_t kNoDigit = 0xFFFFFFFFu;
+constexpr uint32_t kTieStage = 64;  // kept-aside candidates a workgroup stages per slot
+static_assert(kTieStage <= kWave, "one wavefront moves a slot's staged candidates in one step");
+
+// LEVEL 2 counts every candidate of a boundary's level-1 bin: a full histogram per slot.  LEVEL 3 counts the
+// handful of candidates that share a boundary's 21-bit prefix (more only when many keys are equal, and
+// equal keys share the digit): per slot one digit with its count, met first by the workgroup; candidates
+// with another digit are added straight to the client's table.
+template <uint32_t SG, int LEVEL>
 struct SelectShared {
-  uint32_t hist[SG * kDigitBins];
+  uint32_t hist[LEVEL == 2 ? SG * kDigitBins : 1];
+  uint32_t l3_digit[SG], l3_count[SG];
+  // level 3: the candidates kept aside wait here and join the client's lists when the workgroup is done (one
+  // device-wide atomic per slot and workgroup instead of one per wavefront row that holds such a candidate:
+  // a client's counters share a cache line, and atomics to one line queue up); what does not fit goes directly
+  uint2 tie_stage[LEVEL == 3 ? SG : 1][kTieStage];
+  uint32_t tie_n[SG];
   SlotTable<SG> slots;
   // top 11 key bits -> 1 + (level 2: slot, level 3: bin id); 4 bits each for up to 15 slots, 8 bits beyond
   static constexpr uint32_t kTagBits = SG <= 15 ? 4u : 8u, kTagsPerWord = 32u / kTagBits;
@@ -673,16 +687,16 @@ struct SelectShared {
     atomicOr(&bin_slot[top11 / kTagsPerWord], tag << ((top11 % kTagsPerWord) * kTagBits));
   }
 };
-// Up to 15 boundaries a launch: two workgroups to a CU.  All 31 at once: one workgroup, a single round.
-static_assert(sizeof(SelectShared<kSlotGroup>) <= 65536 && sizeof(SelectShared<kSlotGroupWide>) <= 160 * 1024 - 2048,
+// Level 2 for up to 15 boundaries: two workgroups to a CU.  All 31 at once: one workgroup.
+static_assert(sizeof(SelectShared<kSlotGroup, 2>) <= 65536 && sizeof(SelectShared<kSlotGroupWide, 2>) <= 160 * 1024 - 2048,
               "SelectShared must fit the CU's LDS");
 
 // Counts one candidate per lane (`live` lanes only); dense_i is its number in the
 // position-ordered candidate list (which ranks equal keys just as positions do).
 // Must be reached by all lanes of the wavefront.
 template <int LEVEL, uint32_t SG>
-__device__ __forceinline__ void select_count(SelectShared<SG>& S, uint32_t key, uint32_t dense_i,
-                                             bool live, uint32_t* tie_cnt, uint2* __restrict__ ties) {
+__device__ __forceinline__ void select_count(SelectShared<SG, LEVEL>& S, uint32_t key, uint32_t dense_i, bool live,
+                                             uint32_t* tie_cnt, uint2* __restrict__ ties, uint32_t* table) {
   uint32_t q = kNoSlot;
   if (live) {
     const uint32_t tag = S.bin_tag(key >> 20);
@@ -695,27 +709,42 @@ __device__ __forceinline__ void select_count(SelectShared<SG>& S, uint32_t key, 
           const uint32_t pre = key >> 10, ns = S.slots.n;
           for (uint32_t qq = 0; qq < ns; ++qq)
             if (S.slots.prefix[qq] == pre) q = qq;
-          if (q != kNoSlot) atomicAdd(&S.hist[q * kDigitBins + (key & (kDigitBins - 1))], 1u);
         }
       }
     }
   }
   if (LEVEL == 3) {
+    const uint32_t digit = key & (kDigitBins - 1);
     uint64_t todo = __ballot(q != kNoSlot);
-    while (todo) {  // one round per distinct slot present in the wavefront
+    while (todo) {  // one round per distinct (slot, last digit) present in the wavefront
       const uint32_t leader = (uint32_t)__builtin_ctzll(todo);
-      const uint32_t qs = __builtin_amdgcn_readlane(q, leader);
-      const bool mine = q == qs;
+      const uint32_t qs = __builtin_amdgcn_readlane(q, leader), ds = __builtin_amdgcn_readlane(digit, leader);
+      const bool mine = q == qs && digit == ds;
       const uint64_t peers = __ballot(mine);
-      uint32_t base = kTieCap;
-      if (lane_id() == leader && !S.tie_full[qs]) {
-        base = atomicAdd(&tie_cnt[qs], (uint32_t)__popcll(peers));
-        if (base >= kTieCap) S.tie_full[qs] = 1u;  // the count is past the cap for good: stop adding to it
+      const uint32_t n_peers = (uint32_t)__popcll(peers);
+      uint32_t staged = 0;
+      if (lane_id() == leader) {
+        const uint32_t seen = atomicCAS(&S.l3_digit[qs], kNoDigit, ds);
+        if (seen == kNoDigit || seen == ds) atomicAdd(&S.l3_count[qs], n_peers);
+        else atomicAdd(&table[qs * kDigitBins + ds], n_peers);
+        staged = atomicAdd(&S.tie_n[qs], n_peers);  // grows past kTieStage once the stage is full
       }
-      base = __builtin_amdgcn_readlane(base, leader);
-      if (mine) {
-        const uint32_t pos = base + lanes_below(peers);
-        if (pos < kTieCap) ties[qs * kTieCap + pos] = make_uint2(dense_i, key & (kDigitBins - 1));
+      staged = __builtin_amdgcn_readlane(staged, leader);
+      const uint32_t place = staged + lanes_below(peers);
+      if (mine && place < kTieStage) S.tie_stage[qs][place] = make_uint2(dense_i, digit);
+      const uint64_t over = __ballot(mine && place >= kTieStage);
+      if (over) {  // uniform
+        const uint32_t first_over = (uint32_t)__builtin_ctzll(over);
+        uint32_t base = kTieCap;
+        if (lane_id() == first_over && !S.tie_full[qs]) {
+          base = atomicAdd(&tie_cnt[qs], (uint32_t)__popcll(over));
+          if (base >= kTieCap) S.tie_full[qs] = 1u;  // the count is past the cap for good: stop adding to it
+        }
+        base = __builtin_amdgcn_readlane(base, first_over);
+        if (mine && place >= kTieStage) {
+          const uint32_t pos = base + lanes_below(over);
+          if (pos < kTieCap) ties[qs * kTieCap + pos] = make_uint2(dense_i, digit);
+        }
       }
       todo &= ~peers;
     }
@@ -815,10 +844,16 @@ __device__ __forceinline__ void store_partials(const uint32_t* hist, uint32_t us
 
 // Fills the workgroup's slot tables for the plan's boundaries.
 template <int LEVEL, uint32_t SG>
-__device__ __forceinline__ void select_setup(SelectShared<SG>& S, const ClientCtl* ctl, uint32_t nb) {
+__device__ __forceinline__ void select_setup(SelectShared<SG, LEVEL>& S, const ClientCtl* ctl, uint32_t nb) {
   const uint32_t tid = threadIdx.x;
-  for (uint32_t i = tid; i < SG * kDigitBins; i += kWideBlock) S.hist[i] = 0;
-  for (uint32_t i = tid; i < kL1Bins / SelectShared<SG>::kTagsPerWord; i += kWideBlock) S.bin_slot[i] = 0;
+  if (LEVEL == 2)
+    for (uint32_t i = tid; i < SG * kDigitBins; i += kWideBlock) S.hist[i] = 0;
+  if (tid < SG) {
+    S.l3_digit[tid] = kNoDigit;
+    S.l3_count[tid] = 0;
+    S.tie_n[tid] = 0;
+  }
+  for (uint32_t i = tid; i < kL1Bins / SelectShared<SG, LEVEL>::kTagsPerWord; i += kWideBlock) S.bin_slot[i] = 0;
   for (uint32_t i = tid; i < SG * (kDigitBins / 32); i += kWideBlock) (&S.digit_map[0][0])[i] = 0;
   if (tid < SG) S.tie_full[tid] = 0;
   uint32_t pre = 0xFFFFFFFFu;
@@ -853,7 +888,7 @@ __device__ __forceinline__ void select_setup(SelectShared<SG>& S, const ClientCt
 template <uint32_t SG>
 __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParams* __restrict__ params,
                                                                ClientCtl* __restrict__ ctls, Workspace ws) {
-  __shared__ SelectShared<SG> S;
+  __shared__ SelectShared<SG, 2> S;
   const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
@@ -886,7 +921,7 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
           dst_val[i] = v[j];
           dst_idx[i] = x[j];
         }
-        if (nb) select_count<2, SG>(S, v[j] & 0x7FFFFFFFu, 0u, i < cv.n, nullptr, nullptr);
+        if (nb) select_count<2, SG>(S, v[j] & 0x7FFFFFFFu, 0u, i < cv.n, nullptr, nullptr, nullptr);
       }
     }
   };
@@ -897,11 +932,12 @@ __global__ __launch_bounds__(kWideBlock) void gather_l2_kernel(const ClientParam
   store_partials(S.hist, S.slots.n * kDigitBins, part, narrow_partials(cv.n, gridDim.x));
 }
 
-// Level 3 reads the dense list.
+// Level 3 reads the dense list.  (With 31 slots the compiler would keep 90 scalar registers, and past 80 or so a
+// CU takes one workgroup of 1024 threads instead of two: capped.)
 template <uint32_t SG>
-__global__ __launch_bounds__(kWideBlock) void select_pass3_kernel(const ClientParams* __restrict__ params,
+__global__ __launch_bounds__(kWideBlock) __attribute__((amdgpu_num_sgpr(64))) void select_pass3_kernel(const ClientParams* __restrict__ params,
                                                                   ClientCtl* __restrict__ ctls, Workspace ws) {
-  __shared__ SelectShared<SG> S;
+  __shared__ SelectShared<SG, 3> S;
   const uint32_t client = blockIdx.y, tid = threadIdx.x, wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
@@ -911,6 +947,7 @@ __global__ __launch_bounds__(kWideBlock) void select_pass3_kernel(const ClientPa
   const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.dense_cap;
   uint2* ties = ws.tie_list + (size_t)client * SG * kTieCap;
   uint32_t* tie_cnt = ctl->tie_cnt;
+  uint32_t* table = ws.l3_hist + (size_t)client * SG * kDigitBins;
   select_setup<3, SG>(S, ctl, nb);
 
   const uint32_t n = ctl->n_cand;
@@ -930,17 +967,20 @@ __global__ __launch_bounds__(kWideBlock) void select_pass3_kernel(const ClientPa
     for (uint32_t u = 0; u < 8; ++u) {
       const uint32_t i = base + u * kWideBlock + tid;
       if (base + u * kWideBlock + wave * kWave >= end) break;  // uniform per wavefront
-      select_count<3, SG>(S, v[u] & 0x7FFFFFFFu, i, i < end, tie_cnt, ties);
+      select_count<3, SG>(S, v[u] & 0x7FFFFFFFu, i, i < end, tie_cnt, ties, table);
     }
   }
   __syncthreads();
-  // a handful of candidates per slot share a boundary's 21-bit prefix (more only among heavy ties):
-  // the few non-empty counters are added straight to the client's table
-  const uint32_t used = S.slots.n * kDigitBins;
-  uint32_t* table = ws.l3_hist + (size_t)client * SG * kDigitBins;
-  for (uint32_t i = tid; i < used; i += kWideBlock) {
-    const uint32_t h = S.hist[i];
-    if (h) atomicAdd(&table[i], h);
+  // the slots' own digits go to the client's table now, the staged candidates to the kept-aside lists
+  if (tid < S.slots.n && S.l3_count[tid]) atomicAdd(&table[tid * kDigitBins + S.l3_digit[tid]], S.l3_count[tid]);
+  const uint32_t lane = lane_id();
+  for (uint32_t q = wave; q < S.slots.n; q += kWideWaves) {  // a wavefront per slot
+    const uint32_t n_staged = min(S.tie_n[q], kTieStage);
+    if (n_staged == 0) continue;
+    uint32_t base = kTieCap;
+    if (lane == 0) base = atomicAdd(&tie_cnt[q], n_staged);  // a count past the cap only says "too many"
+    base = __builtin_amdgcn_readlane(base, 0);
+    if (lane < n_staged && base + lane < kTieCap) ties[q * kTieCap + base + lane] = S.tie_stage[q][lane];
   }
 }
 
