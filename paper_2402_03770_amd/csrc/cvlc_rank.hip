@@ -26,9 +26,11 @@
 // the ranks.  Given a workspace with room for them (cvlc_fit_workspace_bytes_for)
 // the second pass writes those keys out, every wavefront to a stretch of its
 // own, and the third pass never happens:
-//   collect     all keys: those whose level-1 bin belongs to a class go to the
-//               wavefront's list (rows of 64 through LDS)
-//   pass<2>, walk<2>, pass<3>, walk<3>   as above, the passes reading the lists
+//   collect     (after hist1) the level-1 walk, by every workgroup for itself;
+//               all keys: those whose level-1 bin belongs to a class go to the
+//               wavefront's list (rows of 64 through LDS) and are counted on
+//               their next 9 bits (level 2)
+//   walk<2>, pass<3>, walk<3>   as above, the pass reading the lists
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -73,13 +75,13 @@ struct RankCtl {
 struct RankLayout {
   size_t status, ptrs, ctl, list_cnt, lists, total;
   size_t zero_bytes;  // [status, ptrs) and the ctl array are cleared at the start of a call
-  uint32_t blocks;    // workgroups per client in a streaming pass
+  uint32_t blocks;    // workgroups per client in the collecting pass
   uint32_t wave_cap;  // keys a wavefront's list has room for (0: no lists, three passes)
 };
 
 size_t align256(size_t v) { return (v + 255u) & ~(size_t)255u; }
 
-uint32_t pass_blocks_per_client(uint32_t d, uint32_t n);
+uint32_t pass_blocks_per_client(uint32_t d, uint32_t n, uint32_t per_cu);
 
 // d = 0: the layout without lists.  With lists, every wavefront of the collecting pass owns room for all
 // the keys it reads (whole tiles, plus the last d % 4 coordinates), so nothing has to be counted first.
@@ -94,7 +96,7 @@ RankLayout rank_layout(uint32_t n, uint32_t d) {
   L.blocks = 0;
   L.wave_cap = 0;
   if (d) {
-    L.blocks = pass_blocks_per_client(d, n);
+    L.blocks = pass_blocks_per_client(d, n, 2u);
     const uint32_t tiles = (d / 4u + kRankBlock * kDeep - 1) / (kRankBlock * kDeep);
     const uint32_t tiles_per_block = (tiles + L.blocks - 1) / L.blocks;
     L.wave_cap = tiles_per_block * (kDeep * kWave * 4u) + kWave;
@@ -249,27 +251,34 @@ __global__ __launch_bounds__(kRankBlock) void rank_pass_kernel(const float* cons
 // Ranks ascend, so their prefixes never increase: classes are runs of equal
 // prefixes.  Called by the first 32 threads of a workgroup with the new prefix
 // and inside-rank of rank `lane` (in LDS); writes the client's state.
-__device__ __forceinline__ void write_classes(RankCtl* ctl, const uint32_t* s_prefix, const uint32_t* s_rem,
-                                              uint32_t n_ranks) {
+// `ctl` may be null (nothing is written then).  Returns the number of classes; *cls_out / *opens_out: the
+// caller's rank's class and whether that rank is the first of it.
+__device__ __forceinline__ uint32_t write_classes(RankCtl* ctl, const uint32_t* s_prefix, const uint32_t* s_rem,
+                                                  uint32_t n_ranks, uint32_t* cls_out = nullptr,
+                                                  bool* opens_out = nullptr) {
   const uint32_t j = threadIdx.x;  // < 64, the first wavefront
   const bool live = j < n_ranks;
   const uint32_t mine = live ? s_prefix[j] : 0u;
   const bool opens = live && (j == 0 || s_prefix[j - 1] != mine);
   const uint64_t open_mask = __ballot(opens);
   const uint32_t c = lanes_below(open_mask) + (opens ? 1u : 0u) - 1u;  // classes opened up to and including j
-  if (live) {
+  if (live && ctl) {
     ctl->prefix[j] = mine;
     ctl->rem[j] = s_rem[j];
     ctl->cls[j] = c;
     if (opens) ctl->cls_prefix[c] = mine;
   }
-  if (j == 0) ctl->n_cls = (uint32_t)__popcll(open_mask);
+  const uint32_t n_cls = (uint32_t)__popcll(open_mask);
+  if (j == 0 && ctl) ctl->n_cls = n_cls;
+  if (cls_out) *cls_out = c;
+  if (opens_out) *opens_out = opens;
+  return n_cls;
 }
 
-__global__ __launch_bounds__(kRankBlock) void rank_walk1_kernel(RankCtl* __restrict__ ctls, RankSet ranks) {
-  __shared__ uint32_t scan_tmp[kRankWaves];
-  __shared__ uint32_t s_prefix[kRanksMax], s_rem[kRanksMax];
-  RankCtl* ctl = ctls + blockIdx.x;
+// Level 1, whole workgroup: from the client's counts of key >> 18, the bin of every rank and the rank inside it
+// (into LDS, valid after the next barrier).
+__device__ __forceinline__ void level1_walk(const RankCtl* ctl, const RankSet& ranks, uint32_t* scan_tmp,
+                                            uint32_t* s_prefix, uint32_t* s_rem) {
   // thread t owns `per` bins ending at top = kTopBins - 1 - per * t, largest keys first
   constexpr uint32_t per = kTopBins / kRankBlock;
   const uint32_t top = kTopBins - 1 - per * threadIdx.x;
@@ -295,6 +304,14 @@ __global__ __launch_bounds__(kRankBlock) void rank_walk1_kernel(RankCtl* __restr
       }
     }
   }
+}
+
+// (The three-pass path; with room for the key lists the collecting pass does this walk itself.)
+__global__ __launch_bounds__(kRankBlock) void rank_walk1_kernel(RankCtl* __restrict__ ctls, RankSet ranks) {
+  __shared__ uint32_t scan_tmp[kRankWaves];
+  __shared__ uint32_t s_prefix[kRanksMax], s_rem[kRanksMax];
+  RankCtl* ctl = ctls + blockIdx.x;
+  level1_walk(ctl, ranks, scan_tmp, s_prefix, s_rem);
   __syncthreads();
   if (threadIdx.x < kWave) write_classes(ctl, s_prefix, s_rem, ranks.n);
 }
@@ -384,19 +401,37 @@ __global__ __launch_bounds__(kRankBlock) void rank_walk_kernel(RankCtl* __restri
 // list_cnt[...] keys in no particular order.
 constexpr uint32_t kCollectStage = 512;  // keys a wavefront stages in LDS; rows of 64 leave once 256 are there
 
+//
+// Every workgroup first does the level-1 walk for itself (the counts are in L2; a launch of its own for it costs
+// more), workgroup 0 of a client also leaves the result where the later kernels look for it.  The keys it
+// collects are counted on their next 9 bits as they pass (level 2, per class, 64 KB of LDS).  With its 104 KB
+// of LDS one workgroup has a CU to itself, which suits a streaming pass (241 against 252 us with two).
 __global__ __launch_bounds__(kRankBlock) void rank_collect_kernel(const float* const* __restrict__ updates,
-                                                                  RankCtl* __restrict__ ctls, uint32_t d,
-                                                                  uint32_t* __restrict__ lists,
+                                                                  RankCtl* __restrict__ ctls, RankSet ranks,
+                                                                  uint32_t d, uint32_t* __restrict__ lists,
                                                                   uint32_t* __restrict__ list_cnt, uint32_t wave_cap) {
   __shared__ alignas(16) uint8_t first_cls[kTopBins];
   __shared__ uint32_t stage[kRankWaves][kCollectStage];
   __shared__ uint32_t s_fill[kRankWaves];  // keys a wavefront has staged
+  __shared__ uint32_t level2[kRanksMax * kSubBins];
+  __shared__ uint32_t scan_tmp[kRankWaves];
+  __shared__ uint32_t s_prefix[kRanksMax], s_rem[kRanksMax];
+  __shared__ uint32_t s_n_cls;
   RankCtl* ctl = ctls + blockIdx.y;
-  const uint32_t n_cls = ctl->n_cls;
   for (uint32_t i = threadIdx.x; i < kTopBins / 4u; i += kRankBlock)
     reinterpret_cast<uint32_t*>(first_cls)[i] = 0xFFFFFFFFu;
+  level1_walk(ctl, ranks, scan_tmp, s_prefix, s_rem);
   __syncthreads();
-  if (threadIdx.x < n_cls) first_cls[ctl->cls_prefix[threadIdx.x]] = (uint8_t)threadIdx.x;  // level-1 classes: one per bin
+  if (threadIdx.x < kWave) {
+    uint32_t c;
+    bool opens;
+    const uint32_t n = write_classes(blockIdx.x == 0 ? ctl : nullptr, s_prefix, s_rem, ranks.n, &c, &opens);
+    if (opens) first_cls[s_prefix[threadIdx.x]] = (uint8_t)c;  // level-1 classes: one per bin
+    if (threadIdx.x == 0) s_n_cls = n;
+  }
+  __syncthreads();
+  const uint32_t n_cls = s_n_cls;
+  for (uint32_t i = threadIdx.x; i < n_cls * kSubBins; i += kRankBlock) level2[i] = 0;
   __syncthreads();
   const uint32_t lane = lane_id(), wave = wave_id();
   const size_t list = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * kRankWaves + wave;
@@ -410,12 +445,18 @@ __global__ __launch_bounds__(kRankBlock) void rank_collect_kernel(const float* c
   // Class keys are few (a lane meets one in every sixteenth float4 or so): the lanes that hold some take
   // their places in the wavefront's stage with an LDS atomic; the order of the keys in a list is free.
   auto take = [&](const uint32_t* k, uint32_t n_keys, bool valid) {
-    uint32_t hit = 0;
-    for (uint32_t c = 0; c < n_keys; ++c) hit |= (first_cls[k[c] >> kTopShift] != kNoClass ? 1u : 0u) << c;
+    uint32_t hit = 0, cls[4];
+    for (uint32_t c = 0; c < n_keys; ++c) {
+      cls[c] = first_cls[k[c] >> kTopShift];
+      hit |= (cls[c] != kNoClass ? 1u : 0u) << c;
+    }
     if (valid && hit) {
       uint32_t pos = atomicAdd(&s_fill[wave], (uint32_t)__popc(hit));
       for (uint32_t c = 0; c < n_keys; ++c)
-        if ((hit >> c) & 1u) mine[pos++] = k[c];
+        if ((hit >> c) & 1u) {
+          mine[pos++] = k[c];
+          atomicAdd(&level2[cls[c] * kSubBins + ((k[c] >> kSubBits) & (kSubBins - 1u))], 1u);
+        }
     }
   };
   auto look = [&] {
@@ -472,21 +513,26 @@ __global__ __launch_bounds__(kRankBlock) void rank_collect_kernel(const float* c
   look();
   flush(true);
   if (lane == 0) list_cnt[list] = run;
+  __syncthreads();
+  for (uint32_t i = threadIdx.x; i < n_cls * kSubBins; i += kRankBlock) {
+    const uint32_t h = level2[i];
+    if (h) atomicAdd(&ctl->sub[i], h);
+  }
 }
 
-// Workgroups per client in a streaming pass: enough to fill the device twice
-// over 1024-thread workgroups, never more than there are tiles.
-uint32_t pass_blocks_per_client(uint32_t d, uint32_t n) {
-  static int resident = 0;
-  if (resident == 0) {
-    int dev = 0, cus = 0;
-    resident = 512;
+// Workgroups per client in a streaming pass: per_cu 1024-thread workgroups on every CU, never more than
+// there are tiles.
+uint32_t pass_blocks_per_client(uint32_t d, uint32_t n, uint32_t per_cu) {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, found = 0;
+    cus = 256;
     if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-      resident = 2 * cus;
+        hipDeviceGetAttribute(&found, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && found > 0)
+      cus = found;
   }
   const uint32_t tiles = (d / 4u + kRankBlock * kDeep - 1) / (kRankBlock * kDeep);
-  uint32_t b = ((uint32_t)resident + n - 1) / n;
+  uint32_t b = ((uint32_t)cus * per_cu + n - 1) / n;
   if (b > tiles) b = tiles;
   return b < 1 ? 1u : b;
 }
@@ -548,9 +594,8 @@ int cvlc_fit_alpha(uint32_t n, const float* const* d_updates, uint32_t d, double
                          reinterpret_cast<uint4*>(base), zero_n16);
     }
   }
-  const dim3 pass_grid(pass_blocks_per_client(d, n), n);
+  const dim3 pass_grid(pass_blocks_per_client(d, n, 2u), n);
   hipLaunchKernelGGL(rank_hist1_kernel, pass_grid, dim3(kRankBlock), 0, stream, ptrs, ctls, d, status);
-  hipLaunchKernelGGL(rank_walk1_kernel, dim3(n), dim3(kRankBlock), 0, stream, ctls, ranks);
   KeyLists kl = {nullptr, nullptr, 0u, 0u};
   if (L.wave_cap) {  // two passes: the keys of the class bins are set aside, levels 2 and 3 count among those
     uint32_t* lists = reinterpret_cast<uint32_t*>(base + L.lists);
@@ -559,17 +604,17 @@ int cvlc_fit_alpha(uint32_t n, const float* const* d_updates, uint32_t d, double
     kl.list_cnt = list_cnt;
     kl.per_client = L.blocks * kRankWaves;
     kl.wave_cap = L.wave_cap;
-    hipLaunchKernelGGL(rank_collect_kernel, pass_grid, dim3(kRankBlock), 0, stream, ptrs, ctls, d, lists, list_cnt,
-                       L.wave_cap);
+    hipLaunchKernelGGL(rank_collect_kernel, dim3(L.blocks, n), dim3(kRankBlock), 0, stream, ptrs, ctls, ranks, d, lists,
+                       list_cnt, L.wave_cap);
     // a few workgroups per client: their cost is clearing and adding up the counters, not reading the keys
-    const dim3 list_grid(L.blocks < 16u ? L.blocks : 16u, n), list_grid2(L.blocks < 8u ? L.blocks : 8u, n);
-    hipLaunchKernelGGL((rank_pass_kernel<2, true>), list_grid2, dim3(kRankBlock), 0, stream, ptrs, ctls, d, kl);
+    const dim3 list_grid(L.blocks < 16u ? L.blocks : 16u, n);
     hipLaunchKernelGGL(rank_walk_kernel<2>, dim3(n), dim3(kRankBlock), 0, stream, ctls, ranks, (uint32_t*)nullptr,
                        (double*)nullptr);
     hipLaunchKernelGGL((rank_pass_kernel<3, true>), list_grid, dim3(kRankBlock), 0, stream, ptrs, ctls, d, kl);
     hipLaunchKernelGGL(rank_walk_kernel<3>, dim3(n), dim3(kRankBlock), 0, stream, ctls, ranks, d_keys_out, d_alpha_out);
     return hip_check(hipGetLastError());
   }
+  hipLaunchKernelGGL(rank_walk1_kernel, dim3(n), dim3(kRankBlock), 0, stream, ctls, ranks);
   hipLaunchKernelGGL((rank_pass_kernel<2, false>), pass_grid, dim3(kRankBlock), 0, stream, ptrs, ctls, d, kl);
   hipLaunchKernelGGL(rank_walk_kernel<2>, dim3(n), dim3(kRankBlock), 0, stream, ctls, ranks, (uint32_t*)nullptr,
                      (double*)nullptr);
