@@ -798,6 +798,13 @@ __device__ __forceinline__ SpanWindow span_window(const CandView& cv, uint32_t s
   return w;
 }
 
+// A span that lies in a stretch of nearly empty regions crosses hundreds of runs (it has 512 candidates, so up
+// to 512 of them): walking those one by one, a memory round trip per 63, made single wavefronts the last to
+// finish by far.  So: few runs inside the window (the rule) are walked one by one; many are searched by every
+// row at once (the window's 64 offsets ascend: six shuffle steps); the window after is asked for before
+// the current one is worked on.
+constexpr uint32_t kSerialRuns = 8;
+
 __device__ __forceinline__ void span_slots(const CandView& cv, uint32_t span, const SpanWindow& win,
                                            uint32_t (&slot)[kPerLane]) {
   const uint32_t lane = lane_id();
@@ -809,21 +816,43 @@ __device__ __forceinline__ void span_slots(const CandView& cv, uint32_t span, co
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) slot[j] = shift0;
   while (true) {
-    uint32_t t = 1;
-    for (; t < kWave; ++t) {
-      const uint32_t ot = __builtin_amdgcn_readlane(wo, t);
-      if (ot >= end) break;
-      const uint32_t shift = __builtin_amdgcn_readlane(wr, t) * kRegion - ot;
+    // entries 1..m of the window start inside the span (offsets ascend strictly; the entry after the last run holds n >= end)
+    const uint32_t m = (uint32_t)__popcll(__ballot(wo < end) & ~1ull);
+    const bool more = m == kWave - 1u;  // the window's last entry still starts inside: look at the next window too
+    uint32_t nwo = 0, nwr = 0;
+    if (more) {  // uniform
+      nwo = cv.nz_off[min(base + (kWave - 1u) + lane, cv.n_nz)];
+      nwr = cv.nz_run[min(base + (kWave - 1u) + lane, cv.n_nz)];
+    }
+    if (m <= kSerialRuns) {
+      for (uint32_t t = 1; t <= m; ++t) {
+        const uint32_t ot = __builtin_amdgcn_readlane(wo, t);
+        const uint32_t shift = __builtin_amdgcn_readlane(wr, t) * kRegion - ot;
+#pragma unroll
+        for (uint32_t j = 0; j < kPerLane; ++j) {
+          const uint32_t i = begin + j * kWave + lane;
+          if (i >= ot) slot[j] = shift;
+        }
+      }
+    } else {
+      const uint32_t first_here = __builtin_amdgcn_readlane(wo, 1);  // rows before it keep what they have
 #pragma unroll
       for (uint32_t j = 0; j < kPerLane; ++j) {
         const uint32_t i = begin + j * kWave + lane;
-        if (i >= ot) slot[j] = shift;
+        uint32_t pos = 0;  // last entry in 0..m whose offset is <= i
+#pragma unroll
+        for (uint32_t step = kWave / 2u; step; step >>= 1) {
+          const uint32_t probe = (uint32_t)__shfl((int)wo, (int)min(pos + step, kWave - 1u), kWave);
+          if (pos + step <= m && probe <= i) pos += step;
+        }
+        const uint32_t ro = (uint32_t)__shfl((int)wo, (int)pos, kWave), rr = (uint32_t)__shfl((int)wr, (int)pos, kWave);
+        if (i >= first_here) slot[j] = rr * kRegion - ro;
       }
     }
-    if (t < kWave) break;
+    if (!more) break;
     base += kWave - 1;  // entry 63 of this window is entry 0 of the next
-    wo = cv.nz_off[min(base + lane, cv.n_nz)];
-    wr = cv.nz_run[min(base + lane, cv.n_nz)];
+    wo = nwo;
+    wr = nwr;
   }
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) slot[j] += begin + j * kWave + lane;  // meaningless for i >= n, never used there

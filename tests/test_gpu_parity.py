@@ -340,6 +340,24 @@ def test_workspace_sized_to_the_candidates():
         run(host, cv.encode_workspace_bytes_for(d, n, k_max // 2))
 
 
+def test_candidates_spread_thinly_over_many_regions():
+    """Stretches where the encoder's 8192-coordinate regions keep one or two coordinates each: a span of 512
+    candidates then crosses hundreds of runs (several windows of 64 run offsets), next to a dense stretch
+    where it crosses one."""
+    d = 6_000_000
+    rng = np.random.default_rng(17)
+    U = (rng.standard_normal(d) * 1e-5).astype(np.float32)
+    thin = np.arange(0, 3_600_000, 8192) + rng.integers(0, 8192, size=440)       # one large value per region
+    U[thin] = (rng.standard_normal(thin.size) * 3.0 + np.sign(rng.standard_normal(thin.size)) * 5.0).astype(np.float32)
+    twice = np.arange(100, 1_600_000, 8192 * 2) + 4096                           # and a second one in every other
+    U[twice] = (rng.standard_normal(twice.size) * 2.0 + 6.0).astype(np.float32)
+    U[4_000_000:4_030_000] = (rng.standard_normal(30_000) * 4.0).astype(np.float32)   # the dense stretch
+    U[5_999_000:] = (rng.standard_normal(1000) * 4.0).astype(np.float32)
+    p = orc.plan_manual(d, [10, 6, 3, 1], [300, 700, 9_000, 20_000])
+    refs, _ = check_encode([U, U[::-1].copy()], [p, p], 31, [0, 1])
+    check_decode(refs, d)
+
+
 def test_values_rounded_to_few_mantissa_bits():
     """Updates that were computed in a very short format: thousands of coordinates share each
     magnitude, so every boundary cuts through a large class of equal keys."""
