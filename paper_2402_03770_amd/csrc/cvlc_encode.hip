@@ -1195,6 +1195,7 @@ struct Thresholds {  // group boundaries in LDS
   uint32_t tau[32];
   uint32_t iota[32];
   uint32_t cut[32];  // key < cut[r]  <=>  key <= tau[r] for r < R; 0 (never) for r >= R
+  uint32_t above[33];  // the boundary key just above group g: tau[g - 1]; no key (all ones) above group 0
 };
 
 __device__ __forceinline__ void load_thresholds(Thresholds& t, const ClientCtl* ctl, uint32_t R) {
@@ -1204,6 +1205,8 @@ __device__ __forceinline__ void load_thresholds(Thresholds& t, const ClientCtl* 
     t.tau[threadIdx.x] = tau;
     t.iota[threadIdx.x] = live ? ctl->iota[threadIdx.x] : 0u;
     t.cut[threadIdx.x] = live ? (tau == 0xFFFFFFFFu ? tau : tau + 1u) : 0u;  // keys stay below 2^31
+    t.above[threadIdx.x + 1] = tau;
+    if (threadIdx.x == 0) t.above[0] = 0xFFFFFFFFu;
   }
 }
 
@@ -1221,8 +1224,11 @@ __device__ __forceinline__ void classify_keys(const Thresholds& t, uint32_t R, c
   for (uint32_t j = 0; j < N; ++j) grp[j] = 0;
   // largest power of two <= R: the probes reach entry 2 * top - 2 <= 30 at most, the result 2 * top - 1 >= R
   for (uint32_t step = R ? 1u << (31 - __builtin_clz(R)) : 0u; step; step >>= 1) {
+    uint32_t probe[N];  // all N reads of a step before the first comparison: one LDS round trip per step
 #pragma unroll
-    for (uint32_t j = 0; j < N; ++j) grp[j] += key[j] < t.cut[grp[j] + step - 1u] ? step : 0u;
+    for (uint32_t j = 0; j < N; ++j) probe[j] = t.cut[grp[j] + step - 1u];
+#pragma unroll
+    for (uint32_t j = 0; j < N; ++j) grp[j] += key[j] < probe[j] ? step : 0u;
   }
 }
 
@@ -1234,16 +1240,22 @@ __device__ __forceinline__ uint32_t classify_tie(const Thresholds& t, uint32_t k
   return g;
 }
 
-// Lanes that hold a candidate of the caller's group (5-bit group id); lanes
+// Lanes that hold a candidate of the caller's group (group ids below 2^ID_BITS); lanes
 // with g == kNoGroup match nobody.  Must be reached by the whole wavefront.
+// Per bit of the id: the lanes that have it set, against an all-ones / all-zeros word of the
+// caller's own bit; what differs in any bit is not the caller's group.
+template <uint32_t ID_BITS>
 __device__ __forceinline__ uint64_t same_group_lanes(uint32_t g) {
-  uint64_t same = __ballot(g != kNoGroup);
+  const uint64_t coded = __ballot(g != kNoGroup);
+  uint32_t differ_lo = 0, differ_hi = 0;
 #pragma unroll
-  for (int bit = 0; bit < 5; ++bit) {
-    const uint64_t set = __ballot((g >> bit) & 1u);
-    same &= ((g >> bit) & 1u) ? set : ~set;
+  for (uint32_t bit = 0; bit < ID_BITS; ++bit) {
+    const uint32_t mine = (uint32_t)__builtin_amdgcn_sbfe((int32_t)g, bit, 1u);  // the bit, sign-extended
+    const uint64_t set = __ballot(mine != 0u);
+    differ_lo |= (uint32_t)set ^ mine;
+    differ_hi |= (uint32_t)(set >> 32) ^ mine;
   }
-  return same;
+  return coded & ~(((uint64_t)differ_hi << 32) | differ_lo);
 }
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
@@ -1270,10 +1282,17 @@ __device__ __forceinline__ void classify_span(const Thresholds& thr, uint32_t R,
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) key[j] = v[j] & 0x7FFFFFFFu;
   classify_keys<kPerLane>(thr, R, key, grp);
+  // the boundary key just above every candidate's group, all eight read before the first is looked at:
+  // only a key that equals it (next to none) goes on to the tie rule
+  uint32_t above[kPerLane];
+#pragma unroll
+  for (uint32_t j = 0; j < kPerLane; ++j) above[j] = thr.above[grp[j]];
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) {
     const uint32_t i = mine + j * kWave;
-    grp[j] = i < n ? classify_tie(thr, key[j], grp[j], i) : kNoGroup;
+    uint32_t g = grp[j];
+    if (above[j] == key[j]) g = classify_tie(thr, key[j], g, i);
+    grp[j] = i < n ? g : kNoGroup;
   }
 }
 
@@ -1605,6 +1624,11 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
 }
 
 // ------------------------------------------------------------------ 8. emit: quantise + pack
+// a ^ b ^ c in one instruction (three-operand bitwise op with the truth table of the parity).
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 // Philox4x32-10 (Salmon et al., SC'11), first output word.
 __device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1) {
   uint32_t c2 = 0, c3 = 0;
@@ -1613,9 +1637,9 @@ __device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint3
     const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
     const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
     const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
-    c0 = hi1 ^ c1 ^ k0;
+    c0 = xor3(hi1, c1, k0);
     c1 = lo1;
-    c2 = hi0 ^ c3 ^ k1;
+    c2 = xor3(hi0, c3, k1);
     c3 = lo0;
     k0 += 0x9E3779B9u;
     k1 += 0xBB67AE85u;
@@ -1753,25 +1777,42 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
   for (uint32_t i = tid; i < staged; i += kEmitBlock) s_stage[i] = 0;
 
   uint32_t v[kPerLane], grp[kPerLane], pid[kPerLane];
-  classify_span(thr, R, val, n, c * kChunkSpans + wave, v, grp);
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) {  // unconditional, so that the loads overlap
     const uint32_t i = (c * kChunkSpans + wave) * kSpan + j * kWave + lane;
     pid[j] = idx[min(i, n - 1u)];
   }
+  classify_span(thr, R, val, n, c * kChunkSpans + wave, v, grp);
   __syncthreads();
-  uint32_t* wrun = s_wrun[wave];  // touched by this wavefront only; its LDS accesses complete in order
+  // Record numbers of all eight rows first.  A row's members of a group read the group's running number
+  // and the lowest of them adds the row's members to it; this wavefront alone touches the counters and its
+  // LDS accesses complete in the order they are issued, so no row waits for the one before.
+  uint32_t* wrun = s_wrun[wave];
+  uint32_t start[kPerLane];
+  auto number_rows = [&](auto id_bits) {
+#pragma unroll
+    for (uint32_t j = 0; j < kPerLane; ++j) {
+      const uint32_t g = grp[j] < R ? grp[j] : kNoGroup;  // dropped candidates take no record
+      const uint64_t same = same_group_lanes<decltype(id_bits)::value>(g);
+      const uint32_t below = lanes_below(same);
+      start[j] = 0;
+      grp[j] = kNoGroup;
+      if (g != kNoGroup) {
+        grp[j] = g | (below << 8);  // the group and the members of the row in lower lanes
+        start[j] = wrun[g];
+        if (below == 0) atomicAdd(&wrun[g], (uint32_t)__popcll(same));
+      }
+      asm volatile("" ::: "memory");  // the rows' LDS accesses stay in this order; nothing to wait for
+    }
+  };
+  if (R <= 8u) number_rows(std::integral_constant<uint32_t, 3>());        // group ids 0 .. R - 1
+  else if (R <= 16u) number_rows(std::integral_constant<uint32_t, 4>());
+  else number_rows(std::integral_constant<uint32_t, 5>());
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) {
-    const uint32_t g = grp[j] < R ? grp[j] : kNoGroup;  // dropped candidates take no record
-    const uint64_t same = same_group_lanes(g);
-    uint32_t start = 0;
-    if (g != kNoGroup) start = wrun[g];
-    wave_lds_fence();
-    if (g != kNoGroup && lane == (uint32_t)__builtin_ctzll(same)) wrun[g] = start + (uint32_t)__popcll(same);
-    wave_lds_fence();
-    if (g != kNoGroup) {
-      const uint32_t e = start + lanes_below(same);
+    if (grp[j] != kNoGroup) {
+      const uint32_t g = grp[j] & 0xFFu;
+      const uint32_t e = start[j] + (grp[j] >> 8);
       const EmitGroup eg = s_grp[g];
       if (e < eg.lim) {
         const uint32_t y = eg.y, W = eg.W;
