@@ -1852,12 +1852,15 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
     }
   }
   __syncthreads();
-  // group by group (the loop bounds are uniform), thread t the t-th, t+512-th, ... word of the group's run
-  for (uint32_t g = 0; g < R; ++g) {
+  // A wavefront writes whole groups' runs, lane l the l-th, l+64-th, ... word.  The groups grow with their
+  // number, so they are dealt out going up and coming down in turn (wavefront w: w, 15 - w, 16 + w, 31 - w).
+  for (uint32_t k = 0; k * kEmitWaves < R; ++k) {
+    const uint32_t g = k * kEmitWaves + ((k & 1u) ? kEmitWaves - 1u - wave : wave);
+    if (g >= R) continue;  // uniform per wavefront
     const uint32_t nwords = s_nwords[g];
     const uint32_t* staged_words = s_stage + s_stage_off[g];
     GlobalWordPtr dst = stream + s_payload[g] + s_word0[g];
-    for (uint32_t rel = tid; rel < nwords; rel += kEmitBlock) {
+    for (uint32_t rel = lane; rel < nwords; rel += kWave) {
       const uint32_t word = staged_words[rel];
       if (rel == 0 || rel == nwords - 1) {
         if (word) atomicOr((uint32_t*)(dst + rel), word);
