@@ -1852,8 +1852,10 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
     }
   }
   __syncthreads();
-  // A wavefront writes whole groups' runs, lane l the l-th, l+64-th, ... word.  The groups grow with their
-  // number, so they are dealt out going up and coming down in turn (wavefront w: w, 15 - w, 16 + w, 31 - w).
+  // A wavefront writes whole groups' runs, lane l the l-th, l+64-th, ... word (with all 512 threads on one
+  // group after the other most lanes had nothing to write in every group).  A group's size changes steadily
+  // with its number, so the groups are dealt out going up and coming down in turn (wavefront w: w, 15 - w,
+  // 16 + w, 31 - w).
   for (uint32_t k = 0; k * kEmitWaves < R; ++k) {
     const uint32_t g = k * kEmitWaves + ((k & 1u) ? kEmitWaves - 1u - wave : wave);
     if (g >= R) continue;  // uniform per wavefront
