@@ -1668,6 +1668,7 @@ __device__ __forceinline__ uint32_t quantise(float x, float m, float inv, uint32
 
 
 constexpr uint32_t kChunkCands = kSpan * kChunkSpans;         // 4096
+constexpr uint32_t kEdgeChunks = 8;                           // chunks whose shared stream words a workgroup holds back
 constexpr uint32_t kStageWords = kChunkCands * 2 + 2 * 32;    // every record is < 64 bits; two edge words per group
 
 struct alignas(16) EmitGroup {  // per (chunk, group)
@@ -1702,6 +1703,12 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
   __shared__ uint32_t s_nwords[32];                // words the chunk touches in each group
   __shared__ uint32_t s_stage_off[33];
   __shared__ uint32_t s_payload[32];
+  // The first and the last word of a (chunk, group) run can be shared with a neighbouring chunk and are
+  // OR-ed into the stream by device-wide atomics.  Whatever the wavefront loads next waits for their
+  // acknowledgement (the counter of outstanding memory operations does not tell loads from atomics), so
+  // they are held back, kEdgeChunks chunks' worth, and issued together.
+  __shared__ uint32_t s_edge_word[kEdgeChunks][32][2];  // the bits; 0: nothing to OR
+  __shared__ uint32_t s_edge_at[kEdgeChunks][32][2];    // the stream word they belong to
   const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
@@ -1730,6 +1737,14 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
   }
   const double inv_B = ERR ? 1.0 / (double)p.B : 0.0;  // the scaling operation of Sec. IV-B
   if (ERR && lane < 32) s_err[wave][lane] = 0.0;       // touched by this wavefront only until the end
+  for (uint32_t i = tid; i < kEdgeChunks * 64u; i += kEmitBlock) (&s_edge_word[0][0][0])[i] = 0;  // groups past R stay 0
+  uint32_t held = 0;  // chunks whose edge words are held back
+  auto release_edges = [&]() {  // by the whole workgroup, after a barrier
+    for (uint32_t i = tid; i < held * 64u; i += kEmitBlock) {
+      const uint32_t word = (&s_edge_word[0][0][0])[i];
+      if (word) atomicOr((uint32_t*)(stream + (&s_edge_at[0][0][0])[i]), word);
+    }
+  };
   for (uint32_t c = blockIdx.x; c * kChunkSpans < n_spans; c += gridDim.x) {
   __syncthreads();  // the chunk before is written out
   {  // every wavefront: the record numbers its span starts at
@@ -1861,17 +1876,28 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
     if (g >= R) continue;  // uniform per wavefront
     const uint32_t nwords = s_nwords[g];
     const uint32_t* staged_words = s_stage + s_stage_off[g];
-    GlobalWordPtr dst = stream + s_payload[g] + s_word0[g];
+    const uint32_t first_word = s_payload[g] + s_word0[g];
+    GlobalWordPtr dst = stream + first_word;
+    if (lane < 2) s_edge_word[held][g][lane] = 0;  // (this wavefront's LDS accesses complete in order)
     for (uint32_t rel = lane; rel < nwords; rel += kWave) {
       const uint32_t word = staged_words[rel];
       if (rel == 0 || rel == nwords - 1) {
-        if (word) atomicOr((uint32_t*)(dst + rel), word);
+        const uint32_t which = rel == 0 ? 0u : 1u;
+        s_edge_word[held][g][which] = word;
+        s_edge_at[held][g][which] = first_word + rel;
       } else {
         dst[rel] = word;
       }
     }
   }
+  if (++held == kEdgeChunks) {  // uniform
+    __syncthreads();
+    release_edges();
+    held = 0;
+  }
   }  // chunks
+  __syncthreads();
+  release_edges();
   if (ERR) {
     __syncthreads();
     if (tid < R) {
