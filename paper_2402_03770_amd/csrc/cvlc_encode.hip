@@ -1264,21 +1264,21 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
   return v;
 }
 
-// Loads span `span` of the dense list (kPerLane candidates per lane, row j at
-// span*512 + j*64 + lane, i.e. in position order) and classifies them.
-// grp[j] = kNoGroup past the end of the list.
-__device__ __forceinline__ void classify_span(const Thresholds& thr, uint32_t R, const uint32_t* __restrict__ val,
-                                              uint32_t n, uint32_t span, uint32_t (&v)[kPerLane],
-                                              uint32_t (&grp)[kPerLane]) {
+// Loads span `span` of a dense list (kPerLane entries per lane, row j at
+// span*512 + j*64 + lane, i.e. in position order).  No branch around the loads (a lane past
+// the end reads the last entry again): all eight are in flight before the first is waited for.
+__device__ __forceinline__ void load_span(const uint32_t* __restrict__ list, uint32_t n, uint32_t span,
+                                          uint32_t (&out)[kPerLane]) {
+  const uint32_t mine = span * kSpan + lane_id();
+#pragma unroll
+  for (uint32_t j = 0; j < kPerLane; ++j) out[j] = list[min(mine + j * kWave, n - 1u)];
+}
+
+// Classifies the loaded value bits of span `span`; grp[j] = kNoGroup past the end of the list.
+__device__ __forceinline__ void classify_loaded(const Thresholds& thr, uint32_t R, uint32_t n, uint32_t span,
+                                                const uint32_t (&v)[kPerLane], uint32_t (&grp)[kPerLane]) {
   const uint32_t mine = span * kSpan + lane_id();
   uint32_t key[kPerLane];
-  // no branch around the loads (a lane past the end reads the last candidate again): all eight are in
-  // flight before the first is waited for
-#pragma unroll
-  for (uint32_t j = 0; j < kPerLane; ++j) {
-    const uint32_t i = mine + j * kWave;
-    v[j] = val[min(i, n - 1u)];
-  }
 #pragma unroll
   for (uint32_t j = 0; j < kPerLane; ++j) key[j] = v[j] & 0x7FFFFFFFu;
   classify_keys<kPerLane>(thr, R, key, grp);
@@ -1294,6 +1294,13 @@ __device__ __forceinline__ void classify_span(const Thresholds& thr, uint32_t R,
     if (above[j] == key[j]) g = classify_tie(thr, key[j], g, i);
     grp[j] = i < n ? g : kNoGroup;
   }
+}
+
+__device__ __forceinline__ void classify_span(const Thresholds& thr, uint32_t R, const uint32_t* __restrict__ val,
+                                              uint32_t n, uint32_t span, uint32_t (&v)[kPerLane],
+                                              uint32_t (&grp)[kPerLane]) {
+  load_span(val, n, span, v);
+  classify_loaded(thr, R, n, span, v, grp);
 }
 
 // ------------------------------------------------------------------ 6. group counts and statistics
@@ -1746,11 +1753,24 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
     }
   };
   for (uint32_t c = blockIdx.x; c * kChunkSpans < n_spans; c += gridDim.x) {
-  __syncthreads();  // the chunk before is written out
-  {  // every wavefront: the record numbers its span starts at
+  // Everything the chunk reads from memory is asked for here, what the tables need first (memory
+  // operations of a wavefront complete in the order they were issued): the record numbers the wavefront's
+  // span starts at, the chunk's record runs, then the span's candidates.
+  uint32_t span_row = 0, run_first = 0, run_last = 0;
+  {
     const uint32_t span = c * kChunkSpans + wave;
-    if (lane < 32) s_wrun[wave][lane] = span < n_spans ? prefix[(size_t)span * 32 + lane] : 0u;
+    if (lane < 32 && span < n_spans) span_row = prefix[(size_t)span * 32 + lane];
+    if (tid < 32 && tid < R) {
+      const uint32_t last_span = min((c + 1) * kChunkSpans, n_spans);
+      run_first = prefix[(size_t)c * kChunkSpans * 32 + tid];
+      run_last = prefix[(size_t)last_span * 32 + tid];
+    }
   }
+  uint32_t v[kPerLane], grp[kPerLane], pid[kPerLane];
+  load_span(val, n, c * kChunkSpans + wave, v);
+  load_span(idx, n, c * kChunkSpans + wave, pid);
+  __syncthreads();  // the chunk before is written out
+  if (lane < 32) s_wrun[wave][lane] = span_row;  // every wavefront: the record numbers its span starts at
   if (tid < 32) {
     const uint32_t r = tid;
     uint32_t nwords = 0, W = 0, first = 0, last = 0, bit_in_word = 0;
@@ -1759,9 +1779,8 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
       W = my_W;
       // the chunk's record run of group r: [first, last), clamped so that every write stays inside
       // the group's payload even if an internal check has failed
-      const uint32_t last_span = min((c + 1) * kChunkSpans, n_spans);
-      first = prefix[(size_t)c * kChunkSpans * 32 + r];
-      last = prefix[(size_t)last_span * 32 + r];
+      first = run_first;
+      last = run_last;
       if (last > P) last = P;
       if (first > last) first = last;
       if (last > first) {
@@ -1791,13 +1810,7 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
   const uint32_t staged = s_stage_off[32];
   for (uint32_t i = tid; i < staged; i += kEmitBlock) s_stage[i] = 0;
 
-  uint32_t v[kPerLane], grp[kPerLane], pid[kPerLane];
-#pragma unroll
-  for (uint32_t j = 0; j < kPerLane; ++j) {  // unconditional, so that the loads overlap
-    const uint32_t i = (c * kChunkSpans + wave) * kSpan + j * kWave + lane;
-    pid[j] = idx[min(i, n - 1u)];
-  }
-  classify_span(thr, R, val, n, c * kChunkSpans + wave, v, grp);
+  classify_loaded(thr, R, n, c * kChunkSpans + wave, v, grp);
   __syncthreads();
   // Record numbers of all eight rows first.  A row's members of a group read the group's running number
   // and the lowest of them adds the row's members to it; this wavefront alone touches the counters and its
