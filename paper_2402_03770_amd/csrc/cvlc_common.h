@@ -62,6 +62,7 @@ struct ClientCtl {
   uint32_t n_nz;             // regions that kept at least one coordinate
   uint32_t dead;             // 1: more candidates than the workspace has room for; nothing further is done for the client
   uint32_t claim;            // regions of the filter's claimed part taken so far
+  uint32_t emit_claim;       // chunks of the packing pass taken beyond every workgroup's first
   double seg_sumsq[32];      // energy of every coded group; entry R: candidates below the last boundary (atomic)
   uint32_t tie_cnt[32];      // kept-aside class members per histogram slot
   uint32_t sel_prefix[2][32];  // key prefix of boundary r after level 1 (11 bits) and level 2 (21 bits); 0xFFFFFFFF: Z_r = 0

@@ -1264,9 +1264,9 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
   return v;
 }
 
-// Loads span `span` of a dense list (kPerLane entries per lane, row j at
+// Loads span `span` of the dense list (kPerLane candidates per lane, row j at
 // span*512 + j*64 + lane, i.e. in position order).  No branch around the loads (a lane past
-// the end reads the last entry again): all eight are in flight before the first is waited for.
+// the end reads the last candidate again): all eight are in flight before the first is waited for.
 __device__ __forceinline__ void load_span(const uint32_t* __restrict__ list, uint32_t n, uint32_t span,
                                           uint32_t (&out)[kPerLane]) {
   const uint32_t mine = span * kSpan + lane_id();
@@ -1296,13 +1296,6 @@ __device__ __forceinline__ void classify_loaded(const Thresholds& thr, uint32_t 
   }
 }
 
-__device__ __forceinline__ void classify_span(const Thresholds& thr, uint32_t R, const uint32_t* __restrict__ val,
-                                              uint32_t n, uint32_t span, uint32_t (&v)[kPerLane],
-                                              uint32_t (&grp)[kPerLane]) {
-  load_span(val, n, span, v);
-  classify_loaded(thr, R, n, span, v, grp);
-}
-
 // ------------------------------------------------------------------ 6. group counts and statistics
 // QSGD's header carries the group's l2-norm, and the stream must not depend on
 // the order squares are added in: the sum of squares is kept exactly, as a
@@ -1324,6 +1317,16 @@ __device__ __forceinline__ SquareLimbs square_limbs(uint32_t value_bits) {
   r.part[1] = (uint32_t)(low >> 32);
   r.part[2] = sh ? (uint32_t)(sq >> (64u - sh)) : 0u;
   return r;
+}
+
+// What the counting pass leaves for the packing pass, 16 bits per candidate of the dense list: its group
+// (5 bits) and above it its number among the members of that group in its span of 512 (9 bits); kNoPlace
+// for a dropped candidate.  The array takes the place of the filter's region-slot positions, which nothing
+// reads once the gather has run (d entries per client, the dense list has at most as many).
+constexpr uint32_t kPlaceShift = 5;
+constexpr uint16_t kNoPlace = 0xFFFFu;
+__device__ __forceinline__ uint16_t* span_places(const Workspace& ws, uint32_t client) {
+  return ws.cand_idx + (size_t)client * ws.d;
 }
 
 constexpr uint32_t kLimbBanks = 2;  // copies of a workgroup's limb counters, to thin out colliding LDS atomics
@@ -1361,17 +1364,48 @@ __global__ __launch_bounds__(kEmitBlock) void count_kernel(const ClientParams* _
   if (QSGD)
     for (uint32_t i = tid; i < kLimbBanks * 32 * kNormLimbs; i += kEmitBlock) (&s_limb[0][0][0])[i] = 0;
   __syncthreads();
-  for (uint32_t span = blockIdx.x * kEmitWaves + wave; span < n_spans; span += gridDim.x * kEmitWaves) {
+  uint16_t* __restrict__ place = span_places(ws, client);
+  uint32_t* running = s_cnt[wave];  // members of every group (the dropped ones last) in the rows so far
+  const uint32_t span_step = gridDim.x * kEmitWaves;
+  uint32_t ahead[kPerLane];  // the next span's value bits, asked for before the current span is worked on
+  if (blockIdx.x * kEmitWaves + wave < n_spans) load_span(val, n, blockIdx.x * kEmitWaves + wave, ahead);
+  for (uint32_t span = blockIdx.x * kEmitWaves + wave; span < n_spans; span += span_step) {
     uint32_t v[kPerLane], grp[kPerLane];
-    classify_span(thr, R, val, n, span, v, grp);
-    // the span's size of every group, counted in a row of LDS words private to the wavefront
 #pragma unroll
-    for (uint32_t j = 0; j < kPerLane; ++j)
-      if (grp[j] != kNoGroup) atomicAdd(&s_cnt[wave][grp[j]], 1u);
+    for (uint32_t j = 0; j < kPerLane; ++j) v[j] = ahead[j];
+    if (span + span_step < n_spans) load_span(val, n, span + span_step, ahead);
+    classify_loaded(thr, R, n, span, v, grp);
+    // Every candidate's number among the span's members of its group (row after row, lanes in order): a
+    // row's members of a group read the group's running number and the lowest of them adds the row's
+    // members to it.  This wavefront alone touches the counters and its LDS accesses complete in the order
+    // they are issued, so no row waits for the one before.  What the counters hold after the last row are
+    // the span's group sizes.
+    uint32_t start[kPerLane], below[kPerLane];
+    auto number_rows = [&](auto id_bits) {
+#pragma unroll
+      for (uint32_t j = 0; j < kPerLane; ++j) {
+        const uint64_t same = same_group_lanes<decltype(id_bits)::value>(grp[j]);
+        below[j] = lanes_below(same);
+        start[j] = 0;
+        if (grp[j] != kNoGroup) {
+          start[j] = running[grp[j]];
+          if (below[j] == 0) atomicAdd(&running[grp[j]], (uint32_t)__popcll(same));
+        }
+        asm volatile("" ::: "memory");  // the rows' LDS accesses stay in this order; nothing to wait for
+      }
+    };
+    if (R < 8u) number_rows(std::integral_constant<uint32_t, 3>());  // ids 0 .. R, R for the dropped
+    else if (R < 16u) number_rows(std::integral_constant<uint32_t, 4>());
+    else number_rows(std::integral_constant<uint32_t, 5>());
+#pragma unroll
+    for (uint32_t j = 0; j < kPerLane; ++j) {
+      const uint32_t i = span * kSpan + j * kWave + lane;
+      if (i < n) place[i] = grp[j] < R ? (uint16_t)(grp[j] | ((start[j] + below[j]) << kPlaceShift)) : kNoPlace;
+    }
     wave_lds_fence();
     if (lane < 32) {
-      span_cnt[(size_t)span * 32 + lane] = s_cnt[wave][lane];
-      s_cnt[wave][lane] = 0;
+      span_cnt[(size_t)span * 32 + lane] = running[lane];
+      running[lane] = 0;
     }
     wave_lds_fence();
 #pragma unroll
@@ -1688,11 +1722,11 @@ struct alignas(16) EmitGroup {  // per (chunk, group)
 
 // One workgroup per chunk of 4096 candidates, one wavefront per span.  Every
 // coded candidate gets its record number inside its group (members in earlier
-// spans from the layout's prefix, then earlier rows, then lower lanes), is
-// quantised and OR-ed into an LDS image of the stream words its group's run
-// covers.  The image is then written out: a group's first and last word can be
-// shared with a neighbouring chunk and are OR-ed into the (cleared) stream, all
-// others are stored whole.
+// spans from the layout's prefix, plus its number inside the span, which the
+// counting pass left with its group in 16 bits), is quantised and OR-ed into an
+// LDS image of the stream words its group's run covers.  The image is then
+// written out: a group's first and last word can be shared with a neighbouring
+// chunk and are OR-ed into the (cleared) stream, all others are stored whole.
 // ERR: every record also adds (xtilde / B - x)^2 to its group's error energy in
 // the statistics block (Lemma 1's left side for this draw), xtilde being the
 // centroid value the decoder will compute from the header.
@@ -1701,22 +1735,27 @@ template <bool ERR, bool QSGD>
 __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams* __restrict__ params,
                                                           ClientCtl* __restrict__ ctls, Workspace ws, uint64_t seed,
                                                           cvlc_seg_stats_t* __restrict__ stats_out) {
-  __shared__ Thresholds thr;
   __shared__ double s_err[ERR ? kEmitWaves : 1][32];  // per wavefront, per group
   __shared__ uint32_t s_stage[kStageWords];
-  __shared__ uint32_t s_wrun[kEmitWaves][32];      // per wavefront, per group: record number of its next member
-  __shared__ EmitGroup s_grp[32];                  // what a record of the group needs, read as two 16-byte pieces
-  __shared__ uint32_t s_word0[32];                 // first stream word (group-relative) the chunk touches
-  __shared__ uint32_t s_nwords[32];                // words the chunk touches in each group
-  __shared__ uint32_t s_stage_off[33];
+  // A chunk's tables, two sets: the next chunk's are filled while the current one is written out.
+  __shared__ uint32_t s_wrun[2][kEmitWaves][32];   // per wavefront, per group: record number of its span's first member
+  __shared__ EmitGroup s_grp[2][32];               // what a record of the group needs, read as two 16-byte pieces
+  __shared__ uint32_t s_word0[2][32];              // first stream word (group-relative) the chunk touches
+  __shared__ uint32_t s_nwords[2][32];             // words the chunk touches in each group
+  __shared__ uint32_t s_stage_off[2][33];
   __shared__ uint32_t s_payload[32];
-  // The first and the last word of a (chunk, group) run can be shared with a neighbouring chunk and are
-  // OR-ed into the stream by device-wide atomics.  Whatever the wavefront loads next waits for their
-  // acknowledgement (the counter of outstanding memory operations does not tell loads from atomics), so
-  // they are held back, kEdgeChunks chunks' worth, and issued together.
+  __shared__ uint32_t s_next;                      // the chunk the workgroup takes after the current one
+  // The first and the last word of a (chunk, group) run are OR-ed into the stream by device-wide atomics.
+  // Whatever the wavefront loads next waits for their acknowledgement (the counter of outstanding memory
+  // operations does not tell loads from atomics), so they are held back, kEdgeChunks chunks' worth, and
+  // issued together.
   __shared__ uint32_t s_edge_word[kEdgeChunks][32][2];  // the bits; 0: nothing to OR
   __shared__ uint32_t s_edge_at[kEdgeChunks][32][2];    // the stream word they belong to
-  const uint32_t client = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+  // Workgroups are dispatched in the order of their linear index and a CU serves its oldest first: the
+  // clients' workgroups are interleaved in that order, so that every client has workgroups of every age.
+  const uint32_t linear = blockIdx.y * gridDim.x + blockIdx.x;
+  const uint32_t client = linear % gridDim.y, block_x = linear / gridDim.y;
+  const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
   const ClientParams& p = params[client];
   ClientCtl* ctl = ctls + client;
   if (ctl->dead) return;  // the workspace was too short for this client (whole workgroup)
@@ -1725,11 +1764,11 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
   const uint32_t R = p.R, sbits = position_bits(ws.d);
   const uint32_t* __restrict__ val = ws.dense_val + (size_t)client * ws.dense_cap;
   const uint32_t* __restrict__ idx = ws.dense_idx + (size_t)client * ws.dense_cap;
+  const uint16_t* __restrict__ place = span_places(ws, client);
   const uint32_t* __restrict__ prefix = ws.span_cnt + (size_t)client * (ws.max_spans + 1) * 32;
   GlobalWordPtr stream = (GlobalWordPtr)p.stream;
   const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32), client_id = p.client_id;
 
-  load_thresholds(thr, ctl, R);
   uint32_t my_P = 0, my_W = 0, my_y = 0;
   float my_m = 0.0f, my_inv = 0.0f, my_step = 0.0f;
   if (tid < 32 && tid < R) {
@@ -1744,6 +1783,80 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
   }
   const double inv_B = ERR ? 1.0 / (double)p.B : 0.0;  // the scaling operation of Sec. IV-B
   if (ERR && lane < 32) s_err[wave][lane] = 0.0;       // touched by this wavefront only until the end
+  auto chunk_exists = [&](uint32_t c) { return (uint64_t)c * kChunkSpans < n_spans; };
+  // What a chunk needs of the layout's prefix: the record numbers the wavefront's span starts at (lanes
+  // 0..31: one group each) and, for the first 32 threads, the chunk's record run of a group.
+  uint32_t ahead_row = 0, ahead_first = 0, ahead_last = 0;
+  auto ask_prefix = [&](uint32_t c) {
+    if (!chunk_exists(c)) return;  // uniform
+    const uint32_t span = c * kChunkSpans + wave;
+    if (lane < 32) ahead_row = span < n_spans ? prefix[(size_t)span * 32 + lane] : 0u;
+    if (tid < R && tid < 32) {
+      const uint32_t last_span = min((c + 1) * kChunkSpans, n_spans);
+      ahead_first = prefix[(size_t)c * kChunkSpans * 32 + tid];
+      ahead_last = prefix[(size_t)last_span * 32 + tid];
+    }
+  };
+  // Value bits, position and place of the candidates of the wavefront's span.  Unconditional loads (a
+  // lane past the end reads the last candidate again), so that all of them are in flight together.
+  uint32_t v[kPerLane], pid[kPerLane], plc[kPerLane];
+  auto ask_candidates = [&](uint32_t c) {
+    if (!chunk_exists(c)) return;  // uniform
+#pragma unroll
+    for (uint32_t j = 0; j < kPerLane; ++j) {
+      const uint32_t i = (c * kChunkSpans + wave) * kSpan + j * kWave + lane;
+      const uint32_t at = min(i, n - 1u);
+      v[j] = val[at];
+      pid[j] = idx[at];
+      plc[j] = i < n ? (uint32_t)place[at] : (uint32_t)kNoPlace;
+    }
+  };
+  // Fills set `to` of the chunk tables from what ask_prefix brought.
+  auto set_up = [&](uint32_t to) {
+    if (lane < 32) s_wrun[to][wave][lane] = ahead_row;
+    if (tid < 32) {
+      const uint32_t r = tid;
+      uint32_t nwords = 0, W = 0, first = 0, last = 0, bit_in_word = 0;
+      if (r < R) {
+        const uint32_t P = my_P;
+        W = my_W;
+        // the chunk's record run of group r: [first, last), clamped so that every write stays inside
+        // the group's payload even if an internal check has failed
+        first = ahead_first;
+        last = ahead_last;
+        if (last > P) last = P;
+        if (first > last) first = last;
+        if (last > first) {
+          const uint64_t bit0 = (uint64_t)first * W, bit1 = (uint64_t)last * W;
+          s_word0[to][r] = (uint32_t)(bit0 >> 5);
+          bit_in_word = (uint32_t)(bit0 & 31u);
+          nwords = (uint32_t)(((bit1 - 1) >> 5) - (bit0 >> 5) + 1);
+        }
+      }
+      s_nwords[to][r] = nwords;
+      // exclusive prefix of the staged word counts over the groups
+      const uint32_t incl = wave_incl_scan_u32(nwords);
+      s_stage_off[to][r] = incl - nwords;
+      if (r == 31) s_stage_off[to][32] = incl;
+      EmitGroup eg;
+      eg.first = first;
+      eg.lim = last;
+      eg.W = W;
+      eg.y = my_y;
+      eg.m = my_m;
+      eg.inv = my_inv;
+      eg.stage_bit = (incl - nwords) * 32u + bit_in_word;  // bit of record `first` in the staged image
+      eg.step = my_step;
+      s_grp[to][r] = eg;
+    }
+  };
+  // Which chunks a workgroup takes: its own first, then whichever chunk of the client nobody has
+  // taken yet (a counter of the client's), so that the workgroups of a CU, of which the oldest is served
+  // first, all stay until the work runs out instead of leaving one after the other.  The next chunk is
+  // claimed when the current one begins and known (through s_next) when its records are done.
+  // A chunk goes through two phases with a barrier before each: the records (all wavefronts OR into the
+  // staged image); write the image out, leaving zeros behind.  The next chunk's candidates and prefix
+  // are requested before the current chunk is written out, its tables filled after.
   for (uint32_t i = tid; i < kEdgeChunks * 64u; i += kEmitBlock) (&s_edge_word[0][0][0])[i] = 0;  // groups past R stay 0
   uint32_t held = 0;  // chunks whose edge words are held back
   auto release_edges = [&]() {  // by the whole workgroup, after a barrier
@@ -1752,162 +1865,95 @@ __global__ __launch_bounds__(kEmitBlock, 6) void emit_kernel(const ClientParams*
       if (word) atomicOr((uint32_t*)(stream + (&s_edge_at[0][0][0])[i]), word);
     }
   };
-  for (uint32_t c = blockIdx.x; c * kChunkSpans < n_spans; c += gridDim.x) {
-  // Everything the chunk reads from memory is asked for here, what the tables need first (memory
-  // operations of a wavefront complete in the order they were issued): the record numbers the wavefront's
-  // span starts at, the chunk's record runs, then the span's candidates.
-  uint32_t span_row = 0, run_first = 0, run_last = 0;
-  {
-    const uint32_t span = c * kChunkSpans + wave;
-    if (lane < 32 && span < n_spans) span_row = prefix[(size_t)span * 32 + lane];
-    if (tid < 32 && tid < R) {
-      const uint32_t last_span = min((c + 1) * kChunkSpans, n_spans);
-      run_first = prefix[(size_t)c * kChunkSpans * 32 + tid];
-      run_last = prefix[(size_t)last_span * 32 + tid];
-    }
-  }
-  uint32_t v[kPerLane], grp[kPerLane], pid[kPerLane];
-  load_span(val, n, c * kChunkSpans + wave, v);
-  load_span(idx, n, c * kChunkSpans + wave, pid);
-  __syncthreads();  // the chunk before is written out
-  if (lane < 32) s_wrun[wave][lane] = span_row;  // every wavefront: the record numbers its span starts at
-  if (tid < 32) {
-    const uint32_t r = tid;
-    uint32_t nwords = 0, W = 0, first = 0, last = 0, bit_in_word = 0;
-    if (r < R) {
-      const uint32_t P = my_P;
-      W = my_W;
-      // the chunk's record run of group r: [first, last), clamped so that every write stays inside
-      // the group's payload even if an internal check has failed
-      first = run_first;
-      last = run_last;
-      if (last > P) last = P;
-      if (first > last) first = last;
-      if (last > first) {
-        const uint64_t bit0 = (uint64_t)first * W, bit1 = (uint64_t)last * W;
-        s_word0[r] = (uint32_t)(bit0 >> 5);
-        bit_in_word = (uint32_t)(bit0 & 31u);
-        nwords = (uint32_t)(((bit1 - 1) >> 5) - (bit0 >> 5) + 1);
-      }
-    }
-    s_nwords[r] = nwords;
-    // exclusive prefix of the staged word counts over the groups
-    const uint32_t incl = wave_incl_scan_u32(nwords);
-    s_stage_off[r] = incl - nwords;
-    if (r == 31) s_stage_off[32] = incl;
-    EmitGroup eg;
-    eg.first = first;
-    eg.lim = last;
-    eg.W = W;
-    eg.y = my_y;
-    eg.m = my_m;
-    eg.inv = my_inv;
-    eg.stage_bit = (incl - nwords) * 32u + bit_in_word;  // bit of record `first` in the staged image
-    eg.step = my_step;
-    s_grp[r] = eg;
-  }
-  __syncthreads();
-  const uint32_t staged = s_stage_off[32];
-  for (uint32_t i = tid; i < staged; i += kEmitBlock) s_stage[i] = 0;
-
-  classify_loaded(thr, R, n, c * kChunkSpans + wave, v, grp);
-  __syncthreads();
-  // Record numbers of all eight rows first.  A row's members of a group read the group's running number
-  // and the lowest of them adds the row's members to it; this wavefront alone touches the counters and its
-  // LDS accesses complete in the order they are issued, so no row waits for the one before.
-  uint32_t* wrun = s_wrun[wave];
-  uint32_t start[kPerLane];
-  auto number_rows = [&](auto id_bits) {
+  ask_prefix(block_x);
+  ask_candidates(block_x);
+  for (uint32_t i = tid; i < kStageWords; i += kEmitBlock) s_stage[i] = 0;
+  set_up(0);
+  uint32_t cur = 0;
+  for (uint32_t c = block_x; chunk_exists(c); cur ^= 1u) {
+    uint32_t claimed = 0;
+    if (tid == 0) claimed = atomicAdd(&ctl->emit_claim, 1u);
+    __syncthreads();  // the chunk before is written out (and its image cleared); this chunk's tables are in place
+    const uint32_t* wrun = s_wrun[cur][wave];
 #pragma unroll
     for (uint32_t j = 0; j < kPerLane; ++j) {
-      const uint32_t g = grp[j] < R ? grp[j] : kNoGroup;  // dropped candidates take no record
-      const uint64_t same = same_group_lanes<decltype(id_bits)::value>(g);
-      const uint32_t below = lanes_below(same);
-      start[j] = 0;
-      grp[j] = kNoGroup;
-      if (g != kNoGroup) {
-        grp[j] = g | (below << 8);  // the group and the members of the row in lower lanes
-        start[j] = wrun[g];
-        if (below == 0) atomicAdd(&wrun[g], (uint32_t)__popcll(same));
-      }
-      asm volatile("" ::: "memory");  // the rows' LDS accesses stay in this order; nothing to wait for
-    }
-  };
-  if (R <= 8u) number_rows(std::integral_constant<uint32_t, 3>());        // group ids 0 .. R - 1
-  else if (R <= 16u) number_rows(std::integral_constant<uint32_t, 4>());
-  else number_rows(std::integral_constant<uint32_t, 5>());
-#pragma unroll
-  for (uint32_t j = 0; j < kPerLane; ++j) {
-    if (grp[j] != kNoGroup) {
-      const uint32_t g = grp[j] & 0xFFu;
-      const uint32_t e = start[j] + (grp[j] >> 8);
-      const EmitGroup eg = s_grp[g];
-      if (e < eg.lim) {
-        const uint32_t y = eg.y, W = eg.W;
-        uint32_t cid;
-        if (y == 32) {
-          cid = v[j];
-        } else {
-          const uint32_t u24 = philox_word0(pid[j], client_id, k0, k1) >> 8;
-          if (QSGD)
-            cid = quantise(fabsf(__uint_as_float(v[j])), 0.0f, eg.inv, y - 1u, u24) | ((v[j] >> 31) << (y - 1u));
-          else
-            cid = quantise(__uint_as_float(v[j]), eg.m, eg.inv, y, u24);
-        }
-        if (ERR) {
-          const float x = __uint_as_float(v[j]);
-          float xt = x;
-          if (y != 32) {
-            if (QSGD) {
-              const float mag = __fmaf_rn((float)(cid & ((1u << (y - 1u)) - 1u)), eg.step, 0.0f);
-              xt = (cid >> (y - 1u)) ? -mag : mag;
-            } else {
-              xt = __fmaf_rn((float)cid, eg.step, eg.m);
-            }
+      if (plc[j] != kNoPlace) {
+        const uint32_t g = plc[j] & ((1u << kPlaceShift) - 1u);
+        const uint32_t e = wrun[g] + (plc[j] >> kPlaceShift);
+        const EmitGroup eg = s_grp[cur][g];
+        if (e < eg.lim) {
+          const uint32_t y = eg.y, W = eg.W;
+          uint32_t cid;
+          if (y == 32) {
+            cid = v[j];
+          } else {
+            const uint32_t u24 = philox_word0(pid[j], client_id, k0, k1) >> 8;
+            if (QSGD)
+              cid = quantise(fabsf(__uint_as_float(v[j])), 0.0f, eg.inv, y - 1u, u24) | ((v[j] >> 31) << (y - 1u));
+            else
+              cid = quantise(__uint_as_float(v[j]), eg.m, eg.inv, y, u24);
           }
-          const double err = (double)xt * inv_B - (double)x;
-          atomicAdd(&s_err[wave][g], err * err);
+          if (ERR) {
+            const float x = __uint_as_float(v[j]);
+            float xt = x;
+            if (y != 32) {
+              if (QSGD) {
+                const float mag = __fmaf_rn((float)(cid & ((1u << (y - 1u)) - 1u)), eg.step, 0.0f);
+                xt = (cid >> (y - 1u)) ? -mag : mag;
+              } else {
+                xt = __fmaf_rn((float)cid, eg.step, eg.m);
+              }
+            }
+            const double err = (double)xt * inv_B - (double)x;
+            atomicAdd(&s_err[wave][g], err * err);
+          }
+          const uint64_t record = (uint64_t)pid[j] | ((uint64_t)cid << sbits);
+          // a chunk's run of a group is at most 4096 records of at most 63 bits: 32 bits hold the offset
+          const uint32_t bit = eg.stage_bit + __umul24(e - eg.first, W);
+          const uint32_t w0 = bit >> 5, sh = bit & 31u;
+          const uint64_t lo = record << sh;
+          atomicOr(&s_stage[w0], (uint32_t)lo);
+          if (sh + W > 32u) atomicOr(&s_stage[w0 + 1], (uint32_t)(lo >> 32));
+          if (sh + W > 64u) atomicOr(&s_stage[w0 + 2], (uint32_t)(record >> (64u - sh)));
         }
-        const uint64_t record = (uint64_t)pid[j] | ((uint64_t)cid << sbits);
-        // a chunk's run of a group is at most 4096 records of at most 63 bits: 32 bits hold the offset
-        const uint32_t bit = eg.stage_bit + __umul24(e - eg.first, W);  // fewer than 4096 records, at most 63 bits each
-        const uint32_t w0 = bit >> 5, sh = bit & 31u;
-        const uint64_t lo = record << sh;
-        atomicOr(&s_stage[w0], (uint32_t)lo);
-        if (sh + W > 32u) atomicOr(&s_stage[w0 + 1], (uint32_t)(lo >> 32));
-        if (sh + W > 64u) atomicOr(&s_stage[w0 + 2], (uint32_t)(record >> (64u - sh)));
       }
     }
-  }
-  __syncthreads();
-  // A wavefront writes whole groups' runs, lane l the l-th, l+64-th, ... word (with all 512 threads on one
-  // group after the other most lanes had nothing to write in every group).  A group's size changes steadily
-  // with its number, so the groups are dealt out going up and coming down in turn (wavefront w: w, 15 - w,
-  // 16 + w, 31 - w).
-  for (uint32_t k = 0; k * kEmitWaves < R; ++k) {
-    const uint32_t g = k * kEmitWaves + ((k & 1u) ? kEmitWaves - 1u - wave : wave);
-    if (g >= R) continue;  // uniform per wavefront
-    const uint32_t nwords = s_nwords[g];
-    const uint32_t* staged_words = s_stage + s_stage_off[g];
-    const uint32_t first_word = s_payload[g] + s_word0[g];
-    GlobalWordPtr dst = stream + first_word;
-    if (lane < 2) s_edge_word[held][g][lane] = 0;  // (this wavefront's LDS accesses complete in order)
-    for (uint32_t rel = lane; rel < nwords; rel += kWave) {
-      const uint32_t word = staged_words[rel];
-      if (rel == 0 || rel == nwords - 1) {
-        const uint32_t which = rel == 0 ? 0u : 1u;
-        s_edge_word[held][g][which] = word;
-        s_edge_at[held][g][which] = first_word + rel;
-      } else {
-        dst[rel] = word;
-      }
-    }
-  }
-  if (++held == kEdgeChunks) {  // uniform
+    if (tid == 0) s_next = gridDim.x + claimed;
     __syncthreads();
-    release_edges();
-    held = 0;
-  }
+    const uint32_t c_next = s_next;
+    ask_prefix(c_next);
+    ask_candidates(c_next);
+    // A wavefront writes whole groups' runs, lane l the l-th, l+64-th, ... word (with all 512 threads on one
+    // group after the other most lanes had nothing to write in every group).  A group's size changes steadily
+    // with its number, so the groups are dealt out going up and coming down in turn (wavefront w: w, 15 - w,
+    // 16 + w, 31 - w).
+    for (uint32_t k = 0; k * kEmitWaves < R; ++k) {
+      const uint32_t g = k * kEmitWaves + ((k & 1u) ? kEmitWaves - 1u - wave : wave);
+      if (g >= R) continue;  // uniform per wavefront
+      const uint32_t nwords = s_nwords[cur][g];
+      uint32_t* staged_words = s_stage + s_stage_off[cur][g];
+      const uint32_t first_word = s_payload[g] + s_word0[cur][g];
+      GlobalWordPtr dst = stream + first_word;
+      if (lane < 2) s_edge_word[held][g][lane] = 0;  // (this wavefront's LDS accesses complete in order)
+      for (uint32_t rel = lane; rel < nwords; rel += kWave) {
+        const uint32_t word = staged_words[rel];
+        staged_words[rel] = 0;  // the image is all zeros again when the next chunk begins
+        if (rel == 0 || rel == nwords - 1) {
+          const uint32_t which = rel == 0 ? 0u : 1u;
+          s_edge_word[held][g][which] = word;
+          s_edge_at[held][g][which] = first_word + rel;
+        } else {
+          dst[rel] = word;
+        }
+      }
+    }
+    set_up(cur ^ 1u);  // the next chunk's tables (after the last chunk: tables nobody reads)
+    c = c_next;
+    if (++held == kEdgeChunks) {  // uniform
+      __syncthreads();
+      release_edges();
+      held = 0;
+    }
   }  // chunks
   __syncthreads();
   release_edges();
