@@ -30,13 +30,16 @@
 //                 boundary; after level 3 the exact boundary keys and, where a
 //                 boundary cuts a class of equal magnitudes, the position of
 //                 its last member inside the boundary
-//   count         per span: group of every candidate, per-group count,
-//                 min/max/sum of squares; for the QSGD quantiser also every
-//                 group's exact sum of squares in integer limbs
+//   count         per span: group of every candidate and its number among the
+//                 span's members of that group (left for emit, 16 bits per
+//                 candidate), per-group count, min/max/sum of squares; for the
+//                 QSGD quantiser also every group's exact sum of squares in
+//                 integer limbs
 //   layout        prefix of the per-span counts, headers (QSGD: the group norms
 //                 from the exact sums), statistics
-//   emit          per chunk of 8 spans: stochastic rounding (Philox4x32-10)
-//                 and bit packing; on request the error energy of every group
+//   emit          per chunk of 8 spans: record number from prefix and span
+//                 number, stochastic rounding (Philox4x32-10) and bit packing;
+//                 on request the error energy of every group
 #include <hip/hip_runtime.h>
 
 #include <cmath>
