@@ -1494,16 +1494,41 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
   const uint32_t P = g < R ? p.Z[g] - (g ? p.Z[g - 1] : 0u) : 0u;
   const uint32_t per_wave = (((n_spans + kWideWaves - 1) / kWideWaves + kChunkSpans - 1) / kChunkSpans) * kChunkSpans;
   const uint32_t s0 = min(wave * per_wave, n_spans), s1 = min(s0 + per_wave, n_spans);
-  constexpr uint32_t kBatch = 8;  // loads in flight per lane
+  constexpr uint32_t kBatch = 8;  // loads in flight per lane and batch
+  // A lane's counts of one batch of 2 * kBatch spans from span c on (0 past the wavefront's range); the
+  // loads are not branched around (a lane past the end reads the range's last row), so that they all go out
+  // together.
+  auto load_batch = [&](uint32_t c, uint32_t (&vs)[kBatch]) {
+#pragma unroll
+    for (uint32_t u = 0; u < kBatch; ++u) {
+      const uint32_t cc = c + 2 * u + half;
+      const uint32_t x = cnt[(size_t)min(cc, s1 - 1u) * 32 + g];
+      vs[u] = cc < s1 ? x : 0u;
+    }
+  };
+  // The counts are read twice, for the wavefronts' totals and for the prefix; the first kKeep batches of a
+  // wavefront (all of them up to 768 spans per client) stay in registers in between: this kernel is one
+  // workgroup per client and all latency.
+  constexpr uint32_t kKeep = 3;
+  uint32_t keep[kKeep][kBatch];
   {
     uint32_t acc = 0;
-    for (uint32_t c = s0; c < s1; c += 2 * kBatch) {
-      uint32_t vs[kBatch];
 #pragma unroll
-      for (uint32_t u = 0; u < kBatch; ++u) {
-        const uint32_t cc = c + 2 * u + half;
-        vs[u] = cc < s1 ? cnt[(size_t)cc * 32 + g] : 0u;
+    for (uint32_t b = 0; b < kKeep; ++b) {
+      if (s0 + b * 2 * kBatch < s1) {  // uniform
+        load_batch(s0 + b * 2 * kBatch, keep[b]);
+      } else {
+#pragma unroll
+        for (uint32_t u = 0; u < kBatch; ++u) keep[b][u] = 0;
       }
+    }
+#pragma unroll
+    for (uint32_t b = 0; b < kKeep; ++b)
+#pragma unroll
+      for (uint32_t u = 0; u < kBatch; ++u) acc += keep[b][u];
+    for (uint32_t c = s0 + kKeep * 2 * kBatch; c < s1; c += 2 * kBatch) {
+      uint32_t vs[kBatch];
+      load_batch(c, vs);
 #pragma unroll
       for (uint32_t u = 0; u < kBatch; ++u) acc += vs[u];
     }
@@ -1528,13 +1553,7 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
     }
   };
   uint32_t chunk_begin = run;
-  for (uint32_t c = s0; c < s1; c += 2 * kBatch) {
-    uint32_t vs[kBatch];
-#pragma unroll
-    for (uint32_t u = 0; u < kBatch; ++u) {
-      const uint32_t cc = c + 2 * u + half;
-      vs[u] = cc < s1 ? cnt[(size_t)cc * 32 + g] : 0u;
-    }
+  auto prefix_batch = [&](uint32_t c, const uint32_t (&vs)[kBatch]) {
 #pragma unroll
     for (uint32_t u = 0; u < kBatch; ++u) {
       const uint32_t cp = c + 2 * u;  // the pair's first span
@@ -1547,6 +1566,14 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
       if (cp + half < s1) cnt[(size_t)(cp + half) * 32 + g] = half ? run + other : run;
       run += v + other;
     }
+  };
+#pragma unroll
+  for (uint32_t b = 0; b < kKeep; ++b)
+    if (s0 + b * 2 * kBatch < s1) prefix_batch(s0 + b * 2 * kBatch, keep[b]);  // uniform
+  for (uint32_t c = s0 + kKeep * 2 * kBatch; c < s1; c += 2 * kBatch) {
+    uint32_t vs[kBatch];
+    load_batch(c, vs);
+    prefix_batch(c, vs);
   }
   if (s1 > s0) clear_edges(chunk_begin, run);
   if (wave == 0 && half == 0) {
