@@ -1478,6 +1478,16 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
   const uint32_t lane = lane_id(), wave = tid / kWave;
   GlobalWordPtr stream = (GlobalWordPtr)p.stream;
   uint32_t* cnt = ws.span_cnt + (size_t)client * (ws.max_spans + 1) * 32;
+  // What the headers and the statistics at the end need from memory is asked for here: this kernel is one
+  // workgroup per client and all latency.
+  uint32_t enc_max = 0, enc_negmin = 0;
+  if (tid < R) {
+    enc_max = ctl->seg_max_enc[tid];
+    enc_negmin = ctl->seg_negmin_enc[tid];
+  }
+  const double* rsq = ws.region_sumsq + (size_t)client * ws.n_regions;  // energy the filter dropped, region by region
+  const double tail0 = tid < ws.n_regions ? rsq[tid] : 0.0;
+  const double tail1 = tid + kWideBlock < ws.n_regions ? rsq[tid + kWideBlock] : 0.0;
   if (tid < 32) {  // first stream word of every group's records: exclusive prefix of the payload sizes
     uint32_t words = 0;
     if (tid < R) words = (uint32_t)payload_words(p.Z[tid] - (tid ? p.Z[tid - 1] : 0u), sbits + p.y[tid]);
@@ -1580,10 +1590,9 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
     cnt[(size_t)n_spans * 32 + g] = total;
     if (g < R && total != P) atomicOr(ws.status, CVLC_DEV_INTERNAL);
   }
-  // energy of the coordinates the filter dropped, region by region
-  const double* rsq = ws.region_sumsq + (size_t)client * ws.n_regions;
-  double acc = 0.0;
-  for (uint32_t t = tid; t < ws.n_regions; t += kWideBlock) acc += rsq[t];
+  // energy of the coordinates the filter dropped
+  double acc = tail0 + tail1;
+  for (uint32_t t = tid + 2u * kWideBlock; t < ws.n_regions; t += kWideBlock) acc += rsq[t];
   acc = wave_sum_f64(acc);
   if (lane == 0) s_tail[wave] = acc;
   __syncthreads();
@@ -1592,9 +1601,9 @@ __global__ __launch_bounds__(kWideBlock) void layout_kernel(const ClientParams* 
     const uint32_t r = tid;
     const uint32_t P = p.Z[r] - (r ? p.Z[r - 1] : 0u);
     float m = 0.0f, M = 0.0f;
-    if (P > 0 && ctl->seg_max_enc[r] != 0) {
-      M = from_ordered_bits(ctl->seg_max_enc[r]);
-      m = from_ordered_bits(~ctl->seg_negmin_enc[r]);
+    if (P > 0 && enc_max != 0) {
+      M = from_ordered_bits(enc_max);
+      m = from_ordered_bits(~enc_negmin);
     } else if (P > 0) {
       atomicOr(ws.status, CVLC_DEV_INTERNAL);
     }
