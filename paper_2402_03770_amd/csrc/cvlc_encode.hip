@@ -521,10 +521,15 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
   uint32_t* nz_off = ws.nz_off + (size_t)client * (n_regions + 1);
   uint32_t* nz_run = ws.nz_run + (size_t)client * (n_regions + 1);
   uint32_t* span_first = ws.span_first + (size_t)client * (ws.max_spans + 1);
+  // one workgroup per client, all latency: the first two rounds' counts and the level-1 histogram are
+  // requested before anything is waited for
+  const uint32_t ahead0 = tid < n_regions ? cnt[tid] : 0u;
+  const uint32_t ahead1 = tid + kWideBlock < n_regions ? cnt[tid + kWideBlock] : 0u;
+  const uint32_t l1_even = ctl->hist_l1[2u * tid], l1_odd = ctl->hist_l1[2u * tid + 1];
   uint32_t run = 0, n_nz = 0;
   for (uint32_t base = 0; base < n_regions; base += kWideBlock) {
     const uint32_t j = base + tid;
-    const uint32_t v = j < n_regions ? cnt[j] : 0u;
+    const uint32_t v = base == 0 ? ahead0 : (base == kWideBlock ? ahead1 : (j < n_regions ? cnt[j] : 0u));
     uint32_t tot, tot_nz;
     const uint32_t excl = block_excl_scan<kWideWaves>(v, scan_tmp, &tot);
     const uint32_t q = n_nz + block_excl_scan<kWideWaves>(v ? 1u : 0u, scan_tmp, &tot_nz);
@@ -559,8 +564,8 @@ __global__ __launch_bounds__(kWideBlock) void scan_l1_kernel(const ClientParams*
       ctl->n_cand = run;
       ctl->n_nz = n_nz;
     }
-    hist[2u * tid] = ctl->hist_l1[2u * tid];
-    hist[2u * tid + 1] = ctl->hist_l1[2u * tid + 1];
+    hist[2u * tid] = l1_even;
+    hist[2u * tid + 1] = l1_odd;
   } else {
     const uint32_t d = ws.d;
     __syncthreads();  // the runs written above are overwritten
