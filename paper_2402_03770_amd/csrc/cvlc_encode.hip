@@ -1340,8 +1340,11 @@ __device__ __forceinline__ uint16_t* span_places(const Workspace& ws, uint32_t c
 constexpr uint32_t kLimbBanks = 2;  // copies of a workgroup's limb counters, to thin out colliding LDS atomics
 
 // Every wavefront takes spans of 512 candidates (gw, gw + wavefronts, ...) and
-// writes, per span, the number of members of every group (for the records'
-// places in the stream).  Min, max and sum of squares of the groups go to LDS
+// writes, per span, the number of members of every group and, per candidate,
+// its group and its number among the span's members of that group (together
+// with the layout's prefix over the spans: its record's place in the stream;
+// the packing pass neither classifies nor counts again).  Min, max and sum of
+// squares of the groups go to LDS
 // columns private to a lane id, so that the LDS atomics of one instruction never
 // collide; they are reduced once at the end.  Wavefronts do not wait for each
 // other before that.
