@@ -31,7 +31,10 @@ constexpr uint32_t kL1Bins = 2048;         // level-1 digit: key >> 20 (8 expone
 constexpr uint32_t kDigitBins = 1024;      // level-2 and level-3 digits: 10 bits each
 constexpr uint32_t kSlotGroup = 15;        // boundaries refined per level-2/3 launch (60 KB of LDS) for plans of up to 15 groups
 constexpr uint32_t kSlotGroupWide = 31;    // ... for plans of more groups: all boundaries at once (124 KB of LDS)
-constexpr uint32_t kSampleChunksMax = 16384;  // 64-byte pieces in the sample (256 Ki coordinates)
+constexpr uint32_t kSamplePieceQuads = 16;    // a piece of the sample: 16 float4 = 64 coordinates = 256 bytes (random 64-byte
+                                              // reads run at a fifth of what HBM gives 256-byte ones: 21 against 14 us for the pass)
+constexpr uint32_t kSamplePiece = 4u * kSamplePieceQuads;  // coordinates per piece
+constexpr uint32_t kSampleChunksMax = 4096;   // pieces in the sample (256 Ki coordinates)
 constexpr uint32_t kTieCap = 2048;         // boundary-class members kept per histogram slot for tie resolution
 constexpr uint32_t kSampleBlocks = 16;     // workgroups per client in the sample pass
 constexpr uint32_t kStatsStride = CVLC_STATS_STRIDE;

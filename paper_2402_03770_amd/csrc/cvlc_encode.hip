@@ -197,7 +197,7 @@ constexpr uint32_t kWideBlock = 1024;
 constexpr uint32_t kWideWaves = kWideBlock / kWave;
 
 // ------------------------------------------------------------------ 1. sample histogram
-// Reads n_s 64-byte pieces spread evenly over the vector and histograms the
+// Reads n_s 256-byte pieces spread evenly over the vector and histograms the
 // magnitude keys on their top 13 bits.  kSampleBlocks workgroups per client each
 // take a slice of the pieces, issue their loads eight deep, and add their
 // non-empty bins to the client's histogram.
@@ -212,7 +212,7 @@ __global__ __launch_bounds__(kBlock) void sample_hist_kernel(const ClientParams*
   for (uint32_t i = threadIdx.x; i < kSampleBins; i += kBlock) hist[i] = 0;
   __syncthreads();
   GlobalFloat4Ptr src = (GlobalFloat4Ptr)p.update;
-  const uint32_t total_q = n_s * 4u;
+  const uint32_t total_q = n_s * kSamplePieceQuads;
   const uint32_t per_block = (total_q + gridDim.x - 1) / gridDim.x;
   const uint32_t q_begin = blockIdx.x * per_block;
   const uint32_t q_end = min(total_q, q_begin + per_block);
@@ -225,9 +225,9 @@ __global__ __launch_bounds__(kBlock) void sample_hist_kernel(const ClientParams*
       live[u] = q < q_end;
       v[u] = Float4V{0.0f, 0.0f, 0.0f, 0.0f};
       if (live[u]) {
-        const uint32_t j = q >> 2, part = q & 3u;
+        const uint32_t j = q / kSamplePieceQuads, part = q % kSamplePieceQuads;
         const uint64_t piece = ((uint64_t)j * piece_step) >> 32;  // piece_step = 2^32 * pieces / n_s, rounded down
-        v[u] = src[piece * 4u + part];
+        v[u] = src[piece * kSamplePieceQuads + part];
       }
     }
 #pragma unroll
@@ -2102,8 +2102,8 @@ uint32_t cvlc_plan_candidates_hint(const cvlc_plan_t* plan) {
   const uint32_t d = plan->d;
   uint64_t k = 0;
   for (uint32_t r = 0; r < plan->n_coded; ++r) k += plan->count[r];
-  const uint32_t n_src = d / 16u;
-  const uint32_t n_sampled = (n_src < kSampleChunksMax ? n_src : kSampleChunksMax) * 16u;
+  const uint32_t n_src = d / kSamplePiece;
+  const uint32_t n_sampled = (n_src < kSampleChunksMax ? n_src : kSampleChunksMax) * kSamplePiece;
   const uint32_t rank = sample_rank(d, (uint32_t)k, n_sampled);
   if (rank == 0) return d;  // no threshold is sampled for this plan: every coordinate is a candidate
   // The share of the vector at or above the sample's rank-th largest key is rank / n_sampled give or take
@@ -2155,8 +2155,8 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
   ws.filter_blocks = filter_blocks_per_client(L.n_regions, n, filter_resident_blocks());
   ws.sel_blocks = L.sel_blocks;
 
-  // sample geometry: 64-byte pieces spread evenly; all of them when the vector is short
-  const uint32_t n_src = d / 16u;
+  // sample geometry: 256-byte pieces spread evenly; all of them when the vector is short
+  const uint32_t n_src = d / kSamplePiece;
   const uint32_t n_s = n_src < kSampleChunksMax ? n_src : kSampleChunksMax;
 
   profile_mark(CVLC_STAGE_ENC_SETUP, true, stream);
@@ -2198,7 +2198,7 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
         cp.y[r] = (uint8_t)pl.code_len[r];
       }
       cp.k = z;
-      cp.sample_rank = sample_rank(d, z, n_s * 16u);
+      cp.sample_rank = sample_rank(d, z, n_s * kSamplePiece);
       any_sampled |= cp.sample_rank != 0;
       if (pl.n_coded > max_R) max_R = pl.n_coded;
       for (int attempt = 0; attempt < 2; ++attempt) {
@@ -2231,7 +2231,7 @@ int cvlc_encode_batch(uint32_t n, const cvlc_plan_t* plans, const float* const* 
 
   if (any_sampled) {
     StageScope scope(CVLC_STAGE_ENC_SAMPLE, stream);
-    // n_src < 2^28 and n_s <= 2^14: the step is below 2^60 / n_s and j * step below 2^60
+    // n_src < 2^26 and n_s <= 2^12: the step is below 2^58 / n_s and j * step below 2^58
     hipLaunchKernelGGL(sample_hist_kernel, dim3(kSampleBlocks, n), dim3(kBlock), 0, stream, ws.params, ws.ctl, n_s,
                        n_s ? ((uint64_t)n_src << 32) / n_s : 0u);
     hipLaunchKernelGGL(sample_walk_kernel, dim3(n), dim3(kWideBlock), 0, stream, ws.params, ws.ctl);

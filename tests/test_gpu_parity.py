@@ -192,16 +192,24 @@ def test_tie_heavy_vectors_with_more_than_fifteen_groups(kind):
         check_decode(refs, d)
 
 
+SAMPLE_PIECE, SAMPLE_PIECES = 64, 4096  # the encoder's sample: evenly spread pieces of 64 coordinates
+
+
+def plant_on_the_sampled_pieces(U, rng):
+    """Large values on exactly the coordinates the encoder samples (262 144 of them), in place."""
+    n_src, n_s = U.size // SAMPLE_PIECE, SAMPLE_PIECES
+    pieces = (np.arange(n_s, dtype=np.int64) * n_src) // n_s
+    for off in range(SAMPLE_PIECE):
+        U[pieces * SAMPLE_PIECE + off] = (rng.standard_normal(n_s) * 10.0).astype(np.float32)
+
+
 def test_misjudged_sample_in_a_workspace_sized_to_the_plan():
     """When the sampled threshold keeps fewer than k coordinates every coordinate becomes a candidate, which a
     workspace sized to the plan has no room for: that client is refused, not encoded wrongly."""
     d = 2_000_000
     rng = np.random.default_rng(5)
     U = (rng.standard_normal(d) * 1e-4).astype(np.float32)
-    n_src, n_s = d // 16, 16384
-    pieces = (np.arange(n_s, dtype=np.int64) * n_src) // n_s
-    for off in range(16):
-        U[pieces * 16 + off] = (rng.standard_normal(n_s) * 10.0).astype(np.float32)
+    plant_on_the_sampled_pieces(U, rng)
     po = orc.plan_manual(d, [8, 4, 2], [50_000, 100_000, 150_000])
     p = to_lib_plan(po)
     stream = cv.new_stream_buffer(p, DEV)
@@ -277,16 +285,13 @@ def test_workloads_at_oracle_friendly_sizes(cfg, d, n):
 
 # --------------------------------------------------------------------------- the encoder's internal fallbacks
 def test_sample_that_misjudges_the_threshold():
-    """The encoder places its candidate threshold from a strided sample of 64-byte pieces.
+    """The encoder places its candidate threshold from a strided sample of 256-byte pieces.
     Here exactly the sampled pieces hold large values and everything else small ones, so the
     sampled threshold keeps far fewer than k coordinates and the keep-all pass has to run."""
     d = 2_000_000
     rng = np.random.default_rng(5)
     U = (rng.standard_normal(d) * 1e-4).astype(np.float32)
-    n_src, n_s = d // 16, 16384
-    pieces = (np.arange(n_s, dtype=np.int64) * n_src) // n_s
-    for off in range(16):
-        U[pieces * 16 + off] = (rng.standard_normal(n_s) * 10.0).astype(np.float32)
+    plant_on_the_sampled_pieces(U, rng)
     p = orc.plan_manual(d, [8, 4, 2], [50_000, 100_000, 150_000])   # k = 300 000 > the 262 144 large values
     refs, _ = check_encode([U], [p], 21, [3])
     check_decode(refs, d)
